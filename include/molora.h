@@ -1,0 +1,155 @@
+/*
+ * molora.h -- C ABI of the MI355X (gfx950) routed-LoRA hot path.
+ *
+ * The library computes the per-token routed LoRA projection of the MoLoRA paper
+ * (Eq. "pertok"):
+ *
+ *     h_i = x_i W + x_i A_{r(i)} B_{r(i)},        r : [N] -> [C]
+ *
+ * in the execution order of the paper's physical pipeline (Fig. "molora", right):
+ * router -> histogram & group by adapter -> grouped GEMM -> scatter back to the
+ * original positions.
+ *
+ * Conventions that hold for every entry point
+ * -------------------------------------------
+ *  - Every pointer marked DEVICE is device memory owned by the caller (for example a
+ *    torch tensor's data_ptr()); pointers marked HOST are ordinary host memory read
+ *    during the call.  The library never allocates, frees or retains caller memory.
+ *  - `stream` is a hipStream_t passed as void* (NULL = the default stream).  Every call
+ *    only enqueues work on it and returns without synchronising; results are valid
+ *    once the stream has reached that point.
+ *  - Layouts are dense row-major with no strides (stacked weight shapes of Table
+ *    "tab:moe_adapter": A is (C, d_in, rank), B is (C, rank, d_out)):
+ *        x [N][d_in] bf16      W [d_in][d_out] bf16      G [d_in][C] bf16
+ *        A [C][d_in][rank] bf16          B [C][rank][d_out] bf16
+ *        r [N] int32           offsets [C+1] int32       perm [N] int32
+ *        h [N][d_out] fp32
+ *    bf16 values are raw 16-bit patterns.  Device pointers must be 16-byte aligned.
+ *  - Return value: MOLORA_OK, or a negative code.  Problems the host can see (null
+ *    pointer, bad size, misalignment, workspace too small) are reported before anything
+ *    is enqueued and leave all outputs untouched.  A failed launch maps to MOLORA_EHIP.
+ *  - Data-dependent problems (a routing target outside [0, C)) cannot be seen by the
+ *    host without a synchronisation; they are reported through an optional DEVICE flag
+ *    and handled as "this token has no adapter" (see molora_bucket).
+ *  - Inputs are expected to be finite.  A NaN gate logit never wins the argmax.
+ */
+#ifndef MOLORA_H
+#define MOLORA_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef int molora_status;
+
+enum {
+    MOLORA_OK = 0,
+    MOLORA_EINVAL = -1,     /* null pointer, non-positive or unsupported size          */
+    MOLORA_EALIGN = -2,     /* a device pointer is not 16-byte aligned                 */
+    MOLORA_EWORKSPACE = -3, /* workspace_bytes smaller than molora_apply_workspace_bytes */
+    MOLORA_EHIP = -5        /* the HIP runtime reported an error at launch            */
+};
+
+/* Limits of this implementation (checked, MOLORA_EINVAL beyond them). */
+#define MOLORA_MAX_TARGETS 1024 /* C                                   */
+#define MOLORA_MAX_RANK 128     /* rank, which must be a multiple of 8 */
+#define MOLORA_MAX_BREAKS 64    /* M of molora_route_vocab             */
+
+/*
+ * Learned routing with one selected adapter per token (Sec. "Router Architecture"
+ * with k = 1: the softmax over the single selected logit is 1, which leaves Eq.
+ * "pertok").  The gate is the linear, bias-free form of Table "tab:moe_adapter":
+ *
+ *     r[i] = argmax_c sum_k x[i][k] * G[k][c],     lowest c on ties.
+ *
+ * Each logit is accumulated in fp32 in ascending k, one rounded addition per term
+ * (the bf16 x bf16 products are exact in fp32), so r is a deterministic function of
+ * the input bits.
+ *   x DEVICE bf16 [N][d_in]; G DEVICE bf16 [d_in][C]; r DEVICE int32 [N] (written).
+ *   N >= 0; d_in >= 1 and a multiple of 8; 1 <= C <= MOLORA_MAX_TARGETS.
+ */
+molora_status molora_route(const void *x, const void *G, int32_t *r,
+                           int64_t N, int32_t d_in, int32_t C, void *stream);
+
+/*
+ * Vocabulary routing (Def. "Vocabulary Routing"): with breaks b_0 < b_1 < ... < b_M the
+ * token id v routes to the 0-based range m with b_m <= v < b_{m+1}; ids outside
+ * [b_0, b_M) get -1 ("no adapter").
+ *   v DEVICE int32 [N]; breaks HOST int32 [M+1], strictly increasing, copied during the
+ *   call; r DEVICE int32 [N] (written).  1 <= M <= MOLORA_MAX_BREAKS.
+ */
+molora_status molora_route_vocab(const int32_t *v, const int32_t *breaks, int32_t M,
+                                 int32_t *r, int64_t N, void *stream);
+
+/*
+ * Dispatch (Sec. "Unified Dispatch Infrastructure", Alg. "Unified Dispatch Kernel"):
+ * histogram of tokens per target and a position for every token inside its target's
+ * list.  Where the paper hands out positions with an atomic counter (any order inside a
+ * list), this library orders every list by ascending token index, which makes the
+ * result unique; offsets + perm carry the same information as the paper's per-target
+ * pointer arrays xs/ys (row p of the grouped problem is x[perm[p]] and lands in
+ * h[perm[p]]).
+ *
+ *     offsets[0] = 0,  offsets[c+1] = offsets[c] + |{t : r[t] = c}|      (c < C)
+ *     perm[offsets[c] .. offsets[c+1]) = tokens with r = c, ascending
+ *     perm[offsets[C] .. N)            = tokens with r outside [0, C), ascending
+ *
+ * so perm is always a permutation of 0..N-1 and offsets[C] <= N counts the routed
+ * tokens.  If err_flag is not NULL it is set to 1 when some r[t] is outside [0, C) and
+ * left unchanged otherwise (the caller zeroes it).
+ *   r DEVICE int32 [N]; offsets DEVICE int32 [C+1]; perm DEVICE int32 [N];
+ *   err_flag DEVICE int32 [1] or NULL.  0 <= N < 2^31; 1 <= C <= MOLORA_MAX_TARGETS.
+ */
+molora_status molora_bucket(const int32_t *r, int32_t *offsets, int32_t *perm,
+                            int64_t N, int32_t C, int32_t *err_flag, void *stream);
+
+/*
+ * Bytes of DEVICE workspace molora_apply / molora_apply_bucketed need for these sizes
+ * (0 if the sizes are invalid).  The workspace holds the bucketing (molora_apply only),
+ * the low-rank intermediate t = x A_r in sorted order and small tile tables; its
+ * contents are scratch and need no initialisation.
+ */
+size_t molora_apply_workspace_bytes(int64_t N, int32_t d_in, int32_t d_out,
+                                    int32_t C, int32_t rank);
+
+/*
+ * The routed projection, Eq. "pertok":  h[i][:] = x[i] W + (x[i] A[r[i]]) B[r[i]].
+ * Buckets r internally (as molora_bucket), computes the grouped shrink t = x A_c, then
+ * one GEMM pass that adds the grouped expand t B_c in the epilogue of x W and writes
+ * every row of h once, at its original position.  A token whose r[i] is outside [0, C)
+ * gets h[i] = x[i] W.  bf16 products are accumulated in fp32; t is carried as a pair of
+ * bf16 values (high part + remainder), so its rounding does not limit the result.
+ *   x, W, A, B, r DEVICE (read); h DEVICE fp32 [N][d_out] (every element written);
+ *   workspace DEVICE, 256-byte aligned, workspace_bytes >= molora_apply_workspace_bytes.
+ *   0 <= N < 2^31; d_in, d_out >= 8 and multiples of 8; rank a multiple of 8,
+ *   8 <= rank <= MOLORA_MAX_RANK; 1 <= C <= MOLORA_MAX_TARGETS.
+ */
+molora_status molora_apply(const void *x, const void *W, const void *A, const void *B,
+                           const int32_t *r, float *h,
+                           int64_t N, int32_t d_in, int32_t d_out, int32_t C, int32_t rank,
+                           void *workspace, size_t workspace_bytes, void *stream);
+
+/*
+ * Same as molora_apply for a caller that already holds molora_bucket's output for r
+ * (for example several projections that share one routing decision): offsets and perm
+ * replace r, and the bucketing step is skipped.
+ */
+molora_status molora_apply_bucketed(const void *x, const void *W, const void *A, const void *B,
+                                    const int32_t *offsets, const int32_t *perm, float *h,
+                                    int64_t N, int32_t d_in, int32_t d_out, int32_t C,
+                                    int32_t rank, void *workspace, size_t workspace_bytes,
+                                    void *stream);
+
+/* Human-readable name of a status code (static storage, never NULL). */
+const char *molora_status_string(molora_status status);
+
+/* Library version string, e.g. "molora-gfx950 0.1" (static storage). */
+const char *molora_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* MOLORA_H */

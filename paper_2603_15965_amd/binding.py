@@ -1,0 +1,186 @@
+"""Thin ctypes binding of libmolora.so (the C ABI of include/molora.h).
+
+Argument marshalling only: torch supplies device memory and the current HIP stream, every
+step of the path runs in the library's kernels.  There is no fallback: if the library is
+not built, the first call raises.
+"""
+import ctypes
+import os
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libmolora.so")
+
+MOLORA_OK = 0
+EXPORTS = ["molora_route", "molora_route_vocab", "molora_bucket", "molora_apply_workspace_bytes",
+           "molora_apply", "molora_apply_bucketed", "molora_status_string", "molora_version"]
+
+_lib = None
+
+
+class MoloraError(RuntimeError):
+    def __init__(self, status, what):
+        self.status = status
+        super().__init__(f"{what}: {status_string(status)} ({status})")
+
+
+def load():
+    """dlopen the library and declare the prototypes (no GPU needed for this)."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise FileNotFoundError(
+            f"{LIB_PATH} is not built; run `python -m paper_2603_15965_amd.build` "
+            "(or __graft_entry__.build()) first")
+    lib = ctypes.CDLL(LIB_PATH)
+    vp, i64, i32, sz = ctypes.c_void_p, ctypes.c_int64, ctypes.c_int32, ctypes.c_size_t
+    lib.molora_route.argtypes = [vp, vp, vp, i64, i32, i32, vp]
+    lib.molora_route.restype = ctypes.c_int
+    lib.molora_route_vocab.argtypes = [vp, ctypes.POINTER(i32), i32, vp, i64, vp]
+    lib.molora_route_vocab.restype = ctypes.c_int
+    lib.molora_bucket.argtypes = [vp, vp, vp, i64, i32, vp, vp]
+    lib.molora_bucket.restype = ctypes.c_int
+    lib.molora_apply_workspace_bytes.argtypes = [i64, i32, i32, i32, i32]
+    lib.molora_apply_workspace_bytes.restype = sz
+    lib.molora_apply.argtypes = [vp, vp, vp, vp, vp, vp, i64, i32, i32, i32, i32, vp, sz, vp]
+    lib.molora_apply.restype = ctypes.c_int
+    lib.molora_apply_bucketed.argtypes = [vp, vp, vp, vp, vp, vp, vp, i64, i32, i32, i32, i32, vp, sz, vp]
+    lib.molora_apply_bucketed.restype = ctypes.c_int
+    lib.molora_status_string.argtypes = [ctypes.c_int]
+    lib.molora_status_string.restype = ctypes.c_char_p
+    lib.molora_version.argtypes = []
+    lib.molora_version.restype = ctypes.c_char_p
+    _lib = lib
+    return lib
+
+
+def status_string(status):
+    return load().molora_status_string(int(status)).decode()
+
+
+def version():
+    return load().molora_version().decode()
+
+
+def _check(status, what):
+    if status != MOLORA_OK:
+        raise MoloraError(status, what)
+
+
+def _dev(t, dtype, name):
+    if not isinstance(t, torch.Tensor) or not t.is_cuda:
+        raise TypeError(f"{name} must be a device tensor")
+    if t.dtype != dtype:
+        raise TypeError(f"{name} must be {dtype}, got {t.dtype}")
+    if not t.is_contiguous():
+        raise ValueError(f"{name} must be contiguous")
+    return t.data_ptr()
+
+
+def _stream(stream):
+    if stream is None:
+        return torch.cuda.current_stream().cuda_stream
+    return stream.cuda_stream if hasattr(stream, "cuda_stream") else int(stream)
+
+
+def molora_route(x, G, r=None, stream=None):
+    """r[i] = argmax_c x[i] . G[:, c] (fp32 ascending-k chain, lowest index on ties)."""
+    N, d_in = x.shape
+    C = G.shape[1]
+    if G.shape[0] != d_in:
+        raise ValueError("G must be [d_in][C]")
+    if r is None:
+        r = torch.empty(N, dtype=torch.int32, device=x.device)
+    st = load().molora_route(_dev(x, torch.bfloat16, "x"), _dev(G, torch.bfloat16, "G"),
+                             _dev(r, torch.int32, "r"), N, d_in, C, _stream(stream))
+    _check(st, "molora_route")
+    return r
+
+
+def molora_route_vocab(v, breaks, r=None, stream=None):
+    """r[i] = m with breaks[m] <= v[i] < breaks[m+1], else -1.  breaks: host ints."""
+    N = v.shape[0]
+    b = [int(t) for t in breaks]
+    M = len(b) - 1
+    arr = (ctypes.c_int32 * len(b))(*b)
+    if r is None:
+        r = torch.empty(N, dtype=torch.int32, device=v.device)
+    st = load().molora_route_vocab(_dev(v, torch.int32, "v"), arr, M, _dev(r, torch.int32, "r"), N,
+                                   _stream(stream))
+    _check(st, "molora_route_vocab")
+    return r
+
+
+def molora_bucket(r, C, offsets=None, perm=None, err_flag=None, stream=None):
+    """Stable grouping of tokens by target: returns (offsets[C+1], perm[N])."""
+    N = r.shape[0]
+    if offsets is None:
+        offsets = torch.empty(C + 1, dtype=torch.int32, device=r.device)
+    if perm is None:
+        perm = torch.empty(max(N, 1), dtype=torch.int32, device=r.device)[:N]
+    st = load().molora_bucket(_dev(r, torch.int32, "r"), _dev(offsets, torch.int32, "offsets"),
+                              _dev(perm, torch.int32, "perm"), N, C,
+                              None if err_flag is None else _dev(err_flag, torch.int32, "err_flag"),
+                              _stream(stream))
+    _check(st, "molora_bucket")
+    return offsets, perm
+
+
+def molora_apply_workspace_bytes(N, d_in, d_out, C, rank):
+    return int(load().molora_apply_workspace_bytes(N, d_in, d_out, C, rank))
+
+
+def _shapes(x, W, A, B):
+    N, d_in = x.shape
+    d_out = W.shape[1]
+    C, _, rank = A.shape
+    if W.shape[0] != d_in or A.shape[1] != d_in or tuple(B.shape) != (C, rank, d_out):
+        raise ValueError("expected W [d_in][d_out], A [C][d_in][rank], B [C][rank][d_out]")
+    return N, d_in, d_out, C, rank
+
+
+def new_workspace(N, d_in, d_out, C, rank, device="cuda"):
+    nbytes = molora_apply_workspace_bytes(N, d_in, d_out, C, rank)
+    return torch.empty(max(nbytes, 256), dtype=torch.uint8, device=device)
+
+
+def molora_apply(x, W, A, B, r, h=None, workspace=None, stream=None):
+    """h[i] = x[i] W + (x[i] A[r[i]]) B[r[i]]  (fp32 [N][d_out])."""
+    N, d_in, d_out, C, rank = _shapes(x, W, A, B)
+    if h is None:
+        h = torch.empty((N, d_out), dtype=torch.float32, device=x.device)
+    if workspace is None:
+        workspace = new_workspace(N, d_in, d_out, C, rank, x.device)
+    bf = torch.bfloat16
+    st = load().molora_apply(_dev(x, bf, "x"), _dev(W, bf, "W"), _dev(A, bf, "A"), _dev(B, bf, "B"),
+                             _dev(r, torch.int32, "r"), _dev(h, torch.float32, "h"),
+                             N, d_in, d_out, C, rank, _dev(workspace, torch.uint8, "workspace"),
+                             workspace.numel(), _stream(stream))
+    _check(st, "molora_apply")
+    return h
+
+
+def molora_apply_bucketed(x, W, A, B, offsets, perm, h=None, workspace=None, stream=None):
+    """molora_apply for a caller that already holds molora_bucket's output."""
+    N, d_in, d_out, C, rank = _shapes(x, W, A, B)
+    if h is None:
+        h = torch.empty((N, d_out), dtype=torch.float32, device=x.device)
+    if workspace is None:
+        workspace = new_workspace(N, d_in, d_out, C, rank, x.device)
+    bf = torch.bfloat16
+    st = load().molora_apply_bucketed(
+        _dev(x, bf, "x"), _dev(W, bf, "W"), _dev(A, bf, "A"), _dev(B, bf, "B"),
+        _dev(offsets, torch.int32, "offsets"), _dev(perm, torch.int32, "perm"),
+        _dev(h, torch.float32, "h"), N, d_in, d_out, C, rank,
+        _dev(workspace, torch.uint8, "workspace"), workspace.numel(), _stream(stream))
+    _check(st, "molora_apply_bucketed")
+    return h
+
+
+def bf16_tensor(bits, device="cuda"):
+    """numpy uint16 bit patterns -> torch.bfloat16 tensor on the device (same bits)."""
+    import numpy as np
+    t = torch.from_numpy(np.ascontiguousarray(bits).view(np.int16))
+    return t.to(device).view(torch.bfloat16)

@@ -1,0 +1,149 @@
+// C ABI of libmolora: argument checking and the order of launches.  No arithmetic here.
+#include "../../include/molora.h"
+
+#include "common.h"
+
+namespace {
+
+inline bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+inline bool aligned256(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 255u) == 0; }
+inline size_t round256(size_t b) { return (b + 255u) & ~size_t(255); }
+
+inline bool apply_sizes_ok(int64_t N, int32_t d_in, int32_t d_out, int32_t C, int32_t rank) {
+    return N >= 0 && N < (int64_t(1) << 31) && d_in >= 8 && d_in % 8 == 0 && d_out >= 8 &&
+           d_out % 8 == 0 && C >= 1 && C <= MOLORA_MAX_TARGETS && rank >= 8 && rank % 8 == 0 &&
+           rank <= MOLORA_MAX_RANK;
+}
+
+struct Workspace {
+    int32_t *offsets;
+    int32_t *perm;
+    uint16_t *t2;
+    size_t bytes;
+};
+
+inline Workspace carve(void *base, int64_t N, int32_t C, int32_t rank) {
+    Workspace w;
+    unsigned char *p = static_cast<unsigned char *>(base);
+    size_t off = 0;
+    w.offsets = reinterpret_cast<int32_t *>(p + off);
+    off += round256(size_t(C + 1) * sizeof(int32_t));
+    w.perm = reinterpret_cast<int32_t *>(p + off);
+    off += round256(size_t(N) * sizeof(int32_t));
+    w.t2 = reinterpret_cast<uint16_t *>(p + off);
+    off += round256(size_t(N) * 2 * size_t(rank) * sizeof(uint16_t));
+    w.bytes = off;
+    return w;
+}
+
+inline molora_status from_hip(hipError_t e) { return e == hipSuccess ? MOLORA_OK : MOLORA_EHIP; }
+
+molora_status apply_common(const void *x, const void *W, const void *A, const void *B,
+                           const int32_t *r, const int32_t *offsets, const int32_t *perm, float *h,
+                           int64_t N, int32_t d_in, int32_t d_out, int32_t C, int32_t rank,
+                           void *workspace, size_t workspace_bytes, void *stream) {
+    if (!apply_sizes_ok(N, d_in, d_out, C, rank)) return MOLORA_EINVAL;
+    if (N == 0) return MOLORA_OK;
+    if (!x || !W || !A || !B || !h || !workspace) return MOLORA_EINVAL;
+    if (r == nullptr && (offsets == nullptr || perm == nullptr)) return MOLORA_EINVAL;
+    if (!aligned16(x) || !aligned16(W) || !aligned16(A) || !aligned16(B) || !aligned16(h) ||
+        (r && !aligned16(r)) || (offsets && !aligned16(offsets)) || (perm && !aligned16(perm)) ||
+        !aligned256(workspace))
+        return MOLORA_EALIGN;
+    const Workspace ws = carve(workspace, N, C, rank);
+    if (workspace_bytes < ws.bytes) return MOLORA_EWORKSPACE;
+
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    const uint16_t *xb = static_cast<const uint16_t *>(x);
+    hipError_t e;
+    if (r != nullptr) {
+        e = molora::launch_bucket(r, ws.offsets, ws.perm, N, C, nullptr, s);
+        if (e != hipSuccess) return MOLORA_EHIP;
+        offsets = ws.offsets;
+        perm = ws.perm;
+    }
+    e = molora::launch_shrink(xb, static_cast<const uint16_t *>(A), offsets, perm, ws.t2, N, d_in,
+                              C, rank, s);
+    if (e != hipSuccess) return MOLORA_EHIP;
+    e = molora::launch_fused_gemm(xb, static_cast<const uint16_t *>(W),
+                                  static_cast<const uint16_t *>(B), ws.t2, offsets, perm, h, N,
+                                  d_in, d_out, C, rank, s);
+    return from_hip(e);
+}
+
+}  // namespace
+
+extern "C" {
+
+molora_status molora_route(const void *x, const void *G, int32_t *r, int64_t N, int32_t d_in,
+                           int32_t C, void *stream) {
+    if (N < 0 || N >= (int64_t(1) << 31) || d_in < 8 || d_in % 8 != 0 || C < 1 ||
+        C > MOLORA_MAX_TARGETS)
+        return MOLORA_EINVAL;
+    if (N == 0) return MOLORA_OK;
+    if (!x || !G || !r) return MOLORA_EINVAL;
+    if (!aligned16(x) || !aligned16(G) || !aligned16(r)) return MOLORA_EALIGN;
+    return from_hip(molora::launch_route_gate(static_cast<const uint16_t *>(x),
+                                              static_cast<const uint16_t *>(G), r, N, d_in, C,
+                                              static_cast<hipStream_t>(stream)));
+}
+
+molora_status molora_route_vocab(const int32_t *v, const int32_t *breaks, int32_t M, int32_t *r,
+                                 int64_t N, void *stream) {
+    if (N < 0 || N >= (int64_t(1) << 31) || M < 1 || M > MOLORA_MAX_BREAKS || !breaks)
+        return MOLORA_EINVAL;
+    for (int j = 0; j < M; ++j)
+        if (breaks[j] >= breaks[j + 1]) return MOLORA_EINVAL;
+    if (N == 0) return MOLORA_OK;
+    if (!v || !r) return MOLORA_EINVAL;
+    if (!aligned16(v) || !aligned16(r)) return MOLORA_EALIGN;
+    return from_hip(molora::launch_route_vocab(v, breaks, M, r, N, static_cast<hipStream_t>(stream)));
+}
+
+molora_status molora_bucket(const int32_t *r, int32_t *offsets, int32_t *perm, int64_t N,
+                            int32_t C, int32_t *err_flag, void *stream) {
+    if (N < 0 || N >= (int64_t(1) << 31) || C < 1 || C > MOLORA_MAX_TARGETS) return MOLORA_EINVAL;
+    if (!offsets || (N > 0 && (!r || !perm))) return MOLORA_EINVAL;
+    if (!aligned16(offsets) || (N > 0 && (!aligned16(r) || !aligned16(perm)))) return MOLORA_EALIGN;
+    return from_hip(molora::launch_bucket(r, offsets, perm, N, C, err_flag,
+                                          static_cast<hipStream_t>(stream)));
+}
+
+size_t molora_apply_workspace_bytes(int64_t N, int32_t d_in, int32_t d_out, int32_t C,
+                                    int32_t rank) {
+    if (!apply_sizes_ok(N, d_in, d_out, C, rank)) return 0;
+    return carve(nullptr, N, C, rank).bytes;
+}
+
+molora_status molora_apply(const void *x, const void *W, const void *A, const void *B,
+                           const int32_t *r, float *h, int64_t N, int32_t d_in, int32_t d_out,
+                           int32_t C, int32_t rank, void *workspace, size_t workspace_bytes,
+                           void *stream) {
+    if (N > 0 && !r) return MOLORA_EINVAL;
+    return apply_common(x, W, A, B, r, nullptr, nullptr, h, N, d_in, d_out, C, rank, workspace,
+                        workspace_bytes, stream);
+}
+
+molora_status molora_apply_bucketed(const void *x, const void *W, const void *A, const void *B,
+                                    const int32_t *offsets, const int32_t *perm, float *h,
+                                    int64_t N, int32_t d_in, int32_t d_out, int32_t C, int32_t rank,
+                                    void *workspace, size_t workspace_bytes, void *stream) {
+    if (N > 0 && (!offsets || !perm)) return MOLORA_EINVAL;
+    return apply_common(x, W, A, B, nullptr, offsets, perm, h, N, d_in, d_out, C, rank, workspace,
+                        workspace_bytes, stream);
+}
+
+const char *molora_status_string(molora_status status) {
+    switch (status) {
+        case MOLORA_OK: return "ok";
+        case MOLORA_EINVAL: return "invalid argument (null pointer or unsupported size)";
+        case MOLORA_EALIGN: return "device pointer not sufficiently aligned";
+        case MOLORA_EWORKSPACE: return "workspace too small";
+        case MOLORA_EHIP: return "HIP runtime error at kernel launch";
+        default: return "unknown status";
+    }
+}
+
+const char *molora_version(void) { return "molora-gfx950 0.1"; }
+
+}  // extern "C"

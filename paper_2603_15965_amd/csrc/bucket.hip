@@ -1,0 +1,171 @@
+// Dispatch step (Sec. "Unified Dispatch Infrastructure", Alg. "Unified Dispatch Kernel") and
+// vocabulary routing (Def. "Vocabulary Routing") for gfx950.
+//
+// The paper's dispatch hands out list positions with atomicAdd, which leaves the order
+// inside a target's list to chance.  Here the lists are ordered by token index (a stable
+// counting sort), so the output is unique and no atomics are needed at all: one workgroup
+// of 16 wavefronts splits the tokens into 16 contiguous ranges, every wavefront finds the
+// lanes that share a target with wave-wide ballots, the per-(target, wavefront) counts are
+// prefix-summed in LDS in (target-major, wavefront-minor) order, and a second sweep writes
+// every token to  base[target][wavefront] + (number of lower lanes with the same target).
+//
+// The whole problem (N <= a few 10^4 tokens, <= 131 KB of traffic) is latency bound, which
+// is why it is one workgroup and one launch rather than a multi-pass device-wide sort.
+#include "common.h"
+
+namespace molora {
+
+namespace {
+
+constexpr int kBucketWaves = 16;
+constexpr int kBucketThreads = kBucketWaves * 64;
+constexpr int kUnroll = 8;  // token groups whose loads are in flight together
+
+struct VocabBreaks {
+    int32_t b[65];
+};
+
+__global__ __launch_bounds__(256) void route_vocab_kernel(const int32_t *__restrict__ v,
+                                                          int32_t *__restrict__ r, int64_t N,
+                                                          VocabBreaks br, int M) {
+    int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= N) return;
+    const int32_t id = v[i];
+    int32_t m = 0;
+    for (int j = 1; j < M; ++j)  // M - 1 integer comparisons
+        if (id >= br.b[j]) m = j;
+    if (id < br.b[0] || id >= br.b[M]) m = -1;
+    r[i] = m;
+}
+
+// Lanes of the wavefront that hold the same key as this lane (key < 2^nbits).
+__device__ __forceinline__ uint64_t match_lanes(int key, bool valid, int nbits) {
+    uint64_t mask = __ballot(valid);
+    for (int bit = 0; bit < nbits; ++bit) {
+        const bool one = (key >> bit) & 1;
+        const uint64_t m = __ballot(valid && one);
+        mask &= one ? m : ~m;
+    }
+    return mask;
+}
+
+__device__ __forceinline__ int lane_id() { return __lane_id(); }
+
+__global__ __launch_bounds__(kBucketThreads) void bucket_kernel(const int32_t *__restrict__ r,
+                                                                int32_t *__restrict__ offsets,
+                                                                int32_t *__restrict__ perm, int N,
+                                                                int C, int32_t *err_flag) {
+    // cnt[b * 16 + w]: tokens of target b (b == C: out of range) in wavefront w's range
+    extern __shared__ int32_t lds[];
+    volatile int32_t *cnt = lds;
+    __shared__ int32_t wave_tot[kBucketWaves];
+
+    const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
+    const int E = (C + 1) * kBucketWaves;
+    const int nbits = 32 - __clz(C);  // keys are 0..C
+    for (int i = tid; i < E; i += kBucketThreads) cnt[i] = 0;
+    __syncthreads();
+
+    // contiguous token range of this wavefront, a multiple of 64 long
+    const int per = (int)((((int64_t)N + kBucketWaves * 64 - 1) / (kBucketWaves * 64)) * 64);
+    const int64_t start64 = (int64_t)w * per;
+    const int start = (int)(start64 < N ? start64 : N);
+    const int end = (int)(start64 + per < N ? start64 + per : N);
+    const uint64_t lower = (lane == 0) ? 0ull : (~0ull >> (64 - lane));
+
+    // ---- sweep 1: histogram per (target, wavefront) ----
+    for (int base = start; base < end; base += 64 * kUnroll) {
+        int32_t key[kUnroll];
+#pragma unroll
+        for (int u = 0; u < kUnroll; ++u) {
+            const int t = base + u * 64 + lane;
+            const int32_t c = (t < end) ? r[t] : 0;
+            key[u] = (c >= 0 && c < C) ? c : C;
+        }
+#pragma unroll
+        for (int u = 0; u < kUnroll; ++u) {
+            const int t = base + u * 64 + lane;
+            const bool valid = t < end;
+            const uint64_t same = match_lanes(key[u], valid, nbits);
+            if (valid && (same & lower) == 0)  // lowest lane of its group
+                cnt[key[u] * kBucketWaves + w] += __popcll(same);
+            __builtin_amdgcn_wave_barrier();
+        }
+    }
+    __syncthreads();
+
+    // ---- exclusive prefix sum over cnt[0 .. E) ----
+    const int chunk = (E + kBucketThreads - 1) / kBucketThreads;
+    const int lo = tid * chunk < E ? tid * chunk : E;
+    const int hi = lo + chunk < E ? lo + chunk : E;
+    int32_t mine = 0;
+    for (int i = lo; i < hi; ++i) mine += cnt[i];
+    int32_t incl = mine;
+#pragma unroll
+    for (int d = 1; d < 64; d <<= 1) {
+        const int32_t up = __shfl_up(incl, d, 64);
+        if (lane >= d) incl += up;
+    }
+    if (lane == 63) wave_tot[w] = incl;
+    __syncthreads();
+    int32_t before = incl - mine;
+    for (int j = 0; j < w; ++j) before += wave_tot[j];
+    for (int i = lo; i < hi; ++i) {
+        const int32_t c = cnt[i];
+        cnt[i] = before;
+        before += c;
+    }
+    __syncthreads();
+    for (int c = tid; c <= C; c += kBucketThreads) offsets[c] = cnt[c * kBucketWaves];
+    if (tid == 0 && err_flag != nullptr && cnt[C * kBucketWaves] != N) *err_flag = 1;
+    __syncthreads();
+
+    // ---- sweep 2: scatter token indices to their positions ----
+    for (int base = start; base < end; base += 64 * kUnroll) {
+        int32_t key[kUnroll];
+#pragma unroll
+        for (int u = 0; u < kUnroll; ++u) {
+            const int t = base + u * 64 + lane;
+            const int32_t c = (t < end) ? r[t] : 0;
+            key[u] = (c >= 0 && c < C) ? c : C;
+        }
+#pragma unroll
+        for (int u = 0; u < kUnroll; ++u) {
+            const int t = base + u * 64 + lane;
+            const bool valid = t < end;
+            const uint64_t same = match_lanes(key[u], valid, nbits);
+            const int slot = key[u] * kBucketWaves + w;
+            int32_t pos = 0;
+            if (valid) pos = cnt[slot] + __popcll(same & lower);
+            __builtin_amdgcn_wave_barrier();
+            if (valid) {
+                perm[pos] = t;
+                if ((same & lower) == 0) cnt[slot] += __popcll(same);
+            }
+            __builtin_amdgcn_wave_barrier();
+        }
+    }
+}
+
+}  // namespace
+
+hipError_t launch_route_vocab(const int32_t *v, const int32_t *breaks_host, int M, int32_t *r,
+                              int64_t N, hipStream_t s) {
+    if (N == 0) return hipSuccess;
+    VocabBreaks br;
+    for (int j = 0; j <= M; ++j) br.b[j] = breaks_host[j];
+    for (int j = M + 1; j < 65; ++j) br.b[j] = 0;
+    const unsigned blocks = (unsigned)((N + 255) / 256);
+    hipLaunchKernelGGL(route_vocab_kernel, dim3(blocks), dim3(256), 0, s, v, r, N, br, M);
+    return hipGetLastError();
+}
+
+hipError_t launch_bucket(const int32_t *r, int32_t *offsets, int32_t *perm, int64_t N, int C,
+                         int32_t *err_flag, hipStream_t s) {
+    const size_t lds_bytes = (size_t)(C + 1) * kBucketWaves * sizeof(int32_t);
+    hipLaunchKernelGGL(bucket_kernel, dim3(1), dim3(kBucketThreads), lds_bytes, s, r, offsets,
+                       perm, (int)N, C, err_flag);
+    return hipGetLastError();
+}
+
+}  // namespace molora

@@ -1,0 +1,50 @@
+// Internal declarations shared by the HIP translation units of libmolora (gfx950 only).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace molora {
+
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+typedef __attribute__((ext_vector_type(4))) short i16x4;
+typedef __attribute__((ext_vector_type(8))) short i16x8;
+typedef __attribute__((ext_vector_type(4))) float f32x4;
+typedef __attribute__((ext_vector_type(16))) float f32x16;
+typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
+typedef __attribute__((ext_vector_type(2))) uint32_t u32x2;
+
+#define MOLORA_LDS __attribute__((address_space(3)))
+
+__device__ __forceinline__ float bf16_bits_to_f32(uint32_t b) { return __uint_as_float(b << 16); }
+
+// Round-to-nearest-even fp32 -> bf16 bit pattern (finite inputs).
+__device__ __forceinline__ uint32_t f32_to_bf16_bits(float f) {
+    uint32_t u = __float_as_uint(f);
+    return (u + 0x7FFFu + ((u >> 16) & 1u)) >> 16;
+}
+
+// LDS transpose read of gfx950: inside every group of 16 lanes, lane i receives the
+// (i % 4)-th 16-bit element addressed by lanes i/4, i/4 + 4, i/4 + 8, i/4 + 12.  With lane a
+// of the group pointing at row (a / 4), columns 4 * (a % 4) .. +3 of a row-major [4][16]
+// block, lane i ends up with the 4 rows of column i: a K-major tile becomes the
+// "consecutive k per lane" operand the bf16 MFMA wants.
+__device__ __forceinline__ i16x4 lds_read_tr16(const MOLORA_LDS void *p) {
+    return __builtin_amdgcn_ds_read_tr16_b64_v4i16((MOLORA_LDS i16x4 *)p);
+}
+
+// ---- launchers implemented in the kernel translation units (all asynchronous) ----
+hipError_t launch_route_gate(const uint16_t *x, const uint16_t *G, int32_t *r, int64_t N,
+                             int d_in, int C, hipStream_t s);
+hipError_t launch_route_vocab(const int32_t *v, const int32_t *breaks_host, int M, int32_t *r,
+                              int64_t N, hipStream_t s);
+hipError_t launch_bucket(const int32_t *r, int32_t *offsets, int32_t *perm, int64_t N, int C,
+                         int32_t *err_flag, hipStream_t s);
+hipError_t launch_shrink(const uint16_t *x, const uint16_t *A, const int32_t *offsets,
+                         const int32_t *perm, uint16_t *t2, int64_t N, int d_in, int C, int rank,
+                         hipStream_t s);
+hipError_t launch_fused_gemm(const uint16_t *x, const uint16_t *W, const uint16_t *B,
+                             const uint16_t *t2, const int32_t *offsets, const int32_t *perm,
+                             float *h, int64_t N, int d_in, int d_out, int C, int rank,
+                             hipStream_t s);
+
+}  // namespace molora
