@@ -143,6 +143,26 @@ molora_status molora_apply_bucketed(const void *x, const void *W, const void *A,
                                     int32_t rank, void *workspace, size_t workspace_bytes,
                                     void *stream);
 
+/*
+ * The two kernels of molora_apply_bucketed as separate calls (same semantics, same
+ * kernels), for callers that want to time or schedule them individually.
+ *
+ * molora_shrink:  t_p = x[perm[p]] A_c  for every routed sorted position p in bucket c
+ * (offsets[c] <= p < offsets[c+1]); rows p >= offsets[C] are not touched.  t is written
+ * as two bf16 halves per value, t = hi + lo with hi = bf16(t), lo = bf16(t - hi):
+ *   t DEVICE bf16 [N][2*rank], row p = [hi_0 .. hi_{rank-1} | lo_0 .. lo_{rank-1}].
+ * molora_base_expand:  h[perm[p]][:] = x[perm[p]] W + t_p B_c  (rows without adapter:
+ * x W only), every row of h written once.
+ * offsets and perm must be molora_bucket's output for this N and C.
+ */
+molora_status molora_shrink(const void *x, const void *A, const int32_t *offsets,
+                            const int32_t *perm, void *t, int64_t N, int32_t d_in, int32_t C,
+                            int32_t rank, void *stream);
+molora_status molora_base_expand(const void *x, const void *W, const void *B, const void *t,
+                                 const int32_t *offsets, const int32_t *perm, float *h,
+                                 int64_t N, int32_t d_in, int32_t d_out, int32_t C, int32_t rank,
+                                 void *stream);
+
 /* Human-readable name of a status code (static storage, never NULL). */
 const char *molora_status_string(molora_status status);
 

@@ -14,7 +14,8 @@ LIB_PATH = os.path.join(_HERE, "libmolora.so")
 
 MOLORA_OK = 0
 EXPORTS = ["molora_route", "molora_route_vocab", "molora_bucket", "molora_apply_workspace_bytes",
-           "molora_apply", "molora_apply_bucketed", "molora_status_string", "molora_version"]
+           "molora_apply", "molora_apply_bucketed", "molora_shrink", "molora_base_expand",
+           "molora_status_string", "molora_version"]
 
 _lib = None
 
@@ -48,6 +49,10 @@ def load():
     lib.molora_apply.restype = ctypes.c_int
     lib.molora_apply_bucketed.argtypes = [vp, vp, vp, vp, vp, vp, vp, i64, i32, i32, i32, i32, vp, sz, vp]
     lib.molora_apply_bucketed.restype = ctypes.c_int
+    lib.molora_shrink.argtypes = [vp, vp, vp, vp, vp, i64, i32, i32, i32, vp]
+    lib.molora_shrink.restype = ctypes.c_int
+    lib.molora_base_expand.argtypes = [vp, vp, vp, vp, vp, vp, vp, i64, i32, i32, i32, i32, vp]
+    lib.molora_base_expand.restype = ctypes.c_int
     lib.molora_status_string.argtypes = [ctypes.c_int]
     lib.molora_status_string.restype = ctypes.c_char_p
     lib.molora_version.argtypes = []
@@ -176,6 +181,36 @@ def molora_apply_bucketed(x, W, A, B, offsets, perm, h=None, workspace=None, str
         _dev(h, torch.float32, "h"), N, d_in, d_out, C, rank,
         _dev(workspace, torch.uint8, "workspace"), workspace.numel(), _stream(stream))
     _check(st, "molora_apply_bucketed")
+    return h
+
+
+def molora_shrink(x, A, offsets, perm, t=None, stream=None):
+    """t[p] = x[perm[p]] A_c as [hi | lo] bf16 halves, [N][2*rank]."""
+    N, d_in = x.shape
+    C, _, rank = A.shape
+    if t is None:
+        t = torch.empty((N, 2 * rank), dtype=torch.bfloat16, device=x.device)
+    bf = torch.bfloat16
+    st = load().molora_shrink(_dev(x, bf, "x"), _dev(A, bf, "A"), _dev(offsets, torch.int32, "offsets"),
+                              _dev(perm, torch.int32, "perm"), _dev(t, bf, "t"), N, d_in, C, rank,
+                              _stream(stream))
+    _check(st, "molora_shrink")
+    return t
+
+
+def molora_base_expand(x, W, B, t, offsets, perm, h=None, stream=None):
+    """h[perm[p]] = x[perm[p]] W + t_p B_c, every row written once."""
+    N, d_in = x.shape
+    d_out = W.shape[1]
+    C, rank, _ = B.shape
+    if h is None:
+        h = torch.empty((N, d_out), dtype=torch.float32, device=x.device)
+    bf = torch.bfloat16
+    st = load().molora_base_expand(_dev(x, bf, "x"), _dev(W, bf, "W"), _dev(B, bf, "B"),
+                                   _dev(t, bf, "t"), _dev(offsets, torch.int32, "offsets"),
+                                   _dev(perm, torch.int32, "perm"), _dev(h, torch.float32, "h"),
+                                   N, d_in, d_out, C, rank, _stream(stream))
+    _check(st, "molora_base_expand")
     return h
 
 

@@ -133,6 +133,36 @@ molora_status molora_apply_bucketed(const void *x, const void *W, const void *A,
                         workspace_bytes, stream);
 }
 
+molora_status molora_shrink(const void *x, const void *A, const int32_t *offsets,
+                            const int32_t *perm, void *t, int64_t N, int32_t d_in, int32_t C,
+                            int32_t rank, void *stream) {
+    if (!apply_sizes_ok(N, d_in, 8, C, rank)) return MOLORA_EINVAL;
+    if (N == 0) return MOLORA_OK;
+    if (!x || !A || !offsets || !perm || !t) return MOLORA_EINVAL;
+    if (!aligned16(x) || !aligned16(A) || !aligned16(offsets) || !aligned16(perm) || !aligned16(t))
+        return MOLORA_EALIGN;
+    return from_hip(molora::launch_shrink(static_cast<const uint16_t *>(x),
+                                          static_cast<const uint16_t *>(A), offsets, perm,
+                                          static_cast<uint16_t *>(t), N, d_in, C, rank,
+                                          static_cast<hipStream_t>(stream)));
+}
+
+molora_status molora_base_expand(const void *x, const void *W, const void *B, const void *t,
+                                 const int32_t *offsets, const int32_t *perm, float *h,
+                                 int64_t N, int32_t d_in, int32_t d_out, int32_t C, int32_t rank,
+                                 void *stream) {
+    if (!apply_sizes_ok(N, d_in, d_out, C, rank)) return MOLORA_EINVAL;
+    if (N == 0) return MOLORA_OK;
+    if (!x || !W || !B || !t || !offsets || !perm || !h) return MOLORA_EINVAL;
+    if (!aligned16(x) || !aligned16(W) || !aligned16(B) || !aligned16(t) || !aligned16(offsets) ||
+        !aligned16(perm) || !aligned16(h))
+        return MOLORA_EALIGN;
+    return from_hip(molora::launch_fused_gemm(
+        static_cast<const uint16_t *>(x), static_cast<const uint16_t *>(W),
+        static_cast<const uint16_t *>(B), static_cast<const uint16_t *>(t), offsets, perm, h, N,
+        d_in, d_out, C, rank, static_cast<hipStream_t>(stream)));
+}
+
 const char *molora_status_string(molora_status status) {
     switch (status) {
         case MOLORA_OK: return "ok";
