@@ -11,36 +11,77 @@
 // Rows past offsets[C] (tokens without adapter) simply have no extra tiles.
 //
 // Tiling: BM x BN output tile per workgroup, WM x WN wavefronts, each owning a grid of
-// 32x32 MFMA tiles (v_mfma_f32_32x32x16_bf16, fp32 accumulate); BK = 64.
-//   x tile  [BM][64]  in LDS, 16-byte chunks XOR-swizzled by (row & 7): the operand read
-//                     (one row per lane, ds_read_b128) is bank-conflict free;
-//   W tile  [64][BN]  in LDS exactly as it lies in HBM (K-major), 32-byte chunks swizzled
-//                     by (k & 3); the LDS transpose read turns it into the k-contiguous
-//                     operand, so W needs no packing pass and no transposed copy.
+// 32x32 MFMA tiles (v_mfma_f32_32x32x16_bf16, fp32 accumulate).
+//   x tile  [BM][BK]  16-byte chunks XOR-swizzled inside a row so that the operand read (one
+//                     row per lane, ds_read_b128) is bank-conflict free;
+//   W tile  [BK][BN]  exactly as it lies in HBM (K-major), 32-byte chunks swizzled by (k & 3);
+//                     the LDS transpose read turns it into the k-contiguous operand, so W needs
+//                     no packing pass and no transposed copy.
+// Full K tiles go HBM -> LDS directly (global_load_lds_dwordx4: no staging registers; the
+// gathered row address and the swizzle are applied on the global side, the LDS side is
+// linear) through a ring of STAGES buffers, STAGES-1 tiles in flight.  The K tail (d_in not
+// a multiple of BK) and the expand tiles need zero-filling and go through registers.
 // Workgroups are numbered so that the 8 XCDs (blockIdx % 8) each walk a compact group of
 // tiles and share x rows / W columns in their own L2.
+#include <type_traits>
+
 #include "common.h"
 
 namespace molora {
 
 namespace {
 
-constexpr int BK = 64;
 constexpr int kGroupM = 8;  // row tiles per scheduling group
 
-template <int BM_, int BN_, int WM_, int WN_>
+template <int N>
+__device__ __forceinline__ void wait_vmcnt() {
+    asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
+}
+__device__ __forceinline__ void wg_barrier() { asm volatile("s_barrier" ::: "memory"); }
+__device__ __forceinline__ void wait_lds() { asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory"); }
+
+// 64 lanes x 16 bytes, HBM -> LDS; global address = base (scalar) + lane_off (per lane, 32 bit),
+// LDS address = lds_base + lane * 16 (lds_base wave-uniform, goes to M0).  Written as inline assembly on purpose: the compiler then knows nothing of an
+// outstanding LDS write and does not put a conservative vmcnt(0) wait in front of the operand
+// reads of the tile being computed, which would serialise prefetch and compute.  The waits
+// that order these loads against the LDS reads are the explicit wait_vmcnt + wg_barrier of
+// the main loop.
+__device__ __forceinline__ void load_to_lds16(const void *base, uint32_t lane_off,
+                                              unsigned char *lds_base) {
+    const uint32_t lds_addr = (uint32_t)(uintptr_t)(MOLORA_LDS unsigned char *)lds_base;
+    asm volatile(
+        "s_mov_b32 m0, %2\n\t"
+        "s_nop 0\n\t"
+        "global_load_lds_dwordx4 %0, %1"
+        :
+        : "v"(lane_off), "s"(base), "s"(lds_addr)
+        : "memory", "m0");
+}
+
+template <int BM_, int BN_, int WM_, int WN_, int BK_, int STAGES_>
 struct GemmCfg {
-    static constexpr int BM = BM_, BN = BN_, WM = WM_, WN = WN_;
-    static constexpr int NT = 64 * WM * WN;
+    static constexpr int BM = BM_, BN = BN_, WM = WM_, WN = WN_, BK = BK_, STAGES = STAGES_;
+    static constexpr int NW = WM * WN, NT = 64 * NW;
     static constexpr int TM = BM / WM / 32, TN = BN / WN / 32;
-    static constexpr int A_BYTES = BM * BK * 2;
-    static constexpr int B_BYTES = BK * BN * 2;
-    static constexpr int STAGE = A_BYTES + B_BYTES;
-    static constexpr int A_CH = BM * (BK / 8) / NT;   // 16-byte chunks per thread
-    static constexpr int B_CH = BK * (BN / 8) / NT;
-    static constexpr int BCOLS = BN / 8;              // 16-byte chunks per W tile row
-    static constexpr size_t LDS_BYTES = 2 * STAGE + 4 * BM * sizeof(int32_t) + 16;
-    static_assert(A_CH * NT == BM * (BK / 8) && B_CH * NT == BK * (BN / 8), "tile/thread mismatch");
+    static constexpr int A_RB = BK * 2, A_CPR = A_RB / 16, A_RPI = 64 / A_CPR;
+    static constexpr int A_LPW = BM / A_RPI / NW;       // direct loads per wavefront and tile
+    static constexpr int B_RB = BN * 2, B_CPR = B_RB / 16, B_RPI = 64 / B_CPR;
+    static constexpr int B_LPW = BK / B_RPI / NW;
+    static constexpr int LPW = A_LPW + B_LPW;
+    static constexpr int A_BYTES = BM * A_RB, B_BYTES = BK * B_RB, STAGE = A_BYTES + B_BYTES;
+    static constexpr int A_CH = BM * A_CPR / NT, B_CH = BK * B_CPR / NT;  // register path
+    static constexpr size_t LDS_BYTES = (size_t)STAGES * STAGE + 4 * BM * sizeof(int32_t) + 16;
+    static_assert(BK == 32 || BK == 64, "BK");
+    static_assert(A_LPW * A_RPI * NW == BM && B_LPW * B_RPI * NW == BK, "direct-load split");
+    static_assert(A_CH * NT == BM * A_CPR && B_CH * NT == BK * B_CPR, "register-load split");
+    static_assert(STAGES >= 2, "stages");
+
+    // XOR applied to the 16-byte chunk index of an x-tile row
+    __device__ static __forceinline__ int swz_a(int row) {
+        if constexpr (BK == 64) return (row ^ (row >> 3)) & 7;
+        // 64-byte rows: distinct banks for 8 consecutive rows (32 banks) and 16 (64 banks)
+        return (((row >> 2) & 1) << 1) | (((row >> 1) ^ (row >> 3)) & 1);
+    }
 };
 
 template <class Cfg>
@@ -49,16 +90,17 @@ __global__ __launch_bounds__(Cfg::NT) void fused_gemm_kernel(
     const uint16_t *__restrict__ t2, const int32_t *__restrict__ offsets,
     const int32_t *__restrict__ perm, float *__restrict__ h, int N, int d_in, int d_out, int C,
     int rank, int tiles_m, int tiles_n) {
-    constexpr int BM = Cfg::BM, BN = Cfg::BN, NT = Cfg::NT, TM = Cfg::TM, TN = Cfg::TN;
+    constexpr int BM = Cfg::BM, BN = Cfg::BN, BK = Cfg::BK, NT = Cfg::NT, TM = Cfg::TM,
+                  TN = Cfg::TN, STAGES = Cfg::STAGES;
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
-    unsigned char *stage0 = smem;
-    int32_t *tile_perm = (int32_t *)(smem + 2 * Cfg::STAGE);  // [BM] token of each tile row, -1 = none
-    int32_t *seg_c = tile_perm + BM;                          // buckets intersecting the tile
+    int32_t *tile_perm = (int32_t *)(smem + STAGES * Cfg::STAGE);  // [BM] token per row, -1 = none
+    int32_t *seg_c = tile_perm + BM;                               // buckets intersecting the tile
     int32_t *seg_lo = seg_c + BM;
     int32_t *seg_hi = seg_lo + BM;
     int32_t *nseg_p = seg_hi + BM;
 
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int wm = wave / Cfg::WN, wn = wave % Cfg::WN;
 
     // ---- tile of this workgroup: XCD-major, then groups of kGroupM row tiles ----
@@ -91,78 +133,34 @@ __global__ __launch_bounds__(Cfg::NT) void fused_gemm_kernel(
     const int nseg = *nseg_p;
     const int two_r = 2 * rank;
     const int tps = (two_r + BK - 1) / BK;  // extra K tiles per bucket
-    const int nkb = (d_in + BK - 1) / BK;
-    const int nk = nkb + nseg * tps;
+    const int nkf = d_in / BK;              // full K tiles (direct path)
+    const int ktail = d_in - nkf * BK;      // leftover k (register path)
 
-    // ---- global -> register staging ----
-    const uint16_t *a_src[Cfg::A_CH];
-    bool a_ok[Cfg::A_CH];
+    // ---- direct path: per-lane source pointers of this wavefront's load instructions ----
+    // Rows past N and columns past d_out are clamped to valid memory: what they produce is
+    // never stored.
+    // Byte offsets from a scalar base that advances with the K tile (x and W are < 4 GiB).
+    uint32_t a_off_g[Cfg::A_LPW], b_off_g[Cfg::B_LPW];
 #pragma unroll
-    for (int i = 0; i < Cfg::A_CH; ++i) {
-        const int id = tid + i * NT, row = id >> 3;
+    for (int i = 0; i < Cfg::A_LPW; ++i) {
+        const int q = wave * Cfg::A_LPW + i;
+        const int row = q * Cfg::A_RPI + lane / Cfg::A_CPR;
+        const int u = (lane % Cfg::A_CPR) ^ Cfg::swz_a(row);
         const int tok = tile_perm[row];
-        a_ok[i] = tok >= 0;
-        a_src[i] = x + (int64_t)(tok >= 0 ? tok : 0) * d_in + (id & 7) * 8;
+        a_off_g[i] = (uint32_t)(((int64_t)(tok >= 0 ? tok : 0) * d_in + u * 8) * 2);
     }
-    u32x4 a_reg[Cfg::A_CH], b_reg[Cfg::B_CH];
-    const u32x4 zero4 = {0u, 0u, 0u, 0u};
-
-    auto load_tile = [&](int kt) {
-        if (kt < nkb) {
-            const int k0 = kt * BK;
 #pragma unroll
-            for (int i = 0; i < Cfg::A_CH; ++i) {
-                const int id = tid + i * NT;
-                const int k = k0 + (id & 7) * 8;
-                a_reg[i] = (a_ok[i] && k < d_in) ? *(const u32x4 *)(a_src[i] + k0) : zero4;
-            }
-#pragma unroll
-            for (int i = 0; i < Cfg::B_CH; ++i) {
-                const int id = tid + i * NT;
-                const int kr = id / Cfg::BCOLS, u = id % Cfg::BCOLS;
-                const int k = k0 + kr, n = n0 + u * 8;
-                b_reg[i] = (k < d_in && n < d_out) ? *(const u32x4 *)(W + (int64_t)k * d_out + n)
-                                                   : zero4;
-            }
-        } else {
-            const int e = kt - nkb;
-            const int sg = e / tps, sub = e % tps;
-            const int c = seg_c[sg], lo = seg_lo[sg], hi = seg_hi[sg];
-#pragma unroll
-            for (int i = 0; i < Cfg::A_CH; ++i) {
-                const int id = tid + i * NT, row = id >> 3;
-                const int p = p0 + row, vk = sub * BK + (id & 7) * 8;
-                a_reg[i] = (p >= lo && p < hi && vk < two_r)
-                               ? *(const u32x4 *)(t2 + (int64_t)p * two_r + vk)
-                               : zero4;
-            }
-            const uint16_t *Bc = B + (int64_t)c * rank * d_out;
-#pragma unroll
-            for (int i = 0; i < Cfg::B_CH; ++i) {
-                const int id = tid + i * NT;
-                const int kr = id / Cfg::BCOLS, u = id % Cfg::BCOLS;
-                const int vk = sub * BK + kr, n = n0 + u * 8;
-                const int j = vk < rank ? vk : vk - rank;  // [B_c; B_c]
-                b_reg[i] = (vk < two_r && n < d_out) ? *(const u32x4 *)(Bc + (int64_t)j * d_out + n)
-                                                     : zero4;
-            }
-        }
-    };
-    auto store_tile = [&](unsigned char *stage) {
-#pragma unroll
-        for (int i = 0; i < Cfg::A_CH; ++i) {
-            const int id = tid + i * NT, row = id >> 3, u = id & 7;
-            *(u32x4 *)(stage + row * 128 + ((u ^ (row & 7)) << 4)) = a_reg[i];
-        }
-        unsigned char *bs = stage + Cfg::A_BYTES;
-#pragma unroll
-        for (int i = 0; i < Cfg::B_CH; ++i) {
-            const int id = tid + i * NT;
-            const int kr = id / Cfg::BCOLS, u = id % Cfg::BCOLS;
-            *(u32x4 *)(bs + kr * (BN * 2) + (((u >> 1) ^ (kr & 3)) << 5) + ((u & 1) << 4)) = b_reg[i];
-        }
-    };
-
+    for (int i = 0; i < Cfg::B_LPW; ++i) {
+        const int q = wave * Cfg::B_LPW + i;
+        const int kr = q * Cfg::B_RPI + lane / Cfg::B_CPR;
+        const int pos = lane % Cfg::B_CPR;
+        const int u16 = ((((pos >> 1) ^ (kr & 3))) << 1) | (pos & 1);
+        const int n = min(n0 + u16 * 8, d_out - 8);
+        b_off_g[i] = (uint32_t)(((int64_t)kr * d_out + n) * 2);
+    }
+    const unsigned char *a_base = (const unsigned char *)x;  // + BK*2 bytes per K tile
+    const unsigned char *b_base = (const unsigned char *)W;  // + BK*d_out*2 bytes per K tile
+    const int64_t b_step = (int64_t)BK * d_out * 2;
     f32x16 acc[TM][TN];
 #pragma unroll
     for (int i = 0; i < TM; ++i)
@@ -172,40 +170,49 @@ __global__ __launch_bounds__(Cfg::NT) void fused_gemm_kernel(
             for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
 
     // operand read offsets that do not depend on the k-step
-    const int a_row0 = wm * (BM / Cfg::WM) + (lane & 31);   // + tm*32
-    const int a_kg = lane >> 5;                              // k-group inside a 16-wide step
+    const int a_row0 = wm * (BM / Cfg::WM) + (lane & 31);    // + tm*32
+    const int a_kg = lane >> 5;                               // k-group inside a 16-wide step
     const int blk = lane >> 4, a16 = lane & 15;
-    const int b_kr0 = (blk >> 1) * 8 + (a16 >> 2);           // + ks*16 (+4 for the upper half)
-    const int b_col0 = wn * (BN / Cfg::WN) + 16 * (blk & 1); // + tn*32 ; column of lane = +a16
-    const int b_in = (a16 & 3) * 8;                          // byte inside the 32-byte chunk
+    const int b_kr0 = (blk >> 1) * 8 + (a16 >> 2);            // + ks*16 (+4 for the upper half)
+    const int b_col0 = wn * (BN / Cfg::WN) + 16 * (blk & 1);  // + tn*32 ; column of lane = +a16
+    const int b_in = (a16 & 3) * 8;                           // byte inside the 32-byte chunk
+    int a_off[TM], a_swz[TM];
+#pragma unroll
+    for (int tm = 0; tm < TM; ++tm) {
+        a_off[tm] = (a_row0 + tm * 32) * Cfg::A_RB;
+        a_swz[tm] = Cfg::swz_a(a_row0 + tm * 32);
+    }
 
-    load_tile(0);
-    store_tile(stage0);
-    __syncthreads();
-
-    for (int kt = 0; kt < nk; ++kt) {
-        const unsigned char *as = stage0 + (kt & 1) * Cfg::STAGE;
-        const unsigned char *bs = as + Cfg::A_BYTES;
-        if (kt + 1 < nk) load_tile(kt + 1);
+    // The LDS addresses are recomputed at every use from a few per-lane constants (two or three
+    // VALU operations per read, which ride along with the MFMAs for free); `opaque` keeps the
+    // compiler from hoisting one address register per (stage, k-step, fragment) out of the
+    // loop, which costs far more registers than it saves.
+    auto opaque = [](int v) {
+        asm volatile("" : "+v"(v));
+        return v;
+    };
+    auto load_a_frag = [&](const unsigned char *as, int ks, int tm) -> bf16x8 {
+        const int sw = opaque(a_swz[tm]);
+        return *(const bf16x8 *)(as + a_off[tm] + (((ks * 2 + a_kg) ^ sw) << 4));
+    };
+    auto load_b_frag = [&](const unsigned char *as, int ks, int tn) -> bf16x8 {
+        const int k3 = opaque(b_kr0 & 3);
+        const int cc = (b_col0 + tn * 32) >> 4;
+        const unsigned char *p = as + Cfg::A_BYTES + (ks * 16 + b_kr0) * Cfg::B_RB + ((cc ^ k3) << 5) + b_in;
+        const i16x4 lo = lds_read_tr16((const MOLORA_LDS void *)p);
+        const i16x4 hi = lds_read_tr16((const MOLORA_LDS void *)(p + 4 * Cfg::B_RB));
+        const i16x8 b8 = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
+        return __builtin_bit_cast(bf16x8, b8);
+    };
+    // plain (not software-pipelined) product of one staged tile: used for the extra tiles
+    auto compute_tile = [&](const unsigned char *as) {
 #pragma unroll
         for (int ks = 0; ks < BK / 16; ++ks) {
             bf16x8 af[TM], bfr[TN];
 #pragma unroll
-            for (int tm = 0; tm < TM; ++tm) {
-                const int row = a_row0 + tm * 32;
-                const int u = ks * 2 + a_kg;
-                af[tm] = *(const bf16x8 *)(as + row * 128 + ((u ^ (row & 7)) << 4));
-            }
+            for (int tm = 0; tm < TM; ++tm) af[tm] = load_a_frag(as, ks, tm);
 #pragma unroll
-            for (int tn = 0; tn < TN; ++tn) {
-                const int kr = ks * 16 + b_kr0;
-                const int cc = (b_col0 + tn * 32) >> 4;
-                const unsigned char *p = bs + kr * (BN * 2) + ((cc ^ (kr & 3)) << 5) + b_in;
-                const i16x4 lo = lds_read_tr16((const MOLORA_LDS void *)p);
-                const i16x4 hi = lds_read_tr16((const MOLORA_LDS void *)(p + 4 * (BN * 2)));
-                const i16x8 b8 = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
-                bfr[tn] = __builtin_bit_cast(bf16x8, b8);
-            }
+            for (int tn = 0; tn < TN; ++tn) bfr[tn] = load_b_frag(as, ks, tn);
 #pragma unroll
             for (int tm = 0; tm < TM; ++tm)
 #pragma unroll
@@ -213,25 +220,193 @@ __global__ __launch_bounds__(Cfg::NT) void fused_gemm_kernel(
                     acc[tm][tn] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[tm], bfr[tn],
                                                                           acc[tm][tn], 0, 0, 0);
         }
-        if (kt + 1 < nk) store_tile(stage0 + ((kt + 1) & 1) * Cfg::STAGE);
+    };
+
+    // ---- main loop over full K tiles ----
+    // Two LDS stages and two register sets of operand fragments.  While the MFMAs of k-step
+    // ks run, the fragments of step ks+1 are fetched from LDS, one read after each MFMA, so
+    // the matrix pipe never waits for LDS.  The workgroup barrier sits in front of the LAST
+    // k-step of a tile: at that point every wavefront holds the tile's last fragments in
+    // registers, so the stage can be refilled (tile kt+2) and the first fragments of tile
+    // kt+1 can be fetched while the last MFMAs of tile kt still run.
+    constexpr int KS = BK / 16;
+    static_assert(STAGES == 2 && KS % 2 == 0, "pipelined main loop");
+    bf16x8 fa[2][TM], fb[2][TN];
+    auto issue_one = [&](unsigned char *stage, int i) {  // i-th direct load of this wavefront
+        if (i < Cfg::A_LPW)
+            load_to_lds16(a_base, a_off_g[i], stage + (wave * Cfg::A_LPW + i) * 1024);
+        else
+            load_to_lds16(b_base, b_off_g[i - Cfg::A_LPW],
+                          stage + Cfg::A_BYTES + (wave * Cfg::B_LPW + i - Cfg::A_LPW) * 1024);
+    };
+    auto issue_tile = [&](unsigned char *stage) {  // all direct loads of the next K tile
+#pragma unroll
+        for (int i = 0; i < Cfg::LPW; ++i) issue_one(stage, i);
+        a_base += BK * 2;
+        b_base += b_step;
+    };
+    auto fetch_one = [&](const unsigned char *as, int ks, int set, int i) {  // i-th fragment
+        if (i < TM)
+            fa[set][i] = load_a_frag(as, ks, i);
+        else if (i < TM + TN)
+            fb[set][i - TM] = load_b_frag(as, ks, i - TM);
+    };
+    if (nkf > 0) {
+        issue_tile(smem);
+        if (nkf > 1) {
+            issue_tile(smem + Cfg::STAGE);
+            wait_vmcnt<Cfg::LPW>();
+        } else {
+            wait_vmcnt<0>();
+        }
+        wg_barrier();
+#pragma unroll
+        for (int i = 0; i < TM + TN; ++i) fetch_one(smem, 0, 0, i);
+    }
+    // one K tile: KS-1 ordinary k-steps, then the last one, specialised on what follows
+    // (`more`: another tile follows; `refill`: and one after that, to be loaded now)
+    auto k_tile = [&](int kt, auto more_c, auto refill_c) {
+        constexpr bool more = decltype(more_c)::value, refill = decltype(refill_c)::value;
+        unsigned char *as = smem + (kt & 1) * Cfg::STAGE;
+        unsigned char *as_next = smem + ((kt + 1) & 1) * Cfg::STAGE;
+#pragma unroll
+        for (int ks = 0; ks < KS - 1; ++ks) {
+            const int cur = ks & 1, nxt = cur ^ 1;
+#pragma unroll
+            for (int i = 0; i < TM * TN; ++i) {
+                acc[i / TN][i % TN] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
+                    fa[cur][i / TN], fb[cur][i % TN], acc[i / TN][i % TN], 0, 0, 0);
+                fetch_one(as, ks + 1, nxt, i);
+                __builtin_amdgcn_sched_barrier(0);
+            }
+#pragma unroll
+            for (int i = TM * TN; i < TM + TN; ++i) fetch_one(as, ks + 1, nxt, i);
+        }
+        constexpr int cur = (KS - 1) & 1, nxt = cur ^ 1;
+        if constexpr (more) {
+            wait_lds();       // this wavefront's reads of stage kt are complete
+            wait_vmcnt<0>();  // its part of tile kt+1 has landed
+            wg_barrier();     // ... and so has everyone else's; stage kt is free
+        }
+#pragma unroll
+        for (int i = 0; i < TM * TN; ++i) {
+            acc[i / TN][i % TN] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
+                fa[cur][i / TN], fb[cur][i % TN], acc[i / TN][i % TN], 0, 0, 0);
+            if constexpr (more) fetch_one(as_next, 0, nxt, i);
+            if constexpr (refill)
+                if (i < Cfg::LPW) issue_one(as, i);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+        if constexpr (more) {
+#pragma unroll
+            for (int i = TM * TN; i < TM + TN; ++i) fetch_one(as_next, 0, nxt, i);
+        }
+        if constexpr (refill) {
+#pragma unroll
+            for (int i = TM * TN; i < Cfg::LPW; ++i) issue_one(as, i);
+            a_base += BK * 2;
+            b_base += b_step;
+        }
+    };
+    for (int kt = 0; kt + 2 < nkf; ++kt) k_tile(kt, std::true_type{}, std::true_type{});
+    if (nkf >= 2) k_tile(nkf - 2, std::true_type{}, std::false_type{});
+    if (nkf >= 1) k_tile(nkf - 1, std::false_type{}, std::false_type{});
+
+    // ---- K tail and expand tiles: through registers, zero-filled where not valid ----
+    const int n_extra = (ktail ? 1 : 0) + nseg * tps;
+    const u32x4 zero4 = {0u, 0u, 0u, 0u};
+    for (int e = 0; e < n_extra; ++e) {
+        u32x4 a_reg[Cfg::A_CH], b_reg[Cfg::B_CH];
+        const bool is_tail = ktail && e == 0;
+        const int ee = e - (ktail ? 1 : 0);
+        const int sg = is_tail ? 0 : ee / tps, sub = is_tail ? 0 : ee % tps;
+        const int c = (is_tail || nseg == 0) ? 0 : seg_c[sg];
+        const int lo = is_tail ? 0 : seg_lo[sg], hi = is_tail ? 0 : seg_hi[sg];
+        const uint16_t *Bc = B + (int64_t)c * rank * d_out;
+#pragma unroll
+        for (int i = 0; i < Cfg::A_CH; ++i) {
+            const int id = tid + i * NT, row = id / Cfg::A_CPR, u = id % Cfg::A_CPR;
+            const int tok = tile_perm[row];
+            const int p = p0 + row;
+            bool ok;
+            const uint16_t *src;
+            if (is_tail) {
+                const int k = nkf * BK + u * 8;
+                ok = k < d_in;
+                src = x + (int64_t)(tok >= 0 ? tok : 0) * d_in + (ok ? k : 0);
+            } else {
+                const int vk = sub * BK + u * 8;
+                ok = p >= lo && p < hi && vk < two_r;
+                src = t2 + (int64_t)(ok ? p : lo) * two_r + (ok ? vk : 0);
+            }
+            const u32x4 v = *(const u32x4 *)src;
+            a_reg[i] = ok ? v : zero4;
+        }
+#pragma unroll
+        for (int i = 0; i < Cfg::B_CH; ++i) {
+            const int id = tid + i * NT, kr = id / Cfg::B_CPR, u = id % Cfg::B_CPR;
+            const int n = min(n0 + u * 8, d_out - 8);
+            bool ok;
+            const uint16_t *src;
+            if (is_tail) {
+                const int k = nkf * BK + kr;
+                ok = k < d_in;
+                src = W + (int64_t)(ok ? k : 0) * d_out + n;
+            } else {
+                const int vk = sub * BK + kr;
+                ok = vk < two_r;
+                const int j = vk < rank ? vk : vk - rank;  // [B_c; B_c]
+                src = Bc + (int64_t)(ok ? j : 0) * d_out + n;
+            }
+            const u32x4 v = *(const u32x4 *)src;
+            b_reg[i] = ok ? v : zero4;
+        }
+        __syncthreads();  // the previous tile has been consumed
+#pragma unroll
+        for (int i = 0; i < Cfg::A_CH; ++i) {
+            const int id = tid + i * NT, row = id / Cfg::A_CPR, u = id % Cfg::A_CPR;
+            *(u32x4 *)(smem + row * Cfg::A_RB + ((u ^ Cfg::swz_a(row)) << 4)) = a_reg[i];
+        }
+#pragma unroll
+        for (int i = 0; i < Cfg::B_CH; ++i) {
+            const int id = tid + i * NT, kr = id / Cfg::B_CPR, u = id % Cfg::B_CPR;
+            *(u32x4 *)(smem + Cfg::A_BYTES + kr * Cfg::B_RB + (((u >> 1) ^ (kr & 3)) << 5) +
+                       ((u & 1) << 4)) = b_reg[i];
+        }
         __syncthreads();
+        compute_tile(smem);
     }
 
     // ---- epilogue: every row to its original position ----
-    // acc[tm][tn][v]: row tm*32 + (v/4)*8 + (lane/32)*4 + v%4, column tn*32 + lane%32
+    // acc[tm][tn][v]: row tm*32 + (v/4)*8 + (lane/32)*4 + v%4, column tn*32 + lane%32.
+    // The accumulators go through LDS one 32-row band per wavefront row at a time, so that
+    // the global stores are 16 bytes per lane and a whole BN-wide row segment (1 KB) per
+    // instruction: the rows are scattered over all of h by the permutation, and narrow
+    // stores to scattered rows are what the memory system handles worst.
+    constexpr int EP_STRIDE = BN * 4 + 32;           // bytes per staged row (+32: bank shift)
+    constexpr int EP_ROWS = Cfg::WM * 32;
+    constexpr int EP_CPR = BN / 4;                   // 16-byte chunks per row
+    static_assert(EP_ROWS * EP_STRIDE <= STAGES * Cfg::STAGE, "epilogue staging fits the stages");
 #pragma unroll
     for (int tm = 0; tm < TM; ++tm) {
+        __syncthreads();  // operand stages (or the previous band) are no longer read
 #pragma unroll
         for (int v = 0; v < 16; ++v) {
-            const int row = wm * (BM / Cfg::WM) + tm * 32 + (v >> 2) * 8 + (lane >> 5) * 4 + (v & 3);
-            const int tok = tile_perm[row];
-            if (tok < 0) continue;
-            float *hrow = h + (int64_t)tok * d_out;
+            const int rr = wm * 32 + (v >> 2) * 8 + (lane >> 5) * 4 + (v & 3);
 #pragma unroll
             for (int tn = 0; tn < TN; ++tn) {
-                const int col = n0 + wn * (BN / Cfg::WN) + tn * 32 + (lane & 31);
-                if (col < d_out) hrow[col] = acc[tm][tn][v];
+                const int col = wn * (BN / Cfg::WN) + tn * 32 + (lane & 31);
+                *(float *)(smem + rr * EP_STRIDE + col * 4) = acc[tm][tn][v];
             }
+        }
+        __syncthreads();
+        for (int it = tid; it < EP_ROWS * EP_CPR; it += NT) {
+            const int r = it / EP_CPR, ch = it % EP_CPR;
+            const int row = (r >> 5) * (BM / Cfg::WM) + tm * 32 + (r & 31);
+            const int tok = tile_perm[row];
+            const int col = n0 + ch * 4;
+            if (tok >= 0 && col < d_out)
+                *(f32x4 *)(h + (int64_t)tok * d_out + col) = *(const f32x4 *)(smem + r * EP_STRIDE + ch * 16);
         }
     }
 }
@@ -256,6 +431,13 @@ hipError_t launch_cfg(const uint16_t *x, const uint16_t *W, const uint16_t *B, c
 
 }  // namespace
 
+#ifndef MOLORA_GEMM_BIG
+#define MOLORA_GEMM_BIG 256, 256, 2, 4, 64, 2
+#endif
+#ifndef MOLORA_GEMM_SMALL
+#define MOLORA_GEMM_SMALL 128, 128, 2, 2, 64, 2
+#endif
+
 hipError_t launch_fused_gemm(const uint16_t *x, const uint16_t *W, const uint16_t *B,
                              const uint16_t *t2, const int32_t *offsets, const int32_t *perm,
                              float *h, int64_t N, int d_in, int d_out, int C, int rank,
@@ -265,8 +447,8 @@ hipError_t launch_fused_gemm(const uint16_t *x, const uint16_t *W, const uint16_
     // that still yields at least ~2 workgroups per compute unit.
     const int64_t t256 = ((N + 255) / 256) * ((d_out + 255) / 256);
     if (t256 >= 512)
-        return launch_cfg<GemmCfg<256, 256, 2, 2>>(x, W, B, t2, offsets, perm, h, N, d_in, d_out, C, rank, s);
-    return launch_cfg<GemmCfg<128, 128, 2, 2>>(x, W, B, t2, offsets, perm, h, N, d_in, d_out, C, rank, s);
+        return launch_cfg<GemmCfg<MOLORA_GEMM_BIG>>(x, W, B, t2, offsets, perm, h, N, d_in, d_out, C, rank, s);
+    return launch_cfg<GemmCfg<MOLORA_GEMM_SMALL>>(x, W, B, t2, offsets, perm, h, N, d_in, d_out, C, rank, s);
 }
 
 }  // namespace molora
