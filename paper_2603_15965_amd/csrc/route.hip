@@ -2,205 +2,280 @@
 // "tab:moe_adapter"):  r[i] = argmax_c sum_k x[i][k] G[k][c], lowest index on ties.
 //
 // The result has to be a deterministic function of the input bits, so every logit is the
-// strict fp32 chain  acc <- fl(acc + x_k * g_k),  k ascending.  The chain is run on the
-// matrix cores with the K = 1 fp32 MFMA (v_mfma_f32_4x4x1_16b_f32): one instruction is 16
-// independent 4x4 outer-product updates, i.e. exactly one fused multiply-add per
-// accumulator and therefore one chain step for 256 (token, target) pairs, at twice the
-// rate of the vector ALU.  The bf16 x bf16 product is exact in fp32, so the fused and the
-// unfused step round identically.
+// strict fp32 chain  acc <- fl(acc + x_k * g_k),  k ascending (the bf16 x bf16 product is
+// exact in fp32, so fused and unfused steps round identically).  That chain is exactly what
+// the fp32 matrix instruction v_mfma_f32_16x16x4_f32 computes: it walks its 4 k in order
+// with one fp32 rounding per step, so a sequence of them is the scalar chain for 16 tokens
+// x 16 targets at the full fp32 MFMA rate.  A chain cannot be split over k, so parallelism
+// comes only from (token, target) blocks: one wavefront owns 16 tokens and NB blocks of 16
+// targets; the TB wavefronts that share a token group take different target blocks, so that
+// a SIMD has two or more independent chains to interleave behind the ~44-cycle
+// dependent-issue latency of the instruction, and merge their winners at the end.
 //
-// Work split: a wavefront owns TOK tokens x (4*CG*P) targets; the 16 MFMA blocks are laid
-// out as TG token groups x CG target groups.  x is read straight from HBM (each lane 16 B
-// of its token's row, prefetched), G is converted to fp32 once per workgroup and k-slab
-// into LDS, transposed to [target][k] so a lane fetches 4 consecutive k with one b128 read.
+// Operand layout of the instruction: lane l holds A[row l%16][k = l/16] and B[k = l/16][col
+// l%16], so lane (t, kq) needs x[t][4s + kq] for consecutive steps s.  Both operands are
+// therefore staged in LDS in [row][kq][s] order, which makes a lane's next 8 (x, bf16) or 4
+// (G, fp32) steps one 16-byte read:
+//   x: each lane loads 16 contiguous bytes of its token's row (4 lanes = 64 contiguous bytes
+//      per token and instruction), a ring of kRing loads per wavefront is in flight, and the
+//      loaded pieces are regrouped into a wavefront-private LDS buffer;
+//   G: converted to fp32 once per workgroup and k-slab, shared by the workgroup's wavefronts.
 #include "common.h"
 
 namespace molora {
 
 namespace {
 
-constexpr int kRouteWaves = 4;
-constexpr int kRouteThreads = kRouteWaves * 64;
+constexpr int kRing = 8;        // x loads in flight per wavefront
+constexpr int kXK = 32;         // k per x load instruction (chunk): 16 tokens x 64 bytes
+constexpr int kSCK = kRing * kXK;  // k per unrolled super-chunk
+constexpr int kXRow = 80;       // bytes per token in the x buffer: 4 kq x 16 B + 16 B bank shift
+constexpr int kXBuf = 16 * kXRow;
 
-template <int CG, int P>
+// NB target blocks per wavefront, TB wavefronts per token group, TGW token groups per workgroup
+template <int NB, int TB, int TGW>
 struct RouteCfg {
-    static constexpr int TG = 16 / CG;             // token groups per MFMA
-    static constexpr int S = 2;                    // independent token sets per wavefront
-    static constexpr int TOK_SET = 4 * TG;         // tokens per set
-    static constexpr int TOK_WAVE = S * TOK_SET;
-    static constexpr int TOK_WG = kRouteWaves * TOK_WAVE;
-    static constexpr int CPAD = 4 * CG * P;        // targets covered
-    static constexpr int KS0 = 4096 / CPAD;
-    static constexpr int KS = KS0 > 256 ? 256 : (KS0 < 8 ? 8 : KS0);  // k per G slab
-    static constexpr int XS = KS < 64 ? KS : 64;   // k per x prefetch chunk
-    static constexpr int XL = XS / 8;              // 16-byte x loads per chunk and set
-    static constexpr int LDG = KS + 4;             // padded row of the fp32 slab
-    static constexpr int SLAB_FLOATS = CPAD * LDG;
-    static constexpr int QUADS = CPAD * KS / 4;    // (target, 4 k) items per slab
-    static constexpr int QPT = (QUADS + kRouteThreads - 1) / kRouteThreads;
-    static constexpr size_t LDS_BYTES = 2ull * SLAB_FLOATS * sizeof(float);
+    static constexpr int NWV = TB * TGW;
+    static constexpr int NT = NWV * 64;
+    static constexpr int TOK_WG = TGW * 16;
+    static constexpr int CW = NB * TB * 16;  // targets per pass
+    // k per G slab: about 8 staging items (32 elements) per thread, a power of two in [32, 256]
+    static constexpr int KS0 = 32 * NT / CW;
+    static constexpr int KS = KS0 > 256 ? 256 : (KS0 < 32 ? 32 : KS0);
+    static constexpr int LDG = KS + 4;  // floats per target row: 4 kq x KS/4 steps + bank shift
+    static constexpr int SLAB_FLOATS = CW * LDG;
+    static constexpr size_t LDS_BYTES = 2ull * SLAB_FLOATS * sizeof(float) + (size_t)NWV * 2 * kXBuf;
+    static_assert(kSCK % KS == 0, "slab boundaries fall on static positions of the super-chunk");
 };
 
-template <int CG, int P>
-__global__ __launch_bounds__(kRouteThreads) void route_gate_kernel(
+__device__ __forceinline__ void route_barrier() {
+    // LDS-only workgroup barrier: the x ring stays in flight across it
+    asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+}
+
+template <int NB, int TB, int TGW, bool VEC8>
+__global__ __launch_bounds__(TB * TGW * 64) void route_gate_kernel(
     const uint16_t *__restrict__ x, const uint16_t *__restrict__ G, int32_t *__restrict__ r,
     int64_t N, int d_in, int C) {
-    using K = RouteCfg<CG, P>;
-    extern __shared__ float gs[];  // two fp32 slabs [CPAD][LDG]
+    using K = RouteCfg<NB, TB, TGW>;
+    extern __shared__ __attribute__((aligned(16))) unsigned char route_lds[];
+    float *gs = (float *)route_lds;  // two fp32 slabs [CW][kq][KS/4] (+pad)
+    unsigned char *xs_all = route_lds + 2 * K::SLAB_FLOATS * sizeof(float);
 
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int blk = lane >> 2, q = lane & 3;
-    const int cg = blk % CG, tg = blk / CG;
-    const int64_t tok_wave = (int64_t)blockIdx.x * K::TOK_WG + wave * K::TOK_WAVE;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int l16 = lane & 15, kq = lane >> 4;
+    const int tb = wave % TB, tgw = wave / TB;  // target-block group, token group
+    const int64_t tok_wave = (int64_t)blockIdx.x * K::TOK_WG + tgw * 16;
+    unsigned char *xs = xs_all + wave * 2 * kXBuf;  // two chunk buffers of this wavefront
 
-    // x row of this lane for each set (A operand: row q of block (tg, cg))
-    const uint16_t *xrow[K::S];
-    bool xok[K::S];
+    // load side: lane (t = l16, cq = kq) fetches x[t][k0 + 8*cq .. +8)
+    const int64_t tok = tok_wave + l16;
+    const bool tok_ok = tok < N;
+    const uint16_t *xrow = x + (tok_ok ? tok : 0) * (int64_t)d_in + kq * 8;  // + k0
+    const int xs_wr = l16 * kXRow + kq * 4;   // + kq' * 16 : steps 2cq, 2cq+1 of group kq'
+    const int xs_rd = l16 * kXRow + kq * 16;  // this lane's 8 steps of the chunk
+
+    float best[4];
+    int bidx[4];
 #pragma unroll
-    for (int s = 0; s < K::S; ++s) {
-        const int64_t t = tok_wave + s * K::TOK_SET + tg * 4 + q;
-        xok[s] = t < N;
-        xrow[s] = x + (xok[s] ? t : 0) * (int64_t)d_in;
+    for (int v = 0; v < 4; ++v) {
+        best[v] = -__builtin_huge_valf();
+        bidx[v] = 0x7FFFFFFF;
     }
 
-    f32x4 acc[K::S][P];
+    for (int c0 = 0; c0 < C; c0 += K::CW) {  // passes of up to CW targets (one pass if C <= 128)
+        f32x4 acc[NB];
 #pragma unroll
-    for (int s = 0; s < K::S; ++s)
-#pragma unroll
-        for (int p = 0; p < P; ++p) acc[s][p] = f32x4{0.f, 0.f, 0.f, 0.f};
+        for (int b = 0; b < NB; ++b) acc[b] = f32x4{0.f, 0.f, 0.f, 0.f};
 
-    // ---- G slab staging: thread handles items (target, 4 consecutive k) ----
-    uint32_t greg[K::QPT][2];
-    auto g_load = [&](int k0) {
+        // ---- G slab staging ----
+        // element (k, c) of the slab goes to  c*LDG + (k%4)*(KS/4) + k/4  as fp32.
+        // Fast form (C a multiple of 8): an item is 8 consecutive targets of one k, one 16-byte
+        // load.  Otherwise an item is one element.  Loads are never predicated (addresses are
+        // clamped into G, the value is zeroed afterwards) so that they all stay in flight.
+        constexpr int IPT = K::KS * K::CW / 8 / K::NT;  // 8-element items per thread and slab
+        static_assert(IPT * K::NT * 8 == K::KS * K::CW, "slab staging split");
+        u32x4 greg[IPT];
+        auto g_load = [&](int k0) {
 #pragma unroll
-        for (int m = 0; m < K::QPT; ++m) {
-            const int item = tid + m * kRouteThreads;
-            const int c = item % K::CPAD, kq = item / K::CPAD;
-            uint32_t v[4];
+            for (int m = 0; m < IPT; ++m) {
+                const int item = tid + m * K::NT;
+                const int kk = item / (K::CW / 8), c8 = (item % (K::CW / 8)) * 8;
+                const int k = k0 + kk;
+                const int kc = min(k, d_in - 1);
+                const uint32_t km = (k < d_in) ? 0xFFFFFFFFu : 0u;
+                u32x4 v;
+                if constexpr (VEC8) {
+                    const int cc = min(c0 + c8, C - 8);
+                    v = *(const u32x4 *)(G + (int64_t)kc * C + cc);
+                    asm volatile("" : "+v"(v));  // keep the load unconditional
+                    const uint32_t m8 = (c0 + c8 < C) ? km : 0u;
+                    v = u32x4{v[0] & m8, v[1] & m8, v[2] & m8, v[3] & m8};
+                } else {
+                    uint32_t e[8];
 #pragma unroll
-            for (int e = 0; e < 4; ++e) {
-                const int k = k0 + kq * 4 + e;
-                v[e] = (item < K::QUADS && c < C && k < d_in) ? G[(int64_t)k * C + c] : 0u;
+                    for (int i = 0; i < 8; ++i) {
+                        uint32_t raw = G[(int64_t)kc * C + min(c0 + c8 + i, C - 1)];
+                        asm volatile("" : "+v"(raw));
+                        e[i] = raw & ((c0 + c8 + i < C) ? km : 0u);
+                    }
+                    v = u32x4{e[0] | (e[1] << 16), e[2] | (e[3] << 16), e[4] | (e[5] << 16),
+                              e[6] | (e[7] << 16)};
+                }
+                greg[m] = v;
             }
-            greg[m][0] = v[0] | (v[1] << 16);
-            greg[m][1] = v[2] | (v[3] << 16);
-        }
-    };
-    auto g_store = [&](float *slab) {
+        };
+        auto g_store = [&](float *slab) {
 #pragma unroll
-        for (int m = 0; m < K::QPT; ++m) {
-            const int item = tid + m * kRouteThreads;
-            if (item < K::QUADS) {
-                const int c = item % K::CPAD, kq = item / K::CPAD;
-                f32x4 f;
-                f[0] = __uint_as_float(greg[m][0] << 16);
-                f[1] = __uint_as_float(greg[m][0] & 0xFFFF0000u);
-                f[2] = __uint_as_float(greg[m][1] << 16);
-                f[3] = __uint_as_float(greg[m][1] & 0xFFFF0000u);
-                *(f32x4 *)(slab + c * K::LDG + kq * 4) = f;
+            for (int m = 0; m < IPT; ++m) {
+                const int item = tid + m * K::NT;
+                const int kk = item / (K::CW / 8), c8 = (item % (K::CW / 8)) * 8;
+                float *dst = slab + c8 * K::LDG + (kk & 3) * (K::KS / 4) + (kk >> 2);
+#pragma unroll
+                for (int i = 0; i < 8; ++i) {
+                    const uint32_t w = greg[m][i >> 1];
+                    dst[i * K::LDG] = __uint_as_float((i & 1) ? (w & 0xFFFF0000u) : (w << 16));
+                }
             }
-        }
-    };
+        };
 
-    // ---- x prefetch: XL loads of 8 bf16 per set ----
-    u32x4 xcur[K::S][K::XL], xnext[K::S][K::XL];
-    auto x_load = [&](u32x4(&dst)[K::S][K::XL], int k0) {
-#pragma unroll
-        for (int s = 0; s < K::S; ++s)
-#pragma unroll
-            for (int j = 0; j < K::XL; ++j) {
-                const int k = k0 + j * 8;
-                dst[s][j] = (xok[s] && k < d_in) ? *(const u32x4 *)(xrow[s] + k)
-                                                 : u32x4{0u, 0u, 0u, 0u};
-            }
-    };
+        // ---- x ring: kRing chunks of 32 k in flight ----
+        u32x4 xg[kRing];
+        // Never predicated: a chunk past d_in re-reads the row's last 16 bytes (it meets an
+        // all-zero G slab, so it adds +0), a token past N reads token 0 (never stored).
+        auto x_load = [&](int j, int k0) {  // chunk starting at k0 into ring slot j
+            xg[j] = *(const u32x4 *)(xrow + max(min(k0, d_in - 8 - kq * 8), -kq * 8));
+        };
 
-    g_load(0);
-    x_load(xcur, 0);
-    g_store(gs);
-    __syncthreads();
+#pragma unroll
+        for (int j = 0; j < kRing; ++j) x_load(j, j * kXK);
+        if (c0 > 0) route_barrier();  // the previous pass has finished reading the slabs
+        g_load(0);
+        g_store(gs);
+        g_load(K::KS);
+        route_barrier();
 
-    const int nslab = (d_in + K::KS - 1) / K::KS;
-    for (int sl = 0; sl < nslab; ++sl) {
-        const float *slab = gs + (sl & 1) * K::SLAB_FLOATS;
-        const int k_slab = sl * K::KS;
-        if (sl + 1 < nslab) g_load(k_slab + K::KS);
-#pragma unroll 1
-        for (int sub = 0; sub < K::KS / K::XS; ++sub) {
-            const int k_sub = k_slab + sub * K::XS;
-            x_load(xnext, k_sub + K::XS);  // guarded by k < d_in; harmless past the end
+        int slab_idx = 0;  // slab being consumed
+        const int nsc = (d_in + kSCK - 1) / kSCK;
+        for (int sc = 0; sc < nsc; ++sc) {
+            const int k_sc = sc * kSCK;
 #pragma unroll
-            for (int j = 0; j < K::XL; ++j) {
-                // 8 k per group: fp32 G values of this lane's target(s)
-                f32x4 g[P][2];
+            for (int j = 0; j < kRing; ++j) {
+                const int k_ch = k_sc + j * kXK;  // first k of this chunk (may be past d_in)
+                const int ko = j * kXK;           // static offset inside the super-chunk
+                if (ko % K::KS == 0 && (sc > 0 || ko > 0)) {
+                    // next G slab: it was loaded into registers one slab ago
+                    ++slab_idx;
+                    g_store(gs + (slab_idx & 1) * K::SLAB_FLOATS);
+                    g_load((slab_idx + 1) * K::KS);
+                    route_barrier();
+                }
+                // regroup the chunk: elements (e_kq', e_kq'+4) of the 8 loaded are steps
+                // (2cq, 2cq+1) of lane group kq'
+                unsigned char *xb = xs + (j & 1) * kXBuf;
+                const u32x4 w = xg[j];
+                *(uint32_t *)(xb + xs_wr + 0 * 16) = __builtin_amdgcn_perm(w[2], w[0], 0x05040100u);
+                *(uint32_t *)(xb + xs_wr + 1 * 16) = __builtin_amdgcn_perm(w[2], w[0], 0x07060302u);
+                *(uint32_t *)(xb + xs_wr + 2 * 16) = __builtin_amdgcn_perm(w[3], w[1], 0x05040100u);
+                *(uint32_t *)(xb + xs_wr + 3 * 16) = __builtin_amdgcn_perm(w[3], w[1], 0x07060302u);
+                x_load(j, k_ch + kSCK);  // refill the ring slot
+
+                const float *slab = gs + (slab_idx & 1) * K::SLAB_FLOATS;
+                const u32x4 xr = *(const u32x4 *)(xb + xs_rd);  // steps 0..7 of this lane
+                f32x4 g[NB][2];
+                const int st0 = (ko % K::KS) / 4;  // first step of the chunk inside the slab
 #pragma unroll
-                for (int p = 0; p < P; ++p) {
-                    const float *gp = slab + (p * 4 * CG + cg * 4 + q) * K::LDG + sub * K::XS + j * 8;
-                    g[p][0] = *(const f32x4 *)gp;
-                    g[p][1] = *(const f32x4 *)(gp + 4);
+                for (int b = 0; b < NB; ++b) {
+                    const float *gp = slab + ((tb * NB + b) * 16 + l16) * K::LDG + kq * (K::KS / 4) + st0;
+                    g[b][0] = *(const f32x4 *)gp;
+                    g[b][1] = *(const f32x4 *)(gp + 4);
                 }
 #pragma unroll
-                for (int e = 0; e < 8; ++e) {
+                for (int s = 0; s < 8; ++s) {
+                    const uint32_t ww = xr[s >> 1];
+                    const float xa = __uint_as_float((s & 1) ? (ww & 0xFFFF0000u) : (ww << 16));
 #pragma unroll
-                    for (int s = 0; s < K::S; ++s) {
-                        const uint32_t w = xcur[s][j][e >> 1];
-                        const float xa = __uint_as_float((e & 1) ? (w & 0xFFFF0000u) : (w << 16));
+                    for (int b = 0; b < NB; ++b)
+                        acc[b] = __builtin_amdgcn_mfma_f32_16x16x4f32(xa, g[b][s >> 2][s & 3],
+                                                                      acc[b], 0, 0, 0);
+                }
+            }
+        }
+
+        // ---- running argmax: lexicographic (largest logit, then lowest index) ----
+        // acc[b][v] is the logit of token kq*4 + v and target c0 + (tb*NB + b)*16 + l16.
 #pragma unroll
-                        for (int p = 0; p < P; ++p)
-                            acc[s][p] = __builtin_amdgcn_mfma_f32_4x4x1f32(xa, g[p][e >> 2][e & 3],
-                                                                           acc[s][p], 0, 0, 0);
+        for (int v = 0; v < 4; ++v) {
+#pragma unroll
+            for (int b = 0; b < NB; ++b) {
+                const int tgt = c0 + (tb * NB + b) * 16 + l16;
+                float val = acc[b][v];
+                // a NaN logit never wins, except that target 0 is the scan's starting point
+                if (val != val) val = (tgt == 0) ? __builtin_huge_valf() : -__builtin_huge_valf();
+                if (tgt < C && (val > best[v] || (val == best[v] && tgt < bidx[v]))) {
+                    best[v] = val;
+                    bidx[v] = tgt;
+                }
+            }
+        }
+    }
+
+    // winners of this wavefront's targets: reduce over the 16 lanes that hold a token's row
+#pragma unroll
+    for (int v = 0; v < 4; ++v) {
+#pragma unroll
+        for (int d = 1; d < 16; d <<= 1) {
+            const float ov = __shfl_xor(best[v], d, 64);
+            const int oi = __shfl_xor(bidx[v], d, 64);
+            if (ov > best[v] || (ov == best[v] && oi < bidx[v])) {
+                best[v] = ov;
+                bidx[v] = oi;
+            }
+        }
+    }
+    if constexpr (TB > 1) {
+        // merge the TB wavefronts of a token group through LDS (the slabs are done with)
+        __syncthreads();
+        float *red_v = (float *)route_lds;                 // [TB][TOK_WG]
+        int32_t *red_i = (int32_t *)(red_v + TB * K::TOK_WG);
+        if (l16 == 0) {
+#pragma unroll
+            for (int v = 0; v < 4; ++v) {
+                red_v[tb * K::TOK_WG + tgw * 16 + kq * 4 + v] = best[v];
+                red_i[tb * K::TOK_WG + tgw * 16 + kq * 4 + v] = bidx[v];
+            }
+        }
+        __syncthreads();
+        if (tb == 0 && l16 == 0) {
+#pragma unroll
+            for (int v = 0; v < 4; ++v) {
+#pragma unroll
+                for (int o = 1; o < TB; ++o) {
+                    const float ov = red_v[o * K::TOK_WG + tgw * 16 + kq * 4 + v];
+                    const int oi = red_i[o * K::TOK_WG + tgw * 16 + kq * 4 + v];
+                    if (ov > best[v] || (ov == best[v] && oi < bidx[v])) {
+                        best[v] = ov;
+                        bidx[v] = oi;
                     }
                 }
             }
-#pragma unroll
-            for (int s = 0; s < K::S; ++s)
-#pragma unroll
-                for (int j = 0; j < K::XL; ++j) xcur[s][j] = xnext[s][j];
         }
-        if (sl + 1 < nslab) g_store(gs + ((sl + 1) & 1) * K::SLAB_FLOATS);
-        __syncthreads();
     }
-
-    // ---- argmax: lexicographic (largest logit, then lowest index) ----
-    // acc[s][p][i] is the logit of token (tg*4 + i) of set s and target p*4*CG + cg*4 + q.
-    constexpr float kInf = __builtin_huge_valf();
+    if (tb == 0 && l16 == 0) {
 #pragma unroll
-    for (int s = 0; s < K::S; ++s) {
-#pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            float best = -kInf;
-            int bidx = 0x7FFFFFFF;
-#pragma unroll
-            for (int p = 0; p < P; ++p) {
-                const int tgt = p * 4 * CG + cg * 4 + q;
-                float v = acc[s][p][i];
-                // a NaN logit never wins, except that target 0 is the scan's starting point
-                if (v != v) v = (tgt == 0) ? kInf : -kInf;
-                if (tgt < C && (v > best || (v == best && tgt < bidx))) {
-                    best = v;
-                    bidx = tgt;
-                }
-            }
-#pragma unroll
-            for (int d = 1; d < 4 * CG; d <<= 1) {
-                const float ov = __shfl_xor(best, d, 64);
-                const int oi = __shfl_xor(bidx, d, 64);
-                if (ov > best || (ov == best && oi < bidx)) {
-                    best = ov;
-                    bidx = oi;
-                }
-            }
-            const int64_t t = tok_wave + s * K::TOK_SET + tg * 4 + i;
-            if (cg == 0 && q == 0 && t < N) r[t] = bidx;
+        for (int v = 0; v < 4; ++v) {
+            const int64_t t = tok_wave + kq * 4 + v;
+            if (t < N) r[t] = bidx[v];
         }
     }
 }
 
-template <int CG, int P>
+template <int NB, int TB, int TGW, bool VEC8>
 hipError_t launch_cfg(const uint16_t *x, const uint16_t *G, int32_t *r, int64_t N, int d_in, int C,
                       hipStream_t s) {
-    using K = RouteCfg<CG, P>;
-    auto kern = route_gate_kernel<CG, P>;
+    using K = RouteCfg<NB, TB, TGW>;
+    auto kern = route_gate_kernel<NB, TB, TGW, VEC8>;
     if (K::LDS_BYTES > 64 * 1024) {
         hipError_t e = hipFuncSetAttribute((const void *)kern,
                                            hipFuncAttributeMaxDynamicSharedMemorySize,
@@ -208,9 +283,25 @@ hipError_t launch_cfg(const uint16_t *x, const uint16_t *G, int32_t *r, int64_t 
         if (e != hipSuccess) return e;
     }
     const unsigned blocks = (unsigned)((N + K::TOK_WG - 1) / K::TOK_WG);
-    hipLaunchKernelGGL(kern, dim3(blocks), dim3(kRouteThreads), K::LDS_BYTES, s, x, G, r, N, d_in,
-                       C);
+    hipLaunchKernelGGL(kern, dim3(blocks), dim3(K::NT), K::LDS_BYTES, s, x, G, r, N, d_in, C);
     return hipGetLastError();
+}
+
+// Token groups per workgroup: as many as still leave about two workgroups per compute unit
+// (a workgroup shares one fp32 copy of the G slab; the problem has only N/16 token groups).
+template <int NB, int TB>
+hipError_t launch_tb(const uint16_t *x, const uint16_t *G, int32_t *r, int64_t N, int d_in, int C,
+                     hipStream_t s) {
+    const int64_t groups = (N + 15) / 16;
+    constexpr int kMaxTgw = 8 / TB;  // at most 8 wavefronts per workgroup
+    if (C % 8 == 0) {                // rows of G can be fetched 16 bytes at a time
+        if constexpr (kMaxTgw >= 4)
+            if (groups >= 4 * 512) return launch_cfg<NB, TB, 4, true>(x, G, r, N, d_in, C, s);
+        if constexpr (kMaxTgw >= 2)
+            if (groups >= 2 * 512) return launch_cfg<NB, TB, 2, true>(x, G, r, N, d_in, C, s);
+        return launch_cfg<NB, TB, 1, true>(x, G, r, N, d_in, C, s);
+    }
+    return launch_cfg<NB, TB, 1, false>(x, G, r, N, d_in, C, s);
 }
 
 }  // namespace
@@ -218,15 +309,10 @@ hipError_t launch_cfg(const uint16_t *x, const uint16_t *G, int32_t *r, int64_t 
 hipError_t launch_route_gate(const uint16_t *x, const uint16_t *G, int32_t *r, int64_t N, int d_in,
                              int C, hipStream_t s) {
     if (N == 0) return hipSuccess;
-    if (C <= 4) return launch_cfg<1, 1>(x, G, r, N, d_in, C, s);
-    if (C <= 8) return launch_cfg<2, 1>(x, G, r, N, d_in, C, s);
-    if (C <= 16) return launch_cfg<4, 1>(x, G, r, N, d_in, C, s);
-    if (C <= 32) return launch_cfg<8, 1>(x, G, r, N, d_in, C, s);
-    if (C <= 64) return launch_cfg<16, 1>(x, G, r, N, d_in, C, s);
-    if (C <= 128) return launch_cfg<16, 2>(x, G, r, N, d_in, C, s);
-    if (C <= 256) return launch_cfg<16, 4>(x, G, r, N, d_in, C, s);
-    if (C <= 512) return launch_cfg<16, 8>(x, G, r, N, d_in, C, s);
-    return launch_cfg<16, 16>(x, G, r, N, d_in, C, s);
+    if (C <= 16) return launch_tb<1, 1>(x, G, r, N, d_in, C, s);
+    if (C <= 32) return launch_tb<1, 2>(x, G, r, N, d_in, C, s);
+    if (C <= 64) return launch_tb<2, 2>(x, G, r, N, d_in, C, s);
+    return launch_tb<2, 4>(x, G, r, N, d_in, C, s);  // 128 targets per pass
 }
 
 }  // namespace molora
