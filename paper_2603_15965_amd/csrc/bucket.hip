@@ -79,7 +79,7 @@ __global__ __launch_bounds__(kBucketThreads) void bucket_kernel(const int32_t *_
 #pragma unroll
         for (int u = 0; u < kUnroll; ++u) {
             const int t = base + u * 64 + lane;
-            const int32_t c = (t < end) ? r[t] : 0;
+            const int32_t c = r[t < end ? t : end - 1];  // never predicated: all 8 loads in flight
             key[u] = (c >= 0 && c < C) ? c : C;
         }
 #pragma unroll
@@ -126,7 +126,7 @@ __global__ __launch_bounds__(kBucketThreads) void bucket_kernel(const int32_t *_
 #pragma unroll
         for (int u = 0; u < kUnroll; ++u) {
             const int t = base + u * 64 + lane;
-            const int32_t c = (t < end) ? r[t] : 0;
+            const int32_t c = r[t < end ? t : end - 1];  // never predicated: all 8 loads in flight
             key[u] = (c >= 0 && c < C) ? c : C;
         }
 #pragma unroll

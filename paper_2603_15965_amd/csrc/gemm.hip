@@ -17,10 +17,15 @@
 //   W tile  [BK][BN]  exactly as it lies in HBM (K-major), 32-byte chunks swizzled by (k & 3);
 //                     the LDS transpose read turns it into the k-contiguous operand, so W needs
 //                     no packing pass and no transposed copy.
-// Full K tiles go HBM -> LDS directly (global_load_lds_dwordx4: no staging registers; the
+// Every K tile goes HBM -> LDS directly (global_load_lds_dwordx4: no staging registers; the
 // gathered row address and the swizzle are applied on the global side, the LDS side is
-// linear) through a ring of STAGES buffers, STAGES-1 tiles in flight.  The K tail (d_in not
-// a multiple of BK) and the expand tiles need zero-filling and go through registers.
+// linear).  Whatever has to read as zero -- k past d_in, t rows of other buckets, padding of
+// 2*rank up to the tile depth -- is fetched from a small all-zero page instead, so the K
+// tail and the expand tiles travel the same path as the base tiles.
+// Two main loops share the rest of the kernel: large problems (MFMA bound) use two LDS
+// stages with the operand fragments of the next k-step prefetched into registers behind the
+// MFMAs; small batches (N <= 64, bound by streaming W) use a deep ring of LDS stages so that
+// about 100 KB per compute unit is in flight.
 // Workgroups are numbered so that the 8 XCDs (blockIdx % 8) each walk a compact group of
 // tiles and share x rows / W columns in their own L2.
 #include <type_traits>
@@ -58,23 +63,43 @@ __device__ __forceinline__ void load_to_lds16(const void *base, uint32_t lane_of
         : "memory", "m0");
 }
 
-template <int BM_, int BN_, int WM_, int WN_, int BK_, int STAGES_>
+// same, from a per-lane 64-bit address
+__device__ __forceinline__ void load_to_lds16_ptr(const void *gptr, unsigned char *lds_base) {
+    const uint32_t lds_addr = (uint32_t)(uintptr_t)(MOLORA_LDS unsigned char *)lds_base;
+    asm volatile(
+        "s_mov_b32 m0, %1\n\t"
+        "s_nop 0\n\t"
+        "global_load_lds_dwordx4 %0, off"
+        :
+        : "v"(gptr), "s"(lds_addr)
+        : "memory", "m0");
+}
+
+// 256 bytes of zeros in device memory: the source of every operand chunk that must be zero
+__device__ __attribute__((aligned(256))) uint32_t g_zero_page[64];
+
+// BM x BN output tile, WM x WN x WK wavefronts (WK > 1: the k-steps of a tile are dealt out to
+// WK wavefronts per 32x32-block group and summed at the end; used where the kernel is bound by
+// loading and wants many wavefronts issuing loads), BK deep K tiles, STAGES LDS buffers.
+template <int BM_, int BN_, int WM_, int WN_, int WK_, int BK_, int STAGES_>
 struct GemmCfg {
-    static constexpr int BM = BM_, BN = BN_, WM = WM_, WN = WN_, BK = BK_, STAGES = STAGES_;
-    static constexpr int NW = WM * WN, NT = 64 * NW;
+    static constexpr int BM = BM_, BN = BN_, WM = WM_, WN = WN_, WK = WK_, BK = BK_, STAGES = STAGES_;
+    static constexpr int NW = WM * WN * WK, NT = 64 * NW;
     static constexpr int TM = BM / WM / 32, TN = BN / WN / 32;
+    // A tile = x rows, B tile = W rows; a load instruction fills 1 KB = one "piece"
     static constexpr int A_RB = BK * 2, A_CPR = A_RB / 16, A_RPI = 64 / A_CPR;
-    static constexpr int A_LPW = BM / A_RPI / NW;       // direct loads per wavefront and tile
     static constexpr int B_RB = BN * 2, B_CPR = B_RB / 16, B_RPI = 64 / B_CPR;
-    static constexpr int B_LPW = BK / B_RPI / NW;
-    static constexpr int LPW = A_LPW + B_LPW;
+    static constexpr int A_PIECES = BM / A_RPI, B_PIECES = BK / B_RPI;
+    static constexpr int LPW = (A_PIECES + B_PIECES) / NW;  // pieces (loads) per wavefront and tile
     static constexpr int A_BYTES = BM * A_RB, B_BYTES = BK * B_RB, STAGE = A_BYTES + B_BYTES;
-    static constexpr int A_CH = BM * A_CPR / NT, B_CH = BK * B_CPR / NT;  // register path
     static constexpr size_t LDS_BYTES = (size_t)STAGES * STAGE + 4 * BM * sizeof(int32_t) + 16;
+    static constexpr bool PIPE = (STAGES == 2);  // fragment-pipelined main loop, else deep ring
     static_assert(BK == 32 || BK == 64, "BK");
-    static_assert(A_LPW * A_RPI * NW == BM && B_LPW * B_RPI * NW == BK, "direct-load split");
-    static_assert(A_CH * NT == BM * A_CPR && B_CH * NT == BK * B_CPR, "register-load split");
+    static_assert(LPW * NW == A_PIECES + B_PIECES && LPW >= 1, "pieces split evenly over wavefronts");
+    static_assert(A_PIECES % LPW == 0, "a wavefront loads only x pieces or only W pieces");
     static_assert(STAGES >= 2, "stages");
+    static_assert(!PIPE || WK == 1, "the pipelined loop keeps all k-steps in one wavefront");
+    static_assert((BK / 16) % WK == 0, "k-steps split evenly");
 
     // XOR applied to the 16-byte chunk index of an x-tile row
     __device__ static __forceinline__ int swz_a(int row) {
@@ -101,7 +126,8 @@ __global__ __launch_bounds__(Cfg::NT) void fused_gemm_kernel(
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int wm = wave / Cfg::WN, wn = wave % Cfg::WN;
+    const int wk = wave % Cfg::WK;  // which k-steps of a tile this wavefront multiplies
+    const int wm = (wave / Cfg::WK) / Cfg::WN, wn = (wave / Cfg::WK) % Cfg::WN;
 
     // ---- tile of this workgroup: XCD-major, then groups of kGroupM row tiles ----
     const int total = tiles_m * tiles_n;
@@ -133,34 +159,102 @@ __global__ __launch_bounds__(Cfg::NT) void fused_gemm_kernel(
     const int nseg = *nseg_p;
     const int two_r = 2 * rank;
     const int tps = (two_r + BK - 1) / BK;  // extra K tiles per bucket
-    const int nkf = d_in / BK;              // full K tiles (direct path)
-    const int ktail = d_in - nkf * BK;      // leftover k (register path)
+    const int nkf = d_in / BK;              // full K tiles
+    const int nkb = (d_in + BK - 1) / BK;   // K tiles of x.W, the last one possibly partial
+    const int nk = nkb + nseg * tps;        // all K tiles of this output tile
 
-    // ---- direct path: per-lane source pointers of this wavefront's load instructions ----
+    // ---- per-lane sources of this wavefront's load instructions ----
+    // A stage is A_PIECES + B_PIECES pieces of 1 KB; wavefront w loads pieces w*LPW .. +LPW-1,
+    // which are either all x pieces (A_RPI rows each) or all W pieces (B_RPI k-rows each).
     // Rows past N and columns past d_out are clamped to valid memory: what they produce is
     // never stored.
-    // Byte offsets from a scalar base that advances with the K tile (x and W are < 4 GiB).
-    uint32_t a_off_g[Cfg::A_LPW], b_off_g[Cfg::B_LPW];
+    const int piece0 = wave * Cfg::LPW;
+    const bool is_a = piece0 < Cfg::A_PIECES;  // wave-uniform
+    // geometry of load i of this wavefront: x piece -> (tile row, 8-k chunk index after the
+    // swizzle); W piece -> (k-row, global column).  Recomputed where needed instead of kept in
+    // registers: only the special tiles and the set-up use it.
+    auto slot_geom = [&](int i, int &row, int &col) {
+        if (is_a) {
+            row = (piece0 + i) * Cfg::A_RPI + lane / Cfg::A_CPR;
+            col = (lane % Cfg::A_CPR) ^ Cfg::swz_a(row);
+        } else {
+            row = (piece0 + i - Cfg::A_PIECES) * Cfg::B_RPI + lane / Cfg::B_CPR;
+            const int pos = lane % Cfg::B_CPR;
+            const int u16 = ((((pos >> 1) ^ (row & 3))) << 1) | (pos & 1);
+            col = min(n0 + u16 * 8, d_out - 8);
+        }
+    };
+    uint32_t off_g[Cfg::LPW];  // full tiles: byte offset from the scalar base
 #pragma unroll
-    for (int i = 0; i < Cfg::A_LPW; ++i) {
-        const int q = wave * Cfg::A_LPW + i;
-        const int row = q * Cfg::A_RPI + lane / Cfg::A_CPR;
-        const int u = (lane % Cfg::A_CPR) ^ Cfg::swz_a(row);
-        const int tok = tile_perm[row];
-        a_off_g[i] = (uint32_t)(((int64_t)(tok >= 0 ? tok : 0) * d_in + u * 8) * 2);
+    for (int i = 0; i < Cfg::LPW; ++i) {
+        int row, col;
+        slot_geom(i, row, col);
+        if (is_a) {
+            const int tok = tile_perm[row];
+            off_g[i] = (uint32_t)(((int64_t)(tok >= 0 ? tok : 0) * d_in + col * 8) * 2);
+        } else {
+            off_g[i] = (uint32_t)(((int64_t)row * d_out + col) * 2);
+        }
     }
+    // scalar base of the full tiles, advanced per tile (x and W are < 4 GiB each)
+    const unsigned char *g_base = is_a ? (const unsigned char *)x : (const unsigned char *)W;
+    const int64_t g_step = is_a ? (int64_t)BK * 2 : (int64_t)BK * d_out * 2;
+
+    auto issue_one = [&](unsigned char *stage, int i) {  // i-th load of a full tile
+        load_to_lds16(g_base, off_g[i], stage + (piece0 + i) * 1024);
+    };
+    auto advance_full = [&]() { g_base += g_step; };
+    // Any K tile T, full tiles through the fast form.  A partial last tile of x.W and the
+    // expand tiles compute a source per lane; chunks that must read as zero come from the
+    // zero page.  Tiles must be issued in ascending order (the fast form advances its base).
+    auto issue_tile = [&](unsigned char *stage, int T) {
+        if (T < nkf) {
 #pragma unroll
-    for (int i = 0; i < Cfg::B_LPW; ++i) {
-        const int q = wave * Cfg::B_LPW + i;
-        const int kr = q * Cfg::B_RPI + lane / Cfg::B_CPR;
-        const int pos = lane % Cfg::B_CPR;
-        const int u16 = ((((pos >> 1) ^ (kr & 3))) << 1) | (pos & 1);
-        const int n = min(n0 + u16 * 8, d_out - 8);
-        b_off_g[i] = (uint32_t)(((int64_t)kr * d_out + n) * 2);
-    }
-    const unsigned char *a_base = (const unsigned char *)x;  // + BK*2 bytes per K tile
-    const unsigned char *b_base = (const unsigned char *)W;  // + BK*d_out*2 bytes per K tile
-    const int64_t b_step = (int64_t)BK * d_out * 2;
+            for (int i = 0; i < Cfg::LPW; ++i) issue_one(stage, i);
+            advance_full();
+            return;
+        }
+        const uint16_t *zero = (const uint16_t *)g_zero_page;
+        if (T < nkb) {  // partial tile of x.W: k past d_in reads zero
+#pragma unroll
+            for (int i = 0; i < Cfg::LPW; ++i) {
+                const uint16_t *src;
+                int row, col;
+                slot_geom(i, row, col);
+                if (is_a) {
+                    const int k = T * BK + col * 8;
+                    const int tok = tile_perm[row];
+                    src = (k < d_in) ? x + (int64_t)(tok >= 0 ? tok : 0) * d_in + k : zero;
+                } else {
+                    const int k = T * BK + row;
+                    src = (k < d_in) ? W + (int64_t)k * d_out + col : zero;
+                }
+                load_to_lds16_ptr(src, stage + (piece0 + i) * 1024);
+            }
+            return;
+        }
+        // expand tile: A operand = t rows of one bucket (others zero), B operand = [B_c; B_c]
+        const int e = T - nkb;
+        const int sg = e / tps, sub = e % tps;
+        const int c = seg_c[sg], lo = seg_lo[sg], hi = seg_hi[sg];
+        const uint16_t *Bc = B + (int64_t)c * rank * d_out;
+#pragma unroll
+        for (int i = 0; i < Cfg::LPW; ++i) {
+            const uint16_t *src;
+            int row, col;
+            slot_geom(i, row, col);
+            if (is_a) {
+                const int p = p0 + row, vk = sub * BK + col * 8;
+                src = (p >= lo && p < hi && vk < two_r) ? t2 + (int64_t)p * two_r + vk : zero;
+            } else {
+                const int vk = sub * BK + row;
+                const int j = vk < rank ? vk : vk - rank;
+                src = (vk < two_r) ? Bc + (int64_t)j * d_out + col : zero;
+            }
+            load_to_lds16_ptr(src, stage + (piece0 + i) * 1024);
+        }
+    };
+
     f32x16 acc[TM][TN];
 #pragma unroll
     for (int i = 0; i < TM; ++i)
@@ -204,57 +298,27 @@ __global__ __launch_bounds__(Cfg::NT) void fused_gemm_kernel(
         const i16x8 b8 = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
         return __builtin_bit_cast(bf16x8, b8);
     };
-    // plain (not software-pipelined) product of one staged tile: used for the extra tiles
-    auto compute_tile = [&](const unsigned char *as) {
-#pragma unroll
-        for (int ks = 0; ks < BK / 16; ++ks) {
-            bf16x8 af[TM], bfr[TN];
-#pragma unroll
-            for (int tm = 0; tm < TM; ++tm) af[tm] = load_a_frag(as, ks, tm);
-#pragma unroll
-            for (int tn = 0; tn < TN; ++tn) bfr[tn] = load_b_frag(as, ks, tn);
-#pragma unroll
-            for (int tm = 0; tm < TM; ++tm)
-#pragma unroll
-                for (int tn = 0; tn < TN; ++tn)
-                    acc[tm][tn] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[tm], bfr[tn],
-                                                                          acc[tm][tn], 0, 0, 0);
-        }
-    };
-
-    // ---- main loop over full K tiles ----
-    // Two LDS stages and two register sets of operand fragments.  While the MFMAs of k-step
-    // ks run, the fragments of step ks+1 are fetched from LDS, one read after each MFMA, so
-    // the matrix pipe never waits for LDS.  The workgroup barrier sits in front of the LAST
-    // k-step of a tile: at that point every wavefront holds the tile's last fragments in
-    // registers, so the stage can be refilled (tile kt+2) and the first fragments of tile
-    // kt+1 can be fetched while the last MFMAs of tile kt still run.
     constexpr int KS = BK / 16;
-    static_assert(STAGES == 2 && KS % 2 == 0, "pipelined main loop");
-    bf16x8 fa[2][TM], fb[2][TN];
-    auto issue_one = [&](unsigned char *stage, int i) {  // i-th direct load of this wavefront
-        if (i < Cfg::A_LPW)
-            load_to_lds16(a_base, a_off_g[i], stage + (wave * Cfg::A_LPW + i) * 1024);
-        else
-            load_to_lds16(b_base, b_off_g[i - Cfg::A_LPW],
-                          stage + Cfg::A_BYTES + (wave * Cfg::B_LPW + i - Cfg::A_LPW) * 1024);
-    };
-    auto issue_tile = [&](unsigned char *stage) {  // all direct loads of the next K tile
-#pragma unroll
-        for (int i = 0; i < Cfg::LPW; ++i) issue_one(stage, i);
-        a_base += BK * 2;
-        b_base += b_step;
-    };
-    auto fetch_one = [&](const unsigned char *as, int ks, int set, int i) {  // i-th fragment
-        if (i < TM)
-            fa[set][i] = load_a_frag(as, ks, i);
-        else if (i < TM + TN)
-            fb[set][i - TM] = load_b_frag(as, ks, i - TM);
-    };
-    if (nkf > 0) {
-        issue_tile(smem);
-        if (nkf > 1) {
-            issue_tile(smem + Cfg::STAGE);
+
+    if constexpr (Cfg::PIPE) {
+        // ---- main loop, MFMA-bound shapes ----
+        // Two LDS stages and two register sets of operand fragments.  While the MFMAs of
+        // k-step ks run, the fragments of step ks+1 are fetched from LDS, one read after each
+        // MFMA, so the matrix pipe never waits for LDS.  The workgroup barrier sits in front
+        // of the LAST k-step of a tile: at that point every wavefront holds the tile's last
+        // fragments in registers, so the stage can be refilled (tile kt+2) and the first
+        // fragments of tile kt+1 can be fetched while the last MFMAs of tile kt still run.
+        static_assert(KS % 2 == 0, "two fragment register sets");
+        bf16x8 fa[2][TM], fb[2][TN];
+        auto fetch_one = [&](const unsigned char *as, int ks, int set, int i) {  // i-th fragment
+            if (i < TM)
+                fa[set][i] = load_a_frag(as, ks, i);
+            else if (i < TM + TN)
+                fb[set][i - TM] = load_b_frag(as, ks, i - TM);
+        };
+        issue_tile(smem, 0);
+        if (nk > 1) {
+            issue_tile(smem + Cfg::STAGE, 1);
             wait_vmcnt<Cfg::LPW>();
         } else {
             wait_vmcnt<0>();
@@ -262,119 +326,97 @@ __global__ __launch_bounds__(Cfg::NT) void fused_gemm_kernel(
         wg_barrier();
 #pragma unroll
         for (int i = 0; i < TM + TN; ++i) fetch_one(smem, 0, 0, i);
-    }
-    // one K tile: KS-1 ordinary k-steps, then the last one, specialised on what follows
-    // (`more`: another tile follows; `refill`: and one after that, to be loaded now)
-    auto k_tile = [&](int kt, auto more_c, auto refill_c) {
-        constexpr bool more = decltype(more_c)::value, refill = decltype(refill_c)::value;
-        unsigned char *as = smem + (kt & 1) * Cfg::STAGE;
-        unsigned char *as_next = smem + ((kt + 1) & 1) * Cfg::STAGE;
+
+        // one K tile: KS-1 ordinary k-steps, then the last one.  MORE: another tile follows.
+        // REFILL: 0 = nothing to load, 1 = tile kt+2 is a full tile and its loads are
+        // interleaved with the MFMAs, 2 = tile kt+2 is of any kind, loaded in one go.
+        auto k_tile = [&](int kt, auto more_c, auto refill_c) {
+            constexpr bool MORE = decltype(more_c)::value;
+            constexpr int REFILL = decltype(refill_c)::value;
+            unsigned char *as = smem + (kt & 1) * Cfg::STAGE;
+            unsigned char *as_next = smem + ((kt + 1) & 1) * Cfg::STAGE;
 #pragma unroll
-        for (int ks = 0; ks < KS - 1; ++ks) {
-            const int cur = ks & 1, nxt = cur ^ 1;
+            for (int ks = 0; ks < KS - 1; ++ks) {
+                const int cur = ks & 1, nxt = cur ^ 1;
+#pragma unroll
+                for (int i = 0; i < TM * TN; ++i) {
+                    acc[i / TN][i % TN] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
+                        fa[cur][i / TN], fb[cur][i % TN], acc[i / TN][i % TN], 0, 0, 0);
+                    fetch_one(as, ks + 1, nxt, i);
+                    __builtin_amdgcn_sched_barrier(0);
+                }
+#pragma unroll
+                for (int i = TM * TN; i < TM + TN; ++i) fetch_one(as, ks + 1, nxt, i);
+            }
+            constexpr int cur = (KS - 1) & 1, nxt = cur ^ 1;
+            if constexpr (MORE) {
+                wait_lds();       // this wavefront's reads of stage kt are complete
+                wait_vmcnt<0>();  // its part of tile kt+1 has landed
+                wg_barrier();     // ... and so has everyone else's; stage kt is free
+            }
+            if constexpr (REFILL == 2) issue_tile(as, kt + 2);
 #pragma unroll
             for (int i = 0; i < TM * TN; ++i) {
                 acc[i / TN][i % TN] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
                     fa[cur][i / TN], fb[cur][i % TN], acc[i / TN][i % TN], 0, 0, 0);
-                fetch_one(as, ks + 1, nxt, i);
+                if constexpr (MORE) fetch_one(as_next, 0, nxt, i);
+                if constexpr (REFILL == 1)
+                    if (i < Cfg::LPW) issue_one(as, i);
                 __builtin_amdgcn_sched_barrier(0);
             }
+            if constexpr (MORE) {
 #pragma unroll
-            for (int i = TM * TN; i < TM + TN; ++i) fetch_one(as, ks + 1, nxt, i);
-        }
-        constexpr int cur = (KS - 1) & 1, nxt = cur ^ 1;
-        if constexpr (more) {
-            wait_lds();       // this wavefront's reads of stage kt are complete
-            wait_vmcnt<0>();  // its part of tile kt+1 has landed
-            wg_barrier();     // ... and so has everyone else's; stage kt is free
-        }
-#pragma unroll
-        for (int i = 0; i < TM * TN; ++i) {
-            acc[i / TN][i % TN] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
-                fa[cur][i / TN], fb[cur][i % TN], acc[i / TN][i % TN], 0, 0, 0);
-            if constexpr (more) fetch_one(as_next, 0, nxt, i);
-            if constexpr (refill)
-                if (i < Cfg::LPW) issue_one(as, i);
-            __builtin_amdgcn_sched_barrier(0);
-        }
-        if constexpr (more) {
-#pragma unroll
-            for (int i = TM * TN; i < TM + TN; ++i) fetch_one(as_next, 0, nxt, i);
-        }
-        if constexpr (refill) {
-#pragma unroll
-            for (int i = TM * TN; i < Cfg::LPW; ++i) issue_one(as, i);
-            a_base += BK * 2;
-            b_base += b_step;
-        }
-    };
-    for (int kt = 0; kt + 2 < nkf; ++kt) k_tile(kt, std::true_type{}, std::true_type{});
-    if (nkf >= 2) k_tile(nkf - 2, std::true_type{}, std::false_type{});
-    if (nkf >= 1) k_tile(nkf - 1, std::false_type{}, std::false_type{});
-
-    // ---- K tail and expand tiles: through registers, zero-filled where not valid ----
-    const int n_extra = (ktail ? 1 : 0) + nseg * tps;
-    const u32x4 zero4 = {0u, 0u, 0u, 0u};
-    for (int e = 0; e < n_extra; ++e) {
-        u32x4 a_reg[Cfg::A_CH], b_reg[Cfg::B_CH];
-        const bool is_tail = ktail && e == 0;
-        const int ee = e - (ktail ? 1 : 0);
-        const int sg = is_tail ? 0 : ee / tps, sub = is_tail ? 0 : ee % tps;
-        const int c = (is_tail || nseg == 0) ? 0 : seg_c[sg];
-        const int lo = is_tail ? 0 : seg_lo[sg], hi = is_tail ? 0 : seg_hi[sg];
-        const uint16_t *Bc = B + (int64_t)c * rank * d_out;
-#pragma unroll
-        for (int i = 0; i < Cfg::A_CH; ++i) {
-            const int id = tid + i * NT, row = id / Cfg::A_CPR, u = id % Cfg::A_CPR;
-            const int tok = tile_perm[row];
-            const int p = p0 + row;
-            bool ok;
-            const uint16_t *src;
-            if (is_tail) {
-                const int k = nkf * BK + u * 8;
-                ok = k < d_in;
-                src = x + (int64_t)(tok >= 0 ? tok : 0) * d_in + (ok ? k : 0);
-            } else {
-                const int vk = sub * BK + u * 8;
-                ok = p >= lo && p < hi && vk < two_r;
-                src = t2 + (int64_t)(ok ? p : lo) * two_r + (ok ? vk : 0);
+                for (int i = TM * TN; i < TM + TN; ++i) fetch_one(as_next, 0, nxt, i);
             }
-            const u32x4 v = *(const u32x4 *)src;
-            a_reg[i] = ok ? v : zero4;
-        }
+            if constexpr (REFILL == 1) {
 #pragma unroll
-        for (int i = 0; i < Cfg::B_CH; ++i) {
-            const int id = tid + i * NT, kr = id / Cfg::B_CPR, u = id % Cfg::B_CPR;
-            const int n = min(n0 + u * 8, d_out - 8);
-            bool ok;
-            const uint16_t *src;
-            if (is_tail) {
-                const int k = nkf * BK + kr;
-                ok = k < d_in;
-                src = W + (int64_t)(ok ? k : 0) * d_out + n;
-            } else {
-                const int vk = sub * BK + kr;
-                ok = vk < two_r;
-                const int j = vk < rank ? vk : vk - rank;  // [B_c; B_c]
-                src = Bc + (int64_t)(ok ? j : 0) * d_out + n;
+                for (int i = TM * TN; i < Cfg::LPW; ++i) issue_one(as, i);
+                advance_full();
             }
-            const u32x4 v = *(const u32x4 *)src;
-            b_reg[i] = ok ? v : zero4;
+        };
+        using I0 = std::integral_constant<int, 0>;
+        using I1 = std::integral_constant<int, 1>;
+        using I2 = std::integral_constant<int, 2>;
+        int kt = 0;
+        for (; kt + 2 < nkf; ++kt) k_tile(kt, std::true_type{}, I1{});  // the hot loop
+        for (; kt + 2 < nk; ++kt) k_tile(kt, std::true_type{}, I2{});   // last base + expand tiles
+        if (kt + 1 < nk) {
+            k_tile(kt, std::true_type{}, I0{});
+            ++kt;
         }
-        __syncthreads();  // the previous tile has been consumed
+        k_tile(kt, std::false_type{}, I0{});
+    } else {
+        // ---- main loop, streaming shapes: ring of STAGES stages, STAGES-1 tiles in flight ----
 #pragma unroll
-        for (int i = 0; i < Cfg::A_CH; ++i) {
-            const int id = tid + i * NT, row = id / Cfg::A_CPR, u = id % Cfg::A_CPR;
-            *(u32x4 *)(smem + row * Cfg::A_RB + ((u ^ Cfg::swz_a(row)) << 4)) = a_reg[i];
-        }
+        for (int s = 0; s < STAGES - 1; ++s)
+            if (s < nk) issue_tile(smem + s * Cfg::STAGE, s);
+        for (int kt = 0; kt < nk; ++kt) {
+            // tile kt has landed once at most the younger tiles' loads are outstanding
+            if (kt + STAGES - 2 < nk)
+                wait_vmcnt<Cfg::LPW *(STAGES - 2)>();
+            else
+                wait_vmcnt<0>();
+            wg_barrier();  // everyone's part of tile kt is in LDS; everyone is done with tile kt-1
+            if (kt + STAGES - 1 < nk)
+                issue_tile(smem + ((kt + STAGES - 1) % STAGES) * Cfg::STAGE, kt + STAGES - 1);
+            const unsigned char *as = smem + (kt % STAGES) * Cfg::STAGE;
 #pragma unroll
-        for (int i = 0; i < Cfg::B_CH; ++i) {
-            const int id = tid + i * NT, kr = id / Cfg::B_CPR, u = id % Cfg::B_CPR;
-            *(u32x4 *)(smem + Cfg::A_BYTES + kr * Cfg::B_RB + (((u >> 1) ^ (kr & 3)) << 5) +
-                       ((u & 1) << 4)) = b_reg[i];
+            for (int kk = 0; kk < KS / Cfg::WK; ++kk) {
+                const int ks = kk * Cfg::WK + wk;
+                bf16x8 af[TM], bfr[TN];
+#pragma unroll
+                for (int tm = 0; tm < TM; ++tm) af[tm] = load_a_frag(as, ks, tm);
+#pragma unroll
+                for (int tn = 0; tn < TN; ++tn) bfr[tn] = load_b_frag(as, ks, tn);
+#pragma unroll
+                for (int tm = 0; tm < TM; ++tm)
+#pragma unroll
+                    for (int tn = 0; tn < TN; ++tn)
+                        acc[tm][tn] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[tm], bfr[tn],
+                                                                              acc[tm][tn], 0, 0, 0);
+            }
+            wait_lds();  // the reads of this stage are complete before the next barrier
         }
-        __syncthreads();
-        compute_tile(smem);
     }
 
     // ---- epilogue: every row to its original position ----
@@ -384,29 +426,57 @@ __global__ __launch_bounds__(Cfg::NT) void fused_gemm_kernel(
     // instruction: the rows are scattered over all of h by the permutation, and narrow
     // stores to scattered rows are what the memory system handles worst.
     constexpr int EP_STRIDE = BN * 4 + 32;           // bytes per staged row (+32: bank shift)
-    constexpr int EP_ROWS = Cfg::WM * 32;
     constexpr int EP_CPR = BN / 4;                   // 16-byte chunks per row
-    static_assert(EP_ROWS * EP_STRIDE <= STAGES * Cfg::STAGE, "epilogue staging fits the stages");
-#pragma unroll
-    for (int tm = 0; tm < TM; ++tm) {
-        __syncthreads();  // operand stages (or the previous band) are no longer read
-#pragma unroll
-        for (int v = 0; v < 16; ++v) {
-            const int rr = wm * 32 + (v >> 2) * 8 + (lane >> 5) * 4 + (v & 3);
-#pragma unroll
-            for (int tn = 0; tn < TN; ++tn) {
-                const int col = wn * (BN / Cfg::WN) + tn * 32 + (lane & 31);
-                *(float *)(smem + rr * EP_STRIDE + col * 4) = acc[tm][tn][v];
-            }
-        }
+    if constexpr (Cfg::WK > 1) {
+        // k-split wavefronts: all partial tiles go to LDS at once and are added in a fixed order
+        static_assert(Cfg::WK * BM * EP_STRIDE <= STAGES * Cfg::STAGE, "partial tiles fit the stages");
         __syncthreads();
-        for (int it = tid; it < EP_ROWS * EP_CPR; it += NT) {
-            const int r = it / EP_CPR, ch = it % EP_CPR;
-            const int row = (r >> 5) * (BM / Cfg::WM) + tm * 32 + (r & 31);
+#pragma unroll
+        for (int tm = 0; tm < TM; ++tm)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                const int rr = wm * (BM / Cfg::WM) + tm * 32 + (v >> 2) * 8 + (lane >> 5) * 4 + (v & 3);
+#pragma unroll
+                for (int tn = 0; tn < TN; ++tn) {
+                    const int col = wn * (BN / Cfg::WN) + tn * 32 + (lane & 31);
+                    *(float *)(smem + (wk * BM + rr) * EP_STRIDE + col * 4) = acc[tm][tn][v];
+                }
+            }
+        __syncthreads();
+        for (int it = tid; it < BM * EP_CPR; it += NT) {
+            const int row = it / EP_CPR, ch = it % EP_CPR;
             const int tok = tile_perm[row];
             const int col = n0 + ch * 4;
-            if (tok >= 0 && col < d_out)
-                *(f32x4 *)(h + (int64_t)tok * d_out + col) = *(const f32x4 *)(smem + r * EP_STRIDE + ch * 16);
+            if (tok < 0 || col >= d_out) continue;
+            f32x4 sum = *(const f32x4 *)(smem + row * EP_STRIDE + ch * 16);
+#pragma unroll
+            for (int w = 1; w < Cfg::WK; ++w) sum += *(const f32x4 *)(smem + (w * BM + row) * EP_STRIDE + ch * 16);
+            *(f32x4 *)(h + (int64_t)tok * d_out + col) = sum;
+        }
+    } else {
+        constexpr int EP_ROWS = Cfg::WM * 32;
+        static_assert(EP_ROWS * EP_STRIDE <= STAGES * Cfg::STAGE, "epilogue staging fits the stages");
+#pragma unroll
+        for (int tm = 0; tm < TM; ++tm) {
+            __syncthreads();  // operand stages (or the previous band) are no longer read
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                const int rr = wm * 32 + (v >> 2) * 8 + (lane >> 5) * 4 + (v & 3);
+#pragma unroll
+                for (int tn = 0; tn < TN; ++tn) {
+                    const int col = wn * (BN / Cfg::WN) + tn * 32 + (lane & 31);
+                    *(float *)(smem + rr * EP_STRIDE + col * 4) = acc[tm][tn][v];
+                }
+            }
+            __syncthreads();
+            for (int it = tid; it < EP_ROWS * EP_CPR; it += NT) {
+                const int r = it / EP_CPR, ch = it % EP_CPR;
+                const int row = (r >> 5) * (BM / Cfg::WM) + tm * 32 + (r & 31);
+                const int tok = tile_perm[row];
+                const int col = n0 + ch * 4;
+                if (tok >= 0 && col < d_out)
+                    *(f32x4 *)(h + (int64_t)tok * d_out + col) = *(const f32x4 *)(smem + r * EP_STRIDE + ch * 16);
+            }
         }
     }
 }
@@ -432,10 +502,13 @@ hipError_t launch_cfg(const uint16_t *x, const uint16_t *W, const uint16_t *B, c
 }  // namespace
 
 #ifndef MOLORA_GEMM_BIG
-#define MOLORA_GEMM_BIG 256, 256, 2, 4, 64, 2
+#define MOLORA_GEMM_BIG 256, 256, 2, 4, 1, 64, 2
 #endif
 #ifndef MOLORA_GEMM_SMALL
-#define MOLORA_GEMM_SMALL 128, 128, 2, 2, 64, 2
+#define MOLORA_GEMM_SMALL 128, 128, 2, 2, 1, 64, 2
+#endif
+#ifndef MOLORA_GEMM_STREAM
+#define MOLORA_GEMM_STREAM 64, 64, 2, 2, 4, 64, 8
 #endif
 
 hipError_t launch_fused_gemm(const uint16_t *x, const uint16_t *W, const uint16_t *B,
@@ -443,8 +516,11 @@ hipError_t launch_fused_gemm(const uint16_t *x, const uint16_t *W, const uint16_
                              float *h, int64_t N, int d_in, int d_out, int C, int rank,
                              hipStream_t s) {
     if (N == 0) return hipSuccess;
-    // Tile choice from static shapes only (no host read of the histogram): the largest tile
-    // that still yields at least ~2 workgroups per compute unit.
+    // Tile choice from static shapes only (no host read of the histogram).  Up to 64 tokens
+    // the step is bound by streaming W once: one row tile, narrow column tiles, deep ring.
+    // Otherwise the largest tile that still yields about two workgroups per compute unit.
+    if (N <= 64)
+        return launch_cfg<GemmCfg<MOLORA_GEMM_STREAM>>(x, W, B, t2, offsets, perm, h, N, d_in, d_out, C, rank, s);
     const int64_t t256 = ((N + 255) / 256) * ((d_out + 255) / 256);
     if (t256 >= 512)
         return launch_cfg<GemmCfg<MOLORA_GEMM_BIG>>(x, W, B, t2, offsets, perm, h, N, d_in, d_out, C, rank, s);

@@ -3,12 +3,17 @@
 // GEMM over buckets).
 //
 // The step is HBM bound (2*rank flops per 2 bytes of x), so the kernel is organised around
-// streaming x: a work item is 64 consecutive sorted rows of one bucket; each of the 4
-// wavefronts owns 16 rows and pulls them from HBM directly in the bf16 MFMA operand layout
-// (4 lanes x 16 B = 64 contiguous bytes per row and instruction, prefetched one k-slab
-// ahead).  The bucket's A_c is staged k-slab by k-slab in LDS, shared by the 4 wavefronts,
-// and read back with the LDS transpose read so that the row-major [k][rank] slab becomes the
-// "8 consecutive k per lane" operand.  Accumulation is fp32 (v_mfma_f32_16x16x32_bf16).
+// keeping many bytes of x in flight.  A work item is 32 consecutive sorted rows of one
+// bucket.  Its 4 wavefronts split the K range four ways (a workgroup per 32 rows gives N/32
+// workgroups, enough to cover the chip even at 4096 tokens) and each wavefront streams on
+// its own, with no workgroup barrier inside the loop:
+//   x    straight from HBM into the bf16 MFMA operand layout (row lane%16, 8 consecutive k
+//        per lane: 4 lanes = 64 contiguous bytes per row and instruction), two 16-row blocks;
+//   A_c  its k-slice, 32 k at a time, into a wavefront-private LDS buffer and back through
+//        the LDS transpose read, which turns the row-major [k][rank] slab into the
+//        "8 consecutive k per lane" operand;
+//   a ring of kDepth such steps is in flight per wavefront (v_mfma_f32_16x16x32_bf16, fp32
+//   accumulate).  The four partial sums are added in a fixed order through LDS.
 //
 // The result is written as two bf16 halves, t = hi + lo with hi = bf16(t) and
 // lo = bf16(t - hi), laid out [N][2*rank] = [hi | lo], so the expand step can feed it to a
@@ -20,25 +25,27 @@ namespace molora {
 namespace {
 
 constexpr int kShrinkThreads = 256;
-constexpr int kShrinkRows = 64;   // sorted rows per work item (16 per wavefront)
-constexpr int kSlabK = 128;       // k per A slab
+constexpr int kShrinkRows = 32;  // sorted rows per work item
+constexpr int kStepK = 32;       // k per MFMA step
+constexpr int kDepth = 4;        // steps in flight per wavefront
 
 template <int NJ>  // NJ = number of 16-column blocks covering rank
 __global__ __launch_bounds__(kShrinkThreads) void shrink_kernel(
     const uint16_t *__restrict__ x, const uint16_t *__restrict__ A,
     const int32_t *__restrict__ offsets, const int32_t *__restrict__ perm,
     uint16_t *__restrict__ t2, int d_in, int C, int rank) {
-    constexpr int RP = NJ * 16;                 // padded rank (LDS row length)
-    constexpr int ROWB = RP * 2;                // bytes per LDS row
-    constexpr int SLABB = kSlabK * ROWB;        // bytes per slab
-    constexpr int CHUNKS = kSlabK * (RP / 8);   // 16-byte chunks per slab
-    constexpr int CPT = (CHUNKS + kShrinkThreads - 1) / kShrinkThreads;
-    __shared__ __attribute__((aligned(16))) unsigned char slab_mem[2 * SLABB];
+    constexpr int RP = NJ * 16;                          // padded rank
+    constexpr int ROWB = RP * 2 + (RP >= 64 ? 32 : 0);   // LDS bytes per slab row (bank shift)
+    constexpr int SLABB = kStepK * ROWB;                 // one step's slab of one wavefront
+    constexpr int RED_FLOATS = 4 * kShrinkRows * RP;     // partial sums of the 4 wavefronts
+    constexpr int LDS_BYTES = (4 * 2 * SLABB > RED_FLOATS * 4) ? 4 * 2 * SLABB : RED_FLOATS * 4;
+    __shared__ __attribute__((aligned(16))) unsigned char lds[LDS_BYTES];
     __shared__ int32_t item[3];  // bucket, first sorted row, end row
 
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
 
-    // ---- which (bucket, 64-row chunk) is this workgroup? ----
+    // ---- which (bucket, 32-row chunk) is this workgroup? ----
     if (wave == 0) {
         int found_c = -1, found_lo = 0, found_hi = 0;
         int running = 0;  // work items of the buckets before the current group of 64
@@ -80,95 +87,115 @@ __global__ __launch_bounds__(kShrinkThreads) void shrink_kernel(
     const int p_first = item[1];
     const int p_end = min(item[2], p_first + kShrinkRows);
 
-    // ---- this lane's x row (A operand of the 16x16x32 MFMA: row lane%16, k-group lane/16) ----
-    const int p_lane = p_first + wave * 16 + (lane & 15);
-    const bool row_ok = p_lane < p_end;
-    const uint16_t *xrow = x + (int64_t)(row_ok ? perm[p_lane] : 0) * d_in + (lane >> 4) * 8;
-    const uint16_t *Ac = A + (int64_t)c * d_in * rank;
+    // ---- this wavefront's k range (a multiple of 32 long) and operand addresses ----
+    const int kq_len = ((d_in + 4 * kStepK - 1) / (4 * kStepK)) * kStepK;
+    const int k_begin = wave * kq_len;
+    const int k_end = min(d_in, k_begin + kq_len);
+    const int nsteps = k_begin < k_end ? (k_end - k_begin + kStepK - 1) / kStepK : 0;
 
-    constexpr int XL = kSlabK / 32;  // x loads (k-steps) per slab
-    u32x4 xcur[XL], xnext[XL];
-    auto x_load = [&](u32x4(&dst)[XL], int k0) {
+    const int l16 = lane & 15, kg = lane >> 4;
+    // x rows of this lane in the two 16-row blocks; a row past the chunk's end re-reads the
+    // first row (its result is never stored), k past d_in is clamped and meets a zeroed A.
+    const uint16_t *xrow[2];
 #pragma unroll
-        for (int j = 0; j < XL; ++j) {
-            const int k = k0 + j * 32 + (lane >> 4) * 8;
-            dst[j] = (row_ok && k < d_in) ? *(const u32x4 *)(xrow + k0 + j * 32)
-                                          : u32x4{0u, 0u, 0u, 0u};
-        }
-    };
-    u32x4 areg[CPT];
-    auto a_load = [&](int k0) {
+    for (int rb = 0; rb < 2; ++rb) {
+        const int p = p_first + rb * 16 + l16;
+        xrow[rb] = x + (int64_t)perm[p < p_end ? p : p_first] * d_in;
+    }
+    const uint16_t *Ac = A + (int64_t)c * d_in * rank;
+    // A slab staging: lane loads NJ pieces of 16 bytes of the step's [32][rank] slab
+    // piece id = lane + 64*m -> slab row id / (RP/8), 8-column group id % (RP/8)
+    unsigned char *slab0 = lds + wave * 2 * SLABB;
+
+    u32x4 xg[kDepth][2], ag[kDepth][NJ];
+    auto load_step = [&](int slot, int s) {  // step s of this wavefront into ring slot
+        const int k0 = k_begin + s * kStepK;
+        const int kx = min(k0 + kg * 8, d_in - 8);
 #pragma unroll
-        for (int m = 0; m < CPT; ++m) {
-            const int id = tid + m * kShrinkThreads;
+        for (int rb = 0; rb < 2; ++rb) xg[slot][rb] = *(const u32x4 *)(xrow[rb] + kx);
+#pragma unroll
+        for (int m = 0; m < NJ; ++m) {
+            const int id = lane + 64 * m;
             const int kr = id / (RP / 8), u = id % (RP / 8);
             const int k = k0 + kr;
-            areg[m] = (id < CHUNKS && k < d_in && u * 8 < rank)
-                          ? *(const u32x4 *)(Ac + (int64_t)k * rank + u * 8)
-                          : u32x4{0u, 0u, 0u, 0u};
-        }
-    };
-    auto a_store = [&](unsigned char *slab) {
-#pragma unroll
-        for (int m = 0; m < CPT; ++m) {
-            const int id = tid + m * kShrinkThreads;
-            if (id < CHUNKS) *(u32x4 *)(slab + id * 16) = areg[m];
+            const int uc = min(u * 8, rank - 8);
+            u32x4 v = *(const u32x4 *)(Ac + (int64_t)min(k, d_in - 1) * rank + uc);
+            asm volatile("" : "+v"(v));  // keep the load unconditional
+            const uint32_t ok = (k < k_end && u * 8 < rank) ? 0xFFFFFFFFu : 0u;
+            ag[slot][m] = u32x4{v[0] & ok, v[1] & ok, v[2] & ok, v[3] & ok};
         }
     };
 
-    f32x4 acc[NJ];
+    f32x4 acc[2][NJ];
 #pragma unroll
-    for (int j = 0; j < NJ; ++j) acc[j] = f32x4{0.f, 0.f, 0.f, 0.f};
+    for (int rb = 0; rb < 2; ++rb)
+#pragma unroll
+        for (int j = 0; j < NJ; ++j) acc[rb][j] = f32x4{0.f, 0.f, 0.f, 0.f};
 
-    a_load(0);
-    x_load(xcur, 0);
-    a_store(slab_mem);
-    __syncthreads();
+#pragma unroll
+    for (int d = 0; d < kDepth; ++d) load_step(d, d);  // loads past the range are harmless
 
-    const int nslab = (d_in + kSlabK - 1) / kSlabK;
-    const int a16 = lane & 15, kg = lane >> 4;
-    for (int sl = 0; sl < nslab; ++sl) {
-        const unsigned char *slab = slab_mem + (sl & 1) * SLABB;
-        if (sl + 1 < nslab) a_load((sl + 1) * kSlabK);
-        x_load(xnext, (sl + 1) * kSlabK);  // guarded by k < d_in
+    for (int s0 = 0; s0 < nsteps; s0 += kDepth) {
 #pragma unroll
-        for (int ks = 0; ks < XL; ++ks) {
-            const bf16x8 afrag = __builtin_bit_cast(bf16x8, xcur[ks]);
+        for (int d = 0; d < kDepth; ++d) {
+            const int s = s0 + d;  // steps past nsteps meet an all-zero slab: harmless
+            {
+                unsigned char *slab = slab0 + (d & 1) * SLABB;
 #pragma unroll
-            for (int jb = 0; jb < NJ; ++jb) {
-                // rows ks*32 + kg*8 + {0..3 | 4..7}, columns jb*16 .. +15 of the slab
-                const int krow = ks * 32 + kg * 8 + (a16 >> 2);
-                const unsigned char *p0 = slab + krow * ROWB + jb * 32 + (a16 & 3) * 8;
-                const i16x4 b_lo = lds_read_tr16((const MOLORA_LDS void *)p0);
-                const i16x4 b_hi = lds_read_tr16((const MOLORA_LDS void *)(p0 + 4 * ROWB));
-                const i16x8 b8 = {b_lo[0], b_lo[1], b_lo[2], b_lo[3], b_hi[0], b_hi[1], b_hi[2], b_hi[3]};
-                acc[jb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(
-                    afrag, __builtin_bit_cast(bf16x8, b8), acc[jb], 0, 0, 0);
+                for (int m = 0; m < NJ; ++m) {
+                    const int id = lane + 64 * m;
+                    const int kr = id / (RP / 8), u = id % (RP / 8);
+                    *(u32x4 *)(slab + kr * ROWB + u * 16) = ag[d][m];
+                }
+                const bf16x8 a0 = __builtin_bit_cast(bf16x8, xg[d][0]);
+                const bf16x8 a1 = __builtin_bit_cast(bf16x8, xg[d][1]);
+#pragma unroll
+                for (int jb = 0; jb < NJ; ++jb) {
+                    // rows kg*8 + {0..3 | 4..7}, columns jb*16 .. +15 of the slab
+                    const unsigned char *p0 = slab + (kg * 8 + (l16 >> 2)) * ROWB + jb * 32 + (l16 & 3) * 8;
+                    const i16x4 b_lo = lds_read_tr16((const MOLORA_LDS void *)p0);
+                    const i16x4 b_hi = lds_read_tr16((const MOLORA_LDS void *)(p0 + 4 * ROWB));
+                    const i16x8 b8 = {b_lo[0], b_lo[1], b_lo[2], b_lo[3],
+                                      b_hi[0], b_hi[1], b_hi[2], b_hi[3]};
+                    const bf16x8 bfrag = __builtin_bit_cast(bf16x8, b8);
+                    acc[0][jb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a0, bfrag, acc[0][jb], 0, 0, 0);
+                    acc[1][jb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a1, bfrag, acc[1][jb], 0, 0, 0);
+                }
+                load_step(d, s + kDepth);  // refill the ring slot
             }
         }
-#pragma unroll
-        for (int j = 0; j < XL; ++j) xcur[j] = xnext[j];
-        if (sl + 1 < nslab) a_store(slab_mem + ((sl + 1) & 1) * SLABB);
-        __syncthreads();
     }
 
-    // ---- epilogue: split t into bf16 hi + lo and store [hi | lo] ----
-    // acc[jb][v] = t[row (lane/16)*4 + v][column jb*16 + lane%16] of this wavefront's 16 rows
+    // ---- add the four partial sums in a fixed order, split into bf16 hi + lo, store ----
+    // acc[rb][jb][v] = t[row rb*16 + kg*4 + v][column jb*16 + l16]
+    __syncthreads();  // all wavefronts are done with their slabs
+    float *red = (float *)lds;  // [4][32][RP]
 #pragma unroll
-    for (int jb = 0; jb < NJ; ++jb) {
-        const int col = jb * 16 + (lane & 15);
+    for (int rb = 0; rb < 2; ++rb)
 #pragma unroll
-        for (int v = 0; v < 4; ++v) {
-            const int p = p_first + wave * 16 + (lane >> 4) * 4 + v;
-            if (p < p_end && col < rank) {
-                const float t = acc[jb][v];
-                const uint32_t hi = f32_to_bf16_bits(t);
-                const uint32_t lo = f32_to_bf16_bits(t - bf16_bits_to_f32(hi));
-                uint16_t *dst = t2 + (int64_t)p * 2 * rank;
-                dst[col] = (uint16_t)hi;
-                dst[rank + col] = (uint16_t)lo;
-            }
+        for (int jb = 0; jb < NJ; ++jb)
+#pragma unroll
+            for (int v = 0; v < 4; ++v)
+                red[(wave * kShrinkRows + rb * 16 + kg * 4 + v) * RP + jb * 16 + l16] = acc[rb][jb][v];
+    __syncthreads();
+    for (int e = tid; e < kShrinkRows * RP / 2; e += kShrinkThreads) {
+        const int row = e / (RP / 2), col = (e % (RP / 2)) * 2;
+        const int p = p_first + row;
+        if (p >= p_end || col >= rank) continue;
+        uint32_t hi2 = 0, lo2 = 0;
+#pragma unroll
+        for (int i = 0; i < 2; ++i) {
+            float t = 0.f;
+#pragma unroll
+            for (int w = 0; w < 4; ++w) t += red[(w * kShrinkRows + row) * RP + col + i];
+            const uint32_t hi = f32_to_bf16_bits(t);
+            const uint32_t lo = f32_to_bf16_bits(t - bf16_bits_to_f32(hi));
+            hi2 |= hi << (16 * i);
+            lo2 |= lo << (16 * i);
         }
+        uint16_t *dst = t2 + (int64_t)p * 2 * rank;
+        *(uint32_t *)(dst + col) = hi2;
+        *(uint32_t *)(dst + rank + col) = lo2;
     }
 }
 
