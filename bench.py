@@ -212,8 +212,16 @@ def main():
         ach = work["gemm_bytes"] / t_gemm / 1e9
         roof = {"bound": "hbm", "achieved": ach, "peak": PEAK_HBM_GBS, "unit": "GB/s",
                 "frac": ach / PEAK_HBM_GBS}
+    traffic = None
+    try:  # measured with rocprofv3 --pmc in a separate run (see profiles/)
+        with open(os.path.join(ROOT, "profiles", "traffic.json")) as f:
+            tj = json.load(f).get(shape.name)
+        if tj:
+            traffic = tj["read_bytes"] + tj["write_bytes"]
+    except (OSError, ValueError, KeyError):
+        traffic = None
     roof.update({"kernel": "fused_gemm_kernel (base x.W + grouped expand, unpermuting fp32 store)",
-                 "kernel_us": t_gemm * 1e6, "traffic": None,
+                 "kernel_us": t_gemm * 1e6, "traffic": traffic,
                  "algorithmic_flops": work["gemm_flops"], "algorithmic_bytes": work["gemm_bytes"]})
 
     out = {

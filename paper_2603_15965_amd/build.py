@@ -13,6 +13,7 @@ SOURCES = ["api.hip", "bucket.hip", "route.hip", "shrink.hip", "gemm.hip"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 # -packed-fp32-ops is switched off on purpose: the compiler must not form v_pk_*_f32.
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-unused-function",
+         "-Wno-inline-asm",  # M0 is named as clobbered by the LDS-direct load on purpose
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
 
 

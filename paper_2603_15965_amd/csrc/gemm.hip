@@ -96,7 +96,6 @@ struct GemmCfg {
     static constexpr bool PIPE = (STAGES == 2);  // fragment-pipelined main loop, else deep ring
     static_assert(BK == 32 || BK == 64, "BK");
     static_assert(LPW * NW == A_PIECES + B_PIECES && LPW >= 1, "pieces split evenly over wavefronts");
-    static_assert(A_PIECES % LPW == 0, "a wavefront loads only x pieces or only W pieces");
     static_assert(STAGES >= 2, "stages");
     static_assert(!PIPE || WK == 1, "the pipelined loop keeps all k-steps in one wavefront");
     static_assert((BK / 16) % WK == 0, "k-steps split evenly");
@@ -164,21 +163,25 @@ __global__ __launch_bounds__(Cfg::NT) void fused_gemm_kernel(
     const int nk = nkb + nseg * tps;        // all K tiles of this output tile
 
     // ---- per-lane sources of this wavefront's load instructions ----
-    // A stage is A_PIECES + B_PIECES pieces of 1 KB; wavefront w loads pieces w*LPW .. +LPW-1,
-    // which are either all x pieces (A_RPI rows each) or all W pieces (B_RPI k-rows each).
+    // A stage is A_PIECES + B_PIECES pieces of 1 KB, x pieces (A_RPI rows each) first, then W
+    // pieces (B_RPI k-rows each); load i of wavefront w is piece i*NW + w, so every wavefront
+    // carries its share of the gathered x rows and of the W rows.
     // Rows past N and columns past d_out are clamped to valid memory: what they produce is
     // never stored.
-    const int piece0 = wave * Cfg::LPW;
-    const bool is_a = piece0 < Cfg::A_PIECES;  // wave-uniform
+    auto piece_of = [&](int i) { return i * Cfg::NW + wave; };
+    auto slot_is_a = [&](int i) {  // wave-uniform; a compile-time fact when the pieces divide evenly
+        if constexpr (Cfg::A_PIECES % Cfg::NW == 0) return i < Cfg::A_PIECES / Cfg::NW;
+        return piece_of(i) < Cfg::A_PIECES;
+    };
     // geometry of load i of this wavefront: x piece -> (tile row, 8-k chunk index after the
     // swizzle); W piece -> (k-row, global column).  Recomputed where needed instead of kept in
     // registers: only the special tiles and the set-up use it.
     auto slot_geom = [&](int i, int &row, int &col) {
-        if (is_a) {
-            row = (piece0 + i) * Cfg::A_RPI + lane / Cfg::A_CPR;
+        if (slot_is_a(i)) {
+            row = piece_of(i) * Cfg::A_RPI + lane / Cfg::A_CPR;
             col = (lane % Cfg::A_CPR) ^ Cfg::swz_a(row);
         } else {
-            row = (piece0 + i - Cfg::A_PIECES) * Cfg::B_RPI + lane / Cfg::B_CPR;
+            row = (piece_of(i) - Cfg::A_PIECES) * Cfg::B_RPI + lane / Cfg::B_CPR;
             const int pos = lane % Cfg::B_CPR;
             const int u16 = ((((pos >> 1) ^ (row & 3))) << 1) | (pos & 1);
             col = min(n0 + u16 * 8, d_out - 8);
@@ -189,21 +192,25 @@ __global__ __launch_bounds__(Cfg::NT) void fused_gemm_kernel(
     for (int i = 0; i < Cfg::LPW; ++i) {
         int row, col;
         slot_geom(i, row, col);
-        if (is_a) {
+        if (slot_is_a(i)) {
             const int tok = tile_perm[row];
             off_g[i] = (uint32_t)(((int64_t)(tok >= 0 ? tok : 0) * d_in + col * 8) * 2);
         } else {
             off_g[i] = (uint32_t)(((int64_t)row * d_out + col) * 2);
         }
     }
-    // scalar base of the full tiles, advanced per tile (x and W are < 4 GiB each)
-    const unsigned char *g_base = is_a ? (const unsigned char *)x : (const unsigned char *)W;
-    const int64_t g_step = is_a ? (int64_t)BK * 2 : (int64_t)BK * d_out * 2;
+    // scalar bases of the full tiles, advanced per tile (x and W are < 4 GiB each)
+    const unsigned char *a_base = (const unsigned char *)x;
+    const unsigned char *b_base = (const unsigned char *)W;
+    const int64_t b_step = (int64_t)BK * d_out * 2;
 
     auto issue_one = [&](unsigned char *stage, int i) {  // i-th load of a full tile
-        load_to_lds16(g_base, off_g[i], stage + (piece0 + i) * 1024);
+        load_to_lds16(slot_is_a(i) ? a_base : b_base, off_g[i], stage + piece_of(i) * 1024);
     };
-    auto advance_full = [&]() { g_base += g_step; };
+    auto advance_full = [&]() {
+        a_base += BK * 2;
+        b_base += b_step;
+    };
     // Any K tile T, full tiles through the fast form.  A partial last tile of x.W and the
     // expand tiles compute a source per lane; chunks that must read as zero come from the
     // zero page.  Tiles must be issued in ascending order (the fast form advances its base).
@@ -221,7 +228,7 @@ __global__ __launch_bounds__(Cfg::NT) void fused_gemm_kernel(
                 const uint16_t *src;
                 int row, col;
                 slot_geom(i, row, col);
-                if (is_a) {
+                if (slot_is_a(i)) {
                     const int k = T * BK + col * 8;
                     const int tok = tile_perm[row];
                     src = (k < d_in) ? x + (int64_t)(tok >= 0 ? tok : 0) * d_in + k : zero;
@@ -229,7 +236,7 @@ __global__ __launch_bounds__(Cfg::NT) void fused_gemm_kernel(
                     const int k = T * BK + row;
                     src = (k < d_in) ? W + (int64_t)k * d_out + col : zero;
                 }
-                load_to_lds16_ptr(src, stage + (piece0 + i) * 1024);
+                load_to_lds16_ptr(src, stage + piece_of(i) * 1024);
             }
             return;
         }
@@ -243,7 +250,7 @@ __global__ __launch_bounds__(Cfg::NT) void fused_gemm_kernel(
             const uint16_t *src;
             int row, col;
             slot_geom(i, row, col);
-            if (is_a) {
+            if (slot_is_a(i)) {
                 const int p = p0 + row, vk = sub * BK + col * 8;
                 src = (p >= lo && p < hi && vk < two_r) ? t2 + (int64_t)p * two_r + vk : zero;
             } else {
@@ -251,7 +258,7 @@ __global__ __launch_bounds__(Cfg::NT) void fused_gemm_kernel(
                 const int j = vk < rank ? vk : vk - rank;
                 src = (vk < two_r) ? Bc + (int64_t)j * d_out + col : zero;
             }
-            load_to_lds16_ptr(src, stage + (piece0 + i) * 1024);
+            load_to_lds16_ptr(src, stage + piece_of(i) * 1024);
         }
     };
 
