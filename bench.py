@@ -95,7 +95,7 @@ def main():
     args = parse()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (the path needs no exchange between "
-              "GPUs; see DESIGN.md for how it would shard); use --gpus 1", file=sys.stderr)
+              "GPUs: token ranges are independent); use --gpus 1", file=sys.stderr)
         sys.exit(2)
 
     import numpy as np
