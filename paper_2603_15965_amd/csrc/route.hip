@@ -39,9 +39,9 @@ struct RouteCfg {
     static constexpr int NT = NWV * 64;
     static constexpr int TOK_WG = TGW * 16;
     static constexpr int CW = NB * TB * 16;  // targets per pass
-    // k per G slab: about 8 staging items (32 elements) per thread, a power of two in [32, 256]
+    // k per G slab: about 4 staging items (32 elements) per thread, 128 or 256
     static constexpr int KS0 = 32 * NT / CW;
-    static constexpr int KS = KS0 > 256 ? 256 : (KS0 < 32 ? 32 : KS0);
+    static constexpr int KS = KS0 >= 256 ? 256 : 128;
     static constexpr int LDG = KS + 4;  // floats per target row: 4 kq x KS/4 steps + bank shift
     static constexpr int SLAB_FLOATS = CW * LDG;
     static constexpr size_t LDS_BYTES = 2ull * SLAB_FLOATS * sizeof(float) + (size_t)NWV * 2 * kXBuf;
@@ -91,9 +91,9 @@ __global__ __launch_bounds__(TB * TGW * 64) void route_gate_kernel(
 
         // ---- G slab staging ----
         // element (k, c) of the slab goes to  c*LDG + (k%4)*(KS/4) + k/4  as fp32.
-        // Fast form (C a multiple of 8): an item is 8 consecutive targets of one k, one 16-byte
-        // load.  Otherwise an item is one element.  Loads are never predicated (addresses are
-        // clamped into G, the value is zeroed afterwards) so that they all stay in flight.
+        // An item is 8 consecutive targets of one k: one 16-byte load when C is a multiple of 8,
+        // eight 2-byte loads otherwise.  Loads are never predicated (addresses are clamped into
+        // G, the value is zeroed afterwards) so that they all stay in flight.
         constexpr int IPT = K::KS * K::CW / 8 / K::NT;  // 8-element items per thread and slab
         static_assert(IPT * K::NT * 8 == K::KS * K::CW, "slab staging split");
         u32x4 greg[IPT];
@@ -101,7 +101,11 @@ __global__ __launch_bounds__(TB * TGW * 64) void route_gate_kernel(
 #pragma unroll
             for (int m = 0; m < IPT; ++m) {
                 const int item = tid + m * K::NT;
-                const int kk = item / (K::CW / 8), c8 = (item % (K::CW / 8)) * 8;
+                // lanes of a wavefront: 32 k (4 apart) x 2 groups of 8 targets, so that the 64
+                // lanes of each LDS store below hit 64 different banks (bank = 4c + k/4 mod 64)
+                const int lq = item % 64, gq = item / 64;
+                const int kk = (gq / (4 * (K::CW / 16))) * 128 + 4 * (lq % 32) + gq % 4;
+                const int c8 = 8 * (lq / 32) + 16 * ((gq / 4) % (K::CW / 16));
                 const int k = k0 + kk;
                 const int kc = min(k, d_in - 1);
                 const uint32_t km = (k < d_in) ? 0xFFFFFFFFu : 0u;
@@ -130,7 +134,11 @@ __global__ __launch_bounds__(TB * TGW * 64) void route_gate_kernel(
 #pragma unroll
             for (int m = 0; m < IPT; ++m) {
                 const int item = tid + m * K::NT;
-                const int kk = item / (K::CW / 8), c8 = (item % (K::CW / 8)) * 8;
+                // lanes of a wavefront: 32 k (4 apart) x 2 groups of 8 targets, so that the 64
+                // lanes of each LDS store below hit 64 different banks (bank = 4c + k/4 mod 64)
+                const int lq = item % 64, gq = item / 64;
+                const int kk = (gq / (4 * (K::CW / 16))) * 128 + 4 * (lq % 32) + gq % 4;
+                const int c8 = 8 * (lq / 32) + 16 * ((gq / 4) % (K::CW / 16));
                 float *dst = slab + c8 * K::LDG + (kk & 3) * (K::KS / 4) + (kk >> 2);
 #pragma unroll
                 for (int i = 0; i < 8; ++i) {
