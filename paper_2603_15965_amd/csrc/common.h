@@ -47,4 +47,13 @@ hipError_t launch_fused_gemm(const uint16_t *x, const uint16_t *W, const uint16_
                              float *h, int64_t N, int d_in, int d_out, int C, int rank,
                              hipStream_t s);
 
+// same contract, N <= 64 (the fused GEMM launcher routes such batches here)
+hipError_t launch_small_batch_gemm(const uint16_t *x, const uint16_t *W, const uint16_t *B,
+                                   const uint16_t *t2, const int32_t *offsets, const int32_t *perm,
+                                   float *h, int64_t N, int d_in, int d_out, int C, int rank,
+                                   hipStream_t s);
+hipError_t launch_small_batch_shrink(const uint16_t *x, const uint16_t *A, const int32_t *offsets,
+                                     const int32_t *perm, uint16_t *t2, int64_t N, int d_in, int C,
+                                     int rank, hipStream_t s);
+
 }  // namespace molora

@@ -31,52 +31,13 @@
 #include <type_traits>
 
 #include "common.h"
+#include "lds_dma.h"
 
 namespace molora {
 
 namespace {
 
 constexpr int kGroupM = 8;  // row tiles per scheduling group
-
-template <int N>
-__device__ __forceinline__ void wait_vmcnt() {
-    asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
-}
-__device__ __forceinline__ void wg_barrier() { asm volatile("s_barrier" ::: "memory"); }
-__device__ __forceinline__ void wait_lds() { asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory"); }
-
-// 64 lanes x 16 bytes, HBM -> LDS; global address = base (scalar) + lane_off (per lane, 32 bit),
-// LDS address = lds_base + lane * 16 (lds_base wave-uniform, goes to M0).  Written as inline assembly on purpose: the compiler then knows nothing of an
-// outstanding LDS write and does not put a conservative vmcnt(0) wait in front of the operand
-// reads of the tile being computed, which would serialise prefetch and compute.  The waits
-// that order these loads against the LDS reads are the explicit wait_vmcnt + wg_barrier of
-// the main loop.
-__device__ __forceinline__ void load_to_lds16(const void *base, uint32_t lane_off,
-                                              unsigned char *lds_base) {
-    const uint32_t lds_addr = (uint32_t)(uintptr_t)(MOLORA_LDS unsigned char *)lds_base;
-    asm volatile(
-        "s_mov_b32 m0, %2\n\t"
-        "s_nop 0\n\t"
-        "global_load_lds_dwordx4 %0, %1"
-        :
-        : "v"(lane_off), "s"(base), "s"(lds_addr)
-        : "memory", "m0");
-}
-
-// same, from a per-lane 64-bit address
-__device__ __forceinline__ void load_to_lds16_ptr(const void *gptr, unsigned char *lds_base) {
-    const uint32_t lds_addr = (uint32_t)(uintptr_t)(MOLORA_LDS unsigned char *)lds_base;
-    asm volatile(
-        "s_mov_b32 m0, %1\n\t"
-        "s_nop 0\n\t"
-        "global_load_lds_dwordx4 %0, off"
-        :
-        : "v"(gptr), "s"(lds_addr)
-        : "memory", "m0");
-}
-
-// 256 bytes of zeros in device memory: the source of every operand chunk that must be zero
-__device__ __attribute__((aligned(256))) uint32_t g_zero_page[64];
 
 // BM x BN output tile, WM x WN x WK wavefronts (WK > 1: the k-steps of a tile are dealt out to
 // WK wavefronts per 32x32-block group and summed at the end; used where the kernel is bound by
@@ -526,8 +487,7 @@ hipError_t launch_fused_gemm(const uint16_t *x, const uint16_t *W, const uint16_
     // Tile choice from static shapes only (no host read of the histogram).  Up to 64 tokens
     // the step is bound by streaming W once: one row tile, narrow column tiles, deep ring.
     // Otherwise the largest tile that still yields about two workgroups per compute unit.
-    if (N <= 64)
-        return launch_cfg<GemmCfg<MOLORA_GEMM_STREAM>>(x, W, B, t2, offsets, perm, h, N, d_in, d_out, C, rank, s);
+    if (N <= 64) return launch_small_batch_gemm(x, W, B, t2, offsets, perm, h, N, d_in, d_out, C, rank, s);
     const int64_t t256 = ((N + 255) / 256) * ((d_out + 255) / 256);
     if (t256 >= 512)
         return launch_cfg<GemmCfg<MOLORA_GEMM_BIG>>(x, W, B, t2, offsets, perm, h, N, d_in, d_out, C, rank, s);

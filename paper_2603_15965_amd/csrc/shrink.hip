@@ -205,6 +205,9 @@ hipError_t launch_shrink(const uint16_t *x, const uint16_t *A, const int32_t *of
                          const int32_t *perm, uint16_t *t2, int64_t N, int d_in, int C, int rank,
                          hipStream_t s) {
     if (N == 0) return hipSuccess;
+    // up to 64 tokens the step is bound by the latency of streaming the touched A_c: one
+    // workgroup per bucket with the K range split over its wavefronts
+    if (N <= 64) return launch_small_batch_shrink(x, A, offsets, perm, t2, N, d_in, C, rank, s);
     const unsigned blocks = (unsigned)((N + kShrinkRows - 1) / kShrinkRows + C);
     const int nj = (rank + 15) / 16;
 #define MOLORA_SHRINK_CASE(NJ)                                                                  \

@@ -1,0 +1,371 @@
+// Fused base projection + grouped expand for small batches (N <= 64 tokens; Eq. "pertok"):
+//
+//     h[perm[p]][:] = x[perm[p]] W  +  t_p B_{c(p)}
+//
+// With at most 64 rows the step is bound by reading W (and the touched B_c) once from HBM,
+// so the kernel is built around keeping many bytes in flight per compute unit and around
+// spending few cache-line accesses per byte, with no workgroup barrier in the streaming loop:
+//   * a workgroup owns 64 output columns and all rows; its 8 wavefronts split the K range
+//     (the d_in rows of W, then the 2*rank rows of [B_c; B_c] of every bucket that owns rows)
+//     in units of 64 k and add their partial tiles in LDS at the end, in wavefront order, so
+//     the result does not depend on timing and needs no scratch memory or atomics;
+//   * every wavefront streams its 16 x 64 slabs of W straight from HBM into a private ring of
+//     LDS slots (global_load_lds_dwordx4), 4 slabs ahead of the one it multiplies; the LDS
+//     transpose read turns the K-major slab into the MFMA operand;
+//   * the x (or t) operand of 64 k travels the same way, as whole 128-byte lines of 8 rows per
+//     load instruction, into a private staging tile, one unit ahead; it is moved to registers
+//     at the start of its unit, which frees the staging tile for the next one;
+//   * chunks that must read as zero (k past d_in, t rows of other buckets, padding of a
+//     wavefront's list) come from an all-zero page, so every step issues the same number of
+//     loads and the explicit vmcnt waits are compile-time constants.
+#include <type_traits>
+
+#include "common.h"
+#include "lds_dma.h"
+
+namespace molora {
+
+namespace {
+
+constexpr int kSbWaves = 8;                    // wavefronts per workgroup = K splits
+constexpr int kSbCols = 64;                    // output columns per workgroup
+constexpr int kSbSlot = 16 * kSbCols * 2;      // one 16-k slab of W: 2 KB, two load instructions
+constexpr int kSbRing = 5;                     // slab slots per wavefront
+constexpr int kSbStage = 64 * 128;             // x / t staging tile: 64 rows x 64 k
+constexpr int kSbRowBytes = kSbCols * 4 + 16;  // partial tile row in LDS (+16: bank shift)
+constexpr int kSbWaveLds = kSbRing * kSbSlot + kSbStage;  // per wavefront; partial tile reuses it
+static_assert(64 * kSbRowBytes <= kSbWaveLds, "partial tile fits the wavefront's region");
+constexpr size_t kSbLdsBytes = (size_t)kSbWaves * kSbWaveLds + (4 * 64 + 4) * sizeof(int32_t);
+
+// one unit of a wavefront's work list: 4 steps of 16 k
+struct Unit {
+    int kind;  // 0: rows k0 .. k0+63 of W; 1: rows of [B_c; B_c]; 2: nothing (zeros)
+    int k0;    // kind 0: first k.  kind 1: first row of [B_c; B_c] (0 .. 2*rank)
+    int c, lo, hi;  // kind 1: bucket and its sorted-position range
+};
+
+// SHRINK = false: the fused GEMM above over all N rows (grid: column groups).
+// SHRINK = true:  the shrink step t_p = x[perm[p]] A_c for the rows of bucket c = blockIdx.y
+//                 (grid: column groups of the rank x buckets); W is A, d_out is rank, there
+//                 are no expand units and the result goes to t_out as [hi | lo] bf16 halves.
+template <int TM, bool SHRINK>  // TM: 32-row blocks, 1 (N <= 32) or 2
+__global__ __launch_bounds__(kSbWaves * 64) void small_batch_kernel(
+    const uint16_t *__restrict__ x, const uint16_t *__restrict__ W, const uint16_t *__restrict__ B,
+    const uint16_t *__restrict__ t2, const int32_t *__restrict__ offsets,
+    const int32_t *__restrict__ perm, float *__restrict__ h, uint16_t *__restrict__ t_out, int N,
+    int d_in, int d_out, int C, int rank) {
+    extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+    int32_t *tile_perm = (int32_t *)(smem + kSbWaves * kSbWaveLds);  // [64] token per row, -1 = none
+    int32_t *seg_c = tile_perm + 64;                                 // buckets that own rows,
+    int32_t *seg_lo = seg_c + 64;                                    // ascending, with their
+    int32_t *seg_hi = seg_lo + 64;                                   // sorted-position ranges
+    int32_t *nseg_p = seg_hi + 64;
+
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int n0 = blockIdx.x * kSbCols;
+    unsigned char *ring = smem + wave * kSbWaveLds;
+    unsigned char *stage = ring + kSbRing * kSbSlot;
+    const uint16_t *zero = (const uint16_t *)g_zero_page;
+
+    // ---- rows of this workgroup ----
+    int row_base = 0, nrows = N;
+    if constexpr (SHRINK) {
+        const int c = blockIdx.y;
+        row_base = offsets[c];
+        nrows = offsets[c + 1] - row_base;
+        if (nrows <= 0) return;  // empty bucket: A_c is not touched
+        W += (int64_t)c * d_in * rank;
+    }
+
+    // ---- tables: row -> token, and the non-empty buckets in ascending order ----
+    if (tid < 64) tile_perm[tid] = tid < nrows ? perm[row_base + tid] : -1;
+    if (SHRINK && tid == 0) *nseg_p = 0;
+    if (!SHRINK && wave == kSbWaves - 1) {
+        const uint64_t lower = (lane == 0) ? 0ull : (~0ull >> (64 - lane));
+        int cnt = 0;
+        for (int c0 = 0; c0 < C; c0 += 64) {
+            const int c = min(c0 + lane, C - 1);
+            const int lo = offsets[c], hi = offsets[c + 1];
+            const bool owns = (c0 + lane < C) && hi > lo;
+            const uint64_t m = __ballot(owns);
+            if (owns) {
+                const int idx = cnt + __popcll(m & lower);
+                seg_c[idx] = c;
+                seg_lo[idx] = lo;
+                seg_hi[idx] = hi;
+            }
+            cnt += __popcll(m);
+        }
+        if (lane == 0) *nseg_p = cnt;
+    }
+    __syncthreads();
+    const int nseg = __builtin_amdgcn_readfirstlane(*nseg_p);
+
+    // ---- this wavefront's share of the work list ----
+    // units 0 .. nub-1: W in pieces of 64 rows; then upb units per bucket: [B_c; B_c] in
+    // pieces of 64 rows (the last piece of either kind may be short)
+    const int two_r = 2 * rank;
+    const int nub = (d_in + 63) / 64, upb = (two_r + 63) / 64;
+    const int total = nub + nseg * upb;
+    const int u0 = total * wave / kSbWaves, u1 = total * (wave + 1) / kSbWaves;
+
+    // a cursor walks the list one unit at a time (no division in the loop)
+    struct Cursor {
+        int u, sg, part;
+    };
+    auto cursor_at = [&](int u) {
+        Cursor cu;
+        cu.u = u;
+        const int e = max(u - nub, 0);
+        cu.sg = e / upb;
+        cu.part = e - cu.sg * upb;
+        return cu;
+    };
+    auto unit_of = [&](const Cursor &cu) {
+        Unit un;
+        un.c = un.lo = un.hi = 0;
+        if (cu.u >= u1) {
+            un.kind = 2;
+            un.k0 = 0;
+        } else if (cu.u < nub) {
+            un.kind = 0;
+            un.k0 = cu.u * 64;
+        } else {
+            un.kind = 1;
+            un.k0 = cu.part * 64;
+            un.c = __builtin_amdgcn_readfirstlane(seg_c[cu.sg]);
+            un.lo = __builtin_amdgcn_readfirstlane(seg_lo[cu.sg]);
+            un.hi = __builtin_amdgcn_readfirstlane(seg_hi[cu.sg]);
+        }
+        return un;
+    };
+    auto advance = [&](Cursor &cu) {
+        if (cu.u >= nub && cu.u < u1 && ++cu.part == upb) {
+            cu.part = 0;
+            ++cu.sg;
+        }
+        ++cu.u;
+    };
+
+    // ---- slab loads: 8 k-rows x 128 bytes per instruction ----
+    // lane -> row lane/8 of the 8, 16-byte position lane%8 of the slab row, which holds the
+    // column chunk given by the swizzle.  d_in and rank are multiples of 8, so a load is either
+    // entirely inside its matrix or entirely zero.
+    const int w_rr = lane >> 3, w_pos = lane & 7;
+    const int w_u16 = ((((w_pos >> 1) ^ (w_rr & 3))) << 1) | (w_pos & 1);
+    const int w_col = min(n0 + w_u16 * 8, d_out - 8);  // columns past d_out: clamped, never stored
+    const uint16_t *w_lane = W + (int64_t)w_rr * d_out + w_col;
+    const uint16_t *b_lane = B + (int64_t)w_rr * d_out + w_col;
+    auto issue_slab = [&](const Unit &un, int j, int q) {  // step j of the unit, into slot q % ring
+        unsigned char *slot = ring + (q % kSbRing) * kSbSlot;
+#pragma unroll
+        for (int r = 0; r < 2; ++r) {
+            const int kk = un.k0 + j * 16 + r * 8;  // first of the 8 rows
+            const uint16_t *src = zero;
+            if (un.kind == 0) {
+                if (kk < d_in) src = w_lane + (int64_t)kk * d_out;
+            } else if (un.kind == 1) {
+                if (kk < two_r) src = b_lane + ((int64_t)un.c * rank + (kk < rank ? kk : kk - rank)) * d_out;
+            }
+            load_to_lds16_ptr(src, slot + r * 1024);
+        }
+    };
+
+    // ---- x / t loads: 8 rows x 128 bytes (64 k) per instruction, 4 * TM instructions a unit ----
+    // lane -> row i*8 + lane/8, 16-byte position lane%8 of the staged row, which holds the
+    // 8-k chunk (position ^ swizzle(row)); the operand read below undoes the swizzle.
+    const int a_sub = lane >> 3, a_pos = lane & 7;
+    const uint16_t *a_xrow[4 * TM];
+    int a_ch8[4 * TM];
+#pragma unroll
+    for (int i = 0; i < 4 * TM; ++i) {
+        const int row = i * 8 + a_sub;
+        const int tok = perm[row_base + min(row, nrows - 1)];  // rows past the end repeat the last one; never stored
+        a_ch8[i] = (a_pos ^ ((row ^ (row >> 3)) & 7)) * 8;
+        a_xrow[i] = x + (int64_t)tok * d_in + a_ch8[i];
+    }
+    auto issue_stage = [&](const Unit &un) {
+#pragma unroll
+        for (int i = 0; i < 4 * TM; ++i) {
+            const int row = i * 8 + a_sub;
+            const int kk = un.k0 + a_ch8[i];
+            const uint16_t *src = zero;
+            if (un.kind == 0) {
+                if (kk < d_in) src = a_xrow[i] + un.k0;
+            } else if (un.kind == 1) {
+                if (row >= un.lo && row < un.hi && kk < two_r) src = t2 + (int64_t)row * two_r + kk;
+            }
+            load_to_lds16_ptr(src, stage + i * 1024);
+        }
+    };
+
+    f32x16 acc[TM][2];
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < 2; ++j)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
+
+    // operand reads.  x / t: lane -> row lane%32 (+32), k-group lane/32.  Slab: lane -> column
+    // 16*(blk&1) + a16 of a 32-column block, k-rows (blk>>1)*8 + 0..7, through the transpose read.
+    const int kg = lane >> 5, m_lo = lane & 31;
+    const int blk = lane >> 4, a16 = lane & 15;
+    const int b_kr0 = (blk >> 1) * 8 + (a16 >> 2);
+    const int b_k3 = b_kr0 & 3;
+    const int b_in = (a16 & 3) * 8;
+    auto load_a_frag = [&](int j, int tm) -> bf16x8 {
+        const int row = tm * 32 + m_lo;
+        const int sw = (row ^ (row >> 3)) & 7;
+        return *(const bf16x8 *)(stage + row * 128 + (((j * 2 + kg) ^ sw) << 4));
+    };
+    auto load_b_frag = [&](const unsigned char *slot, int tn) -> bf16x8 {
+        const int cc = tn * 2 + (blk & 1);  // 32-byte chunk of the slab row
+        const unsigned char *p = slot + b_kr0 * (kSbCols * 2) + ((cc ^ b_k3) << 5) + b_in;
+        const i16x4 lo = lds_read_tr16((const MOLORA_LDS void *)p);
+        const i16x4 hi = lds_read_tr16((const MOLORA_LDS void *)(p + 4 * kSbCols * 2));
+        const i16x8 b8 = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
+        return __builtin_bit_cast(bf16x8, b8);
+    };
+
+    // ---- streaming loop ----
+    // Step s = 4 * unit + j.  Iteration s issues slab s + 4, and at j == 0 (after the staged
+    // operand of its own unit has been moved to registers) the staged operand of the next
+    // unit.  Loads return in order, so "at most n outstanding", n = the number of loads issued
+    // after the needed one, is exactly "the needed one has landed":
+    //   staged operand of the unit, at j == 0: the three slabs issued since         -> 6
+    //   slab s at j > 0: 4 slabs and one staged operand issued since                -> 8 + XD
+    //   slab s at j == 0: older than the staged operand, already there.
+    constexpr int XD = 4 * TM;
+    constexpr int AHEAD = kSbRing - 1;
+    static_assert(AHEAD == 4, "the wait counts above assume slabs are issued 4 steps ahead");
+    Cursor cw = cursor_at(u0), cx = cursor_at(u0);  // slab stream, staged-operand stream
+    Unit uw = unit_of(cw);
+    int qw = 0;  // step index of the next slab to issue; its unit is uw, its step qw % 4
+    auto next_slab = [&]() {
+        issue_slab(uw, qw & 3, qw);
+        if ((++qw & 3) == 0) {
+            advance(cw);
+            uw = unit_of(cw);
+        }
+    };
+    // what iterations -4 .. -1 would have issued
+    next_slab();
+    issue_stage(unit_of(cx));
+    advance(cx);
+    next_slab();
+    next_slab();
+    next_slab();
+
+    const int nunits = u1 - u0;
+    for (int ui = 0; ui < nunits; ++ui) {
+        bf16x8 fa[4][TM];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const int s = ui * 4 + j;
+            if (j == 0) {
+                wait_vmcnt<6>();
+#pragma unroll
+                for (int jj = 0; jj < 4; ++jj)
+#pragma unroll
+                    for (int tm = 0; tm < TM; ++tm) fa[jj][tm] = load_a_frag(jj, tm);
+                wait_lds();  // the staging tile is in registers before it is refilled
+            }
+            next_slab();
+            if (j == 0) {
+                issue_stage(unit_of(cx));
+                advance(cx);
+            } else {
+                wait_vmcnt<8 + XD>();
+            }
+            const unsigned char *slot = ring + (s % kSbRing) * kSbSlot;
+            bf16x8 bfr[2];
+            bfr[0] = load_b_frag(slot, 0);
+            bfr[1] = load_b_frag(slot, 1);
+#pragma unroll
+            for (int tm = 0; tm < TM; ++tm)
+#pragma unroll
+                for (int tn = 0; tn < 2; ++tn)
+                    acc[tm][tn] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[j][tm], bfr[tn],
+                                                                          acc[tm][tn], 0, 0, 0);
+            wait_lds();  // the slab has been read before its slot is refilled
+        }
+    }
+    wait_vmcnt<0>();  // the trailing loads (zeros) land before the memory is reused
+
+    // ---- add the 8 partial tiles, every row to its original position ----
+    // acc[tm][tn][v]: row tm*32 + (v/4)*8 + (lane/32)*4 + v%4, column tn*32 + lane%32
+#pragma unroll
+    for (int tm = 0; tm < TM; ++tm)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+            const int row = tm * 32 + (v >> 2) * 8 + kg * 4 + (v & 3);
+#pragma unroll
+            for (int tn = 0; tn < 2; ++tn)
+                *(float *)(ring + row * kSbRowBytes + (tn * 32 + m_lo) * 4) = acc[tm][tn][v];
+        }
+    __syncthreads();
+    for (int it = tid; it < TM * 32 * (kSbCols / 4); it += kSbWaves * 64) {
+        const int row = it / (kSbCols / 4), ch = it % (kSbCols / 4);
+        const int tok = tile_perm[row];
+        const int col = n0 + ch * 4;
+        if (tok < 0 || col >= d_out) continue;
+        f32x4 sum = *(const f32x4 *)(smem + row * kSbRowBytes + ch * 16);
+#pragma unroll
+        for (int w = 1; w < kSbWaves; ++w)
+            sum += *(const f32x4 *)(smem + w * kSbWaveLds + row * kSbRowBytes + ch * 16);
+        if constexpr (SHRINK) {
+            // t = hi + lo with hi = bf16(t), lo = bf16(t - hi); row of t_out = [hi | lo]
+            u32x2 hi2 = {0, 0}, lo2 = {0, 0};
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const uint32_t hi = f32_to_bf16_bits(sum[i]);
+                const uint32_t lo = f32_to_bf16_bits(sum[i] - bf16_bits_to_f32(hi));
+                hi2[i >> 1] |= hi << (16 * (i & 1));
+                lo2[i >> 1] |= lo << (16 * (i & 1));
+            }
+            uint16_t *dst = t_out + (int64_t)(row_base + row) * 2 * rank;
+            *(u32x2 *)(dst + col) = hi2;
+            *(u32x2 *)(dst + rank + col) = lo2;
+        } else {
+            *(f32x4 *)(h + (int64_t)tok * d_out + col) = sum;
+        }
+    }
+}
+
+template <int TM, bool SHRINK>
+hipError_t launch_small(const uint16_t *x, const uint16_t *W, const uint16_t *B, const uint16_t *t2,
+                        const int32_t *offsets, const int32_t *perm, float *h, uint16_t *t_out, int N,
+                        int d_in, int d_out, int C, int rank, hipStream_t s) {
+    auto kern = small_batch_kernel<TM, SHRINK>;
+    hipError_t e = hipFuncSetAttribute((const void *)kern,
+                                       hipFuncAttributeMaxDynamicSharedMemorySize,
+                                       (int)kSbLdsBytes);
+    if (e != hipSuccess) return e;
+    const unsigned groups = (unsigned)((d_out + kSbCols - 1) / kSbCols);
+    hipLaunchKernelGGL(kern, dim3(groups, SHRINK ? C : 1), dim3(kSbWaves * 64), kSbLdsBytes, s, x, W,
+                       B, t2, offsets, perm, h, t_out, N, d_in, d_out, C, rank);
+    return hipGetLastError();
+}
+
+}  // namespace
+
+hipError_t launch_small_batch_gemm(const uint16_t *x, const uint16_t *W, const uint16_t *B,
+                                   const uint16_t *t2, const int32_t *offsets, const int32_t *perm,
+                                   float *h, int64_t N, int d_in, int d_out, int C, int rank,
+                                   hipStream_t s) {
+    if (N <= 32)
+        return launch_small<1, false>(x, W, B, t2, offsets, perm, h, nullptr, (int)N, d_in, d_out, C, rank, s);
+    return launch_small<2, false>(x, W, B, t2, offsets, perm, h, nullptr, (int)N, d_in, d_out, C, rank, s);
+}
+
+hipError_t launch_small_batch_shrink(const uint16_t *x, const uint16_t *A, const int32_t *offsets,
+                                     const int32_t *perm, uint16_t *t_out, int64_t N, int d_in, int C,
+                                     int rank, hipStream_t s) {
+    if (N <= 32)
+        return launch_small<1, true>(x, A, nullptr, nullptr, offsets, perm, nullptr, t_out, (int)N, d_in, rank, C, rank, s);
+    return launch_small<2, true>(x, A, nullptr, nullptr, offsets, perm, nullptr, t_out, (int)N, d_in, rank, C, rank, s);
+}
+
+}  // namespace molora

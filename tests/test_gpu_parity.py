@@ -113,6 +113,9 @@ def test_route_gate_bit_exact_full_configs(gpu, name):
     (515, 520, 264, 7, 24, "uniform"),      # rank not a multiple of 16
     (700, 256, 512, 40, 32, "zipf"),        # many small and empty buckets inside one tile
     (64, 512, 1024, 16, 64, "zipf"),
+    (50, 1024, 520, 5, 16, "uniform"),      # small-batch path with the K range split, ragged
+    (64, 2048, 1024, 16, 64, "zipf"),       # small-batch path, many buckets in the one row tile
+    (7, 1096, 264, 3, 8, "uniform"),        # small-batch path, K tail
     (1000, 128, 136, 4, 128, "uniform"),    # maximum rank
     (2304, 192, 2560, 6, 16, "all0"),       # large-tile path (>= 512 tiles), one bucket
     (2500, 128, 4000, 9, 8, "uniform"),     # large-tile path, ragged everything
