@@ -8,9 +8,14 @@ default workload is configuration 1 (N = 4096 tokens, Qwen3-1.7B q_proj 2048 -> 
 adapters of rank 16, vocabulary-routed interleaved text/image runs).
 
 Prints ONE JSON line: whole-step throughput in tokens/s, the roofline of the dominant kernel
-(the fused GEMM) from HIP-event timing of that kernel inside the timed region, and the CPU
-oracle timed on the host cores.  Inputs rotate through several independent copies so that
-consecutive steps do not find their operands in the 256 MB Infinity Cache.
+(the fused GEMM) from HIP-event timing of that kernel inside the timed region, the per-step
+latency distribution (median, P99, coefficient of variation) and the CPU oracle timed on the
+host cores.  Inputs rotate through several independent copies so that consecutive steps do
+not find their operands in the 256 MB Infinity Cache.
+
+--workload prefill8_layer runs all seven projections of configuration 4 in one step;
+--graph replays the step from a recorded launch sequence (one per input copy) instead of
+launching the kernels one by one.
 """
 import argparse
 import json
@@ -32,7 +37,10 @@ def parse():
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--workload", default="vocab_q17",
-                    help="a shape name from paper_2603_15965_amd.workloads.shapes()")
+                    help="a shape name from paper_2603_15965_amd.workloads.shapes(), or "
+                         "prefill8_layer / prefill8_layer_deg (the seven projections of one layer)")
+    ap.add_argument("--graph", action="store_true",
+                    help="replay each step from a recorded launch sequence (HIP graph)")
     ap.add_argument("--sets", type=int, default=0,
                     help="independent input copies to rotate through (0 = enough for > 600 MB)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -58,7 +66,10 @@ def algorithmic_work(shape, n_routed, touched):
             "layer_flops": gemm_flops + shrink_flops + gate_flops}
 
 
-def cpu_baseline(wl_mod, shape):
+LAYER = ["q", "k", "v", "o", "gate", "up", "down"]
+
+
+def cpu_baseline(wl_mod, shape, budget_flops=1.5e12):
     """The oracle, as it stands, on the host cores: route + bucket + apply on a bounded
     sample of the same workload."""
     import numpy as np
@@ -67,7 +78,7 @@ def cpu_baseline(wl_mod, shape):
     N = shape.N
     # bound the CPU work to roughly 10-30 s: ~1e11 flops per second of 8-core work
     flops_per_token = 2.0 * shape.d_in * shape.d_out + 2.0 * shape.rank * (shape.d_in + shape.d_out)
-    n_sample = int(min(N, max(64, 1.5e12 // flops_per_token)))
+    n_sample = int(min(N, max(64, budget_flops // flops_per_token)))
     rows = np.arange(n_sample, dtype=np.int64)
     reps = 3 if n_sample == N and N * flops_per_token < 2e11 else 1
     best = None
@@ -108,51 +119,63 @@ def main():
         sys.exit(1)
     torch.cuda.set_device(0)
     mb.load()
-    shape = wl_mod.shapes()[args.workload]
-    N, di, do, C, rk = shape.N, shape.d_in, shape.d_out, shape.C, shape.rank
+    all_shapes = wl_mod.shapes()
+    if args.workload in ("prefill8_layer", "prefill8_layer_deg"):
+        suffix = "_deg" if args.workload.endswith("_deg") else ""
+        shapes = [all_shapes[f"prefill8_{p}{suffix}"] for p in LAYER]
+    else:
+        shapes = [all_shapes[args.workload]]
+    N = shapes[0].N
 
     # ---- resident inputs: `sets` independent copies (different seeds for x), rotated ----
-    per_set = 2.0 * N * di + 2.0 * di * do + 2.0 * C * rk * (di + do) + 4.0 * N * do
+    per_set = sum(2.0 * sh.N * sh.d_in + 2.0 * sh.d_in * sh.d_out
+                  + 2.0 * sh.C * sh.rank * (sh.d_in + sh.d_out) + 4.0 * sh.N * sh.d_out for sh in shapes)
     sets = args.sets if args.sets > 0 else int(max(2, min(64, -(-600e6 // per_set))))
-    base = wl_mod.make(shape)
     rng = np.random.default_rng(123)
-    S = []
-    for s in range(sets):
-        d = {}
-        # every copy holds the same distributions; copies > 0 are row/element shuffles of copy 0
-        x_bits = base.x if s == 0 else base.x[rng.permutation(N)]
-        d["x"] = mb.bf16_tensor(x_bits)
-        d["W"] = mb.bf16_tensor(base.W if s == 0 else np.roll(base.W, s, axis=0))
-        d["A"] = mb.bf16_tensor(base.A if s == 0 else np.roll(base.A, s, axis=1))
-        d["B"] = mb.bf16_tensor(base.B if s == 0 else np.roll(base.B, s, axis=1))
-        if base.G is not None:
-            d["G"] = mb.bf16_tensor(base.G)
-        if base.v is not None:
-            d["v"] = torch.from_numpy(base.v if s == 0 else np.roll(base.v, 17 * s)).cuda()
-        if base.r is not None:
-            d["r_given"] = torch.from_numpy(base.r if s == 0 else np.roll(base.r, 17 * s)).cuda()
-        d["r"] = torch.empty(N, dtype=torch.int32, device="cuda")
-        d["offsets"] = torch.empty(C + 1, dtype=torch.int32, device="cuda")
-        d["perm"] = torch.empty(N, dtype=torch.int32, device="cuda")
-        d["t"] = torch.empty((N, 2 * rk), dtype=torch.bfloat16, device="cuda")
-        d["h"] = torch.empty((N, do), dtype=torch.float32, device="cuda")
-        S.append(d)
-    breaks = base.breaks
+    S = [[] for _ in range(sets)]
+    for sh in shapes:
+        base = wl_mod.make(sh)
+        C, rk = sh.C, sh.rank
+        for s in range(sets):
+            d = {"shape": sh, "breaks": base.breaks}
+            # every copy holds the same distributions; copies > 0 are row/element shuffles of copy 0
+            x_bits = base.x if s == 0 else base.x[rng.permutation(sh.N)]
+            d["x"] = mb.bf16_tensor(x_bits)
+            d["W"] = mb.bf16_tensor(base.W if s == 0 else np.roll(base.W, s, axis=0))
+            d["A"] = mb.bf16_tensor(base.A if s == 0 else np.roll(base.A, s, axis=1))
+            d["B"] = mb.bf16_tensor(base.B if s == 0 else np.roll(base.B, s, axis=1))
+            if base.G is not None:
+                d["G"] = mb.bf16_tensor(base.G)
+            if base.v is not None:
+                d["v"] = torch.from_numpy(base.v if s == 0 else np.roll(base.v, 17 * s)).cuda()
+            if base.r is not None:
+                d["r_given"] = torch.from_numpy(base.r if s == 0 else np.roll(base.r, 17 * s)).cuda()
+            d["r"] = torch.empty(sh.N, dtype=torch.int32, device="cuda")
+            d["offsets"] = torch.empty(C + 1, dtype=torch.int32, device="cuda")
+            d["perm"] = torch.empty(sh.N, dtype=torch.int32, device="cuda")
+            d["t"] = torch.empty((sh.N, 2 * rk), dtype=torch.bfloat16, device="cuda")
+            d["h"] = torch.empty((sh.N, sh.d_out), dtype=torch.float32, device="cuda")
+            S[s].append(d)
+        del base
 
-    def step(d, ev=None):
+    def route(d, stream=None):
         if "G" in d:
-            r = mb.molora_route(d["x"], d["G"], d["r"])
-        elif "v" in d:
-            r = mb.molora_route_vocab(d["v"], breaks, d["r"])
-        else:
-            r = d["r_given"]
-        mb.molora_bucket(r, C, d["offsets"], d["perm"])
-        mb.molora_shrink(d["x"], d["A"], d["offsets"], d["perm"], d["t"])
-        if ev is not None:
-            ev[0].record()
-        mb.molora_base_expand(d["x"], d["W"], d["B"], d["t"], d["offsets"], d["perm"], d["h"])
-        if ev is not None:
-            ev[1].record()
+            return mb.molora_route(d["x"], d["G"], d["r"], stream=stream)
+        if "v" in d:
+            return mb.molora_route_vocab(d["v"], d["breaks"], d["r"], stream=stream)
+        return d["r_given"]
+
+    def step(projs, ev=None, stream=None):
+        for j, d in enumerate(projs):
+            r = route(d, stream)
+            mb.molora_bucket(r, d["shape"].C, d["offsets"], d["perm"], stream=stream)
+            mb.molora_shrink(d["x"], d["A"], d["offsets"], d["perm"], d["t"], stream=stream)
+            if ev is not None:
+                ev[2 * j].record()
+            mb.molora_base_expand(d["x"], d["W"], d["B"], d["t"], d["offsets"], d["perm"], d["h"],
+                                  stream=stream)
+            if ev is not None:
+                ev[2 * j + 1].record()
 
     if args.copy_calibration:
         a = torch.empty(256 << 20, dtype=torch.uint8, device="cuda")
@@ -160,47 +183,83 @@ def main():
         b.copy_(a)
         torch.cuda.synchronize()
 
+    # ---- how a step is launched: kernel by kernel, or one recorded sequence per input copy ----
+    run_stream = torch.cuda.current_stream()
+    graphs = None
+    if args.graph:
+        run_stream = torch.cuda.Stream()
+        step(S[0], stream=run_stream)  # first launches (module load, attributes) outside capture
+        run_stream.synchronize()
+        graphs = []
+        for s in range(sets):
+            g = mb.Graph(run_stream)
+            with g.capture():
+                step(S[s], stream=run_stream)
+            graphs.append(g)
+
+    def run_step(i, ev=None):
+        if graphs is not None:
+            graphs[i % sets].launch()
+        else:
+            step(S[i % sets], ev)
+
     for i in range(args.warmup):
-        step(S[i % sets])
+        run_step(i)
     torch.cuda.synchronize()
 
-    use_ev = not args.no_kernel_events
-    evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True))
+    use_ev = not args.no_kernel_events and graphs is None
+    P = len(shapes)
+    evs = [[torch.cuda.Event(enable_timing=True) for _ in range(2 * P)]
            for _ in range(args.steps)] if use_ev else None
+    ticks = [torch.cuda.Event(enable_timing=True) for _ in range(args.steps + 1)]
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for i in range(args.steps):
-        step(S[i % sets], evs[i] if use_ev else None)
+        ticks[i].record(run_stream)
+        run_step(i, evs[i] if use_ev else None)
+    ticks[args.steps].record(run_stream)
     torch.cuda.synchronize()
     elapsed = time.perf_counter() - t0
     ms_per_step = 1e3 * elapsed / args.steps
-    gemm_us = (sum(a.elapsed_time(b) for a, b in evs) / args.steps * 1e3) if use_ev else None
+    lat = np.array([ticks[i].elapsed_time(ticks[i + 1]) * 1e3 for i in range(args.steps)])
+    latency = {"p50_us": float(np.percentile(lat, 50)), "p99_us": float(np.percentile(lat, 99)),
+               "mean_us": float(lat.mean()), "cv": float(lat.std() / lat.mean()),
+               "how": "HIP events between consecutive steps on the launch stream"}
+    gemm_us = None
+    if use_ev:
+        gemm_us = sum(e[2 * j].elapsed_time(e[2 * j + 1]) for e in evs for j in range(P)) / args.steps * 1e3
 
-    # ---- untimed breakdown of the other kernels (events around each call) ----
-    def timed_calls(fn, reps=50):
-        es = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(reps)]
-        for i in range(reps):
-            d = S[i % sets]
-            es[i][0].record()
-            fn(d)
-            es[i][1].record()
-        torch.cuda.synchronize()
-        return sum(a.elapsed_time(b) for a, b in es) / reps * 1e3
+    # ---- untimed breakdown of the kernels (events around each call), summed over projections ----
+    def timed_calls(fn, reps=30):
+        total = 0.0
+        for j in range(P):
+            es = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(reps)]
+            for i in range(reps):
+                d = S[i % sets][j]
+                es[i][0].record()
+                fn(d)
+                es[i][1].record()
+            torch.cuda.synchronize()
+            total += sum(a.elapsed_time(b) for a, b in es) / reps * 1e3
+        return total
 
     breakdown = {}
-    if "G" in S[0]:
-        breakdown["route_us"] = timed_calls(lambda d: mb.molora_route(d["x"], d["G"], d["r"]))
-    elif "v" in S[0]:
-        breakdown["route_us"] = timed_calls(lambda d: mb.molora_route_vocab(d["v"], breaks, d["r"]))
-    rsrc = (lambda d: d["r"]) if ("G" in S[0] or "v" in S[0]) else (lambda d: d["r_given"])
-    breakdown["bucket_us"] = timed_calls(lambda d: mb.molora_bucket(rsrc(d), C, d["offsets"], d["perm"]))
+    if "G" in S[0][0] or "v" in S[0][0]:
+        breakdown["route_us"] = timed_calls(lambda d: route(d))
+    rsrc = (lambda d: d["r"]) if ("G" in S[0][0] or "v" in S[0][0]) else (lambda d: d["r_given"])
+    breakdown["bucket_us"] = timed_calls(lambda d: mb.molora_bucket(rsrc(d), d["shape"].C, d["offsets"], d["perm"]))
     breakdown["shrink_us"] = timed_calls(lambda d: mb.molora_shrink(d["x"], d["A"], d["offsets"], d["perm"], d["t"]))
     breakdown["gemm_us"] = timed_calls(lambda d: mb.molora_base_expand(d["x"], d["W"], d["B"], d["t"], d["offsets"], d["perm"], d["h"]))
 
-    offs = S[0]["offsets"].cpu().numpy()
-    n_routed = int(offs[C])
-    touched = int((np.diff(offs) > 0).sum())
-    work = algorithmic_work(shape, n_routed, touched)
+    work = None
+    n_routed_all, touched_all = [], []
+    for d in S[0]:
+        offs = d["offsets"].cpu().numpy()
+        n_routed, touched = int(offs[d["shape"].C]), int((np.diff(offs) > 0).sum())
+        n_routed_all.append(n_routed)
+        touched_all.append(touched)
+        w1 = algorithmic_work(d["shape"], n_routed, touched)
+        work = w1 if work is None else {k: work[k] + w1[k] for k in work}
 
     t_gemm = (gemm_us if gemm_us is not None else breakdown["gemm_us"]) * 1e-6
     ai = work["gemm_flops"] / work["gemm_bytes"]
@@ -215,15 +274,28 @@ def main():
     traffic = None
     try:  # measured with rocprofv3 --pmc in a separate run (see profiles/)
         with open(os.path.join(ROOT, "profiles", "traffic.json")) as f:
-            tj = json.load(f).get(shape.name)
+            tj = json.load(f).get(args.workload)
         if tj:
             traffic = tj["read_bytes"] + tj["write_bytes"]
     except (OSError, ValueError, KeyError):
         traffic = None
-    roof.update({"kernel": "fused_gemm_kernel (base x.W + grouped expand, unpermuting fp32 store)",
-                 "kernel_us": t_gemm * 1e6, "traffic": traffic,
+    kname = ("small_batch_kernel" if N <= 64 else "fused_gemm_kernel") + \
+        " (base x.W + grouped expand, unpermuting fp32 store)"
+    if P > 1:
+        kname += f", {P} launches per step summed"
+    roof.update({"kernel": kname, "kernel_us": t_gemm * 1e6, "traffic": traffic,
+                 "kernel_us_from": "HIP events in the timed region" if gemm_us is not None
+                 else "HIP events around the call, outside the timed region",
                  "algorithmic_flops": work["gemm_flops"], "algorithmic_bytes": work["gemm_bytes"]})
 
+    if P == 1:
+        sh = shapes[0]
+        wname = (f"{sh.name}: N={sh.N} tokens, {sh.d_in}->{sh.d_out}, C={sh.C} adapters of rank {sh.rank}, "
+                 f"route={sh.route}")
+    else:
+        wname = (f"{args.workload}: N={N} tokens through the seven projections of a Qwen3-8B-shaped layer "
+                 f"(q, o 4096->4096; k, v 4096->1024; gate, up 4096->12288; down 12288->4096), "
+                 f"C={shapes[0].C} adapters of rank {shapes[0].rank}, route={shapes[0].route} per projection")
     out = {
         "metric": "routed-LoRA layer tokens/s",
         "value": N * args.steps / elapsed,
@@ -232,17 +304,29 @@ def main():
         "ms_per_step": ms_per_step,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16", "data": "synthetic",
-        "config": {"workload": f"{shape.name}: N={N} tokens, {di}->{do}, C={C} adapters of rank {rk}, "
-                               f"route={shape.route}", "rotating_sets": sets,
+        "config": {"workload": wname, "rotating_sets": sets,
+                   "launch": "recorded sequence (HIP graph) per step" if graphs is not None
+                   else "kernel by kernel",
                    "kernel_events_in_timed_region": use_ev},
         "roofline": roof,
+        "latency": latency,
         "layer": {"tflops": work["layer_flops"] / (elapsed / args.steps) / 1e12,
                   "gbs": work["layer_bytes"] / (elapsed / args.steps) / 1e9,
-                  "routed_tokens": n_routed, "touched_adapters": touched},
+                  "routed_tokens": n_routed_all if P > 1 else n_routed_all[0],
+                  "touched_adapters": touched_all if P > 1 else touched_all[0]},
         "breakdown_us": breakdown,
     }
     if not args.no_cpu_baseline:
-        out["cpu_baseline"] = cpu_baseline(wl_mod, shape)
+        if P == 1:
+            out["cpu_baseline"] = cpu_baseline(wl_mod, shapes[0])
+        else:  # the same bounded sample of tokens through every projection
+            parts = [cpu_baseline(wl_mod, sh, budget_flops=2.5e11) for sh in shapes]
+            n_s = min(int(p["value"] * p["seconds"] + 0.5) for p in parts)
+            secs = sum(n_s / p["value"] for p in parts)
+            out["cpu_baseline"] = {"value": n_s / secs, "unit": "tokens/s", "cores": parts[0]["cores"],
+                                   "kind": "oracle", "seconds": secs,
+                                   "sample": f"{n_s} tokens per projection (rates of the per-projection "
+                                             f"samples combined), route+bucket+apply, seven projections"}
     print(json.dumps(out))
 
 

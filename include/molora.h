@@ -163,6 +163,26 @@ molora_status molora_base_expand(const void *x, const void *W, const void *B, co
                                  int64_t N, int32_t d_in, int32_t d_out, int32_t C, int32_t rank,
                                  void *stream);
 
+/*
+ * Replayable launch sequences (Sec. "CUDA Graph Compatibility": fixed shapes and fixed
+ * addresses allow a serving step to be recorded once and replayed).
+ *
+ * molora_graph_begin puts `stream` (a hipStream_t other than the null stream) into capture
+ * mode; every molora_* call issued on that stream until molora_graph_end is recorded instead
+ * of executed (all of them are capturable: no allocation, no synchronisation, no host read of
+ * device memory).  molora_graph_end stops the capture and returns an executable graph, owned
+ * by the caller, in *graph (NULL on error).  molora_graph_launch replays it on `stream`
+ * (asynchronous, any stream of the same device); the recorded calls read and write the same
+ * device addresses as at capture time, so the caller refreshes inputs in place.
+ * molora_graph_destroy frees the graph (NULL is ignored; the graph must not be running).
+ * Errors: MOLORA_EINVAL for NULL arguments, MOLORA_EHIP when the runtime refuses.
+ */
+typedef struct molora_graph molora_graph;
+molora_status molora_graph_begin(void *stream);
+molora_status molora_graph_end(void *stream, molora_graph **graph);
+molora_status molora_graph_launch(molora_graph *graph, void *stream);
+void molora_graph_destroy(molora_graph *graph);
+
 /* Human-readable name of a status code (static storage, never NULL). */
 const char *molora_status_string(molora_status status);
 

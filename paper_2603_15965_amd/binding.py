@@ -15,6 +15,7 @@ LIB_PATH = os.path.join(_HERE, "libmolora.so")
 MOLORA_OK = 0
 EXPORTS = ["molora_route", "molora_route_vocab", "molora_bucket", "molora_apply_workspace_bytes",
            "molora_apply", "molora_apply_bucketed", "molora_shrink", "molora_base_expand",
+           "molora_graph_begin", "molora_graph_end", "molora_graph_launch", "molora_graph_destroy",
            "molora_status_string", "molora_version"]
 
 _lib = None
@@ -53,6 +54,14 @@ def load():
     lib.molora_shrink.restype = ctypes.c_int
     lib.molora_base_expand.argtypes = [vp, vp, vp, vp, vp, vp, vp, i64, i32, i32, i32, i32, vp]
     lib.molora_base_expand.restype = ctypes.c_int
+    lib.molora_graph_begin.argtypes = [vp]
+    lib.molora_graph_begin.restype = ctypes.c_int
+    lib.molora_graph_end.argtypes = [vp, ctypes.POINTER(vp)]
+    lib.molora_graph_end.restype = ctypes.c_int
+    lib.molora_graph_launch.argtypes = [vp, vp]
+    lib.molora_graph_launch.restype = ctypes.c_int
+    lib.molora_graph_destroy.argtypes = [vp]
+    lib.molora_graph_destroy.restype = None
     lib.molora_status_string.argtypes = [ctypes.c_int]
     lib.molora_status_string.restype = ctypes.c_char_p
     lib.molora_version.argtypes = []
@@ -219,3 +228,47 @@ def bf16_tensor(bits, device="cuda"):
     import numpy as np
     t = torch.from_numpy(np.ascontiguousarray(bits).view(np.int16))
     return t.to(device).view(torch.bfloat16)
+
+
+class Graph:
+    """A recorded sequence of molora_* calls.
+
+        g = Graph(stream)            # a torch.cuda.Stream other than the default one
+        with g.capture():
+            molora_route(..., stream=stream); molora_bucket(..., stream=stream); ...
+        g.launch()                   # replays on `stream`
+    """
+
+    def __init__(self, stream):
+        self.stream = stream
+        self._handle = None
+
+    def capture(self):
+        graph = self
+
+        class _Capture:
+            def __enter__(self):
+                _check(load().molora_graph_begin(_stream(graph.stream)), "molora_graph_begin")
+
+            def __exit__(self, et, ev, tb):
+                h = ctypes.c_void_p()
+                st = load().molora_graph_end(_stream(graph.stream), ctypes.byref(h))
+                if et is None:
+                    _check(st, "molora_graph_end")
+                    graph._handle = h
+                elif st == MOLORA_OK:
+                    load().molora_graph_destroy(h)
+                return False
+
+        return _Capture()
+
+    def launch(self, stream=None):
+        if self._handle is None:
+            raise RuntimeError("nothing captured")
+        _check(load().molora_graph_launch(self._handle, _stream(stream or self.stream)),
+               "molora_graph_launch")
+
+    def destroy(self):
+        if self._handle is not None:
+            load().molora_graph_destroy(self._handle)
+            self._handle = None

@@ -454,9 +454,10 @@ hipError_t launch_cfg(const uint16_t *x, const uint16_t *W, const uint16_t *B, c
                       const int32_t *offsets, const int32_t *perm, float *h, int64_t N, int d_in,
                       int d_out, int C, int rank, hipStream_t s) {
     auto kern = fused_gemm_kernel<Cfg>;
-    hipError_t e = hipFuncSetAttribute((const void *)kern,
-                                       hipFuncAttributeMaxDynamicSharedMemorySize,
-                                       (int)Cfg::LDS_BYTES);
+    // once per kernel: more than 64 KB of dynamic LDS has to be asked for
+    static const hipError_t e = hipFuncSetAttribute((const void *)kern,
+                                                    hipFuncAttributeMaxDynamicSharedMemorySize,
+                                                    (int)Cfg::LDS_BYTES);
     if (e != hipSuccess) return e;
     const int tiles_m = (int)((N + Cfg::BM - 1) / Cfg::BM);
     const int tiles_n = (d_out + Cfg::BN - 1) / Cfg::BN;

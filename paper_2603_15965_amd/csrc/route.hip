@@ -284,10 +284,9 @@ hipError_t launch_cfg(const uint16_t *x, const uint16_t *G, int32_t *r, int64_t 
                       hipStream_t s) {
     using K = RouteCfg<NB, TB, TGW>;
     auto kern = route_gate_kernel<NB, TB, TGW, VEC8>;
-    if (K::LDS_BYTES > 64 * 1024) {
-        hipError_t e = hipFuncSetAttribute((const void *)kern,
-                                           hipFuncAttributeMaxDynamicSharedMemorySize,
-                                           (int)K::LDS_BYTES);
+    if (K::LDS_BYTES > 64 * 1024) {  // once per kernel
+        static const hipError_t e = hipFuncSetAttribute(
+            (const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)K::LDS_BYTES);
         if (e != hipSuccess) return e;
     }
     const unsigned blocks = (unsigned)((N + K::TOK_WG - 1) / K::TOK_WG);

@@ -339,9 +339,10 @@ hipError_t launch_small(const uint16_t *x, const uint16_t *W, const uint16_t *B,
                         const int32_t *offsets, const int32_t *perm, float *h, uint16_t *t_out, int N,
                         int d_in, int d_out, int C, int rank, hipStream_t s) {
     auto kern = small_batch_kernel<TM, SHRINK>;
-    hipError_t e = hipFuncSetAttribute((const void *)kern,
-                                       hipFuncAttributeMaxDynamicSharedMemorySize,
-                                       (int)kSbLdsBytes);
+    // once per kernel: more than 64 KB of dynamic LDS has to be asked for
+    static const hipError_t e = hipFuncSetAttribute((const void *)kern,
+                                                    hipFuncAttributeMaxDynamicSharedMemorySize,
+                                                    (int)kSbLdsBytes);
     if (e != hipSuccess) return e;
     const unsigned groups = (unsigned)((d_out + kSbCols - 1) / kSbCols);
     hipLaunchKernelGGL(kern, dim3(groups, SHRINK ? C : 1), dim3(kSbWaves * 64), kSbLdsBytes, s, x, W,

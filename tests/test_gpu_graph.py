@@ -1,0 +1,71 @@
+"""Recorded launch sequences (Sec. "CUDA Graph Compatibility"): a captured route -> bucket ->
+apply step must give, on every replay and with refreshed inputs, what the eager calls give,
+and what the oracle gives."""
+import numpy as np
+import pytest
+
+from paper_2603_15965_amd import workloads as wl
+
+pytestmark = pytest.mark.gpu
+
+
+def _setup(w):
+    import torch
+    from paper_2603_15965_amd import binding as mb
+    shape = w.shape
+    d = dict(x=mb.bf16_tensor(w.x), W=mb.bf16_tensor(w.W), A=mb.bf16_tensor(w.A), B=mb.bf16_tensor(w.B),
+             G=mb.bf16_tensor(w.G))
+    N, C = shape.N, shape.C
+    d["r"] = torch.empty(N, dtype=torch.int32, device="cuda")
+    d["offsets"] = torch.empty(C + 1, dtype=torch.int32, device="cuda")
+    d["perm"] = torch.empty(N, dtype=torch.int32, device="cuda")
+    d["h"] = torch.empty((N, shape.d_out), dtype=torch.float32, device="cuda")
+    d["ws"] = mb.new_workspace(N, shape.d_in, shape.d_out, C, shape.rank)
+    return d
+
+
+@pytest.mark.parametrize("N", [300, 48])
+def test_captured_step_replays(N):
+    import torch
+    import oracle
+    from paper_2603_15965_amd import binding as mb
+    import gpu_helpers as gpu
+    print(f"graph replay N={N}", flush=True)
+    w = wl.custom("graph_step", N, 512, 384, 5, 16, wl.BASE_SEED + 7700 + N, route="gate")
+    shape = w.shape
+    d = _setup(w)
+    side = torch.cuda.Stream()
+
+    def step(stream):
+        mb.molora_route(d["x"], d["G"], d["r"], stream=stream)
+        mb.molora_bucket(d["r"], shape.C, d["offsets"], d["perm"], stream=stream)
+        mb.molora_apply_bucketed(d["x"], d["W"], d["A"], d["B"], d["offsets"], d["perm"], d["h"],
+                                 workspace=d["ws"], stream=stream)
+
+    torch.cuda.synchronize()
+    g = mb.Graph(side)
+    with g.capture():
+        step(side)
+    rng = np.random.default_rng(5)
+    x_bits = w.x
+    for replay in range(4):
+        # eager work and a synchronisation between replays; inputs refreshed in place
+        if replay > 0:
+            x_bits = w.x[rng.permutation(N)]
+            d["x"].copy_(mb.bf16_tensor(x_bits))
+        d["h"].zero_()
+        d["r"].fill_(-7)
+        torch.cuda.synchronize()
+        g.launch()
+        side.synchronize()
+        r_gpu = d["r"].cpu().numpy()
+        h_gpu = d["h"].cpu().numpy()
+        r_ref = oracle.route_gate(x_bits, w.G)
+        assert np.array_equal(r_gpu, r_ref), f"replay {replay}"
+        gpu.assert_h_close(h_gpu, oracle.apply(x_bits, w.W, w.A, w.B, r_ref), f"replay {replay}")
+        # the eager path on the same inputs gives the same bits
+        d["h"].zero_()
+        step(None)
+        torch.cuda.synchronize()
+        assert np.array_equal(d["h"].cpu().numpy(), h_gpu), f"replay {replay} vs eager"
+    g.destroy()
