@@ -4,7 +4,7 @@ import subprocess
 import sys
 
 HERE = os.path.dirname(os.path.abspath(__file__))
-SRC = os.path.join(HERE, "molora_oracle.c")
+SRCS = [os.path.join(HERE, "molora_oracle.c"), os.path.join(HERE, "molora_oracle_mix.c")]
 LIB = os.path.join(HERE, "libmolora_oracle.so")
 
 # -ffp-contract=off / no fast-math: the loops' written summation order is the order run.
@@ -14,9 +14,9 @@ CFLAGS = ["-O3", "-std=c11", "-fPIC", "-shared", "-fopenmp", "-ffp-contract=off"
 
 
 def build(force=True):
-    if not force and os.path.exists(LIB) and os.path.getmtime(LIB) >= os.path.getmtime(SRC):
+    if not force and os.path.exists(LIB) and os.path.getmtime(LIB) >= max(os.path.getmtime(f) for f in SRCS):
         return LIB
-    cmd = ["gcc", *CFLAGS, SRC, "-o", LIB, "-lm"]
+    cmd = ["gcc", *CFLAGS, *SRCS, "-o", LIB, "-lm"]
     subprocess.run(cmd, check=True)
     return LIB
 

@@ -32,6 +32,19 @@ def _lib():
         lib.oracle_bucket.restype = i64
         lib.oracle_apply_rows.argtypes = [vp, vp, vp, vp, vp, vp, i64, vp, i64, i32, i32, i32, i32]
         lib.oracle_apply_rows.restype = ctypes.c_int
+        f32 = ctypes.c_float
+        lib.oracle_expf.argtypes = [f32]
+        lib.oracle_expf.restype = f32
+        lib.oracle_gelu.argtypes = [f32]
+        lib.oracle_gelu.restype = f32
+        lib.oracle_mlp_logits.argtypes = [vp, vp, vp, vp, vp, vp, i64, i32, i32, i32]
+        lib.oracle_mlp_logits.restype = ctypes.c_int
+        lib.oracle_topk_softmax.argtypes = [vp, vp, vp, i64, i32, i32]
+        lib.oracle_topk_softmax.restype = None
+        lib.oracle_apply_mix.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, i64, i32, i32, i32, i32, i32]
+        lib.oracle_apply_mix.restype = ctypes.c_int
+        lib.oracle_route_compose.argtypes = [vp, vp, vp, i32, i32, vp, i64]
+        lib.oracle_route_compose.restype = None
         lib.oracle_num_threads.argtypes = []
         lib.oracle_num_threads.restype = ctypes.c_int
         _LIB = lib
@@ -132,3 +145,88 @@ def apply_rows(x_bits, W_bits, A_bits, B_bits, r, rows=None):
 
 def apply(x_bits, W_bits, A_bits, B_bits, r):
     return apply_rows(x_bits, W_bits, A_bits, B_bits, r, None)
+
+
+def expf(y):
+    return float(_lib().oracle_expf(float(y)))
+
+
+def gelu(u):
+    return float(_lib().oracle_gelu(float(u)))
+
+
+def mlp_logits(x_bits, W1_bits, b1, W2_bits, b2):
+    """Router logits W2^T GELU(W1^T x + b1) + b2, fp32 [N][K]."""
+    x = _c(x_bits, np.uint16)
+    N, d = x.shape
+    W1 = _c(W1_bits, np.uint16)
+    H = W1.shape[1]
+    if W1.shape[0] != d:
+        raise ValueError("W1 must be [d][H]")
+    W2 = _c(W2_bits, np.uint16)
+    K = W2.shape[1]
+    if W2.shape[0] != H:
+        raise ValueError("W2 must be [H][K]")
+    b1 = _c(b1, np.float32, (H,))
+    b2 = _c(b2, np.float32, (K,))
+    logits = np.empty((N, K), dtype=np.float32)
+    if _lib().oracle_mlp_logits(_p(x), _p(W1), _p(b1), _p(W2), _p(b2), _p(logits), N, d, H, K) != 0:
+        raise MemoryError
+    return logits
+
+
+def topk_softmax(logits, k):
+    """(idx [N][k] int32 in descending logit order, w [N][k] fp32 softmax over the selected)."""
+    l = _c(logits, np.float32)
+    N, K = l.shape
+    if not 1 <= k <= K:
+        raise ValueError("k must be in [1, K]")
+    idx = np.empty((N, k), dtype=np.int32)
+    w = np.empty((N, k), dtype=np.float32)
+    _lib().oracle_topk_softmax(_p(l), _p(idx), _p(w), N, K, k)
+    return idx, w
+
+
+def apply_mix(x_bits, W_bits, A_bits, B_bits, idx, w=None, slots=None, C=None):
+    """h_i = x_i W + sum_j w_ij (x_i A_s) B_s, s = slots[idx_ij] (slots None: s = idx_ij).
+    A, B are pools [S][...]; C (number of targets) defaults to S."""
+    x = _c(x_bits, np.uint16)
+    N, d_in = x.shape
+    W = _c(W_bits, np.uint16)
+    d_out = W.shape[1]
+    A = _c(A_bits, np.uint16)
+    S, _, rank = A.shape
+    B = _c(B_bits, np.uint16, (S, rank, d_out))
+    idx = _c(idx, np.int32)
+    if idx.ndim == 1:
+        idx = idx.reshape(N, 1)
+    k = idx.shape[1]
+    wp = None
+    if w is not None:
+        w = _c(w, np.float32, (N, k))
+        wp = _p(w)
+    sp = None
+    if slots is not None:
+        slots = _c(slots, np.int32)
+        if slots.size and (slots.min() < 0 or slots.max() >= S):
+            raise ValueError("slot out of range")
+        sp = _p(slots)
+        C = slots.shape[0] if C is None else C
+    C = S if C is None else C
+    h = np.empty((N, d_out), dtype=np.float32)
+    if _lib().oracle_apply_mix(_p(x), _p(W), _p(A), _p(B), _p(idx), wp, sp, _p(h), N, d_in, d_out,
+                               C, rank, k) != 0:
+        raise MemoryError
+    return h
+
+
+def route_compose(v, adapter, breaks, n_adapters):
+    """c = adapter * M + modality(v); -1 when either part is out of range."""
+    v = _c(v, np.int32)
+    N = v.shape[0]
+    adapter = _c(adapter, np.int32, (N,))
+    b = _c(breaks, np.int32)
+    M = b.shape[0] - 1
+    r = np.empty(N, dtype=np.int32)
+    _lib().oracle_route_compose(_p(v), _p(adapter), _p(b), M, n_adapters, _p(r), N)
+    return r
