@@ -57,6 +57,8 @@ enum {
 #define MOLORA_MAX_TARGETS 1024 /* C                                   */
 #define MOLORA_MAX_RANK 128     /* rank, which must be a multiple of 8 */
 #define MOLORA_MAX_BREAKS 64    /* M of molora_route_vocab             */
+#define MOLORA_MAX_HIDDEN 256   /* H of molora_route_mlp, a multiple of 8 */
+#define MOLORA_MAX_TOPK 4       /* k of molora_route_mlp / molora_apply_mix */
 
 /*
  * Learned routing with one selected adapter per token (Sec. "Router Architecture"
@@ -162,6 +164,62 @@ molora_status molora_base_expand(const void *x, const void *W, const void *B, co
                                  const int32_t *offsets, const int32_t *perm, float *h,
                                  int64_t N, int32_t d_in, int32_t d_out, int32_t C, int32_t rank,
                                  void *stream);
+
+/*
+ * Learned router with top-k selection (Sec. "Router Architecture"):
+ *
+ *     logits_i = W2^T GELU(W1^T x_i + b1) + b2,   idx_i = TopK(logits_i, k),
+ *     w_i = softmax(logits_i[idx_i])
+ *
+ * x [N][d_in], W1 [d_in][H], W2 [H][K] bf16 device pointers; b1 [H], b2 [K] fp32 device
+ * pointers; idx [N][k] int32 and w [N][k] fp32 device outputs, the selected targets in
+ * descending order of their logit (lowest index first among equal logits) and their mixture
+ * weights.  H (a multiple of 8, <= MOLORA_MAX_HIDDEN) is 64 in the paper; K <=
+ * MOLORA_MAX_TARGETS; 1 <= k <= min(K, MOLORA_MAX_TOPK).  Arithmetic: fp32 throughout, every
+ * sum sequential in ascending index order with the bias added last, GELU in its exact erf form
+ * evaluated by a fixed sequence of fp32 operations (so the selection is reproducible bit for
+ * bit).  workspace: device scratch of molora_route_mlp_workspace_bytes(N, H) bytes, 256-byte
+ * aligned, owned by the caller (holds the hidden pre-activations).  Errors as molora_apply.
+ */
+size_t molora_route_mlp_workspace_bytes(int64_t N, int32_t H);
+molora_status molora_route_mlp(const void *x, const void *W1, const float *b1, const void *W2,
+                               const float *b2, int32_t *idx, float *w, int64_t N, int32_t d_in,
+                               int32_t H, int32_t K, int32_t k, void *workspace,
+                               size_t workspace_bytes, void *stream);
+
+/*
+ * Compositional gating (Alg. "Compositional Gating Kernel"): the composite target of token i
+ * is  r[i] = adapter[i] * M + m,  m the modality of vocabulary index v[i] as in
+ * molora_route_vocab (breaks: HOST pointer to M + 1 ascending ints), adapter[i] the slot of
+ * the request the token belongs to.  r[i] = -1 when v[i] is outside [breaks[0], breaks[M]) or
+ * adapter[i] outside [0, n_adapters).  v, adapter, r: device int32 [N];
+ * n_adapters * M <= MOLORA_MAX_TARGETS.  With the hot-set layout A [S][M][d][r] the composite
+ * target indexes the flattened pool directly.
+ */
+molora_status molora_route_compose(const int32_t *v, const int32_t *adapter, const int32_t *breaks,
+                                   int32_t M, int32_t n_adapters, int32_t *r, int64_t N,
+                                   void *stream);
+
+/*
+ * Weighted top-k mixture with an optional slot table (Sec. "Router Architecture", Def.
+ * "Hot-Set Layout"):
+ *
+ *     h[i][:] = x[i] W + sum_{j<k} w[i][j] (x[i] A_s) B_s,   s = slots[idx[i][j]]
+ *
+ * idx [N][k] int32 targets in [0, C) (an entry outside contributes nothing); w [N][k] fp32
+ * weights (NULL: all 1); slots [C] int32 device table from target to position in the pools
+ * A [S][d_in][rank], B [S][rank][d_out] (NULL: position = target; the caller guarantees
+ * 0 <= slots[c] < S).  Tokens are grouped by their tuple of targets, so C^k must not exceed
+ * MOLORA_MAX_TARGETS and k * rank must not exceed MOLORA_MAX_RANK; k <= MOLORA_MAX_TOPK.
+ * k = 1, w = NULL, slots = NULL is molora_apply.  workspace as for molora_apply, of
+ * molora_apply_mix_workspace_bytes(...) bytes.  Errors as molora_apply.
+ */
+size_t molora_apply_mix_workspace_bytes(int64_t N, int32_t d_in, int32_t d_out, int32_t C,
+                                        int32_t rank, int32_t k);
+molora_status molora_apply_mix(const void *x, const void *W, const void *A, const void *B,
+                               const int32_t *idx, const float *w, const int32_t *slots, float *h,
+                               int64_t N, int32_t d_in, int32_t d_out, int32_t C, int32_t rank,
+                               int32_t k, void *workspace, size_t workspace_bytes, void *stream);
 
 /*
  * Replayable launch sequences (Sec. "CUDA Graph Compatibility": fixed shapes and fixed

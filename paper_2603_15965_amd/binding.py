@@ -15,6 +15,8 @@ LIB_PATH = os.path.join(_HERE, "libmolora.so")
 MOLORA_OK = 0
 EXPORTS = ["molora_route", "molora_route_vocab", "molora_bucket", "molora_apply_workspace_bytes",
            "molora_apply", "molora_apply_bucketed", "molora_shrink", "molora_base_expand",
+           "molora_route_mlp_workspace_bytes", "molora_route_mlp", "molora_route_compose",
+           "molora_apply_mix_workspace_bytes", "molora_apply_mix",
            "molora_graph_begin", "molora_graph_end", "molora_graph_launch", "molora_graph_destroy",
            "molora_status_string", "molora_version"]
 
@@ -54,6 +56,16 @@ def load():
     lib.molora_shrink.restype = ctypes.c_int
     lib.molora_base_expand.argtypes = [vp, vp, vp, vp, vp, vp, vp, i64, i32, i32, i32, i32, vp]
     lib.molora_base_expand.restype = ctypes.c_int
+    lib.molora_route_mlp_workspace_bytes.argtypes = [i64, i32]
+    lib.molora_route_mlp_workspace_bytes.restype = sz
+    lib.molora_route_mlp.argtypes = [vp, vp, vp, vp, vp, vp, vp, i64, i32, i32, i32, i32, vp, sz, vp]
+    lib.molora_route_mlp.restype = ctypes.c_int
+    lib.molora_route_compose.argtypes = [vp, vp, ctypes.POINTER(i32), i32, i32, vp, i64, vp]
+    lib.molora_route_compose.restype = ctypes.c_int
+    lib.molora_apply_mix_workspace_bytes.argtypes = [i64, i32, i32, i32, i32, i32]
+    lib.molora_apply_mix_workspace_bytes.restype = sz
+    lib.molora_apply_mix.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, i64, i32, i32, i32, i32, i32, vp, sz, vp]
+    lib.molora_apply_mix.restype = ctypes.c_int
     lib.molora_graph_begin.argtypes = [vp]
     lib.molora_graph_begin.restype = ctypes.c_int
     lib.molora_graph_end.argtypes = [vp, ctypes.POINTER(vp)]
@@ -228,6 +240,67 @@ def bf16_tensor(bits, device="cuda"):
     import numpy as np
     t = torch.from_numpy(np.ascontiguousarray(bits).view(np.int16))
     return t.to(device).view(torch.bfloat16)
+
+
+def molora_route_mlp(x, W1, b1, W2, b2, k, idx=None, w=None, workspace=None, stream=None):
+    """Router MLP + top-k + softmax: returns (idx [N][k] int32, w [N][k] fp32)."""
+    N, d_in = x.shape
+    H, K = W2.shape
+    if W1.shape != (d_in, H):
+        raise ValueError("W1 must be [d_in][H]")
+    if idx is None:
+        idx = torch.empty((N, k), dtype=torch.int32, device=x.device)
+    if w is None:
+        w = torch.empty((N, k), dtype=torch.float32, device=x.device)
+    if workspace is None:
+        nbytes = int(load().molora_route_mlp_workspace_bytes(N, H))
+        workspace = torch.empty(max(nbytes, 256), dtype=torch.uint8, device=x.device)
+    bf = torch.bfloat16
+    st = load().molora_route_mlp(_dev(x, bf, "x"), _dev(W1, bf, "W1"), _dev(b1, torch.float32, "b1"),
+                                 _dev(W2, bf, "W2"), _dev(b2, torch.float32, "b2"),
+                                 _dev(idx, torch.int32, "idx"), _dev(w, torch.float32, "w"),
+                                 N, d_in, H, K, k, _dev(workspace, torch.uint8, "workspace"),
+                                 workspace.numel(), _stream(stream))
+    _check(st, "molora_route_mlp")
+    return idx, w
+
+
+def molora_route_compose(v, adapter, breaks, n_adapters, r=None, stream=None):
+    """r[i] = adapter[i] * M + modality(v[i]), -1 when either part is out of range."""
+    N = v.shape[0]
+    b = [int(t) for t in breaks]
+    M = len(b) - 1
+    arr = (ctypes.c_int32 * len(b))(*b)
+    if r is None:
+        r = torch.empty(N, dtype=torch.int32, device=v.device)
+    st = load().molora_route_compose(_dev(v, torch.int32, "v"), _dev(adapter, torch.int32, "adapter"),
+                                     arr, M, n_adapters, _dev(r, torch.int32, "r"), N, _stream(stream))
+    _check(st, "molora_route_compose")
+    return r
+
+
+def molora_apply_mix(x, W, A, B, idx, w=None, slots=None, C=None, h=None, workspace=None, stream=None):
+    """h[i] = x[i] W + sum_j w[i][j] (x[i] A_s) B_s, s = slots[idx[i][j]] (slots None: idx)."""
+    N, d_in, d_out, S, rank = _shapes(x, W, A, B)
+    if idx.dim() == 1:
+        idx = idx.reshape(N, 1)
+    k = idx.shape[1]
+    if C is None:
+        C = S if slots is None else slots.shape[0]
+    if h is None:
+        h = torch.empty((N, d_out), dtype=torch.float32, device=x.device)
+    if workspace is None:
+        nbytes = int(load().molora_apply_mix_workspace_bytes(N, d_in, d_out, C, rank, k))
+        workspace = torch.empty(max(nbytes, 256), dtype=torch.uint8, device=x.device)
+    bf = torch.bfloat16
+    st = load().molora_apply_mix(
+        _dev(x, bf, "x"), _dev(W, bf, "W"), _dev(A, bf, "A"), _dev(B, bf, "B"),
+        _dev(idx, torch.int32, "idx"), None if w is None else _dev(w, torch.float32, "w"),
+        None if slots is None else _dev(slots, torch.int32, "slots"), _dev(h, torch.float32, "h"),
+        N, d_in, d_out, C, rank, k, _dev(workspace, torch.uint8, "workspace"), workspace.numel(),
+        _stream(stream))
+    _check(st, "molora_apply_mix")
+    return h
 
 
 class Graph:

@@ -62,12 +62,13 @@ molora_status apply_common(const void *x, const void *W, const void *A, const vo
         offsets = ws.offsets;
         perm = ws.perm;
     }
+    const molora::Mix plain{1, C, nullptr, nullptr};
     e = molora::launch_shrink(xb, static_cast<const uint16_t *>(A), offsets, perm, ws.t2, N, d_in,
-                              C, rank, s);
+                              C, rank, plain, s);
     if (e != hipSuccess) return MOLORA_EHIP;
     e = molora::launch_fused_gemm(xb, static_cast<const uint16_t *>(W),
                                   static_cast<const uint16_t *>(B), ws.t2, offsets, perm, h, N,
-                                  d_in, d_out, C, rank, s);
+                                  d_in, d_out, C, rank, plain, s);
     return from_hip(e);
 }
 
@@ -84,7 +85,7 @@ molora_status molora_route(const void *x, const void *G, int32_t *r, int64_t N, 
     if (!x || !G || !r) return MOLORA_EINVAL;
     if (!aligned16(x) || !aligned16(G) || !aligned16(r)) return MOLORA_EALIGN;
     return from_hip(molora::launch_route_gate(static_cast<const uint16_t *>(x),
-                                              static_cast<const uint16_t *>(G), r, N, d_in, C,
+                                              static_cast<const uint16_t *>(G), r, nullptr, N, d_in, C,
                                               static_cast<hipStream_t>(stream)));
 }
 
@@ -144,6 +145,7 @@ molora_status molora_shrink(const void *x, const void *A, const int32_t *offsets
     return from_hip(molora::launch_shrink(static_cast<const uint16_t *>(x),
                                           static_cast<const uint16_t *>(A), offsets, perm,
                                           static_cast<uint16_t *>(t), N, d_in, C, rank,
+                                          molora::Mix{1, C, nullptr, nullptr},
                                           static_cast<hipStream_t>(stream)));
 }
 
@@ -160,7 +162,131 @@ molora_status molora_base_expand(const void *x, const void *W, const void *B, co
     return from_hip(molora::launch_fused_gemm(
         static_cast<const uint16_t *>(x), static_cast<const uint16_t *>(W),
         static_cast<const uint16_t *>(B), static_cast<const uint16_t *>(t), offsets, perm, h, N,
-        d_in, d_out, C, rank, static_cast<hipStream_t>(stream)));
+        d_in, d_out, C, rank, molora::Mix{1, C, nullptr, nullptr}, static_cast<hipStream_t>(stream)));
+}
+
+size_t molora_route_mlp_workspace_bytes(int64_t N, int32_t H) {
+    if (N < 0 || N >= (int64_t(1) << 31) || H < 8 || H % 8 != 0 || H > MOLORA_MAX_HIDDEN) return 0;
+    return round256(size_t(N) * size_t(H) * sizeof(float));
+}
+
+molora_status molora_route_mlp(const void *x, const void *W1, const float *b1, const void *W2,
+                               const float *b2, int32_t *idx, float *w, int64_t N, int32_t d_in,
+                               int32_t H, int32_t K, int32_t k, void *workspace,
+                               size_t workspace_bytes, void *stream) {
+    if (N < 0 || N >= (int64_t(1) << 31) || d_in < 8 || d_in % 8 != 0 || H < 8 || H % 8 != 0 ||
+        H > MOLORA_MAX_HIDDEN || K < 1 || K > MOLORA_MAX_TARGETS || k < 1 || k > MOLORA_MAX_TOPK ||
+        k > K)
+        return MOLORA_EINVAL;
+    if (N == 0) return MOLORA_OK;
+    if (!x || !W1 || !b1 || !W2 || !b2 || !idx || !w || !workspace) return MOLORA_EINVAL;
+    if (!aligned16(x) || !aligned16(W1) || !aligned16(b1) || !aligned16(W2) || !aligned16(b2) ||
+        !aligned16(idx) || !aligned16(w) || !aligned256(workspace))
+        return MOLORA_EALIGN;
+    if (workspace_bytes < molora_route_mlp_workspace_bytes(N, H)) return MOLORA_EWORKSPACE;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    float *u = static_cast<float *>(workspace);
+    hipError_t e = molora::launch_route_gate(static_cast<const uint16_t *>(x),
+                                             static_cast<const uint16_t *>(W1), nullptr, u, N, d_in,
+                                             H, s);
+    if (e != hipSuccess) return MOLORA_EHIP;
+    return from_hip(molora::launch_router_finish(u, b1, static_cast<const uint16_t *>(W2), b2, idx, w,
+                                                 N, H, K, k, s));
+}
+
+molora_status molora_route_compose(const int32_t *v, const int32_t *adapter, const int32_t *breaks,
+                                   int32_t M, int32_t n_adapters, int32_t *r, int64_t N,
+                                   void *stream) {
+    if (N < 0 || N >= (int64_t(1) << 31) || M < 1 || M > MOLORA_MAX_BREAKS || !breaks ||
+        n_adapters < 1 || int64_t(n_adapters) * M > MOLORA_MAX_TARGETS)
+        return MOLORA_EINVAL;
+    for (int j = 0; j < M; ++j)
+        if (breaks[j] >= breaks[j + 1]) return MOLORA_EINVAL;
+    if (N == 0) return MOLORA_OK;
+    if (!v || !adapter || !r) return MOLORA_EINVAL;
+    if (!aligned16(v) || !aligned16(adapter) || !aligned16(r)) return MOLORA_EALIGN;
+    return from_hip(molora::launch_route_compose(v, adapter, breaks, M, n_adapters, r, N,
+                                                 static_cast<hipStream_t>(stream)));
+}
+
+namespace {
+
+// number of tuples C^k, or 0 when it exceeds the bucket limit
+inline int64_t mix_buckets(int32_t C, int32_t k) {
+    int64_t cb = 1;
+    for (int j = 0; j < k; ++j) {
+        cb *= C;
+        if (cb > MOLORA_MAX_TARGETS) return 0;
+    }
+    return cb;
+}
+
+inline bool mix_sizes_ok(int64_t N, int32_t d_in, int32_t d_out, int32_t C, int32_t rank, int32_t k) {
+    return k >= 1 && k <= MOLORA_MAX_TOPK && apply_sizes_ok(N, d_in, d_out, C, rank) &&
+           int64_t(k) * rank <= MOLORA_MAX_RANK && mix_buckets(C, k) > 0;
+}
+
+struct MixWorkspace {
+    int32_t *key;
+    float *wq;
+    int32_t *offsets;
+    int32_t *perm;
+    uint16_t *t2;
+    size_t bytes;
+};
+
+inline MixWorkspace carve_mix(void *base, int64_t N, int32_t C, int32_t rank, int32_t k) {
+    MixWorkspace w;
+    unsigned char *p = static_cast<unsigned char *>(base);
+    size_t off = 0;
+    w.key = reinterpret_cast<int32_t *>(p + off);
+    off += round256(size_t(N) * sizeof(int32_t));
+    w.wq = reinterpret_cast<float *>(p + off);
+    off += round256(size_t(N) * size_t(k) * sizeof(float));
+    w.offsets = reinterpret_cast<int32_t *>(p + off);
+    off += round256(size_t(mix_buckets(C, k) + 1) * sizeof(int32_t));
+    w.perm = reinterpret_cast<int32_t *>(p + off);
+    off += round256(size_t(N) * sizeof(int32_t));
+    w.t2 = reinterpret_cast<uint16_t *>(p + off);
+    off += round256(size_t(N) * 2 * size_t(k) * size_t(rank) * sizeof(uint16_t));
+    w.bytes = off;
+    return w;
+}
+
+}  // namespace
+
+size_t molora_apply_mix_workspace_bytes(int64_t N, int32_t d_in, int32_t d_out, int32_t C,
+                                        int32_t rank, int32_t k) {
+    if (!mix_sizes_ok(N, d_in, d_out, C, rank, k)) return 0;
+    return carve_mix(nullptr, N, C, rank, k).bytes;
+}
+
+molora_status molora_apply_mix(const void *x, const void *W, const void *A, const void *B,
+                               const int32_t *idx, const float *w, const int32_t *slots, float *h,
+                               int64_t N, int32_t d_in, int32_t d_out, int32_t C, int32_t rank,
+                               int32_t k, void *workspace, size_t workspace_bytes, void *stream) {
+    if (!mix_sizes_ok(N, d_in, d_out, C, rank, k)) return MOLORA_EINVAL;
+    if (N == 0) return MOLORA_OK;
+    if (!x || !W || !A || !B || !idx || !h || !workspace) return MOLORA_EINVAL;
+    if (!aligned16(x) || !aligned16(W) || !aligned16(A) || !aligned16(B) || !aligned16(idx) ||
+        (w && !aligned16(w)) || (slots && !aligned16(slots)) || !aligned16(h) ||
+        !aligned256(workspace))
+        return MOLORA_EALIGN;
+    const MixWorkspace ws = carve_mix(workspace, N, C, rank, k);
+    if (workspace_bytes < ws.bytes) return MOLORA_EWORKSPACE;
+    const int Cb = (int)mix_buckets(C, k);
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    const uint16_t *xb = static_cast<const uint16_t *>(x);
+    if (molora::launch_mix_key(idx, w, ws.key, ws.wq, N, C, k, s) != hipSuccess) return MOLORA_EHIP;
+    if (molora::launch_bucket(ws.key, ws.offsets, ws.perm, N, Cb, nullptr, s) != hipSuccess)
+        return MOLORA_EHIP;
+    const molora::Mix mix{k, C, slots, ws.wq};
+    if (molora::launch_shrink(xb, static_cast<const uint16_t *>(A), ws.offsets, ws.perm, ws.t2, N,
+                              d_in, Cb, rank, mix, s) != hipSuccess)
+        return MOLORA_EHIP;
+    return from_hip(molora::launch_fused_gemm(xb, static_cast<const uint16_t *>(W),
+                                              static_cast<const uint16_t *>(B), ws.t2, ws.offsets,
+                                              ws.perm, h, N, d_in, d_out, Cb, rank, mix, s));
 }
 
 const char *molora_status_string(molora_status status) {

@@ -32,28 +32,60 @@ __device__ __forceinline__ i16x4 lds_read_tr16(const MOLORA_LDS void *p) {
     return __builtin_amdgcn_ds_read_tr16_b64_v4i16((MOLORA_LDS i16x4 *)p);
 }
 
+// How a bucket maps to adapters (weighted top-k mixture of Sec. "Router Architecture", slot
+// table of Def. "Hot-Set Layout").  Bucket b stands for the ordered tuple of k adapters
+// c_j = (b / C^j) % C, j < k; adapter c lives in position slots[c] of the A / B pools
+// (slots == nullptr: position c).  The low-rank intermediate of a bucket is k * rank wide,
+// piece j scaled by w[token * k + j] (w == nullptr: 1).  {1, C, nullptr, nullptr} is the plain
+// one-adapter-per-token case.
+struct Mix {
+    int k;
+    int C;
+    const int32_t *slots;
+    const float *w;
+};
+__device__ __forceinline__ int mix_adapter(const Mix &m, int b, int j) {
+    int c = b;
+    if (m.k > 1) {
+        for (int i = 0; i < j; ++i) c /= m.C;
+        c %= m.C;
+    }
+    return m.slots != nullptr ? m.slots[c] : c;
+}
+
 // ---- launchers implemented in the kernel translation units (all asynchronous) ----
-hipError_t launch_route_gate(const uint16_t *x, const uint16_t *G, int32_t *r, int64_t N,
-                             int d_in, int C, hipStream_t s);
+// rank is the rank of one adapter; buckets number C (the tuples, when mix.k > 1)
+// r and logits_out (fp32 [N][C], the chains themselves) are each optional
+hipError_t launch_route_gate(const uint16_t *x, const uint16_t *G, int32_t *r, float *logits_out,
+                             int64_t N, int d_in, int C, hipStream_t s);
+// second half of the router MLP: u [N][H] = x W1 (fp32 chains) -> idx [N][k], w [N][k]
+hipError_t launch_router_finish(const float *u, const float *b1, const uint16_t *W2, const float *b2,
+                                int32_t *idx, float *w, int64_t N, int H, int K, int k, hipStream_t s);
+// key[i] = sum_j idx[i][j] C^j and wq[i][j] = w[i][j] (1 if w == nullptr), with an index outside
+// [0, C) replaced by adapter 0 at weight 0
+hipError_t launch_mix_key(const int32_t *idx, const float *w, int32_t *key, float *wq, int64_t N,
+                          int C, int k, hipStream_t s);
+hipError_t launch_route_compose(const int32_t *v, const int32_t *adapter, const int32_t *breaks_host,
+                                int M, int n_adapters, int32_t *r, int64_t N, hipStream_t s);
 hipError_t launch_route_vocab(const int32_t *v, const int32_t *breaks_host, int M, int32_t *r,
                               int64_t N, hipStream_t s);
 hipError_t launch_bucket(const int32_t *r, int32_t *offsets, int32_t *perm, int64_t N, int C,
                          int32_t *err_flag, hipStream_t s);
 hipError_t launch_shrink(const uint16_t *x, const uint16_t *A, const int32_t *offsets,
                          const int32_t *perm, uint16_t *t2, int64_t N, int d_in, int C, int rank,
-                         hipStream_t s);
+                         Mix mix, hipStream_t s);
 hipError_t launch_fused_gemm(const uint16_t *x, const uint16_t *W, const uint16_t *B,
                              const uint16_t *t2, const int32_t *offsets, const int32_t *perm,
-                             float *h, int64_t N, int d_in, int d_out, int C, int rank,
+                             float *h, int64_t N, int d_in, int d_out, int C, int rank, Mix mix,
                              hipStream_t s);
 
 // same contract, N <= 64 (the fused GEMM launcher routes such batches here)
 hipError_t launch_small_batch_gemm(const uint16_t *x, const uint16_t *W, const uint16_t *B,
                                    const uint16_t *t2, const int32_t *offsets, const int32_t *perm,
-                                   float *h, int64_t N, int d_in, int d_out, int C, int rank,
+                                   float *h, int64_t N, int d_in, int d_out, int C, int rank, Mix mix,
                                    hipStream_t s);
 hipError_t launch_small_batch_shrink(const uint16_t *x, const uint16_t *A, const int32_t *offsets,
                                      const int32_t *perm, uint16_t *t2, int64_t N, int d_in, int C,
-                                     int rank, hipStream_t s);
+                                     int rank, Mix mix, hipStream_t s);
 
 }  // namespace molora

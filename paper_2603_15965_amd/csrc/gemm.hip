@@ -74,7 +74,7 @@ __global__ __launch_bounds__(Cfg::NT) void fused_gemm_kernel(
     const uint16_t *__restrict__ x, const uint16_t *__restrict__ W, const uint16_t *__restrict__ B,
     const uint16_t *__restrict__ t2, const int32_t *__restrict__ offsets,
     const int32_t *__restrict__ perm, float *__restrict__ h, int N, int d_in, int d_out, int C,
-    int rank, int tiles_m, int tiles_n) {
+    int rank, int tiles_m, int tiles_n, Mix mix) {
     constexpr int BM = Cfg::BM, BN = Cfg::BN, BK = Cfg::BK, NT = Cfg::NT, TM = Cfg::TM,
                   TN = Cfg::TN, STAGES = Cfg::STAGES;
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
@@ -117,7 +117,8 @@ __global__ __launch_bounds__(Cfg::NT) void fused_gemm_kernel(
     }
     __syncthreads();
     const int nseg = *nseg_p;
-    const int two_r = 2 * rank;
+    const int R = mix.k * rank;  // width of a bucket's intermediate (k adapters side by side)
+    const int two_r = 2 * R;
     const int tps = (two_r + BK - 1) / BK;  // extra K tiles per bucket
     const int nkf = d_in / BK;              // full K tiles
     const int nkb = (d_in + BK - 1) / BK;   // K tiles of x.W, the last one possibly partial
@@ -205,7 +206,6 @@ __global__ __launch_bounds__(Cfg::NT) void fused_gemm_kernel(
         const int e = T - nkb;
         const int sg = e / tps, sub = e % tps;
         const int c = seg_c[sg], lo = seg_lo[sg], hi = seg_hi[sg];
-        const uint16_t *Bc = B + (int64_t)c * rank * d_out;
 #pragma unroll
         for (int i = 0; i < Cfg::LPW; ++i) {
             const uint16_t *src;
@@ -216,8 +216,10 @@ __global__ __launch_bounds__(Cfg::NT) void fused_gemm_kernel(
                 src = (p >= lo && p < hi && vk < two_r) ? t2 + (int64_t)p * two_r + vk : zero;
             } else {
                 const int vk = sub * BK + row;
-                const int j = vk < rank ? vk : vk - rank;
-                src = (vk < two_r) ? Bc + (int64_t)j * d_out + col : zero;
+                const int j = vk < R ? vk : vk - R;        // row of the tuple's stacked B
+                const int jj = mix.k > 1 ? j / rank : 0;   // which adapter of the tuple
+                const int64_t brow = (int64_t)mix_adapter(mix, c, jj) * rank + (j - jj * rank);
+                src = (vk < two_r) ? B + brow * d_out + col : zero;
             }
             load_to_lds16_ptr(src, stage + piece_of(i) * 1024);
         }
@@ -452,7 +454,7 @@ __global__ __launch_bounds__(Cfg::NT) void fused_gemm_kernel(
 template <class Cfg>
 hipError_t launch_cfg(const uint16_t *x, const uint16_t *W, const uint16_t *B, const uint16_t *t2,
                       const int32_t *offsets, const int32_t *perm, float *h, int64_t N, int d_in,
-                      int d_out, int C, int rank, hipStream_t s) {
+                      int d_out, int C, int rank, Mix mix, hipStream_t s) {
     auto kern = fused_gemm_kernel<Cfg>;
     // once per kernel: more than 64 KB of dynamic LDS has to be asked for
     static const hipError_t e = hipFuncSetAttribute((const void *)kern,
@@ -464,7 +466,7 @@ hipError_t launch_cfg(const uint16_t *x, const uint16_t *W, const uint16_t *B, c
     const int total = tiles_m * tiles_n;
     const unsigned blocks = (unsigned)(((total + 7) / 8) * 8);
     hipLaunchKernelGGL(kern, dim3(blocks), dim3(Cfg::NT), Cfg::LDS_BYTES, s, x, W, B, t2, offsets,
-                       perm, h, (int)N, d_in, d_out, C, rank, tiles_m, tiles_n);
+                       perm, h, (int)N, d_in, d_out, C, rank, tiles_m, tiles_n, mix);
     return hipGetLastError();
 }
 
@@ -482,17 +484,17 @@ hipError_t launch_cfg(const uint16_t *x, const uint16_t *W, const uint16_t *B, c
 
 hipError_t launch_fused_gemm(const uint16_t *x, const uint16_t *W, const uint16_t *B,
                              const uint16_t *t2, const int32_t *offsets, const int32_t *perm,
-                             float *h, int64_t N, int d_in, int d_out, int C, int rank,
+                             float *h, int64_t N, int d_in, int d_out, int C, int rank, Mix mix,
                              hipStream_t s) {
     if (N == 0) return hipSuccess;
     // Tile choice from static shapes only (no host read of the histogram).  Up to 64 tokens
     // the step is bound by streaming W once: one row tile, narrow column tiles, deep ring.
     // Otherwise the largest tile that still yields about two workgroups per compute unit.
-    if (N <= 64) return launch_small_batch_gemm(x, W, B, t2, offsets, perm, h, N, d_in, d_out, C, rank, s);
+    if (N <= 64) return launch_small_batch_gemm(x, W, B, t2, offsets, perm, h, N, d_in, d_out, C, rank, mix, s);
     const int64_t t256 = ((N + 255) / 256) * ((d_out + 255) / 256);
     if (t256 >= 512)
-        return launch_cfg<GemmCfg<MOLORA_GEMM_BIG>>(x, W, B, t2, offsets, perm, h, N, d_in, d_out, C, rank, s);
-    return launch_cfg<GemmCfg<MOLORA_GEMM_SMALL>>(x, W, B, t2, offsets, perm, h, N, d_in, d_out, C, rank, s);
+        return launch_cfg<GemmCfg<MOLORA_GEMM_BIG>>(x, W, B, t2, offsets, perm, h, N, d_in, d_out, C, rank, mix, s);
+    return launch_cfg<GemmCfg<MOLORA_GEMM_SMALL>>(x, W, B, t2, offsets, perm, h, N, d_in, d_out, C, rank, mix, s);
 }
 
 }  // namespace molora

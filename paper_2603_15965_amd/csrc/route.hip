@@ -56,7 +56,7 @@ __device__ __forceinline__ void route_barrier() {
 template <int NB, int TB, int TGW, bool VEC8>
 __global__ __launch_bounds__(TB * TGW * 64) void route_gate_kernel(
     const uint16_t *__restrict__ x, const uint16_t *__restrict__ G, int32_t *__restrict__ r,
-    int64_t N, int d_in, int C) {
+    float *__restrict__ logits_out, int64_t N, int d_in, int C) {
     using K = RouteCfg<NB, TB, TGW>;
     extern __shared__ __attribute__((aligned(16))) unsigned char route_lds[];
     float *gs = (float *)route_lds;  // two fp32 slabs [CW][kq][KS/4] (+pad)
@@ -211,8 +211,19 @@ __global__ __launch_bounds__(TB * TGW * 64) void route_gate_kernel(
             }
         }
 
-        // ---- running argmax: lexicographic (largest logit, then lowest index) ----
         // acc[b][v] is the logit of token kq*4 + v and target c0 + (tb*NB + b)*16 + l16.
+        if (logits_out != nullptr) {  // the chains themselves are wanted (first layer of a router MLP)
+#pragma unroll
+            for (int v = 0; v < 4; ++v) {
+                const int64_t t = tok_wave + kq * 4 + v;
+#pragma unroll
+                for (int b = 0; b < NB; ++b) {
+                    const int tgt = c0 + (tb * NB + b) * 16 + l16;
+                    if (t < N && tgt < C) logits_out[t * C + tgt] = acc[b][v];
+                }
+            }
+        }
+        // ---- running argmax: lexicographic (largest logit, then lowest index) ----
 #pragma unroll
         for (int v = 0; v < 4; ++v) {
 #pragma unroll
@@ -274,14 +285,14 @@ __global__ __launch_bounds__(TB * TGW * 64) void route_gate_kernel(
 #pragma unroll
         for (int v = 0; v < 4; ++v) {
             const int64_t t = tok_wave + kq * 4 + v;
-            if (t < N) r[t] = bidx[v];
+            if (t < N && r != nullptr) r[t] = bidx[v];
         }
     }
 }
 
 template <int NB, int TB, int TGW, bool VEC8>
-hipError_t launch_cfg(const uint16_t *x, const uint16_t *G, int32_t *r, int64_t N, int d_in, int C,
-                      hipStream_t s) {
+hipError_t launch_cfg(const uint16_t *x, const uint16_t *G, int32_t *r, float *lo, int64_t N,
+                      int d_in, int C, hipStream_t s) {
     using K = RouteCfg<NB, TB, TGW>;
     auto kern = route_gate_kernel<NB, TB, TGW, VEC8>;
     if (K::LDS_BYTES > 64 * 1024) {  // once per kernel
@@ -290,36 +301,36 @@ hipError_t launch_cfg(const uint16_t *x, const uint16_t *G, int32_t *r, int64_t 
         if (e != hipSuccess) return e;
     }
     const unsigned blocks = (unsigned)((N + K::TOK_WG - 1) / K::TOK_WG);
-    hipLaunchKernelGGL(kern, dim3(blocks), dim3(K::NT), K::LDS_BYTES, s, x, G, r, N, d_in, C);
+    hipLaunchKernelGGL(kern, dim3(blocks), dim3(K::NT), K::LDS_BYTES, s, x, G, r, lo, N, d_in, C);
     return hipGetLastError();
 }
 
 // Token groups per workgroup: as many as still leave about two workgroups per compute unit
 // (a workgroup shares one fp32 copy of the G slab; the problem has only N/16 token groups).
 template <int NB, int TB>
-hipError_t launch_tb(const uint16_t *x, const uint16_t *G, int32_t *r, int64_t N, int d_in, int C,
-                     hipStream_t s) {
+hipError_t launch_tb(const uint16_t *x, const uint16_t *G, int32_t *r, float *lo, int64_t N,
+                     int d_in, int C, hipStream_t s) {
     const int64_t groups = (N + 15) / 16;
     constexpr int kMaxTgw = 8 / TB;  // at most 8 wavefronts per workgroup
     if (C % 8 == 0) {                // rows of G can be fetched 16 bytes at a time
         if constexpr (kMaxTgw >= 4)
-            if (groups >= 4 * 512) return launch_cfg<NB, TB, 4, true>(x, G, r, N, d_in, C, s);
+            if (groups >= 4 * 512) return launch_cfg<NB, TB, 4, true>(x, G, r, lo, N, d_in, C, s);
         if constexpr (kMaxTgw >= 2)
-            if (groups >= 2 * 512) return launch_cfg<NB, TB, 2, true>(x, G, r, N, d_in, C, s);
-        return launch_cfg<NB, TB, 1, true>(x, G, r, N, d_in, C, s);
+            if (groups >= 2 * 512) return launch_cfg<NB, TB, 2, true>(x, G, r, lo, N, d_in, C, s);
+        return launch_cfg<NB, TB, 1, true>(x, G, r, lo, N, d_in, C, s);
     }
-    return launch_cfg<NB, TB, 1, false>(x, G, r, N, d_in, C, s);
+    return launch_cfg<NB, TB, 1, false>(x, G, r, lo, N, d_in, C, s);
 }
 
 }  // namespace
 
-hipError_t launch_route_gate(const uint16_t *x, const uint16_t *G, int32_t *r, int64_t N, int d_in,
-                             int C, hipStream_t s) {
+hipError_t launch_route_gate(const uint16_t *x, const uint16_t *G, int32_t *r, float *logits_out,
+                             int64_t N, int d_in, int C, hipStream_t s) {
     if (N == 0) return hipSuccess;
-    if (C <= 16) return launch_tb<1, 1>(x, G, r, N, d_in, C, s);
-    if (C <= 32) return launch_tb<1, 2>(x, G, r, N, d_in, C, s);
-    if (C <= 64) return launch_tb<2, 2>(x, G, r, N, d_in, C, s);
-    return launch_tb<2, 4>(x, G, r, N, d_in, C, s);  // 128 targets per pass
+    if (C <= 16) return launch_tb<1, 1>(x, G, r, logits_out, N, d_in, C, s);
+    if (C <= 32) return launch_tb<1, 2>(x, G, r, logits_out, N, d_in, C, s);
+    if (C <= 64) return launch_tb<2, 2>(x, G, r, logits_out, N, d_in, C, s);
+    return launch_tb<2, 4>(x, G, r, logits_out, N, d_in, C, s);  // 128 targets per pass
 }
 
 }  // namespace molora

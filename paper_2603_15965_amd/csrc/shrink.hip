@@ -29,11 +29,14 @@ constexpr int kShrinkRows = 32;  // sorted rows per work item
 constexpr int kStepK = 32;       // k per MFMA step
 constexpr int kDepth = 4;        // steps in flight per wavefront
 
-template <int NJ>  // NJ = number of 16-column blocks covering rank
+// R = mix.k * rank is the width of a bucket's intermediate: piece j of it is x A of the j-th
+// adapter of the bucket's tuple, scaled by the token's j-th mixture weight.
+template <int NJ>  // NJ = number of 16-column blocks covering R
 __global__ __launch_bounds__(kShrinkThreads) void shrink_kernel(
     const uint16_t *__restrict__ x, const uint16_t *__restrict__ A,
     const int32_t *__restrict__ offsets, const int32_t *__restrict__ perm,
-    uint16_t *__restrict__ t2, int d_in, int C, int rank) {
+    uint16_t *__restrict__ t2, int d_in, int C, int rank, Mix mix) {
+    const int R = mix.k * rank;
     constexpr int RP = NJ * 16;                          // padded rank
     constexpr int ROWB = RP * 2 + (RP >= 64 ? 32 : 0);   // LDS bytes per slab row (bank shift)
     constexpr int SLABB = kStepK * ROWB;                 // one step's slab of one wavefront
@@ -102,9 +105,16 @@ __global__ __launch_bounds__(kShrinkThreads) void shrink_kernel(
         const int p = p_first + rb * 16 + l16;
         xrow[rb] = x + (int64_t)perm[p < p_end ? p : p_first] * d_in;
     }
-    const uint16_t *Ac = A + (int64_t)c * d_in * rank;
-    // A slab staging: lane loads NJ pieces of 16 bytes of the step's [32][rank] slab
-    // piece id = lane + 64*m -> slab row id / (RP/8), 8-column group id % (RP/8)
+    // A slab staging: lane loads NJ pieces of 16 bytes of the step's [32][R] slab
+    // piece id = lane + 64*m -> slab row id / (RP/8), 8-column group id % (RP/8); a group of
+    // 8 columns lies inside one adapter of the tuple (rank is a multiple of 8)
+    const uint16_t *acol[NJ];
+#pragma unroll
+    for (int m = 0; m < NJ; ++m) {
+        const int u = (lane + 64 * m) % (RP / 8);
+        const int uc = min(u * 8, R - 8);
+        acol[m] = A + (int64_t)mix_adapter(mix, c, uc / rank) * d_in * rank + uc % rank;
+    }
     unsigned char *slab0 = lds + wave * 2 * SLABB;
 
     u32x4 xg[kDepth][2], ag[kDepth][NJ];
@@ -118,10 +128,9 @@ __global__ __launch_bounds__(kShrinkThreads) void shrink_kernel(
             const int id = lane + 64 * m;
             const int kr = id / (RP / 8), u = id % (RP / 8);
             const int k = k0 + kr;
-            const int uc = min(u * 8, rank - 8);
-            u32x4 v = *(const u32x4 *)(Ac + (int64_t)min(k, d_in - 1) * rank + uc);
+            u32x4 v = *(const u32x4 *)(acol[m] + (int64_t)min(k, d_in - 1) * rank);
             asm volatile("" : "+v"(v));  // keep the load unconditional
-            const uint32_t ok = (k < k_end && u * 8 < rank) ? 0xFFFFFFFFu : 0u;
+            const uint32_t ok = (k < k_end && u * 8 < R) ? 0xFFFFFFFFu : 0u;
             ag[slot][m] = u32x4{v[0] & ok, v[1] & ok, v[2] & ok, v[3] & ok};
         }
     };
@@ -181,21 +190,23 @@ __global__ __launch_bounds__(kShrinkThreads) void shrink_kernel(
     for (int e = tid; e < kShrinkRows * RP / 2; e += kShrinkThreads) {
         const int row = e / (RP / 2), col = (e % (RP / 2)) * 2;
         const int p = p_first + row;
-        if (p >= p_end || col >= rank) continue;
+        if (p >= p_end || col >= R) continue;
+        const float wj = mix.w != nullptr ? mix.w[(int64_t)perm[p] * mix.k + col / rank] : 1.f;
         uint32_t hi2 = 0, lo2 = 0;
 #pragma unroll
         for (int i = 0; i < 2; ++i) {
             float t = 0.f;
 #pragma unroll
             for (int w = 0; w < 4; ++w) t += red[(w * kShrinkRows + row) * RP + col + i];
+            t *= wj;
             const uint32_t hi = f32_to_bf16_bits(t);
             const uint32_t lo = f32_to_bf16_bits(t - bf16_bits_to_f32(hi));
             hi2 |= hi << (16 * i);
             lo2 |= lo << (16 * i);
         }
-        uint16_t *dst = t2 + (int64_t)p * 2 * rank;
+        uint16_t *dst = t2 + (int64_t)p * 2 * R;
         *(uint32_t *)(dst + col) = hi2;
-        *(uint32_t *)(dst + rank + col) = lo2;
+        *(uint32_t *)(dst + R + col) = lo2;
     }
 }
 
@@ -203,17 +214,17 @@ __global__ __launch_bounds__(kShrinkThreads) void shrink_kernel(
 
 hipError_t launch_shrink(const uint16_t *x, const uint16_t *A, const int32_t *offsets,
                          const int32_t *perm, uint16_t *t2, int64_t N, int d_in, int C, int rank,
-                         hipStream_t s) {
+                         Mix mix, hipStream_t s) {
     if (N == 0) return hipSuccess;
     // up to 64 tokens the step is bound by the latency of streaming the touched A_c: one
     // workgroup per bucket with the K range split over its wavefronts
-    if (N <= 64) return launch_small_batch_shrink(x, A, offsets, perm, t2, N, d_in, C, rank, s);
+    if (N <= 64) return launch_small_batch_shrink(x, A, offsets, perm, t2, N, d_in, C, rank, mix, s);
     const unsigned blocks = (unsigned)((N + kShrinkRows - 1) / kShrinkRows + C);
-    const int nj = (rank + 15) / 16;
+    const int nj = (mix.k * rank + 15) / 16;
 #define MOLORA_SHRINK_CASE(NJ)                                                                  \
     case NJ:                                                                                    \
         hipLaunchKernelGGL(shrink_kernel<NJ>, dim3(blocks), dim3(kShrinkThreads), 0, s, x, A,   \
-                           offsets, perm, t2, d_in, C, rank);                                   \
+                           offsets, perm, t2, d_in, C, rank, mix);                              \
         break;
     switch (nj) {
         MOLORA_SHRINK_CASE(1)

@@ -53,7 +53,7 @@ __global__ __launch_bounds__(kSbWaves * 64) void small_batch_kernel(
     const uint16_t *__restrict__ x, const uint16_t *__restrict__ W, const uint16_t *__restrict__ B,
     const uint16_t *__restrict__ t2, const int32_t *__restrict__ offsets,
     const int32_t *__restrict__ perm, float *__restrict__ h, uint16_t *__restrict__ t_out, int N,
-    int d_in, int d_out, int C, int rank) {
+    int d_in, int d_out, int C, int rank, Mix mix) {
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
     int32_t *tile_perm = (int32_t *)(smem + kSbWaves * kSbWaveLds);  // [64] token per row, -1 = none
     int32_t *seg_c = tile_perm + 64;                                 // buckets that own rows,
@@ -69,13 +69,13 @@ __global__ __launch_bounds__(kSbWaves * 64) void small_batch_kernel(
     const uint16_t *zero = (const uint16_t *)g_zero_page;
 
     // ---- rows of this workgroup ----
-    int row_base = 0, nrows = N;
+    const int R = mix.k * rank;  // width of a bucket's intermediate (k adapters side by side)
+    int row_base = 0, nrows = N, bucket = 0;
     if constexpr (SHRINK) {
-        const int c = blockIdx.y;
-        row_base = offsets[c];
-        nrows = offsets[c + 1] - row_base;
-        if (nrows <= 0) return;  // empty bucket: A_c is not touched
-        W += (int64_t)c * d_in * rank;
+        bucket = blockIdx.y;
+        row_base = offsets[bucket];
+        nrows = offsets[bucket + 1] - row_base;
+        if (nrows <= 0) return;  // empty bucket: its adapters are not touched
     }
 
     // ---- tables: row -> token, and the non-empty buckets in ascending order ----
@@ -105,7 +105,7 @@ __global__ __launch_bounds__(kSbWaves * 64) void small_batch_kernel(
     // ---- this wavefront's share of the work list ----
     // units 0 .. nub-1: W in pieces of 64 rows; then upb units per bucket: [B_c; B_c] in
     // pieces of 64 rows (the last piece of either kind may be short)
-    const int two_r = 2 * rank;
+    const int two_r = 2 * R;
     const int nub = (d_in + 63) / 64, upb = (two_r + 63) / 64;
     const int total = nub + nseg * upb;
     const int u0 = total * wave / kSbWaves, u1 = total * (wave + 1) / kSbWaves;
@@ -155,7 +155,12 @@ __global__ __launch_bounds__(kSbWaves * 64) void small_batch_kernel(
     const int w_rr = lane >> 3, w_pos = lane & 7;
     const int w_u16 = ((((w_pos >> 1) ^ (w_rr & 3))) << 1) | (w_pos & 1);
     const int w_col = min(n0 + w_u16 * 8, d_out - 8);  // columns past d_out: clamped, never stored
-    const uint16_t *w_lane = W + (int64_t)w_rr * d_out + w_col;
+    // SHRINK: the "matrix" is the tuple's A side by side, [d_in][R]; a group of 8 columns lies
+    // inside one adapter, whose rows are rank elements apart
+    const int pitch = SHRINK ? rank : d_out;
+    const uint16_t *w_lane = SHRINK
+        ? W + ((int64_t)mix_adapter(mix, bucket, w_col / rank) * d_in + w_rr) * rank + w_col % rank
+        : W + (int64_t)w_rr * d_out + w_col;
     const uint16_t *b_lane = B + (int64_t)w_rr * d_out + w_col;
     auto issue_slab = [&](const Unit &un, int j, int q) {  // step j of the unit, into slot q % ring
         unsigned char *slot = ring + (q % kSbRing) * kSbSlot;
@@ -164,9 +169,13 @@ __global__ __launch_bounds__(kSbWaves * 64) void small_batch_kernel(
             const int kk = un.k0 + j * 16 + r * 8;  // first of the 8 rows
             const uint16_t *src = zero;
             if (un.kind == 0) {
-                if (kk < d_in) src = w_lane + (int64_t)kk * d_out;
+                if (kk < d_in) src = w_lane + (int64_t)kk * pitch;
             } else if (un.kind == 1) {
-                if (kk < two_r) src = b_lane + ((int64_t)un.c * rank + (kk < rank ? kk : kk - rank)) * d_out;
+                if (kk < two_r) {
+                    const int j = kk < R ? kk : kk - R;       // row of the tuple's stacked B
+                    const int jj = mix.k > 1 ? j / rank : 0;  // which adapter of the tuple
+                    src = b_lane + ((int64_t)mix_adapter(mix, un.c, jj) * rank + (j - jj * rank)) * d_out;
+                }
             }
             load_to_lds16_ptr(src, slot + r * 1024);
         }
@@ -316,18 +325,21 @@ __global__ __launch_bounds__(kSbWaves * 64) void small_batch_kernel(
         for (int w = 1; w < kSbWaves; ++w)
             sum += *(const f32x4 *)(smem + w * kSbWaveLds + row * kSbRowBytes + ch * 16);
         if constexpr (SHRINK) {
+            // piece j of the row is scaled by the token's j-th mixture weight; then
             // t = hi + lo with hi = bf16(t), lo = bf16(t - hi); row of t_out = [hi | lo]
+            const float wj = mix.w != nullptr ? mix.w[(int64_t)tok * mix.k + col / rank] : 1.f;
             u32x2 hi2 = {0, 0}, lo2 = {0, 0};
 #pragma unroll
             for (int i = 0; i < 4; ++i) {
-                const uint32_t hi = f32_to_bf16_bits(sum[i]);
-                const uint32_t lo = f32_to_bf16_bits(sum[i] - bf16_bits_to_f32(hi));
+                const float tv = sum[i] * wj;
+                const uint32_t hi = f32_to_bf16_bits(tv);
+                const uint32_t lo = f32_to_bf16_bits(tv - bf16_bits_to_f32(hi));
                 hi2[i >> 1] |= hi << (16 * (i & 1));
                 lo2[i >> 1] |= lo << (16 * (i & 1));
             }
-            uint16_t *dst = t_out + (int64_t)(row_base + row) * 2 * rank;
+            uint16_t *dst = t_out + (int64_t)(row_base + row) * 2 * R;
             *(u32x2 *)(dst + col) = hi2;
-            *(u32x2 *)(dst + rank + col) = lo2;
+            *(u32x2 *)(dst + R + col) = lo2;
         } else {
             *(f32x4 *)(h + (int64_t)tok * d_out + col) = sum;
         }
@@ -337,7 +349,7 @@ __global__ __launch_bounds__(kSbWaves * 64) void small_batch_kernel(
 template <int TM, bool SHRINK>
 hipError_t launch_small(const uint16_t *x, const uint16_t *W, const uint16_t *B, const uint16_t *t2,
                         const int32_t *offsets, const int32_t *perm, float *h, uint16_t *t_out, int N,
-                        int d_in, int d_out, int C, int rank, hipStream_t s) {
+                        int d_in, int d_out, int C, int rank, Mix mix, hipStream_t s) {
     auto kern = small_batch_kernel<TM, SHRINK>;
     // once per kernel: more than 64 KB of dynamic LDS has to be asked for
     static const hipError_t e = hipFuncSetAttribute((const void *)kern,
@@ -346,7 +358,7 @@ hipError_t launch_small(const uint16_t *x, const uint16_t *W, const uint16_t *B,
     if (e != hipSuccess) return e;
     const unsigned groups = (unsigned)((d_out + kSbCols - 1) / kSbCols);
     hipLaunchKernelGGL(kern, dim3(groups, SHRINK ? C : 1), dim3(kSbWaves * 64), kSbLdsBytes, s, x, W,
-                       B, t2, offsets, perm, h, t_out, N, d_in, d_out, C, rank);
+                       B, t2, offsets, perm, h, t_out, N, d_in, d_out, C, rank, mix);
     return hipGetLastError();
 }
 
@@ -354,19 +366,20 @@ hipError_t launch_small(const uint16_t *x, const uint16_t *W, const uint16_t *B,
 
 hipError_t launch_small_batch_gemm(const uint16_t *x, const uint16_t *W, const uint16_t *B,
                                    const uint16_t *t2, const int32_t *offsets, const int32_t *perm,
-                                   float *h, int64_t N, int d_in, int d_out, int C, int rank,
+                                   float *h, int64_t N, int d_in, int d_out, int C, int rank, Mix mix,
                                    hipStream_t s) {
     if (N <= 32)
-        return launch_small<1, false>(x, W, B, t2, offsets, perm, h, nullptr, (int)N, d_in, d_out, C, rank, s);
-    return launch_small<2, false>(x, W, B, t2, offsets, perm, h, nullptr, (int)N, d_in, d_out, C, rank, s);
+        return launch_small<1, false>(x, W, B, t2, offsets, perm, h, nullptr, (int)N, d_in, d_out, C, rank, mix, s);
+    return launch_small<2, false>(x, W, B, t2, offsets, perm, h, nullptr, (int)N, d_in, d_out, C, rank, mix, s);
 }
 
 hipError_t launch_small_batch_shrink(const uint16_t *x, const uint16_t *A, const int32_t *offsets,
                                      const int32_t *perm, uint16_t *t_out, int64_t N, int d_in, int C,
-                                     int rank, hipStream_t s) {
+                                     int rank, Mix mix, hipStream_t s) {
+    const int R = mix.k * rank;  // the kernel's "d_out" is the width of the intermediate
     if (N <= 32)
-        return launch_small<1, true>(x, A, nullptr, nullptr, offsets, perm, nullptr, t_out, (int)N, d_in, rank, C, rank, s);
-    return launch_small<2, true>(x, A, nullptr, nullptr, offsets, perm, nullptr, t_out, (int)N, d_in, rank, C, rank, s);
+        return launch_small<1, true>(x, A, nullptr, nullptr, offsets, perm, nullptr, t_out, (int)N, d_in, R, C, rank, mix, s);
+    return launch_small<2, true>(x, A, nullptr, nullptr, offsets, perm, nullptr, t_out, (int)N, d_in, R, C, rank, mix, s);
 }
 
 }  // namespace molora

@@ -1,0 +1,151 @@
+"""GPU parity of the learned router with top-k selection, compositional gating and the
+weighted mixture with a slot table (Sec. "Router Architecture", Alg. "Compositional Gating
+Kernel", Def. "Hot-Set Layout") against the CPU oracle, through the C ABI."""
+import math
+import sys
+
+import numpy as np
+import pytest
+
+from paper_2603_15965_amd import workloads as wl
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def gpu():
+    import torch
+    assert torch.cuda.is_available(), "these tests need the MI355X"
+    from paper_2603_15965_amd import binding
+    binding.load()
+    import gpu_helpers
+    return gpu_helpers
+
+
+def say(msg):
+    print(msg, flush=True)
+    sys.stdout.flush()
+
+
+def bf16(a):
+    return wl.to_bf16_bits(np.asarray(a, dtype=np.float32))
+
+
+def router_inputs(seed, N, d, H, K):
+    rng = np.random.default_rng(seed)
+    x = bf16(rng.standard_normal((N, d)))
+    W1 = bf16(rng.standard_normal((d, H)) / math.sqrt(d))
+    b1 = (0.1 * rng.standard_normal(H)).astype(np.float32)
+    W2 = bf16(rng.standard_normal((H, K)) / math.sqrt(H))
+    b2 = (0.1 * rng.standard_normal(K)).astype(np.float32)
+    return x, W1, b1, W2, b2
+
+
+@pytest.mark.parametrize("N,d,H,K,k", [
+    (300, 256, 64, 8, 2),
+    (4100, 2048, 64, 32, 2),
+    (1000, 512, 64, 100, 4),
+    (50, 1024, 128, 16, 1),
+    (7, 64, 8, 3, 3),
+])
+def test_route_mlp_topk_bit_exact(gpu, N, d, H, K, k):
+    import oracle
+    import torch
+    from paper_2603_15965_amd import binding as mb
+    say(f"route_mlp N={N} d={d} H={H} K={K} k={k}")
+    x, W1, b1, W2, b2 = router_inputs(100 + N, N, d, H, K)
+    idx, w = mb.molora_route_mlp(gpu.dev_bf16(x), gpu.dev_bf16(W1), torch.from_numpy(b1).cuda(),
+                                 gpu.dev_bf16(W2), torch.from_numpy(b2).cuda(), k)
+    torch.cuda.synchronize()
+    logits = oracle.mlp_logits(x, W1, b1, W2, b2)
+    idx_ref, w_ref = oracle.topk_softmax(logits, k)
+    assert np.array_equal(idx.cpu().numpy(), idx_ref)
+    assert np.array_equal(w.cpu().numpy().view(np.uint32), w_ref.view(np.uint32))
+
+
+def test_route_compose_bit_exact(gpu):
+    import oracle
+    import torch
+    from paper_2603_15965_amd import binding as mb
+    rng = np.random.default_rng(9)
+    breaks = (0, 32768, 40960, 50000)
+    n_ad = 7
+    N = 10001
+    v = rng.integers(-100, 50100, size=N).astype(np.int32)
+    a = rng.integers(-1, n_ad + 1, size=N).astype(np.int32)
+    r = mb.molora_route_compose(gpu.dev_i32(v), gpu.dev_i32(a), breaks, n_ad)
+    torch.cuda.synchronize()
+    assert np.array_equal(r.cpu().numpy(), oracle.route_compose(v, a, np.array(breaks, dtype=np.int32), n_ad))
+
+
+def mix_case(seed, N, d_in, d_out, C, rank, k, S=None, bad=False, weights=True):
+    w = wl.custom("mix", N, d_in, d_out, S or C, rank, wl.BASE_SEED + seed)
+    rng = np.random.default_rng(seed)
+    idx = np.stack([rng.permutation(C)[:k] for _ in range(N)]).astype(np.int32)
+    wts = None
+    if weights:
+        wts = rng.random((N, k)).astype(np.float32) + 0.05
+        wts /= wts.sum(axis=1, keepdims=True)
+    if bad:
+        idx[rng.random((N, k)) < 0.1] = -1
+        idx[0, 0] = C + 3
+    slots = None
+    if S is not None:
+        slots = rng.permutation(S)[:C].astype(np.int32)
+    return w, idx, wts, slots
+
+
+@pytest.mark.parametrize("N,d_in,d_out,C,rank,k,S,bad", [
+    (300, 256, 384, 5, 16, 2, None, False),     # tuples of two adapters, several row tiles
+    (1000, 512, 520, 8, 16, 2, None, True),     # ragged columns, entries outside [0, C)
+    (700, 256, 256, 4, 8, 3, None, False),      # three adapters per token
+    (40, 1024, 512, 6, 32, 2, None, False),     # small-batch path
+    (64, 512, 264, 5, 8, 4, None, True),        # small-batch path, four per token, bad entries
+    (500, 256, 256, 6, 16, 1, 9, False),        # one adapter per token through a slot table
+    (48, 512, 256, 5, 16, 2, 8, False),         # small-batch path, slot table and tuples
+    (2000, 512, 1024, 16, 32, 2, 20, False),    # 256 tuples, wide intermediate
+])
+def test_apply_mix_matches_oracle(gpu, N, d_in, d_out, C, rank, k, S, bad):
+    import oracle
+    import torch
+    from paper_2603_15965_amd import binding as mb
+    say(f"apply_mix N={N} {d_in}->{d_out} C={C} rank={rank} k={k} S={S} bad={bad}")
+    w, idx, wts, slots = mix_case(N + 13 * k, N, d_in, d_out, C, rank, k, S, bad)
+    h = mb.molora_apply_mix(gpu.dev_bf16(w.x), gpu.dev_bf16(w.W), gpu.dev_bf16(w.A), gpu.dev_bf16(w.B),
+                            gpu.dev_i32(idx), None if wts is None else torch.from_numpy(wts).cuda(),
+                            None if slots is None else gpu.dev_i32(slots), C=C)
+    torch.cuda.synchronize()
+    ref = oracle.apply_mix(w.x, w.W, w.A, w.B, idx, wts, slots, C=C)
+    gpu.assert_h_close(h.cpu().numpy(), ref, "apply_mix")
+
+
+def test_apply_mix_k1_equals_apply(gpu):
+    import torch
+    from paper_2603_15965_amd import binding as mb
+    w = wl.custom("mix1", 777, 512, 384, 7, 16, wl.BASE_SEED + 4242)
+    x, W, A, B = (gpu.dev_bf16(t) for t in (w.x, w.W, w.A, w.B))
+    r = gpu.dev_i32(w.r)
+    h1 = mb.molora_apply(x, W, A, B, r)
+    h2 = mb.molora_apply_mix(x, W, A, B, r.reshape(-1, 1))
+    torch.cuda.synchronize()
+    assert np.array_equal(h1.cpu().numpy(), h2.cpu().numpy())
+
+
+def test_router_to_mixture_end_to_end(gpu):
+    """route_mlp -> apply_mix on the GPU against mlp_logits -> topk_softmax -> apply_mix of
+    the oracle."""
+    import oracle
+    import torch
+    from paper_2603_15965_amd import binding as mb
+    N, d, H, K, k, rank, d_out = 1500, 512, 64, 8, 2, 16, 768
+    x, W1, b1, W2, b2 = router_inputs(77, N, d, H, K)
+    w = wl.custom("e2e", N, d, d_out, K, rank, wl.BASE_SEED + 5151)
+    xd = gpu.dev_bf16(x)
+    idx, wt = mb.molora_route_mlp(xd, gpu.dev_bf16(W1), torch.from_numpy(b1).cuda(), gpu.dev_bf16(W2),
+                                  torch.from_numpy(b2).cuda(), k)
+    h = mb.molora_apply_mix(xd, gpu.dev_bf16(w.W), gpu.dev_bf16(w.A), gpu.dev_bf16(w.B), idx, wt)
+    torch.cuda.synchronize()
+    idx_ref, w_ref = oracle.topk_softmax(oracle.mlp_logits(x, W1, b1, W2, b2), k)
+    assert np.array_equal(idx.cpu().numpy(), idx_ref)
+    ref = oracle.apply_mix(x, w.W, w.A, w.B, idx_ref, w_ref)
+    gpu.assert_h_close(h.cpu().numpy(), ref, "router -> mixture")
