@@ -1,0 +1,169 @@
+#!/usr/bin/env python3
+"""Side measurements of the routed-LoRA path on one MI355X (bench.py holds the headline
+number).  Each sub-benchmark prints ONE JSON line; all inputs are seeded and synthetic, all
+calls go through the C ABI, times are HIP-event averages over back-to-back launches.
+
+  topk    weighted top-k mixture behind the router MLP (Sec. "Router Architecture"; the
+          paper's cost context is Table "tab:molora_inference_appendix": k = 1, 2, 4)
+  slots   direct indexing of the adapter pools against indexing through a slot table
+          (Table "tab:memory_layout", 4 .. 64 adapters)
+  kpass   per-token routing in one pass against K per-sequence passes built from the same
+          kernels (Table "tab:passes")
+  skew    bucket-size distributions uniform / 80-10-5-5 / 95-2-2-1 (Table "tab:adaptive_tiling")
+  batch   batch sweep 64 .. 1024 tokens at d = 4096, rank 64, 8 adapters (Fig.
+          "kernel_benchmark")
+"""
+import argparse
+import json
+import math
+import os
+import sys
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("which", nargs="*", default=["topk", "slots", "kpass", "skew", "batch"])
+    ap.add_argument("--reps", type=int, default=50)
+    args = ap.parse_args()
+
+    import numpy as np
+    import torch
+    from paper_2603_15965_amd import binding as mb
+    from paper_2603_15965_amd import workloads as wl
+
+    if not torch.cuda.is_available():
+        print("bench_ablations.py: no GPU visible", file=sys.stderr)
+        sys.exit(1)
+    torch.cuda.set_device(0)
+    mb.load()
+
+    def timed(fn, reps=args.reps, warm=5):
+        for _ in range(warm):
+            fn()
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        torch.cuda.synchronize()
+        a.record()
+        for _ in range(reps):
+            fn()
+        b.record()
+        torch.cuda.synchronize()
+        return a.elapsed_time(b) / reps * 1e3  # us
+
+    def dev(w):
+        return (mb.bf16_tensor(w.x), mb.bf16_tensor(w.W), mb.bf16_tensor(w.A), mb.bf16_tensor(w.B))
+
+    def i32(a):
+        return torch.from_numpy(np.ascontiguousarray(a, dtype=np.int32)).cuda()
+
+    def bits(a):
+        return mb.bf16_tensor(wl.to_bf16_bits(np.asarray(a, dtype=np.float32)))
+
+    rng = np.random.default_rng(2026)
+
+    if "topk" in args.which:
+        N, d_in, d_out, C, rank, H = 8192, 2048, 6144, 8, 16, 64
+        w = wl.custom("topk", N, d_in, d_out, C, rank, wl.BASE_SEED + 9100)
+        x, W, A, B = dev(w)
+        W1 = bits(rng.standard_normal((d_in, H)) / math.sqrt(d_in))
+        W2 = bits(rng.standard_normal((H, C)) / math.sqrt(H))
+        b1 = torch.from_numpy((0.1 * rng.standard_normal(H)).astype(np.float32)).cuda()
+        b2 = torch.from_numpy((0.1 * rng.standard_normal(C)).astype(np.float32)).cuda()
+        h = torch.empty((N, d_out), dtype=torch.float32, device="cuda")
+        rows = []
+        for k in (1, 2, 3):
+            idx, wt = mb.molora_route_mlp(x, W1, b1, W2, b2, k)
+            nb = int(mb.load().molora_apply_mix_workspace_bytes(N, d_in, d_out, C, rank, k))
+            ws = torch.empty(nb, dtype=torch.uint8, device="cuda")
+            t_route = timed(lambda: mb.molora_route_mlp(x, W1, b1, W2, b2, k, idx, wt))
+            t_apply = timed(lambda: mb.molora_apply_mix(x, W, A, B, idx, wt, h=h, workspace=ws))
+            rows.append({"k": k, "route_mlp_us": t_route, "apply_mix_us": t_apply,
+                         "tokens_per_s": N / ((t_route + t_apply) * 1e-6)})
+        r1 = i32(w.r)
+        wsa = mb.new_workspace(N, d_in, d_out, C, rank)
+        t_plain = timed(lambda: mb.molora_apply(x, W, A, B, r1, h=h, workspace=wsa))
+        print(json.dumps({"bench": "topk", "shape": f"N={N} {d_in}->{d_out} C={C} rank={rank} H={H}",
+                          "apply_one_adapter_us": t_plain, "rows": rows,
+                          "paper_context": "H100, other shape: k=1 0.995 ms, k=2 2.267 ms, k=4 4.001 ms"}))
+
+    if "slots" in args.which:
+        N, d_in, d_out, rank = 4096, 4096, 4096, 16
+        rows = []
+        for C in (4, 8, 16, 32, 64):
+            w = wl.custom("slots", N, d_in, d_out, C, rank, wl.BASE_SEED + 9200 + C)
+            x, W, A, B = dev(w)
+            r = i32(w.r)
+            h = torch.empty((N, d_out), dtype=torch.float32, device="cuda")
+            ws = mb.new_workspace(N, d_in, d_out, C, rank)
+            nb = int(mb.load().molora_apply_mix_workspace_bytes(N, d_in, d_out, C, rank, 1))
+            wsm = torch.empty(nb, dtype=torch.uint8, device="cuda")
+            slots = i32(rng.permutation(C))
+            idx = r.reshape(-1, 1).contiguous()
+            t_d = timed(lambda: mb.molora_apply(x, W, A, B, r, h=h, workspace=ws))
+            t_i = timed(lambda: mb.molora_apply_mix(x, W, A, B, idx, None, slots, h=h, workspace=wsm))
+            rows.append({"adapters": C, "direct_us": t_d, "slot_table_us": t_i, "ratio": t_i / t_d})
+        print(json.dumps({"bench": "slots", "shape": f"N={N} {d_in}->{d_out} rank={rank}", "rows": rows,
+                          "paper_context": "H100: direct indexing 1.14x faster than indirect on average"}))
+
+    if "kpass" in args.which:
+        N, d_in, d_out, rank = 4096, 2048, 2048, 16
+        rows = []
+        for K in (2, 4, 8):
+            w = wl.custom("kpass", N, d_in, d_out, K, rank, wl.BASE_SEED + 9300 + K)
+            x, W, A, B = dev(w)
+            r = i32(w.r)
+            h = torch.empty((N, d_out), dtype=torch.float32, device="cuda")
+            ws = mb.new_workspace(N, d_in, d_out, K, rank)
+            t_tok = timed(lambda: mb.molora_apply(x, W, A, B, r, h=h, workspace=ws))
+            r_c = [torch.full((N,), c, dtype=torch.int32, device="cuda") for c in range(K)]
+
+            def passes():
+                for c in range(K):  # one pass of the whole batch per adapter
+                    mb.molora_apply(x, W, A, B, r_c[c], h=h, workspace=ws)
+
+            t_seq = timed(passes, reps=max(5, args.reps // K))
+            rows.append({"adapters": K, "per_token_us": t_tok, "per_sequence_K_passes_us": t_seq,
+                         "ratio": t_seq / t_tok})
+        print(json.dumps({"bench": "kpass", "shape": f"N={N} {d_in}->{d_out} rank={rank}", "rows": rows,
+                          "paper_context": "work K*N against N (Thm. Computational Optimality)"}))
+
+    if "skew" in args.which:
+        N, d_in, d_out, C, rank = 4096, 4096, 4096, 4, 16
+        w = wl.custom("skew", N, d_in, d_out, C, rank, wl.BASE_SEED + 9400)
+        x, W, A, B = dev(w)
+        h = torch.empty((N, d_out), dtype=torch.float32, device="cuda")
+        ws = mb.new_workspace(N, d_in, d_out, C, rank)
+        rows = []
+        for name, p in (("uniform", [0.25, 0.25, 0.25, 0.25]), ("80-10-5-5", [0.8, 0.1, 0.05, 0.05]),
+                        ("95-2-2-1", [0.95, 0.02, 0.02, 0.01])):
+            r = i32(rng.choice(C, size=N, p=p))
+            t = timed(lambda: mb.molora_apply(x, W, A, B, r, h=h, workspace=ws))
+            rows.append({"distribution": name, "apply_us": t})
+        print(json.dumps({"bench": "skew", "shape": f"N={N} {d_in}->{d_out} C={C} rank={rank}", "rows": rows,
+                          "paper_context": "adaptive tiling up to 1.4x on skewed loads; here tiles do not "
+                                           "depend on the histogram, time should not depend on skew"}))
+
+    if "batch" in args.which:
+        d_in, d_out, C, rank = 4096, 4096, 8, 64
+        rows = []
+        for N in (64, 128, 256, 512, 1024):
+            w = wl.custom("batch", N, d_in, d_out, C, rank, wl.BASE_SEED + 9500 + N)
+            x, W, A, B = dev(w)
+            r = i32(w.r)
+            h = torch.empty((N, d_out), dtype=torch.float32, device="cuda")
+            ws = mb.new_workspace(N, d_in, d_out, C, rank)
+            offsets, perm = mb.molora_bucket(r, C)
+            t = torch.empty((N, 2 * rank), dtype=torch.bfloat16, device="cuda")
+            t_apply = timed(lambda: mb.molora_apply(x, W, A, B, r, h=h, workspace=ws))
+            t_shrink = timed(lambda: mb.molora_shrink(x, A, offsets, perm, t))
+            t_gemm = timed(lambda: mb.molora_base_expand(x, W, B, t, offsets, perm, h))
+            rows.append({"N": N, "apply_us": t_apply, "shrink_us": t_shrink, "base_expand_us": t_gemm})
+        print(json.dumps({"bench": "batch", "shape": f"{d_in}->{d_out} C={C} rank={rank}", "rows": rows,
+                          "paper_context": "H100 LoRA-only kernel, crossover to compute bound near batch 160"}))
+
+
+if __name__ == "__main__":
+    main()

@@ -472,6 +472,9 @@ hipError_t launch_cfg(const uint16_t *x, const uint16_t *W, const uint16_t *B, c
 
 }  // namespace
 
+#ifndef MOLORA_SMALL_BATCH_MAX
+#define MOLORA_SMALL_BATCH_MAX 512  // up to here W is streamed once per 64-row tile instead (measured crossover)
+#endif
 #ifndef MOLORA_GEMM_BIG
 #define MOLORA_GEMM_BIG 256, 256, 2, 4, 1, 64, 2
 #endif
@@ -490,7 +493,7 @@ hipError_t launch_fused_gemm(const uint16_t *x, const uint16_t *W, const uint16_
     // Tile choice from static shapes only (no host read of the histogram).  Up to 64 tokens
     // the step is bound by streaming W once: one row tile, narrow column tiles, deep ring.
     // Otherwise the largest tile that still yields about two workgroups per compute unit.
-    if (N <= 64) return launch_small_batch_gemm(x, W, B, t2, offsets, perm, h, N, d_in, d_out, C, rank, mix, s);
+    if (N <= MOLORA_SMALL_BATCH_MAX) return launch_small_batch_gemm(x, W, B, t2, offsets, perm, h, N, d_in, d_out, C, rank, mix, s);
     const int64_t t256 = ((N + 255) / 256) * ((d_out + 255) / 256);
     if (t256 >= 512)
         return launch_cfg<GemmCfg<MOLORA_GEMM_BIG>>(x, W, B, t2, offsets, perm, h, N, d_in, d_out, C, rank, mix, s);

@@ -44,7 +44,8 @@ struct Unit {
     int c, lo, hi;  // kind 1: bucket and its sorted-position range
 };
 
-// SHRINK = false: the fused GEMM above over all N rows (grid: column groups).
+// SHRINK = false: the fused GEMM above (grid: column groups x row tiles of 64 sorted rows; a
+//                 batch of more than 64 rows re-reads W once per row tile, from L2).
 // SHRINK = true:  the shrink step t_p = x[perm[p]] A_c for the rows of bucket c = blockIdx.y
 //                 (grid: column groups of the rank x buckets); W is A, d_out is rank, there
 //                 are no expand units and the result goes to t_out as [hi | lo] bf16 halves.
@@ -76,6 +77,9 @@ __global__ __launch_bounds__(kSbWaves * 64) void small_batch_kernel(
         row_base = offsets[bucket];
         nrows = offsets[bucket + 1] - row_base;
         if (nrows <= 0) return;  // empty bucket: its adapters are not touched
+    } else {
+        row_base = blockIdx.y * 64;  // row tile of 64 sorted positions
+        nrows = min(64, N - row_base);
     }
 
     // ---- tables: row -> token, and the non-empty buckets in ascending order ----
@@ -86,7 +90,8 @@ __global__ __launch_bounds__(kSbWaves * 64) void small_batch_kernel(
         int cnt = 0;
         for (int c0 = 0; c0 < C; c0 += 64) {
             const int c = min(c0 + lane, C - 1);
-            const int lo = offsets[c], hi = offsets[c + 1];
+            // the bucket's rows inside this row tile, relative to the tile
+            const int lo = max(offsets[c] - row_base, 0), hi = min(offsets[c + 1] - row_base, nrows);
             const bool owns = (c0 + lane < C) && hi > lo;
             const uint64_t m = __ballot(owns);
             if (owns) {
@@ -203,7 +208,8 @@ __global__ __launch_bounds__(kSbWaves * 64) void small_batch_kernel(
             if (un.kind == 0) {
                 if (kk < d_in) src = a_xrow[i] + un.k0;
             } else if (un.kind == 1) {
-                if (row >= un.lo && row < un.hi && kk < two_r) src = t2 + (int64_t)row * two_r + kk;
+                if (row >= un.lo && row < un.hi && kk < two_r)
+                    src = t2 + (int64_t)(row_base + row) * two_r + kk;
             }
             load_to_lds16_ptr(src, stage + i * 1024);
         }
@@ -357,7 +363,8 @@ hipError_t launch_small(const uint16_t *x, const uint16_t *W, const uint16_t *B,
                                                     (int)kSbLdsBytes);
     if (e != hipSuccess) return e;
     const unsigned groups = (unsigned)((d_out + kSbCols - 1) / kSbCols);
-    hipLaunchKernelGGL(kern, dim3(groups, SHRINK ? C : 1), dim3(kSbWaves * 64), kSbLdsBytes, s, x, W,
+    const unsigned tiles = SHRINK ? (unsigned)C : (unsigned)((N + 63) / 64);  // buckets | row tiles
+    hipLaunchKernelGGL(kern, dim3(groups, tiles), dim3(kSbWaves * 64), kSbLdsBytes, s, x, W,
                        B, t2, offsets, perm, h, t_out, N, d_in, d_out, C, rank, mix);
     return hipGetLastError();
 }
