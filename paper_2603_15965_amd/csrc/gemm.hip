@@ -39,13 +39,11 @@ namespace {
 
 constexpr int kGroupM = 8;  // row tiles per scheduling group
 
-// BM x BN output tile, WM x WN x WK wavefronts (WK > 1: the k-steps of a tile are dealt out to
-// WK wavefronts per 32x32-block group and summed at the end; used where the kernel is bound by
-// loading and wants many wavefronts issuing loads), BK deep K tiles, STAGES LDS buffers.
-template <int BM_, int BN_, int WM_, int WN_, int WK_, int BK_, int STAGES_>
+// BM x BN output tile, WM x WN wavefronts, BK deep K tiles, STAGES LDS buffers.
+template <int BM_, int BN_, int WM_, int WN_, int BK_, int STAGES_>
 struct GemmCfg {
-    static constexpr int BM = BM_, BN = BN_, WM = WM_, WN = WN_, WK = WK_, BK = BK_, STAGES = STAGES_;
-    static constexpr int NW = WM * WN * WK, NT = 64 * NW;
+    static constexpr int BM = BM_, BN = BN_, WM = WM_, WN = WN_, BK = BK_, STAGES = STAGES_;
+    static constexpr int NW = WM * WN, NT = 64 * NW;
     static constexpr int TM = BM / WM / 32, TN = BN / WN / 32;
     // A tile = x rows, B tile = W rows; a load instruction fills 1 KB = one "piece"
     static constexpr int A_RB = BK * 2, A_CPR = A_RB / 16, A_RPI = 64 / A_CPR;
@@ -54,12 +52,9 @@ struct GemmCfg {
     static constexpr int LPW = (A_PIECES + B_PIECES) / NW;  // pieces (loads) per wavefront and tile
     static constexpr int A_BYTES = BM * A_RB, B_BYTES = BK * B_RB, STAGE = A_BYTES + B_BYTES;
     static constexpr size_t LDS_BYTES = (size_t)STAGES * STAGE + 4 * BM * sizeof(int32_t) + 16;
-    static constexpr bool PIPE = (STAGES == 2);  // fragment-pipelined main loop, else deep ring
     static_assert(BK == 32 || BK == 64, "BK");
     static_assert(LPW * NW == A_PIECES + B_PIECES && LPW >= 1, "pieces split evenly over wavefronts");
-    static_assert(STAGES >= 2, "stages");
-    static_assert(!PIPE || WK == 1, "the pipelined loop keeps all k-steps in one wavefront");
-    static_assert((BK / 16) % WK == 0, "k-steps split evenly");
+    static_assert(STAGES >= 2 && STAGES <= 4, "stages");
 
     // XOR applied to the 16-byte chunk index of an x-tile row
     __device__ static __forceinline__ int swz_a(int row) {
@@ -86,8 +81,7 @@ __global__ __launch_bounds__(Cfg::NT) void fused_gemm_kernel(
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int wk = wave % Cfg::WK;  // which k-steps of a tile this wavefront multiplies
-    const int wm = (wave / Cfg::WK) / Cfg::WN, wn = (wave / Cfg::WK) % Cfg::WN;
+    const int wm = wave / Cfg::WN, wn = wave % Cfg::WN;
 
     // ---- tile of this workgroup: XCD-major, then groups of kGroupM row tiles ----
     const int total = tiles_m * tiles_n;
@@ -270,124 +264,101 @@ __global__ __launch_bounds__(Cfg::NT) void fused_gemm_kernel(
     };
     constexpr int KS = BK / 16;
 
-    if constexpr (Cfg::PIPE) {
-        // ---- main loop, MFMA-bound shapes ----
-        // Two LDS stages and two register sets of operand fragments.  While the MFMAs of
-        // k-step ks run, the fragments of step ks+1 are fetched from LDS, one read after each
-        // MFMA, so the matrix pipe never waits for LDS.  The workgroup barrier sits in front
-        // of the LAST k-step of a tile: at that point every wavefront holds the tile's last
-        // fragments in registers, so the stage can be refilled (tile kt+2) and the first
-        // fragments of tile kt+1 can be fetched while the last MFMAs of tile kt still run.
-        static_assert(KS % 2 == 0, "two fragment register sets");
-        bf16x8 fa[2][TM], fb[2][TN];
-        auto fetch_one = [&](const unsigned char *as, int ks, int set, int i) {  // i-th fragment
-            if (i < TM)
-                fa[set][i] = load_a_frag(as, ks, i);
-            else if (i < TM + TN)
-                fb[set][i - TM] = load_b_frag(as, ks, i - TM);
-        };
-        issue_tile(smem, 0);
-        if (nk > 1) {
-            issue_tile(smem + Cfg::STAGE, 1);
-            wait_vmcnt<Cfg::LPW>();
-        } else {
-            wait_vmcnt<0>();
-        }
-        wg_barrier();
+    // ---- main loop ----
+    // STAGES LDS stages (tile kt lives in stage kt % STAGES, tiles kt+1 .. kt+STAGES-1 are in
+    // flight) and two register sets of operand fragments.  While the MFMAs of k-step ks run,
+    // the fragments of step ks+1 are fetched from LDS, one read after each MFMA, so the matrix
+    // pipe never waits for LDS.  The workgroup barrier sits in front of the LAST k-step of a
+    // tile: at that point every wavefront holds the tile's last fragments in registers, so the
+    // stage can be refilled (tile kt+STAGES) and the first fragments of tile kt+1 can be
+    // fetched while the last MFMAs of tile kt still run.  Two stages are enough when a tile's
+    // MFMAs outlast the load latency (256 x 256 tiles); smaller tiles need the next tiles
+    // further ahead.
+    static_assert(KS % 2 == 0, "two fragment register sets");
+    bf16x8 fa[2][TM], fb[2][TN];
+    auto fetch_one = [&](const unsigned char *as, int ks, int set, int i) {  // i-th fragment
+        if (i < TM)
+            fa[set][i] = load_a_frag(as, ks, i);
+        else if (i < TM + TN)
+            fb[set][i - TM] = load_b_frag(as, ks, i - TM);
+    };
+    // loads return in order: tile T has landed once at most the loads of the `younger` tiles
+    // issued after it are outstanding
+    auto wait_tiles = [&](int younger) {
+        if constexpr (STAGES >= 4)
+            if (younger >= 2) return wait_vmcnt<2 * Cfg::LPW>();
+        if constexpr (STAGES >= 3)
+            if (younger >= 1) return wait_vmcnt<Cfg::LPW>();
+        wait_vmcnt<0>();
+    };
+    auto stage_of = [&](int T) { return smem + (T % STAGES) * Cfg::STAGE; };
 #pragma unroll
-        for (int i = 0; i < TM + TN; ++i) fetch_one(smem, 0, 0, i);
+    for (int T = 0; T < STAGES; ++T)
+        if (T < nk) issue_tile(smem + T * Cfg::STAGE, T);
+    wait_tiles(min(nk, STAGES) - 1);
+    wg_barrier();
+#pragma unroll
+    for (int i = 0; i < TM + TN; ++i) fetch_one(smem, 0, 0, i);
 
-        // one K tile: KS-1 ordinary k-steps, then the last one.  MORE: another tile follows.
-        // REFILL: 0 = nothing to load, 1 = tile kt+2 is a full tile and its loads are
-        // interleaved with the MFMAs, 2 = tile kt+2 is of any kind, loaded in one go.
-        auto k_tile = [&](int kt, auto more_c, auto refill_c) {
-            constexpr bool MORE = decltype(more_c)::value;
-            constexpr int REFILL = decltype(refill_c)::value;
-            unsigned char *as = smem + (kt & 1) * Cfg::STAGE;
-            unsigned char *as_next = smem + ((kt + 1) & 1) * Cfg::STAGE;
+    // one K tile: KS-1 ordinary k-steps, then the last one.  MORE: another tile follows.
+    // REFILL: 0 = nothing to load, 1 = tile kt+STAGES is a full tile and its loads are
+    // interleaved with the MFMAs, 2 = tile kt+STAGES is of any kind, loaded in one go.
+    auto k_tile = [&](int kt, auto more_c, auto refill_c) {
+        constexpr bool MORE = decltype(more_c)::value;
+        constexpr int REFILL = decltype(refill_c)::value;
+        unsigned char *as = stage_of(kt);
+        unsigned char *as_next = stage_of(kt + 1);
 #pragma unroll
-            for (int ks = 0; ks < KS - 1; ++ks) {
-                const int cur = ks & 1, nxt = cur ^ 1;
-#pragma unroll
-                for (int i = 0; i < TM * TN; ++i) {
-                    acc[i / TN][i % TN] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
-                        fa[cur][i / TN], fb[cur][i % TN], acc[i / TN][i % TN], 0, 0, 0);
-                    fetch_one(as, ks + 1, nxt, i);
-                    __builtin_amdgcn_sched_barrier(0);
-                }
-#pragma unroll
-                for (int i = TM * TN; i < TM + TN; ++i) fetch_one(as, ks + 1, nxt, i);
-            }
-            constexpr int cur = (KS - 1) & 1, nxt = cur ^ 1;
-            if constexpr (MORE) {
-                wait_lds();       // this wavefront's reads of stage kt are complete
-                wait_vmcnt<0>();  // its part of tile kt+1 has landed
-                wg_barrier();     // ... and so has everyone else's; stage kt is free
-            }
-            if constexpr (REFILL == 2) issue_tile(as, kt + 2);
+        for (int ks = 0; ks < KS - 1; ++ks) {
+            const int cur = ks & 1, nxt = cur ^ 1;
 #pragma unroll
             for (int i = 0; i < TM * TN; ++i) {
                 acc[i / TN][i % TN] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
                     fa[cur][i / TN], fb[cur][i % TN], acc[i / TN][i % TN], 0, 0, 0);
-                if constexpr (MORE) fetch_one(as_next, 0, nxt, i);
-                if constexpr (REFILL == 1)
-                    if (i < Cfg::LPW) issue_one(as, i);
+                fetch_one(as, ks + 1, nxt, i);
                 __builtin_amdgcn_sched_barrier(0);
             }
-            if constexpr (MORE) {
 #pragma unroll
-                for (int i = TM * TN; i < TM + TN; ++i) fetch_one(as_next, 0, nxt, i);
-            }
-            if constexpr (REFILL == 1) {
-#pragma unroll
-                for (int i = TM * TN; i < Cfg::LPW; ++i) issue_one(as, i);
-                advance_full();
-            }
-        };
-        using I0 = std::integral_constant<int, 0>;
-        using I1 = std::integral_constant<int, 1>;
-        using I2 = std::integral_constant<int, 2>;
-        int kt = 0;
-        for (; kt + 2 < nkf; ++kt) k_tile(kt, std::true_type{}, I1{});  // the hot loop
-        for (; kt + 2 < nk; ++kt) k_tile(kt, std::true_type{}, I2{});   // last base + expand tiles
-        if (kt + 1 < nk) {
-            k_tile(kt, std::true_type{}, I0{});
-            ++kt;
+            for (int i = TM * TN; i < TM + TN; ++i) fetch_one(as, ks + 1, nxt, i);
         }
-        k_tile(kt, std::false_type{}, I0{});
-    } else {
-        // ---- main loop, streaming shapes: ring of STAGES stages, STAGES-1 tiles in flight ----
-#pragma unroll
-        for (int s = 0; s < STAGES - 1; ++s)
-            if (s < nk) issue_tile(smem + s * Cfg::STAGE, s);
-        for (int kt = 0; kt < nk; ++kt) {
-            // tile kt has landed once at most the younger tiles' loads are outstanding
-            if (kt + STAGES - 2 < nk)
-                wait_vmcnt<Cfg::LPW *(STAGES - 2)>();
+        constexpr int cur = (KS - 1) & 1, nxt = cur ^ 1;
+        if constexpr (MORE) {
+            wait_lds();  // this wavefront's reads of stage kt are complete
+            // its part of tile kt+1 has landed; tiles kt+2 .. may still be in flight
+            if constexpr (REFILL != 0)
+                wait_tiles(STAGES - 2);
             else
-                wait_vmcnt<0>();
-            wg_barrier();  // everyone's part of tile kt is in LDS; everyone is done with tile kt-1
-            if (kt + STAGES - 1 < nk)
-                issue_tile(smem + ((kt + STAGES - 1) % STAGES) * Cfg::STAGE, kt + STAGES - 1);
-            const unsigned char *as = smem + (kt % STAGES) * Cfg::STAGE;
-#pragma unroll
-            for (int kk = 0; kk < KS / Cfg::WK; ++kk) {
-                const int ks = kk * Cfg::WK + wk;
-                bf16x8 af[TM], bfr[TN];
-#pragma unroll
-                for (int tm = 0; tm < TM; ++tm) af[tm] = load_a_frag(as, ks, tm);
-#pragma unroll
-                for (int tn = 0; tn < TN; ++tn) bfr[tn] = load_b_frag(as, ks, tn);
-#pragma unroll
-                for (int tm = 0; tm < TM; ++tm)
-#pragma unroll
-                    for (int tn = 0; tn < TN; ++tn)
-                        acc[tm][tn] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[tm], bfr[tn],
-                                                                              acc[tm][tn], 0, 0, 0);
-            }
-            wait_lds();  // the reads of this stage are complete before the next barrier
+                wait_tiles(min(nk - 2 - kt, STAGES - 2));
+            wg_barrier();  // ... and so has everyone else's; stage kt is free
         }
-    }
+        if constexpr (REFILL == 2) issue_tile(as, kt + STAGES);
+#pragma unroll
+        for (int i = 0; i < TM * TN; ++i) {
+            acc[i / TN][i % TN] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
+                fa[cur][i / TN], fb[cur][i % TN], acc[i / TN][i % TN], 0, 0, 0);
+            if constexpr (MORE) fetch_one(as_next, 0, nxt, i);
+            if constexpr (REFILL == 1)
+                if (i < Cfg::LPW) issue_one(as, i);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+        if constexpr (MORE) {
+#pragma unroll
+            for (int i = TM * TN; i < TM + TN; ++i) fetch_one(as_next, 0, nxt, i);
+        }
+        if constexpr (REFILL == 1) {
+#pragma unroll
+            for (int i = TM * TN; i < Cfg::LPW; ++i) issue_one(as, i);
+            advance_full();
+        }
+    };
+    using I0 = std::integral_constant<int, 0>;
+    using I1 = std::integral_constant<int, 1>;
+    using I2 = std::integral_constant<int, 2>;
+    int kt = 0;
+    for (; kt + STAGES < nkf; ++kt) k_tile(kt, std::true_type{}, I1{});  // the hot loop
+    for (; kt + STAGES < nk; ++kt) k_tile(kt, std::true_type{}, I2{});   // last base + expand tiles
+    for (; kt + 1 < nk; ++kt) k_tile(kt, std::true_type{}, I0{});        // nothing left to load
+    k_tile(kt, std::false_type{}, I0{});
 
     // ---- epilogue: every row to its original position ----
     // acc[tm][tn][v]: row tm*32 + (v/4)*8 + (lane/32)*4 + v%4, column tn*32 + lane%32.
@@ -397,33 +368,7 @@ __global__ __launch_bounds__(Cfg::NT) void fused_gemm_kernel(
     // stores to scattered rows are what the memory system handles worst.
     constexpr int EP_STRIDE = BN * 4 + 32;           // bytes per staged row (+32: bank shift)
     constexpr int EP_CPR = BN / 4;                   // 16-byte chunks per row
-    if constexpr (Cfg::WK > 1) {
-        // k-split wavefronts: all partial tiles go to LDS at once and are added in a fixed order
-        static_assert(Cfg::WK * BM * EP_STRIDE <= STAGES * Cfg::STAGE, "partial tiles fit the stages");
-        __syncthreads();
-#pragma unroll
-        for (int tm = 0; tm < TM; ++tm)
-#pragma unroll
-            for (int v = 0; v < 16; ++v) {
-                const int rr = wm * (BM / Cfg::WM) + tm * 32 + (v >> 2) * 8 + (lane >> 5) * 4 + (v & 3);
-#pragma unroll
-                for (int tn = 0; tn < TN; ++tn) {
-                    const int col = wn * (BN / Cfg::WN) + tn * 32 + (lane & 31);
-                    *(float *)(smem + (wk * BM + rr) * EP_STRIDE + col * 4) = acc[tm][tn][v];
-                }
-            }
-        __syncthreads();
-        for (int it = tid; it < BM * EP_CPR; it += NT) {
-            const int row = it / EP_CPR, ch = it % EP_CPR;
-            const int tok = tile_perm[row];
-            const int col = n0 + ch * 4;
-            if (tok < 0 || col >= d_out) continue;
-            f32x4 sum = *(const f32x4 *)(smem + row * EP_STRIDE + ch * 16);
-#pragma unroll
-            for (int w = 1; w < Cfg::WK; ++w) sum += *(const f32x4 *)(smem + (w * BM + row) * EP_STRIDE + ch * 16);
-            *(f32x4 *)(h + (int64_t)tok * d_out + col) = sum;
-        }
-    } else {
+    {
         constexpr int EP_ROWS = Cfg::WM * 32;
         static_assert(EP_ROWS * EP_STRIDE <= STAGES * Cfg::STAGE, "epilogue staging fits the stages");
 #pragma unroll
@@ -476,13 +421,13 @@ hipError_t launch_cfg(const uint16_t *x, const uint16_t *W, const uint16_t *B, c
 #define MOLORA_SMALL_BATCH_MAX 512  // up to here W is streamed once per 64-row tile instead (measured crossover)
 #endif
 #ifndef MOLORA_GEMM_BIG
-#define MOLORA_GEMM_BIG 256, 256, 2, 4, 1, 64, 2
+#define MOLORA_GEMM_BIG 256, 256, 2, 4, 64, 2
 #endif
 #ifndef MOLORA_GEMM_SMALL
-#define MOLORA_GEMM_SMALL 128, 128, 2, 2, 1, 64, 2
+#define MOLORA_GEMM_SMALL 128, 128, 2, 2, 64, 2
 #endif
-#ifndef MOLORA_GEMM_STREAM
-#define MOLORA_GEMM_STREAM 64, 64, 2, 2, 4, 64, 8
+#ifndef MOLORA_GEMM_MID
+#define MOLORA_GEMM_MID 128, 128, 2, 2, 64, 3
 #endif
 
 hipError_t launch_fused_gemm(const uint16_t *x, const uint16_t *W, const uint16_t *B,
@@ -497,6 +442,11 @@ hipError_t launch_fused_gemm(const uint16_t *x, const uint16_t *W, const uint16_
     const int64_t t256 = ((N + 255) / 256) * ((d_out + 255) / 256);
     if (t256 >= 512)
         return launch_cfg<GemmCfg<MOLORA_GEMM_BIG>>(x, W, B, t2, offsets, perm, h, N, d_in, d_out, C, rank, mix, s);
+    // 128 x 128 tiles: with at most one workgroup per compute unit a third stage replaces the
+    // second resident workgroup as the way to cover the load latency
+    const int64_t t128 = ((N + 127) / 128) * ((d_out + 127) / 128);
+    if (t128 <= 256)
+        return launch_cfg<GemmCfg<MOLORA_GEMM_MID>>(x, W, B, t2, offsets, perm, h, N, d_in, d_out, C, rank, mix, s);
     return launch_cfg<GemmCfg<MOLORA_GEMM_SMALL>>(x, W, B, t2, offsets, perm, h, N, d_in, d_out, C, rank, mix, s);
 }
 
