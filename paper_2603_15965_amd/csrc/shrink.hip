@@ -25,18 +25,20 @@ namespace molora {
 namespace {
 
 constexpr int kShrinkThreads = 256;
-constexpr int kShrinkRows = 32;  // sorted rows per work item
 constexpr int kStepK = 32;       // k per MFMA step
 constexpr int kDepth = 4;        // steps in flight per wavefront
 
 // R = mix.k * rank is the width of a bucket's intermediate: piece j of it is x A of the j-th
 // adapter of the bucket's tuple, scaled by the token's j-th mixture weight.
-template <int NJ>  // NJ = number of 16-column blocks covering R
+// NJ = number of 16-column blocks covering R; RB = 16-row blocks per work item (2 for large
+// batches, 1 when 32-row items would leave compute units without work)
+template <int NJ, int RB>
 __global__ __launch_bounds__(kShrinkThreads) void shrink_kernel(
     const uint16_t *__restrict__ x, const uint16_t *__restrict__ A,
     const int32_t *__restrict__ offsets, const int32_t *__restrict__ perm,
     uint16_t *__restrict__ t2, int d_in, int C, int rank, Mix mix) {
     const int R = mix.k * rank;
+    constexpr int kShrinkRows = 16 * RB;                 // sorted rows per work item
     constexpr int RP = NJ * 16;                          // padded rank
     constexpr int ROWB = RP * 2 + (RP >= 64 ? 32 : 0);   // LDS bytes per slab row (bank shift)
     constexpr int SLABB = kStepK * ROWB;                 // one step's slab of one wavefront
@@ -99,9 +101,9 @@ __global__ __launch_bounds__(kShrinkThreads) void shrink_kernel(
     const int l16 = lane & 15, kg = lane >> 4;
     // x rows of this lane in the two 16-row blocks; a row past the chunk's end re-reads the
     // first row (its result is never stored), k past d_in is clamped and meets a zeroed A.
-    const uint16_t *xrow[2];
+    const uint16_t *xrow[RB];
 #pragma unroll
-    for (int rb = 0; rb < 2; ++rb) {
+    for (int rb = 0; rb < RB; ++rb) {
         const int p = p_first + rb * 16 + l16;
         xrow[rb] = x + (int64_t)perm[p < p_end ? p : p_first] * d_in;
     }
@@ -117,12 +119,12 @@ __global__ __launch_bounds__(kShrinkThreads) void shrink_kernel(
     }
     unsigned char *slab0 = lds + wave * 2 * SLABB;
 
-    u32x4 xg[kDepth][2], ag[kDepth][NJ];
+    u32x4 xg[kDepth][RB], ag[kDepth][NJ];
     auto load_step = [&](int slot, int s) {  // step s of this wavefront into ring slot
         const int k0 = k_begin + s * kStepK;
         const int kx = min(k0 + kg * 8, d_in - 8);
 #pragma unroll
-        for (int rb = 0; rb < 2; ++rb) xg[slot][rb] = *(const u32x4 *)(xrow[rb] + kx);
+        for (int rb = 0; rb < RB; ++rb) xg[slot][rb] = *(const u32x4 *)(xrow[rb] + kx);
 #pragma unroll
         for (int m = 0; m < NJ; ++m) {
             const int id = lane + 64 * m;
@@ -135,9 +137,9 @@ __global__ __launch_bounds__(kShrinkThreads) void shrink_kernel(
         }
     };
 
-    f32x4 acc[2][NJ];
+    f32x4 acc[RB][NJ];
 #pragma unroll
-    for (int rb = 0; rb < 2; ++rb)
+    for (int rb = 0; rb < RB; ++rb)
 #pragma unroll
         for (int j = 0; j < NJ; ++j) acc[rb][j] = f32x4{0.f, 0.f, 0.f, 0.f};
 
@@ -156,8 +158,6 @@ __global__ __launch_bounds__(kShrinkThreads) void shrink_kernel(
                     const int kr = id / (RP / 8), u = id % (RP / 8);
                     *(u32x4 *)(slab + kr * ROWB + u * 16) = ag[d][m];
                 }
-                const bf16x8 a0 = __builtin_bit_cast(bf16x8, xg[d][0]);
-                const bf16x8 a1 = __builtin_bit_cast(bf16x8, xg[d][1]);
 #pragma unroll
                 for (int jb = 0; jb < NJ; ++jb) {
                     // rows kg*8 + {0..3 | 4..7}, columns jb*16 .. +15 of the slab
@@ -167,8 +167,10 @@ __global__ __launch_bounds__(kShrinkThreads) void shrink_kernel(
                     const i16x8 b8 = {b_lo[0], b_lo[1], b_lo[2], b_lo[3],
                                       b_hi[0], b_hi[1], b_hi[2], b_hi[3]};
                     const bf16x8 bfrag = __builtin_bit_cast(bf16x8, b8);
-                    acc[0][jb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a0, bfrag, acc[0][jb], 0, 0, 0);
-                    acc[1][jb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a1, bfrag, acc[1][jb], 0, 0, 0);
+#pragma unroll
+                    for (int rb = 0; rb < RB; ++rb)
+                        acc[rb][jb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(
+                            __builtin_bit_cast(bf16x8, xg[d][rb]), bfrag, acc[rb][jb], 0, 0, 0);
                 }
                 load_step(d, s + kDepth);  // refill the ring slot
             }
@@ -178,9 +180,9 @@ __global__ __launch_bounds__(kShrinkThreads) void shrink_kernel(
     // ---- add the four partial sums in a fixed order, split into bf16 hi + lo, store ----
     // acc[rb][jb][v] = t[row rb*16 + kg*4 + v][column jb*16 + l16]
     __syncthreads();  // all wavefronts are done with their slabs
-    float *red = (float *)lds;  // [4][32][RP]
+    float *red = (float *)lds;  // [4][rows][RP]
 #pragma unroll
-    for (int rb = 0; rb < 2; ++rb)
+    for (int rb = 0; rb < RB; ++rb)
 #pragma unroll
         for (int jb = 0; jb < NJ; ++jb)
 #pragma unroll
@@ -216,15 +218,25 @@ hipError_t launch_shrink(const uint16_t *x, const uint16_t *A, const int32_t *of
                          const int32_t *perm, uint16_t *t2, int64_t N, int d_in, int C, int rank,
                          Mix mix, hipStream_t s) {
     if (N == 0) return hipSuccess;
-    // up to 64 tokens the step is bound by the latency of streaming the touched A_c: one
-    // workgroup per bucket with the K range split over its wavefronts
-    if (N <= 64) return launch_small_batch_shrink(x, A, offsets, perm, t2, N, d_in, C, rank, mix, s);
-    const unsigned blocks = (unsigned)((N + kShrinkRows - 1) / kShrinkRows + C);
+    // small batches are bound by the latency of streaming the touched A_c: one workgroup per
+    // 64 rows of a bucket with the K range split over its wavefronts
+    // (up to 64 tokens always; up to 2048 tokens when a bucket's A is large enough that the
+    // row-item kernel below, which splits K four ways only, would be latency bound: measured)
+    if (N <= 64 || (N <= 2048 && (int64_t)d_in * mix.k * rank >= 131072))
+        return launch_small_batch_shrink(x, A, offsets, perm, t2, N, d_in, C, rank, mix, s);
+    // 32-row items when they still cover the chip twice, 16-row items otherwise
+    const bool small_items = (N + 31) / 32 + C < 512;
+    const int rows = small_items ? 16 : 32;
+    const unsigned blocks = (unsigned)((N + rows - 1) / rows + C);
     const int nj = (mix.k * rank + 15) / 16;
-#define MOLORA_SHRINK_CASE(NJ)                                                                  \
-    case NJ:                                                                                    \
-        hipLaunchKernelGGL(shrink_kernel<NJ>, dim3(blocks), dim3(kShrinkThreads), 0, s, x, A,   \
-                           offsets, perm, t2, d_in, C, rank, mix);                              \
+#define MOLORA_SHRINK_CASE(NJ)                                                                   \
+    case NJ:                                                                                     \
+        if (small_items)                                                                         \
+            hipLaunchKernelGGL((shrink_kernel<NJ, 1>), dim3(blocks), dim3(kShrinkThreads), 0, s, \
+                               x, A, offsets, perm, t2, d_in, C, rank, mix);                     \
+        else                                                                                     \
+            hipLaunchKernelGGL((shrink_kernel<NJ, 2>), dim3(blocks), dim3(kShrinkThreads), 0, s, \
+                               x, A, offsets, perm, t2, d_in, C, rank, mix);                     \
         break;
     switch (nj) {
         MOLORA_SHRINK_CASE(1)

@@ -47,8 +47,9 @@ struct Unit {
 // SHRINK = false: the fused GEMM above (grid: column groups x row tiles of 64 sorted rows; a
 //                 batch of more than 64 rows re-reads W once per row tile, from L2).
 // SHRINK = true:  the shrink step t_p = x[perm[p]] A_c for the rows of bucket c = blockIdx.y
-//                 (grid: column groups of the rank x buckets); W is A, d_out is rank, there
-//                 are no expand units and the result goes to t_out as [hi | lo] bf16 halves.
+//                 (grid: column groups of the rank x buckets x 64-row tiles of a bucket); W is
+//                 A, d_out is rank, there are no expand units and the result goes to t_out as
+//                 [hi | lo] bf16 halves.
 template <int TM, bool SHRINK>  // TM: 32-row blocks, 1 (N <= 32) or 2
 __global__ __launch_bounds__(kSbWaves * 64) void small_batch_kernel(
     const uint16_t *__restrict__ x, const uint16_t *__restrict__ W, const uint16_t *__restrict__ B,
@@ -74,9 +75,9 @@ __global__ __launch_bounds__(kSbWaves * 64) void small_batch_kernel(
     int row_base = 0, nrows = N, bucket = 0;
     if constexpr (SHRINK) {
         bucket = blockIdx.y;
-        row_base = offsets[bucket];
-        nrows = offsets[bucket + 1] - row_base;
-        if (nrows <= 0) return;  // empty bucket: its adapters are not touched
+        row_base = offsets[bucket] + 64 * blockIdx.z;  // 64-row tile of the bucket
+        nrows = min(64, offsets[bucket + 1] - row_base);
+        if (nrows <= 0) return;  // nothing (left) in this bucket: its adapters are not touched
     } else {
         row_base = blockIdx.y * 64;  // row tile of 64 sorted positions
         nrows = min(64, N - row_base);
@@ -363,8 +364,11 @@ hipError_t launch_small(const uint16_t *x, const uint16_t *W, const uint16_t *B,
                                                     (int)kSbLdsBytes);
     if (e != hipSuccess) return e;
     const unsigned groups = (unsigned)((d_out + kSbCols - 1) / kSbCols);
-    const unsigned tiles = SHRINK ? (unsigned)C : (unsigned)((N + 63) / 64);  // buckets | row tiles
-    hipLaunchKernelGGL(kern, dim3(groups, tiles), dim3(kSbWaves * 64), kSbLdsBytes, s, x, W,
+    const unsigned row_tiles = (unsigned)((N + 63) / 64);
+    // GEMM: row tiles of the batch.  SHRINK: buckets x row tiles a bucket can have at most
+    // (workgroups past a bucket's end leave at once)
+    const dim3 grid = SHRINK ? dim3(groups, (unsigned)C, row_tiles) : dim3(groups, row_tiles);
+    hipLaunchKernelGGL(kern, grid, dim3(kSbWaves * 64), kSbLdsBytes, s, x, W,
                        B, t2, offsets, perm, h, t_out, N, d_in, d_out, C, rank, mix);
     return hipGetLastError();
 }

@@ -117,6 +117,7 @@ def test_route_gate_bit_exact_full_configs(gpu, name):
     (64, 2048, 1024, 16, 64, "zipf"),       # small-batch path, many buckets in the one row tile
     (7, 1096, 264, 3, 8, "uniform"),        # small-batch path, K tail
     (200, 520, 328, 9, 24, "zipf"),         # small-batch path, four row tiles, ragged everywhere
+    (700, 2048, 136, 3, 64, "zipf"),        # buckets of several 64-row tiles in the small-batch shrink
     (600, 328, 1000, 7, 24, "zipf"),        # 128 x 128 tiles with three stages, K shorter than the ring
     (1500, 1096, 392, 5, 16, "uniform"),    # same, K tail tile
     (1000, 128, 136, 4, 128, "uniform"),    # maximum rank
