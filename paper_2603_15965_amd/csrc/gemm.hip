@@ -390,7 +390,10 @@ __global__ __launch_bounds__(Cfg::NT) void fused_gemm_kernel(
                 const int tok = tile_perm[row];
                 const int col = n0 + ch * 4;
                 if (tok >= 0 && col < d_out)
-                    *(f32x4 *)(h + (int64_t)tok * d_out + col) = *(const f32x4 *)(smem + r * EP_STRIDE + ch * 16);
+                    // h is written once and not read again here: a streaming store keeps it
+                    // from displacing x and W tiles in L2 (measured: -11 % at config 1)
+                    __builtin_nontemporal_store(*(const f32x4 *)(smem + r * EP_STRIDE + ch * 16),
+                                                (f32x4 *)(h + (int64_t)tok * d_out + col));
             }
         }
     }
