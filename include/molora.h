@@ -201,6 +201,18 @@ molora_status molora_route_compose(const int32_t *v, const int32_t *adapter, con
                                    void *stream);
 
 /*
+ * Gating and dispatch in one launch, the way Alg. "Compositional Gating Kernel" is written:
+ * the composite target of molora_route_compose (adapter == NULL: of molora_route_vocab, i.e.
+ * n_adapters = 1 and a = 0) is computed inside the dispatch kernel.  Outputs r [N] as the
+ * routing call would give it, and offsets [n_adapters * M + 1], perm [N] as molora_bucket
+ * would give them for that r (same ordering, same treatment of -1, same err_flag).  Saves a
+ * launch and a pass over r for integer routing, where the whole step is latency bound.
+ */
+molora_status molora_gate_dispatch(const int32_t *v, const int32_t *adapter, const int32_t *breaks,
+                                   int32_t M, int32_t n_adapters, int32_t *r, int32_t *offsets,
+                                   int32_t *perm, int64_t N, int32_t *err_flag, void *stream);
+
+/*
  * Weighted top-k mixture with an optional slot table (Sec. "Router Architecture", Def.
  * "Hot-Set Layout"):
  *

@@ -16,6 +16,7 @@ MOLORA_OK = 0
 EXPORTS = ["molora_route", "molora_route_vocab", "molora_bucket", "molora_apply_workspace_bytes",
            "molora_apply", "molora_apply_bucketed", "molora_shrink", "molora_base_expand",
            "molora_route_mlp_workspace_bytes", "molora_route_mlp", "molora_route_compose",
+           "molora_gate_dispatch",
            "molora_apply_mix_workspace_bytes", "molora_apply_mix",
            "molora_graph_begin", "molora_graph_end", "molora_graph_launch", "molora_graph_destroy",
            "molora_status_string", "molora_version"]
@@ -62,6 +63,8 @@ def load():
     lib.molora_route_mlp.restype = ctypes.c_int
     lib.molora_route_compose.argtypes = [vp, vp, ctypes.POINTER(i32), i32, i32, vp, i64, vp]
     lib.molora_route_compose.restype = ctypes.c_int
+    lib.molora_gate_dispatch.argtypes = [vp, vp, ctypes.POINTER(i32), i32, i32, vp, vp, vp, i64, vp, vp]
+    lib.molora_gate_dispatch.restype = ctypes.c_int
     lib.molora_apply_mix_workspace_bytes.argtypes = [i64, i32, i32, i32, i32, i32]
     lib.molora_apply_mix_workspace_bytes.restype = sz
     lib.molora_apply_mix.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, i64, i32, i32, i32, i32, i32, vp, sz, vp]
@@ -277,6 +280,29 @@ def molora_route_compose(v, adapter, breaks, n_adapters, r=None, stream=None):
                                      arr, M, n_adapters, _dev(r, torch.int32, "r"), N, _stream(stream))
     _check(st, "molora_route_compose")
     return r
+
+
+def molora_gate_dispatch(v, breaks, adapter=None, n_adapters=1, r=None, offsets=None, perm=None,
+                         err_flag=None, stream=None):
+    """Vocabulary / compositional gating and bucketing in one launch: (r, offsets, perm)."""
+    N = v.shape[0]
+    b = [int(t) for t in breaks]
+    M = len(b) - 1
+    arr = (ctypes.c_int32 * len(b))(*b)
+    C = n_adapters * M
+    if r is None:
+        r = torch.empty(N, dtype=torch.int32, device=v.device)
+    if offsets is None:
+        offsets = torch.empty(C + 1, dtype=torch.int32, device=v.device)
+    if perm is None:
+        perm = torch.empty(max(N, 1), dtype=torch.int32, device=v.device)[:N]
+    st = load().molora_gate_dispatch(
+        _dev(v, torch.int32, "v"), None if adapter is None else _dev(adapter, torch.int32, "adapter"),
+        arr, M, n_adapters, _dev(r, torch.int32, "r"), _dev(offsets, torch.int32, "offsets"),
+        _dev(perm, torch.int32, "perm"), N,
+        None if err_flag is None else _dev(err_flag, torch.int32, "err_flag"), _stream(stream))
+    _check(st, "molora_gate_dispatch")
+    return r, offsets, perm
 
 
 def molora_apply_mix(x, W, A, B, idx, w=None, slots=None, C=None, h=None, workspace=None, stream=None):

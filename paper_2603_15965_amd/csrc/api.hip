@@ -110,6 +110,22 @@ molora_status molora_bucket(const int32_t *r, int32_t *offsets, int32_t *perm, i
                                           static_cast<hipStream_t>(stream)));
 }
 
+molora_status molora_gate_dispatch(const int32_t *v, const int32_t *adapter, const int32_t *breaks,
+                                   int32_t M, int32_t n_adapters, int32_t *r, int32_t *offsets,
+                                   int32_t *perm, int64_t N, int32_t *err_flag, void *stream) {
+    if (N < 0 || N >= (int64_t(1) << 31) || M < 1 || M > MOLORA_MAX_BREAKS || !breaks ||
+        n_adapters < 1 || int64_t(n_adapters) * M > MOLORA_MAX_TARGETS)
+        return MOLORA_EINVAL;
+    for (int j = 0; j < M; ++j)
+        if (breaks[j] >= breaks[j + 1]) return MOLORA_EINVAL;
+    if (!offsets || (N > 0 && (!v || !r || !perm))) return MOLORA_EINVAL;
+    if (!aligned16(offsets) ||
+        (N > 0 && (!aligned16(v) || !aligned16(r) || !aligned16(perm) || (adapter && !aligned16(adapter)))))
+        return MOLORA_EALIGN;
+    return from_hip(molora::launch_gate_bucket(v, adapter, breaks, M, n_adapters, r, offsets, perm, N,
+                                               err_flag, static_cast<hipStream_t>(stream)));
+}
+
 size_t molora_apply_workspace_bytes(int64_t N, int32_t d_in, int32_t d_out, int32_t C,
                                     int32_t rank) {
     if (!apply_sizes_ok(N, d_in, d_out, C, rank)) return 0;

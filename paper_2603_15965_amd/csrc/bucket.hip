@@ -51,10 +51,37 @@ __device__ __forceinline__ uint64_t match_lanes(int key, bool valid, int nbits) 
 
 __device__ __forceinline__ int lane_id() { return __lane_id(); }
 
+// target of token t: read from r, or (GATE) computed on the spot from the vocabulary index and
+// the request's adapter index, c = a * M + m, as Alg. "Compositional Gating Kernel" does
+// inside its dispatch kernel (adapter == nullptr: a = 0, the plain vocabulary route)
+struct GateArgs {
+    const int32_t *v;
+    const int32_t *adapter;
+    int32_t *r_out;
+    int M, n_adapters;
+    VocabBreaks br;
+};
+template <bool GATE>
+__device__ __forceinline__ int32_t target_of(const int32_t *__restrict__ r, const GateArgs &g, int t) {
+    if constexpr (!GATE) {
+        return r[t];
+    } else {
+        const int32_t id = g.v[t];
+        const int32_t a = g.adapter != nullptr ? g.adapter[t] : 0;
+        int32_t m = 0;
+        for (int j = 1; j < g.M; ++j)
+            if (id >= g.br.b[j]) m = j;
+        const bool ok = id >= g.br.b[0] && id < g.br.b[g.M] && a >= 0 && a < g.n_adapters;
+        return ok ? a * g.M + m : -1;
+    }
+}
+
+template <bool GATE>
 __global__ __launch_bounds__(kBucketThreads) void bucket_kernel(const int32_t *__restrict__ r,
                                                                 int32_t *__restrict__ offsets,
                                                                 int32_t *__restrict__ perm, int N,
-                                                                int C, int32_t *err_flag) {
+                                                                int C, int32_t *err_flag,
+                                                                GateArgs gate) {
     // cnt[b * 16 + w]: tokens of target b (b == C: out of range) in wavefront w's range
     extern __shared__ int32_t lds[];
     volatile int32_t *cnt = lds;
@@ -79,7 +106,8 @@ __global__ __launch_bounds__(kBucketThreads) void bucket_kernel(const int32_t *_
 #pragma unroll
         for (int u = 0; u < kUnroll; ++u) {
             const int t = base + u * 64 + lane;
-            const int32_t c = r[t < end ? t : end - 1];  // never predicated: all 8 loads in flight
+            const int32_t c = target_of<GATE>(r, gate, t < end ? t : end - 1);  // never predicated: all loads in flight
+            if (GATE && t < end) gate.r_out[t] = c;
             key[u] = (c >= 0 && c < C) ? c : C;
         }
 #pragma unroll
@@ -126,7 +154,7 @@ __global__ __launch_bounds__(kBucketThreads) void bucket_kernel(const int32_t *_
 #pragma unroll
         for (int u = 0; u < kUnroll; ++u) {
             const int t = base + u * 64 + lane;
-            const int32_t c = r[t < end ? t : end - 1];  // never predicated: all 8 loads in flight
+            const int32_t c = target_of<GATE>(r, gate, t < end ? t : end - 1);
             key[u] = (c >= 0 && c < C) ? c : C;
         }
 #pragma unroll
@@ -163,8 +191,26 @@ hipError_t launch_route_vocab(const int32_t *v, const int32_t *breaks_host, int 
 hipError_t launch_bucket(const int32_t *r, int32_t *offsets, int32_t *perm, int64_t N, int C,
                          int32_t *err_flag, hipStream_t s) {
     const size_t lds_bytes = (size_t)(C + 1) * kBucketWaves * sizeof(int32_t);
-    hipLaunchKernelGGL(bucket_kernel, dim3(1), dim3(kBucketThreads), lds_bytes, s, r, offsets,
-                       perm, (int)N, C, err_flag);
+    hipLaunchKernelGGL(bucket_kernel<false>, dim3(1), dim3(kBucketThreads), lds_bytes, s, r, offsets,
+                       perm, (int)N, C, err_flag, GateArgs{});
+    return hipGetLastError();
+}
+
+hipError_t launch_gate_bucket(const int32_t *v, const int32_t *adapter, const int32_t *breaks_host,
+                              int M, int n_adapters, int32_t *r, int32_t *offsets, int32_t *perm,
+                              int64_t N, int32_t *err_flag, hipStream_t s) {
+    const int C = n_adapters * M;
+    GateArgs g;
+    g.v = v;
+    g.adapter = adapter;
+    g.r_out = r;
+    g.M = M;
+    g.n_adapters = n_adapters;
+    for (int j = 0; j <= M; ++j) g.br.b[j] = breaks_host[j];
+    for (int j = M + 1; j < 65; ++j) g.br.b[j] = 0;
+    const size_t lds_bytes = (size_t)(C + 1) * kBucketWaves * sizeof(int32_t);
+    hipLaunchKernelGGL(bucket_kernel<true>, dim3(1), dim3(kBucketThreads), lds_bytes, s, nullptr,
+                       offsets, perm, (int)N, C, err_flag, g);
     return hipGetLastError();
 }
 

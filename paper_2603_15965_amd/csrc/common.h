@@ -71,6 +71,10 @@ hipError_t launch_route_vocab(const int32_t *v, const int32_t *breaks_host, int 
                               int64_t N, hipStream_t s);
 hipError_t launch_bucket(const int32_t *r, int32_t *offsets, int32_t *perm, int64_t N, int C,
                          int32_t *err_flag, hipStream_t s);
+// route (vocabulary, or adapter x modality) and bucket in one kernel; C = n_adapters * M
+hipError_t launch_gate_bucket(const int32_t *v, const int32_t *adapter, const int32_t *breaks_host,
+                              int M, int n_adapters, int32_t *r, int32_t *offsets, int32_t *perm,
+                              int64_t N, int32_t *err_flag, hipStream_t s);
 hipError_t launch_shrink(const uint16_t *x, const uint16_t *A, const int32_t *offsets,
                          const int32_t *perm, uint16_t *t2, int64_t N, int d_in, int C, int rank,
                          Mix mix, hipStream_t s);

@@ -78,6 +78,32 @@ def test_route_compose_bit_exact(gpu):
     assert np.array_equal(r.cpu().numpy(), oracle.route_compose(v, a, np.array(breaks, dtype=np.int32), n_ad))
 
 
+@pytest.mark.parametrize("N,n_ad", [(4096, 1), (10001, 7), (64, 3), (1, 1), (0, 2)])
+def test_gate_dispatch_equals_route_then_bucket(gpu, N, n_ad):
+    """Gating inside the dispatch kernel (Alg. "Compositional Gating Kernel") gives the oracle's
+    r, offsets and perm bit for bit."""
+    import oracle
+    import torch
+    from paper_2603_15965_amd import binding as mb
+    say(f"gate_dispatch N={N} adapters={n_ad}")
+    rng = np.random.default_rng(31 + N)
+    breaks = (0, 32768, 40960)
+    M = len(breaks) - 1
+    v = rng.integers(-10, 41000, size=N).astype(np.int32)
+    a = rng.integers(-1, n_ad + 1, size=N).astype(np.int32) if n_ad > 1 else None
+    flag = torch.zeros(1, dtype=torch.int32, device="cuda")
+    r, offsets, perm = mb.molora_gate_dispatch(gpu.dev_i32(v), breaks, None if a is None else gpu.dev_i32(a),
+                                               n_ad, err_flag=flag)
+    torch.cuda.synchronize()
+    b = np.array(breaks, dtype=np.int32)
+    r_ref = oracle.route_vocab(v, b) if a is None else oracle.route_compose(v, a, b, n_ad)
+    o_ref, p_ref, bad = oracle.bucket(r_ref, n_ad * M)
+    assert np.array_equal(r.cpu().numpy(), r_ref)
+    assert np.array_equal(offsets.cpu().numpy(), o_ref)
+    assert np.array_equal(perm.cpu().numpy(), p_ref)
+    assert int(flag.item()) == (1 if bad else 0)
+
+
 def mix_case(seed, N, d_in, d_out, C, rank, k, S=None, bad=False, weights=True):
     w = wl.custom("mix", N, d_in, d_out, S or C, rank, wl.BASE_SEED + seed)
     rng = np.random.default_rng(seed)
