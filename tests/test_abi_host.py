@@ -73,3 +73,55 @@ def test_bad_arguments_are_rejected_before_launch(lib):
     assert lib.molora_apply(*args(a, 1 << 20, rank=12)) == EINVAL
     assert lib.molora_apply(*args(a, 1 << 20, x=0)) == EINVAL
     assert lib.molora_apply_bucketed(p(a), p(a), p(a), p(a), None, p(a), p(a), 16, 64, 64, 4, 8, p(a), 1 << 20, None) == EINVAL
+
+
+def test_widened_entry_points_reject_bad_arguments(lib):
+    EINVAL, EALIGN, EWORKSPACE = -1, -2, -3
+    p = ctypes.c_void_p
+    buf = (ctypes.c_char * 8192)()
+    a = ctypes.addressof(buf)
+    a += (-a) % 256
+    r256 = lambda b: (b + 255) // 256 * 256
+    # router MLP: hidden pre-activations are the only scratch
+    f = lib.molora_route_mlp_workspace_bytes
+    assert f(100, 64) == r256(100 * 64 * 4)
+    assert f(100, 60) == 0 and f(100, 512) == 0 and f(-1, 64) == 0
+    mlp = lambda k=2, H=64, K=8, ws=a, nb=1 << 20, x=a: lib.molora_route_mlp(
+        p(x), p(a), p(a), p(a), p(a), p(a), p(a), 16, 64, H, K, k, p(ws), nb, None)
+    assert mlp(k=0) == EINVAL and mlp(k=5) == EINVAL and mlp(k=3, K=2) == EINVAL
+    assert mlp(H=12) == EINVAL and mlp(K=2000) == EINVAL
+    assert mlp(x=0) == EINVAL
+    assert mlp(ws=a + 16) == EALIGN
+    assert mlp(nb=100) == EWORKSPACE
+    # compositional gating
+    br = (ctypes.c_int32 * 3)(0, 10, 20)
+    bad = (ctypes.c_int32 * 3)(0, 10, 5)
+    assert lib.molora_route_compose(p(a), p(a), bad, 2, 3, p(a), 16, None) == EINVAL
+    assert lib.molora_route_compose(p(a), p(a), br, 2, 0, p(a), 16, None) == EINVAL
+    assert lib.molora_route_compose(p(a), p(a), br, 2, 600, p(a), 16, None) == EINVAL   # 1200 targets
+    assert lib.molora_route_compose(p(a), None, br, 2, 3, p(a), 16, None) == EINVAL
+    assert lib.molora_route_compose(p(a + 4), p(a), br, 2, 3, p(a), 16, None) == EALIGN
+    assert lib.molora_route_compose(None, None, br, 2, 3, None, 0, None) == 0
+    assert lib.molora_gate_dispatch(p(a), None, bad, 2, 1, p(a), p(a), p(a), 16, None, None) == EINVAL
+    assert lib.molora_gate_dispatch(p(a), None, br, 2, 1, p(a), None, p(a), 16, None, None) == EINVAL
+    assert lib.molora_gate_dispatch(p(a), None, br, 2, 1, p(a), p(a + 4), p(a), 16, None, None) == EALIGN
+    # mixture: tuples must fit the bucket limit, the stacked rank the rank limit
+    g = lib.molora_apply_mix_workspace_bytes
+    N, C, rk, k = 300, 8, 16, 2
+    assert g(N, 64, 64, C, rk, k) == (r256(4 * N) + r256(4 * N * k) + r256(4 * (C ** k + 1)) + r256(4 * N)
+                                      + r256(N * 2 * k * rk * 2))
+    assert g(N, 64, 64, 40, rk, 2) == 0          # 1600 tuples
+    assert g(N, 64, 64, 4, 64, 4) == 0           # stacked rank 256
+    assert g(N, 64, 64, 4, 8, 5) == 0            # k above the limit
+    assert g(N, 64, 64, C, rk, 1) == r256(4 * N) + r256(4 * N) + r256(4 * (C + 1)) + r256(4 * N) + r256(N * 2 * rk * 2)
+    mix = lambda k=2, C=8, ws=a, nb=1 << 20, idx=a: lib.molora_apply_mix(
+        p(a), p(a), p(a), p(a), p(idx), None, None, p(a), 16, 64, 64, C, 8, k, p(ws), nb, None)
+    assert mix(k=0) == EINVAL and mix(C=40) == EINVAL and mix(idx=0) == EINVAL
+    assert mix(ws=a + 16) == EALIGN
+    assert mix(nb=64) == EWORKSPACE
+    # recorded sequences: the null stream cannot be captured, NULL handles are rejected
+    h = ctypes.c_void_p()
+    assert lib.molora_graph_begin(None) == EINVAL
+    assert lib.molora_graph_end(None, ctypes.byref(h)) == EINVAL
+    assert lib.molora_graph_launch(None, None) == EINVAL
+    lib.molora_graph_destroy(None)
