@@ -164,48 +164,59 @@ __global__ __launch_bounds__(TB * TGW * 64) void route_gate_kernel(
         g_load(K::KS);
         route_barrier();
 
-        int slab_idx = 0;  // slab being consumed
+        // The loop is software-pipelined by one chunk: while the 8 MFMA steps of chunk j run,
+        // chunk j+1 is regrouped into the other x buffer and its x and G fragments are read
+        // from LDS into a second register set, so a chain never waits for an LDS round trip.
+        int slab_idx = 0;  // slab of the chunk whose fragments are being read
+        auto regroup = [&](int j) {  // ring slot j -> x buffer j & 1 (steps in MFMA order)
+            unsigned char *xb = xs + (j & 1) * kXBuf;
+            const u32x4 w = xg[j];
+            *(uint32_t *)(xb + xs_wr + 0 * 16) = __builtin_amdgcn_perm(w[2], w[0], 0x05040100u);
+            *(uint32_t *)(xb + xs_wr + 1 * 16) = __builtin_amdgcn_perm(w[2], w[0], 0x07060302u);
+            *(uint32_t *)(xb + xs_wr + 2 * 16) = __builtin_amdgcn_perm(w[3], w[1], 0x05040100u);
+            *(uint32_t *)(xb + xs_wr + 3 * 16) = __builtin_amdgcn_perm(w[3], w[1], 0x07060302u);
+        };
+        u32x4 xr[2];
+        f32x4 g[2][NB][2];
+        auto read_frags = [&](int j, int set) {  // fragments of the chunk in ring position j
+            const float *slab = gs + (slab_idx & 1) * K::SLAB_FLOATS;
+            xr[set] = *(const u32x4 *)(xs + (j & 1) * kXBuf + xs_rd);  // steps 0..7 of this lane
+            const int st0 = ((j * kXK) % K::KS) / 4;  // first step of the chunk inside the slab
+#pragma unroll
+            for (int b = 0; b < NB; ++b) {
+                const float *gp = slab + ((tb * NB + b) * 16 + l16) * K::LDG + kq * (K::KS / 4) + st0;
+                g[set][b][0] = *(const f32x4 *)gp;
+                g[set][b][1] = *(const f32x4 *)(gp + 4);
+            }
+        };
+        regroup(0);
+        x_load(0, kSCK);
+        read_frags(0, 0);
         const int nsc = (d_in + kSCK - 1) / kSCK;
         for (int sc = 0; sc < nsc; ++sc) {
             const int k_sc = sc * kSCK;
 #pragma unroll
             for (int j = 0; j < kRing; ++j) {
-                const int k_ch = k_sc + j * kXK;  // first k of this chunk (may be past d_in)
-                const int ko = j * kXK;           // static offset inside the super-chunk
-                if (ko % K::KS == 0 && (sc > 0 || ko > 0)) {
-                    // next G slab: it was loaded into registers one slab ago
+                const int jn = (j + 1) % kRing;            // ring position of the next chunk
+                const int k_next = k_sc + (j + 1) * kXK;   // its first k (may be past d_in)
+                const int cur = j & 1, nxt = cur ^ 1;
+                regroup(jn);
+                x_load(jn, k_next + kSCK);  // refill the ring slot
+                if (((j + 1) * kXK) % K::KS == 0) {
+                    // the next chunk starts a G slab: it was loaded into registers one slab ago
                     ++slab_idx;
                     g_store(gs + (slab_idx & 1) * K::SLAB_FLOATS);
                     g_load((slab_idx + 1) * K::KS);
                     route_barrier();
                 }
-                // regroup the chunk: elements (e_kq', e_kq'+4) of the 8 loaded are steps
-                // (2cq, 2cq+1) of lane group kq'
-                unsigned char *xb = xs + (j & 1) * kXBuf;
-                const u32x4 w = xg[j];
-                *(uint32_t *)(xb + xs_wr + 0 * 16) = __builtin_amdgcn_perm(w[2], w[0], 0x05040100u);
-                *(uint32_t *)(xb + xs_wr + 1 * 16) = __builtin_amdgcn_perm(w[2], w[0], 0x07060302u);
-                *(uint32_t *)(xb + xs_wr + 2 * 16) = __builtin_amdgcn_perm(w[3], w[1], 0x05040100u);
-                *(uint32_t *)(xb + xs_wr + 3 * 16) = __builtin_amdgcn_perm(w[3], w[1], 0x07060302u);
-                x_load(j, k_ch + kSCK);  // refill the ring slot
-
-                const float *slab = gs + (slab_idx & 1) * K::SLAB_FLOATS;
-                const u32x4 xr = *(const u32x4 *)(xb + xs_rd);  // steps 0..7 of this lane
-                f32x4 g[NB][2];
-                const int st0 = (ko % K::KS) / 4;  // first step of the chunk inside the slab
-#pragma unroll
-                for (int b = 0; b < NB; ++b) {
-                    const float *gp = slab + ((tb * NB + b) * 16 + l16) * K::LDG + kq * (K::KS / 4) + st0;
-                    g[b][0] = *(const f32x4 *)gp;
-                    g[b][1] = *(const f32x4 *)(gp + 4);
-                }
+                read_frags(jn, nxt);
 #pragma unroll
                 for (int s = 0; s < 8; ++s) {
-                    const uint32_t ww = xr[s >> 1];
+                    const uint32_t ww = xr[cur][s >> 1];
                     const float xa = __uint_as_float((s & 1) ? (ww & 0xFFFF0000u) : (ww << 16));
 #pragma unroll
                     for (int b = 0; b < NB; ++b)
-                        acc[b] = __builtin_amdgcn_mfma_f32_16x16x4f32(xa, g[b][s >> 2][s & 3],
+                        acc[b] = __builtin_amdgcn_mfma_f32_16x16x4f32(xa, g[cur][b][s >> 2][s & 3],
                                                                       acc[b], 0, 0, 0);
                 }
             }
