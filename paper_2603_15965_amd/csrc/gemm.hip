@@ -51,7 +51,7 @@ struct GemmCfg {
     static constexpr int A_PIECES = BM / A_RPI, B_PIECES = BK / B_RPI;
     static constexpr int LPW = (A_PIECES + B_PIECES) / NW;  // pieces (loads) per wavefront and tile
     static constexpr int A_BYTES = BM * A_RB, B_BYTES = BK * B_RB, STAGE = A_BYTES + B_BYTES;
-    static constexpr size_t LDS_BYTES = (size_t)STAGES * STAGE + 4 * BM * sizeof(int32_t) + 16;
+    static constexpr size_t LDS_BYTES = (size_t)STAGES * STAGE + 8 * BM * sizeof(int32_t) + 16;
     static_assert(BK == 32 || BK == 64, "BK");
     static_assert(LPW * NW == A_PIECES + B_PIECES && LPW >= 1, "pieces split evenly over wavefronts");
     static_assert(STAGES >= 2 && STAGES <= 4, "stages");
@@ -78,6 +78,7 @@ __global__ __launch_bounds__(Cfg::NT) void fused_gemm_kernel(
     int32_t *seg_lo = seg_c + BM;
     int32_t *seg_hi = seg_lo + BM;
     int32_t *nseg_p = seg_hi + BM;
+    int32_t *seg_ad = nseg_p + 4;  // [BM][4] pool positions of the adapters of a bucket's tuple
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -107,6 +108,8 @@ __global__ __launch_bounds__(Cfg::NT) void fused_gemm_kernel(
             seg_c[idx] = c;
             seg_lo[idx] = lo;
             seg_hi[idx] = hi;
+            // slot table and tuple decoded once here, not inside the K loop
+            for (int j = 0; j < mix.k; ++j) seg_ad[idx * 4 + j] = mix_adapter(mix, c, j);
         }
     }
     __syncthreads();
@@ -199,7 +202,7 @@ __global__ __launch_bounds__(Cfg::NT) void fused_gemm_kernel(
         // expand tile: A operand = t rows of one bucket (others zero), B operand = [B_c; B_c]
         const int e = T - nkb;
         const int sg = e / tps, sub = e % tps;
-        const int c = seg_c[sg], lo = seg_lo[sg], hi = seg_hi[sg];
+        const int lo = seg_lo[sg], hi = seg_hi[sg];
 #pragma unroll
         for (int i = 0; i < Cfg::LPW; ++i) {
             const uint16_t *src;
@@ -212,7 +215,7 @@ __global__ __launch_bounds__(Cfg::NT) void fused_gemm_kernel(
                 const int vk = sub * BK + row;
                 const int j = vk < R ? vk : vk - R;        // row of the tuple's stacked B
                 const int jj = mix.k > 1 ? j / rank : 0;   // which adapter of the tuple
-                const int64_t brow = (int64_t)mix_adapter(mix, c, jj) * rank + (j - jj * rank);
+                const int64_t brow = (int64_t)seg_ad[sg * 4 + jj] * rank + (j - jj * rank);
                 src = (vk < two_r) ? B + brow * d_out + col : zero;
             }
             load_to_lds16_ptr(src, stage + piece_of(i) * 1024);

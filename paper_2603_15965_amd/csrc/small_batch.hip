@@ -5,7 +5,8 @@
 // With at most 64 rows the step is bound by reading W (and the touched B_c) once from HBM,
 // so the kernel is built around keeping many bytes in flight per compute unit and around
 // spending few cache-line accesses per byte, with no workgroup barrier in the streaming loop:
-//   * a workgroup owns 64 output columns and all rows; its 8 wavefronts split the K range
+//   * a workgroup owns 64 (or 32, where that is needed to occupy the chip) output columns and
+//     up to 64 rows; its 8 wavefronts split the K range
 //     (the d_in rows of W, then the 2*rank rows of [B_c; B_c] of every bucket that owns rows)
 //     in units of 64 k and add their partial tiles in LDS at the end, in wavefront order, so
 //     the result does not depend on timing and needs no scratch memory or atomics;
@@ -28,20 +29,36 @@ namespace molora {
 namespace {
 
 constexpr int kSbWaves = 8;                    // wavefronts per workgroup = K splits
-constexpr int kSbCols = 64;                    // output columns per workgroup
-constexpr int kSbSlot = 16 * kSbCols * 2;      // one 16-k slab of W: 2 KB, two load instructions
 constexpr int kSbRing = 5;                     // slab slots per wavefront
 constexpr int kSbStage = 64 * 128;             // x / t staging tile: 64 rows x 64 k
-constexpr int kSbRowBytes = kSbCols * 4 + 16;  // partial tile row in LDS (+16: bank shift)
-constexpr int kSbWaveLds = kSbRing * kSbSlot + kSbStage;  // per wavefront; partial tile reuses it
-static_assert(64 * kSbRowBytes <= kSbWaveLds, "partial tile fits the wavefront's region");
-constexpr size_t kSbLdsBytes = (size_t)kSbWaves * kSbWaveLds + (4 * 64 + 4) * sizeof(int32_t);
+
+// TN = 32-column blocks per workgroup: 2 (64 columns, 128-byte pieces of W rows) where the
+// column groups alone fill the chip, 1 (32 columns) where they would leave it idle.
+template <int TN>
+struct SbGeom {
+    static constexpr int COLS = 32 * TN;                // output columns per workgroup
+    static constexpr int SLOT = 16 * COLS * 2;          // one 16-k slab of W
+    static constexpr int NR = SLOT / 1024;              // load instructions per slab
+    static constexpr int CPR = COLS / 8;                // 16-byte chunks per slab row
+    static constexpr int RPD = 64 / CPR;                // slab rows per load instruction
+    static constexpr int ROW_BYTES = COLS * 4 + 16;     // partial tile row in LDS (+16: bank shift)
+    static constexpr int WAVE_LDS = kSbRing * SLOT + kSbStage;  // per wavefront; partial tile reuses it
+    static constexpr size_t LDS_BYTES = (size_t)kSbWaves * WAVE_LDS + (8 * 64 + 4) * sizeof(int32_t);
+    static_assert(64 * ROW_BYTES <= WAVE_LDS, "partial tile fits the wavefront's region");
+    // 32-byte chunk position inside a slab row that holds column chunk cc of k-row `row`
+    // (keeps the transpose reads of the four 16-lane groups on different banks)
+    __device__ static __forceinline__ int swz32(int cc, int row) {
+        if constexpr (TN == 2) return cc ^ (row & 3);
+        return cc ^ ((row >> 3) & 1);
+    }
+};
 
 // one unit of a wavefront's work list: 4 steps of 16 k
 struct Unit {
     int kind;  // 0: rows k0 .. k0+63 of W; 1: rows of [B_c; B_c]; 2: nothing (zeros)
     int k0;    // kind 0: first k.  kind 1: first row of [B_c; B_c] (0 .. 2*rank)
-    int c, lo, hi;  // kind 1: bucket and its sorted-position range
+    int lo, hi;  // kind 1: the bucket's sorted-position range ...
+    int ad[4];   // ... and the pool positions of the adapters of its tuple
 };
 
 // SHRINK = false: the fused GEMM above (grid: column groups x row tiles of 64 sorted rows; a
@@ -50,18 +67,22 @@ struct Unit {
 //                 (grid: column groups of the rank x buckets x 64-row tiles of a bucket); W is
 //                 A, d_out is rank, there are no expand units and the result goes to t_out as
 //                 [hi | lo] bf16 halves.
-template <int TM, bool SHRINK>  // TM: 32-row blocks, 1 (N <= 32) or 2
+template <int TM, int TN, bool SHRINK>  // TM: 32-row blocks, 1 (N <= 32) or 2
 __global__ __launch_bounds__(kSbWaves * 64) void small_batch_kernel(
     const uint16_t *__restrict__ x, const uint16_t *__restrict__ W, const uint16_t *__restrict__ B,
     const uint16_t *__restrict__ t2, const int32_t *__restrict__ offsets,
     const int32_t *__restrict__ perm, float *__restrict__ h, uint16_t *__restrict__ t_out, int N,
     int d_in, int d_out, int C, int rank, Mix mix) {
+    using Geo = SbGeom<TN>;
+    constexpr int kSbCols = Geo::COLS, kSbSlot = Geo::SLOT, kSbRowBytes = Geo::ROW_BYTES,
+                  kSbWaveLds = Geo::WAVE_LDS;
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
     int32_t *tile_perm = (int32_t *)(smem + kSbWaves * kSbWaveLds);  // [64] token per row, -1 = none
     int32_t *seg_c = tile_perm + 64;                                 // buckets that own rows,
     int32_t *seg_lo = seg_c + 64;                                    // ascending, with their
     int32_t *seg_hi = seg_lo + 64;                                   // sorted-position ranges
     int32_t *nseg_p = seg_hi + 64;
+    int32_t *seg_ad = nseg_p + 4;  // [64][4] pool positions of the adapters of a bucket's tuple
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -100,6 +121,9 @@ __global__ __launch_bounds__(kSbWaves * 64) void small_batch_kernel(
                 seg_c[idx] = c;
                 seg_lo[idx] = lo;
                 seg_hi[idx] = hi;
+                // decoded here, once: a slot-table read inside the streaming loop would have to
+                // wait for every load in flight
+                for (int j = 0; j < 4; ++j) seg_ad[idx * 4 + j] = j < mix.k ? mix_adapter(mix, c, j) : 0;
             }
             cnt += __popcll(m);
         }
@@ -130,7 +154,8 @@ __global__ __launch_bounds__(kSbWaves * 64) void small_batch_kernel(
     };
     auto unit_of = [&](const Cursor &cu) {
         Unit un;
-        un.c = un.lo = un.hi = 0;
+        un.lo = un.hi = 0;
+        un.ad[0] = un.ad[1] = un.ad[2] = un.ad[3] = 0;
         if (cu.u >= u1) {
             un.kind = 2;
             un.k0 = 0;
@@ -140,9 +165,11 @@ __global__ __launch_bounds__(kSbWaves * 64) void small_batch_kernel(
         } else {
             un.kind = 1;
             un.k0 = cu.part * 64;
-            un.c = __builtin_amdgcn_readfirstlane(seg_c[cu.sg]);
             un.lo = __builtin_amdgcn_readfirstlane(seg_lo[cu.sg]);
             un.hi = __builtin_amdgcn_readfirstlane(seg_hi[cu.sg]);
+            const u32x4 ad4 = *(const u32x4 *)(seg_ad + cu.sg * 4);  // all four: no loop over mix.k here
+#pragma unroll
+            for (int j = 0; j < 4; ++j) un.ad[j] = __builtin_amdgcn_readfirstlane((int)ad4[j]);
         }
         return un;
     };
@@ -154,33 +181,62 @@ __global__ __launch_bounds__(kSbWaves * 64) void small_batch_kernel(
         ++cu.u;
     };
 
-    // ---- slab loads: 8 k-rows x 128 bytes per instruction ----
-    // lane -> row lane/8 of the 8, 16-byte position lane%8 of the slab row, which holds the
-    // column chunk given by the swizzle.  d_in and rank are multiples of 8, so a load is either
-    // entirely inside its matrix or entirely zero.
-    const int w_rr = lane >> 3, w_pos = lane & 7;
-    const int w_u16 = ((((w_pos >> 1) ^ (w_rr & 3))) << 1) | (w_pos & 1);
-    const int w_col = min(n0 + w_u16 * 8, d_out - 8);  // columns past d_out: clamped, never stored
+    // ---- slab loads: 1 KB per instruction = RPD k-rows x (2 * COLS) bytes ----
+    // lane -> row lane / CPR of the instruction's rows, 16-byte position lane % CPR of the slab
+    // row, which holds the column chunk given by the swizzle.  A row past the end of its matrix
+    // reads zeros instead.
+    const int w_rr = lane / Geo::CPR, w_pos = lane % Geo::CPR;
+    auto w_col_of = [&](int r) {  // columns of this lane in load r of a slab
+        const int row = r * Geo::RPD + w_rr;
+        const int u16 = (Geo::swz32(w_pos >> 1, row) << 1) | (w_pos & 1);
+        return min(n0 + u16 * 8, d_out - 8);  // columns past d_out: clamped, never stored
+    };
     // SHRINK: the "matrix" is the tuple's A side by side, [d_in][R]; a group of 8 columns lies
     // inside one adapter, whose rows are rank elements apart
     const int pitch = SHRINK ? rank : d_out;
-    const uint16_t *w_lane = SHRINK
-        ? W + ((int64_t)mix_adapter(mix, bucket, w_col / rank) * d_in + w_rr) * rank + w_col % rank
-        : W + (int64_t)w_rr * d_out + w_col;
-    const uint16_t *b_lane = B + (int64_t)w_rr * d_out + w_col;
+    const uint16_t *w_lane[Geo::NR], *b_lane[Geo::NR];
+    int w_colv[Geo::NR];
+#pragma unroll
+    for (int r = 0; r < Geo::NR; ++r) {
+        const int col = w_col_of(r);
+        w_colv[r] = col;
+        const int row = r * Geo::RPD + w_rr;
+        w_lane[r] = SHRINK
+            ? W + ((int64_t)mix_adapter(mix, bucket, col / rank) * d_in + row) * rank + col % rank
+            : W + (int64_t)row * d_out + col;
+        b_lane[r] = B + (int64_t)w_rr * d_out + col;  // + (row of the pool) * d_out
+    }
     auto issue_slab = [&](const Unit &un, int j, int q) {  // step j of the unit, into slot q % ring
         unsigned char *slot = ring + (q % kSbRing) * kSbSlot;
 #pragma unroll
-        for (int r = 0; r < 2; ++r) {
-            const int kk = un.k0 + j * 16 + r * 8;  // first of the 8 rows
+        for (int r = 0; r < Geo::NR; ++r) {
+            const int kk = un.k0 + j * 16;  // first row of the slab
             const uint16_t *src = zero;
-            if (un.kind == 0) {
-                if (kk < d_in) src = w_lane + (int64_t)kk * pitch;
-            } else if (un.kind == 1) {
-                if (kk < two_r) {
-                    const int j = kk < R ? kk : kk - R;       // row of the tuple's stacked B
-                    const int jj = mix.k > 1 ? j / rank : 0;  // which adapter of the tuple
-                    src = b_lane + ((int64_t)mix_adapter(mix, un.c, jj) * rank + (j - jj * rank)) * d_out;
+            if constexpr (Geo::RPD == 8) {
+                // d_in and rank are multiples of 8: the 8 rows of a load are inside their matrix,
+                // and inside one adapter of the tuple, as a whole; nothing here is per lane
+                const int k8 = kk + r * 8;
+                if (un.kind == 0) {
+                    if (k8 < d_in) src = w_lane[r] + (int64_t)kk * pitch;
+                } else if (un.kind == 1) {
+                    if (k8 < two_r) {
+                        const int jr = k8 < R ? k8 : k8 - R;        // row of the tuple's stacked B
+                        const int jj = mix.k > 1 ? jr / rank : 0;   // which adapter of the tuple
+                        const int ad = jj == 0 ? un.ad[0] : jj == 1 ? un.ad[1] : jj == 2 ? un.ad[2] : un.ad[3];
+                        src = b_lane[r] + ((int64_t)ad * rank + (jr - jj * rank)) * d_out;
+                    }
+                }
+            } else {
+                const int row = kk + r * Geo::RPD + w_rr;  // this lane's row
+                if (un.kind == 0) {
+                    if (row < d_in) src = w_lane[r] + (int64_t)kk * pitch;
+                } else if (un.kind == 1) {
+                    if (row < two_r) {
+                        const int jr = row < R ? row : row - R;
+                        const int jj = mix.k > 1 ? jr / rank : 0;
+                        const int ad = jj == 0 ? un.ad[0] : jj == 1 ? un.ad[1] : jj == 2 ? un.ad[2] : un.ad[3];
+                        src = B + ((int64_t)ad * rank + (jr - jj * rank)) * d_out + w_colv[r];
+                    }
                 }
             }
             load_to_lds16_ptr(src, slot + r * 1024);
@@ -216,11 +272,11 @@ __global__ __launch_bounds__(kSbWaves * 64) void small_batch_kernel(
         }
     };
 
-    f32x16 acc[TM][2];
+    f32x16 acc[TM][TN];
 #pragma unroll
     for (int i = 0; i < TM; ++i)
 #pragma unroll
-        for (int j = 0; j < 2; ++j)
+        for (int j = 0; j < TN; ++j)
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
 
@@ -229,7 +285,6 @@ __global__ __launch_bounds__(kSbWaves * 64) void small_batch_kernel(
     const int kg = lane >> 5, m_lo = lane & 31;
     const int blk = lane >> 4, a16 = lane & 15;
     const int b_kr0 = (blk >> 1) * 8 + (a16 >> 2);
-    const int b_k3 = b_kr0 & 3;
     const int b_in = (a16 & 3) * 8;
     auto load_a_frag = [&](int j, int tm) -> bf16x8 {
         const int row = tm * 32 + m_lo;
@@ -238,7 +293,7 @@ __global__ __launch_bounds__(kSbWaves * 64) void small_batch_kernel(
     };
     auto load_b_frag = [&](const unsigned char *slot, int tn) -> bf16x8 {
         const int cc = tn * 2 + (blk & 1);  // 32-byte chunk of the slab row
-        const unsigned char *p = slot + b_kr0 * (kSbCols * 2) + ((cc ^ b_k3) << 5) + b_in;
+        const unsigned char *p = slot + b_kr0 * (kSbCols * 2) + (Geo::swz32(cc, b_kr0) << 5) + b_in;
         const i16x4 lo = lds_read_tr16((const MOLORA_LDS void *)p);
         const i16x4 hi = lds_read_tr16((const MOLORA_LDS void *)(p + 4 * kSbCols * 2));
         const i16x8 b8 = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
@@ -250,8 +305,8 @@ __global__ __launch_bounds__(kSbWaves * 64) void small_batch_kernel(
     // operand of its own unit has been moved to registers) the staged operand of the next
     // unit.  Loads return in order, so "at most n outstanding", n = the number of loads issued
     // after the needed one, is exactly "the needed one has landed":
-    //   staged operand of the unit, at j == 0: the three slabs issued since         -> 6
-    //   slab s at j > 0: 4 slabs and one staged operand issued since                -> 8 + XD
+    //   staged operand of the unit, at j == 0: the three slabs issued since         -> 3 NR
+    //   slab s at j > 0: 4 slabs and one staged operand issued since                -> 4 NR + XD
     //   slab s at j == 0: older than the staged operand, already there.
     constexpr int XD = 4 * TM;
     constexpr int AHEAD = kSbRing - 1;
@@ -281,7 +336,7 @@ __global__ __launch_bounds__(kSbWaves * 64) void small_batch_kernel(
         for (int j = 0; j < 4; ++j) {
             const int s = ui * 4 + j;
             if (j == 0) {
-                wait_vmcnt<6>();
+                wait_vmcnt<3 * Geo::NR>();
 #pragma unroll
                 for (int jj = 0; jj < 4; ++jj)
 #pragma unroll
@@ -293,16 +348,16 @@ __global__ __launch_bounds__(kSbWaves * 64) void small_batch_kernel(
                 issue_stage(unit_of(cx));
                 advance(cx);
             } else {
-                wait_vmcnt<8 + XD>();
+                wait_vmcnt<4 * Geo::NR + XD>();
             }
             const unsigned char *slot = ring + (s % kSbRing) * kSbSlot;
-            bf16x8 bfr[2];
-            bfr[0] = load_b_frag(slot, 0);
-            bfr[1] = load_b_frag(slot, 1);
+            bf16x8 bfr[TN];
+#pragma unroll
+            for (int tn = 0; tn < TN; ++tn) bfr[tn] = load_b_frag(slot, tn);
 #pragma unroll
             for (int tm = 0; tm < TM; ++tm)
 #pragma unroll
-                for (int tn = 0; tn < 2; ++tn)
+                for (int tn = 0; tn < TN; ++tn)
                     acc[tm][tn] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[j][tm], bfr[tn],
                                                                           acc[tm][tn], 0, 0, 0);
             wait_lds();  // the slab has been read before its slot is refilled
@@ -318,7 +373,7 @@ __global__ __launch_bounds__(kSbWaves * 64) void small_batch_kernel(
         for (int v = 0; v < 16; ++v) {
             const int row = tm * 32 + (v >> 2) * 8 + kg * 4 + (v & 3);
 #pragma unroll
-            for (int tn = 0; tn < 2; ++tn)
+            for (int tn = 0; tn < TN; ++tn)
                 *(float *)(ring + row * kSbRowBytes + (tn * 32 + m_lo) * 4) = acc[tm][tn][v];
         }
     __syncthreads();
@@ -353,24 +408,41 @@ __global__ __launch_bounds__(kSbWaves * 64) void small_batch_kernel(
     }
 }
 
-template <int TM, bool SHRINK>
+template <int TM, int TN, bool SHRINK>
 hipError_t launch_small(const uint16_t *x, const uint16_t *W, const uint16_t *B, const uint16_t *t2,
                         const int32_t *offsets, const int32_t *perm, float *h, uint16_t *t_out, int N,
                         int d_in, int d_out, int C, int rank, Mix mix, hipStream_t s) {
-    auto kern = small_batch_kernel<TM, SHRINK>;
+    using Geo = SbGeom<TN>;
+    auto kern = small_batch_kernel<TM, TN, SHRINK>;
     // once per kernel: more than 64 KB of dynamic LDS has to be asked for
     static const hipError_t e = hipFuncSetAttribute((const void *)kern,
                                                     hipFuncAttributeMaxDynamicSharedMemorySize,
-                                                    (int)kSbLdsBytes);
+                                                    (int)Geo::LDS_BYTES);
     if (e != hipSuccess) return e;
-    const unsigned groups = (unsigned)((d_out + kSbCols - 1) / kSbCols);
+    const unsigned groups = (unsigned)((d_out + Geo::COLS - 1) / Geo::COLS);
     const unsigned row_tiles = (unsigned)((N + 63) / 64);
     // GEMM: row tiles of the batch.  SHRINK: buckets x row tiles a bucket can have at most
     // (workgroups past a bucket's end leave at once)
     const dim3 grid = SHRINK ? dim3(groups, (unsigned)C, row_tiles) : dim3(groups, row_tiles);
-    hipLaunchKernelGGL(kern, grid, dim3(kSbWaves * 64), kSbLdsBytes, s, x, W,
-                       B, t2, offsets, perm, h, t_out, N, d_in, d_out, C, rank, mix);
+    hipLaunchKernelGGL(kern, grid, dim3(kSbWaves * 64), Geo::LDS_BYTES, s, x, W, B, t2, offsets, perm,
+                       h, t_out, N, d_in, d_out, C, rank, mix);
     return hipGetLastError();
+}
+
+template <bool SHRINK>
+hipError_t launch_small_tn(const uint16_t *x, const uint16_t *W, const uint16_t *B, const uint16_t *t2,
+                           const int32_t *offsets, const int32_t *perm, float *h, uint16_t *t_out,
+                           int N, int d_in, int d_out, int C, int rank, Mix mix, hipStream_t s) {
+    // 32-column groups when 64-column groups would occupy at most half of the compute units:
+    // a workgroup draws ~40 GB/s from HBM whatever its width, so more, narrower ones win there.
+    // The shrink has at most a few workgroups per bucket and always takes the narrow form.
+    const int64_t wgs64 = (int64_t)((d_out + 63) / 64) * ((N + 63) / 64);
+    const bool narrow = SHRINK || wgs64 <= 128;
+#define MOLORA_SB_LAUNCH(TM, TN) \
+    launch_small<TM, TN, SHRINK>(x, W, B, t2, offsets, perm, h, t_out, N, d_in, d_out, C, rank, mix, s)
+    if (N <= 32) return narrow ? MOLORA_SB_LAUNCH(1, 1) : MOLORA_SB_LAUNCH(1, 2);
+    return narrow ? MOLORA_SB_LAUNCH(2, 1) : MOLORA_SB_LAUNCH(2, 2);
+#undef MOLORA_SB_LAUNCH
 }
 
 }  // namespace
@@ -379,18 +451,16 @@ hipError_t launch_small_batch_gemm(const uint16_t *x, const uint16_t *W, const u
                                    const uint16_t *t2, const int32_t *offsets, const int32_t *perm,
                                    float *h, int64_t N, int d_in, int d_out, int C, int rank, Mix mix,
                                    hipStream_t s) {
-    if (N <= 32)
-        return launch_small<1, false>(x, W, B, t2, offsets, perm, h, nullptr, (int)N, d_in, d_out, C, rank, mix, s);
-    return launch_small<2, false>(x, W, B, t2, offsets, perm, h, nullptr, (int)N, d_in, d_out, C, rank, mix, s);
+    return launch_small_tn<false>(x, W, B, t2, offsets, perm, h, nullptr, (int)N, d_in, d_out, C, rank,
+                                  mix, s);
 }
 
 hipError_t launch_small_batch_shrink(const uint16_t *x, const uint16_t *A, const int32_t *offsets,
                                      const int32_t *perm, uint16_t *t_out, int64_t N, int d_in, int C,
                                      int rank, Mix mix, hipStream_t s) {
     const int R = mix.k * rank;  // the kernel's "d_out" is the width of the intermediate
-    if (N <= 32)
-        return launch_small<1, true>(x, A, nullptr, nullptr, offsets, perm, nullptr, t_out, (int)N, d_in, R, C, rank, mix, s);
-    return launch_small<2, true>(x, A, nullptr, nullptr, offsets, perm, nullptr, t_out, (int)N, d_in, R, C, rank, mix, s);
+    return launch_small_tn<true>(x, A, nullptr, nullptr, offsets, perm, nullptr, t_out, (int)N, d_in, R,
+                                 C, rank, mix, s);
 }
 
 }  // namespace molora
