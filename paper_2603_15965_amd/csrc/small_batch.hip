@@ -59,6 +59,11 @@ struct Unit {
     int k0;    // kind 0: first k.  kind 1: first row of [B_c; B_c] (0 .. 2*rank)
     int lo, hi;  // kind 1: the bucket's sorted-position range ...
     int ad[4];   // ... and the pool positions of the adapters of its tuple
+    // fast: all 64 rows lie inside their matrix and follow one another in memory from `base`
+    // (always so for W away from the K tail, and for B_c when rank is a multiple of 64); the
+    // loads of such a unit are a scalar base plus a fixed per-lane offset, nothing to decide
+    bool fast;
+    const unsigned char *base;
 };
 
 // SHRINK = false: the fused GEMM above (grid: column groups x row tiles of 64 sorted rows; a
@@ -140,6 +145,8 @@ __global__ __launch_bounds__(kSbWaves * 64) void small_batch_kernel(
     const int total = nub + nseg * upb;
     const int u0 = total * wave / kSbWaves, u1 = total * (wave + 1) / kSbWaves;
 
+    const int pitch = SHRINK ? rank : d_out;  // elements between consecutive k-rows of W (A)
+    bool fast_allowed = false;  // set below once the per-lane offsets are known to fit 32 bits
     // a cursor walks the list one unit at a time (no division in the loop)
     struct Cursor {
         int u, sg, part;
@@ -156,12 +163,16 @@ __global__ __launch_bounds__(kSbWaves * 64) void small_batch_kernel(
         Unit un;
         un.lo = un.hi = 0;
         un.ad[0] = un.ad[1] = un.ad[2] = un.ad[3] = 0;
+        un.fast = false;
+        un.base = (const unsigned char *)zero;
         if (cu.u >= u1) {
             un.kind = 2;
             un.k0 = 0;
         } else if (cu.u < nub) {
             un.kind = 0;
             un.k0 = cu.u * 64;
+            un.fast = un.k0 + 64 <= d_in;
+            un.base = (const unsigned char *)(W + (int64_t)un.k0 * pitch);
         } else {
             un.kind = 1;
             un.k0 = cu.part * 64;
@@ -170,6 +181,13 @@ __global__ __launch_bounds__(kSbWaves * 64) void small_batch_kernel(
             const u32x4 ad4 = *(const u32x4 *)(seg_ad + cu.sg * 4);  // all four: no loop over mix.k here
 #pragma unroll
             for (int j = 0; j < 4; ++j) un.ad[j] = __builtin_amdgcn_readfirstlane((int)ad4[j]);
+            if ((rank & 63) == 0) {  // the unit is 64 consecutive rows of one adapter's B
+                const int jr = un.k0 < R ? un.k0 : un.k0 - R;
+                const int jj = jr / rank;
+                const int ad = jj == 0 ? un.ad[0] : jj == 1 ? un.ad[1] : jj == 2 ? un.ad[2] : un.ad[3];
+                un.fast = true;
+                un.base = (const unsigned char *)(B + ((int64_t)ad * rank + (jr - jj * rank)) * d_out);
+            }
         }
         return un;
     };
@@ -193,8 +211,9 @@ __global__ __launch_bounds__(kSbWaves * 64) void small_batch_kernel(
     };
     // SHRINK: the "matrix" is the tuple's A side by side, [d_in][R]; a group of 8 columns lies
     // inside one adapter, whose rows are rank elements apart
-    const int pitch = SHRINK ? rank : d_out;
     const uint16_t *w_lane[Geo::NR], *b_lane[Geo::NR];
+    uint32_t w_off[Geo::NR];  // fast units: byte offset of this lane from the unit's base + row term
+    bool off32_ok = true;     // ... which must fit 32 bits in every lane for the fast form
     int w_colv[Geo::NR];
 #pragma unroll
     for (int r = 0; r < Geo::NR; ++r) {
@@ -205,12 +224,22 @@ __global__ __launch_bounds__(kSbWaves * 64) void small_batch_kernel(
             ? W + ((int64_t)mix_adapter(mix, bucket, col / rank) * d_in + row) * rank + col % rank
             : W + (int64_t)row * d_out + col;
         b_lane[r] = B + (int64_t)w_rr * d_out + col;  // + (row of the pool) * d_out
+        // the same lane offset serves W and B in the GEMM (both have d_out columns)
+        const int64_t off = ((const unsigned char *)w_lane[r] - (const unsigned char *)W) -
+                            (int64_t)r * Geo::RPD * pitch * 2;
+        w_off[r] = (uint32_t)off;
+        off32_ok = off32_ok && (off >> 32) == 0;
     }
     auto issue_slab = [&](const Unit &un, int j, int q) {  // step j of the unit, into slot q % ring
         unsigned char *slot = ring + (q % kSbRing) * kSbSlot;
 #pragma unroll
         for (int r = 0; r < Geo::NR; ++r) {
             const int kk = un.k0 + j * 16;  // first row of the slab
+            if (un.fast && fast_allowed) {
+                load_to_lds16(un.base + (int64_t)(j * 16 + r * Geo::RPD) * (pitch * 2), w_off[r],
+                              slot + r * 1024);
+                continue;
+            }
             const uint16_t *src = zero;
             if constexpr (Geo::RPD == 8) {
                 // d_in and rank are multiples of 8: the 8 rows of a load are inside their matrix,
@@ -256,7 +285,21 @@ __global__ __launch_bounds__(kSbWaves * 64) void small_batch_kernel(
         a_ch8[i] = (a_pos ^ ((row ^ (row >> 3)) & 7)) * 8;
         a_xrow[i] = x + (int64_t)tok * d_in + a_ch8[i];
     }
+    uint32_t a_off[4 * TM];  // byte offset of this lane's chunk from x + k0
+#pragma unroll
+    for (int i = 0; i < 4 * TM; ++i) {
+        const int64_t off = (const unsigned char *)a_xrow[i] - (const unsigned char *)x;
+        a_off[i] = (uint32_t)off;
+        off32_ok = off32_ok && (off >> 32) == 0;
+    }
+    fast_allowed = __all(off32_ok) != 0;
     auto issue_stage = [&](const Unit &un) {
+        if (un.kind == 0 && un.fast && fast_allowed) {  // 64 k of x, all inside d_in
+            const unsigned char *xb = (const unsigned char *)(x + un.k0);
+#pragma unroll
+            for (int i = 0; i < 4 * TM; ++i) load_to_lds16(xb, a_off[i], stage + i * 1024);
+            return;
+        }
 #pragma unroll
         for (int i = 0; i < 4 * TM; ++i) {
             const int row = i * 8 + a_sub;
