@@ -218,12 +218,16 @@ hipError_t launch_shrink(const uint16_t *x, const uint16_t *A, const int32_t *of
                          const int32_t *perm, uint16_t *t2, int64_t N, int d_in, int C, int rank,
                          Mix mix, hipStream_t s) {
     if (N == 0) return hipSuccess;
-    // small batches are bound by the latency of streaming the touched A_c: one workgroup per
-    // 64 rows of a bucket with the K range split over its wavefronts
-    // (up to 64 tokens always; up to 2048 tokens when a bucket's A is large enough that the
-    // row-item kernel below, which splits K four ways only, would be latency bound: measured)
-    if (N <= 64 || (N <= 2048 && (int64_t)d_in * mix.k * rank >= 131072))
-        return launch_small_batch_shrink(x, A, offsets, perm, t2, N, d_in, C, rank, mix, s);
+    // Two kernels (measured crossovers).  The streaming kernel (one workgroup per 64 rows of a
+    // bucket, K split over its 8 wavefronts, x staged as whole 128-byte lines) wins for small
+    // batches, which are bound by the latency of streaming the touched A_c, and for large ones
+    // whose buckets fill its 64-row tiles (3.2-4.2 TB/s of x against 2.4-2.7 TB/s); the
+    // row-item kernel below wins in between and when buckets are small.
+    const int64_t R = (int64_t)mix.k * rank;
+    const bool stream = N <= 64 || (N <= 2048 && d_in * R >= (1 << 17)) ||
+                        (N * (int64_t)d_in >= (1 << 24) && N >= 128 * (int64_t)C &&
+                         ((N + 63) / 64) * C <= 65536);  // its grid has a slot per (bucket, tile)
+    if (stream) return launch_small_batch_shrink(x, A, offsets, perm, t2, N, d_in, C, rank, mix, s);
     // 32-row items when they still cover the chip twice, 16-row items otherwise
     const bool small_items = (N + 31) / 32 + C < 512;
     const int rows = small_items ? 16 : 32;
