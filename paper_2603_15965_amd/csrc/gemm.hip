@@ -426,6 +426,9 @@ hipError_t launch_cfg(const uint16_t *x, const uint16_t *W, const uint16_t *B, c
 #ifndef MOLORA_SMALL_BATCH_MAX
 #define MOLORA_SMALL_BATCH_MAX 512  // up to here W is streamed once per 64-row tile instead (measured crossover)
 #endif
+#ifndef MOLORA_BIG_MIN_TILES
+#define MOLORA_BIG_MIN_TILES 256
+#endif
 #ifndef MOLORA_GEMM_BIG
 #define MOLORA_GEMM_BIG 256, 256, 2, 4, 64, 2
 #endif
@@ -441,12 +444,13 @@ hipError_t launch_fused_gemm(const uint16_t *x, const uint16_t *W, const uint16_
                              float *h, int64_t N, int d_in, int d_out, int C, int rank, Mix mix,
                              hipStream_t s) {
     if (N == 0) return hipSuccess;
-    // Tile choice from static shapes only (no host read of the histogram).  Up to 64 tokens
-    // the step is bound by streaming W once: one row tile, narrow column tiles, deep ring.
-    // Otherwise the largest tile that still yields about two workgroups per compute unit.
+    // Kernel and tile choice from static shapes only (no host read of the histogram); the
+    // thresholds are measured crossovers.  Up to 512 tokens W is streamed once per 64-row tile
+    // by the small-batch kernel; 256 x 256 tiles as soon as they number one per compute unit
+    // (with fewer, 128 x 128 tiles keep more of the chip busy).
     if (N <= MOLORA_SMALL_BATCH_MAX) return launch_small_batch_gemm(x, W, B, t2, offsets, perm, h, N, d_in, d_out, C, rank, mix, s);
     const int64_t t256 = ((N + 255) / 256) * ((d_out + 255) / 256);
-    if (t256 >= 512)
+    if (t256 >= MOLORA_BIG_MIN_TILES)
         return launch_cfg<GemmCfg<MOLORA_GEMM_BIG>>(x, W, B, t2, offsets, perm, h, N, d_in, d_out, C, rank, mix, s);
     // 128 x 128 tiles: with at most one workgroup per compute unit a third stage replaces the
     // second resident workgroup as the way to cover the load latency
