@@ -41,6 +41,9 @@ def parse():
     ap.add_argument("--workload", default="vocab_q17",
                     help="a shape name from paper_2603_15965_amd.workloads.shapes(), or "
                          "prefill8_layer / prefill8_layer_deg (the seven projections of one layer)")
+    ap.add_argument("--streams", type=int, default=1,
+                    help="launch consecutive steps round-robin on this many streams (independent "
+                         "batches overlap; 1 = every step after the previous one)")
     ap.add_argument("--graph", action="store_true",
                     help="replay each step from a recorded launch sequence (HIP graph)")
     ap.add_argument("--sets", type=int, default=0,
@@ -133,6 +136,8 @@ def main():
     per_set = sum(2.0 * sh.N * sh.d_in + 2.0 * sh.d_in * sh.d_out
                   + 2.0 * sh.C * sh.rank * (sh.d_in + sh.d_out) + 4.0 * sh.N * sh.d_out for sh in shapes)
     sets = args.sets if args.sets > 0 else int(max(2, min(64, -(-600e6 // per_set))))
+    if args.sets <= 0 and sets % 2:
+        sets += 1  # even: the two-stream pass below gives every copy to one stream
     rng = np.random.default_rng(123)
     S = [[] for _ in range(sets)]
     for sh in shapes:
@@ -203,9 +208,20 @@ def main():
                 step(S[s], stream=run_stream)
             graphs.append(g)
 
+    # several streams: step i runs on stream i % streams with input copy i % sets; the number
+    # of copies is a multiple of the number of streams, so a copy is always used by one stream
+    extra = []
+    if args.streams > 1:
+        if graphs is not None or sets % args.streams != 0:
+            print("bench.py: --streams needs eager launches and --sets a multiple of it", file=sys.stderr)
+            sys.exit(2)
+        extra = [torch.cuda.Stream() for _ in range(args.streams)]
+
     def run_step(i, ev=None):
         if graphs is not None:
             graphs[i % sets].launch()
+        elif extra:
+            step(S[i % sets], None, stream=extra[i % args.streams])
         else:
             step(S[i % sets], ev)
 
@@ -217,7 +233,7 @@ def main():
     # step, so the dominant kernel is bracketed on every EV_EVERY-th step of the timed region
     # only, and the per-step latency distribution is taken in a second pass of the same length
     # after the timed region.
-    use_ev = not args.no_kernel_events and graphs is None
+    use_ev = not args.no_kernel_events and graphs is None and not extra
     P = len(shapes)
     EV_EVERY = 8
     ev_steps = [i for i in range(args.steps) if i % EV_EVERY == EV_EVERY - 1] or [args.steps - 1]
@@ -240,10 +256,28 @@ def main():
     ticks[args.steps].record(run_stream)
     torch.cuda.synchronize()
     lat = np.array([ticks[i].elapsed_time(ticks[i + 1]) * 1e3 for i in range(args.steps)])
-    latency = {"p50_us": float(np.percentile(lat, 50)), "p99_us": float(np.percentile(lat, 99)),
+    latency = None if extra else {"p50_us": float(np.percentile(lat, 50)), "p99_us": float(np.percentile(lat, 99)),
                "mean_us": float(lat.mean()), "cv": float(lat.std() / lat.mean()),
                "how": "HIP events between consecutive steps on the launch stream, in a second pass "
                       "after the timed region (one event per step adds ~3 us to each)"}
+
+    # ---- same K steps with independent batches overlapping (reported beside `value`) ----
+    pipelined = None
+    if graphs is None and not extra and sets % 2 == 0:
+        two = [torch.cuda.Stream(), torch.cuda.Stream()]
+        for i in range(min(args.warmup, 4)):
+            step(S[i % sets], None, stream=two[i % 2])
+        torch.cuda.synchronize()
+        t1 = time.perf_counter()
+        for i in range(args.steps):
+            step(S[i % sets], None, stream=two[i % 2])
+        torch.cuda.synchronize()
+        el2 = time.perf_counter() - t1
+        pipelined = {"streams": 2, "value": N * args.steps / el2, "unit": "tokens/s",
+                     "ms_per_step": 1e3 * el2 / args.steps,
+                     "what": "the same steps launched round-robin on two streams, so that the "
+                             "latency-bound dispatch and shrink of one batch overlap the GEMM of "
+                             "the previous one (every input copy belongs to one stream)"}
 
     # ---- untimed breakdown of the kernels (events around each call), summed over projections ----
     def timed_calls(fn, reps=30):
@@ -323,10 +357,11 @@ def main():
         "dtype": "bf16", "data": "synthetic",
         "config": {"workload": wname, "rotating_sets": sets,
                    "launch": "recorded sequence (HIP graph) per step" if graphs is not None
-                   else "kernel by kernel",
+                   else "kernel by kernel" + (f", steps round-robin on {args.streams} streams" if extra else ""),
                    "kernel_events_in_timed_region": (f"every {EV_EVERY}th step" if use_ev else False)},
         "roofline": roof,
         "latency": latency,
+        "pipelined": pipelined,
         "layer": {"tflops": work["layer_flops"] / (elapsed / args.steps) / 1e12,
                   "gbs": work["layer_bytes"] / (elapsed / args.steps) / 1e9,
                   "routed_tokens": n_routed_all if P > 1 else n_routed_all[0],
