@@ -226,7 +226,7 @@ hipError_t launch_shrink(const uint16_t *x, const uint16_t *A, const int32_t *of
     const int64_t R = (int64_t)mix.k * rank;
     const bool stream = N <= 64 || (N <= 2048 && d_in * R >= (1 << 17)) ||
                         (N * (int64_t)d_in >= (1 << 24) && N >= 128 * (int64_t)C &&
-                         ((N + 63) / 64) * C <= 65536);  // its grid has a slot per (bucket, tile)
+                         ((N + 63) / 64) * C <= 32768);  // its grid has a slot per (bucket, tile)
     if (stream) return launch_small_batch_shrink(x, A, offsets, perm, t2, N, d_in, C, rank, mix, s);
     // 32-row items when they still cover the chip twice, 16-row items otherwise
     const bool small_items = (N + 31) / 32 + C < 512;
