@@ -24,16 +24,20 @@ namespace molora {
 
 namespace {
 
-constexpr int kShrinkThreads = 256;
 constexpr int kStepK = 32;       // k per MFMA step
-constexpr int kDepth = 4;        // steps in flight per wavefront
+#ifndef MOLORA_SHRINK_TINY_MAX
+#define MOLORA_SHRINK_TINY_MAX 64  // batches up to this size take the many-wavefront form
+#endif
 
 // R = mix.k * rank is the width of a bucket's intermediate: piece j of it is x A of the j-th
 // adapter of the bucket's tuple, scaled by the token's j-th mixture weight.
 // NJ = number of 16-column blocks covering R; RB = 16-row blocks per work item (2 for large
-// batches, 1 when 32-row items would leave compute units without work)
-template <int NJ, int RB>
-__global__ __launch_bounds__(kShrinkThreads) void shrink_kernel(
+// batches, 1 when 32-row items would leave compute units without work); KW = wavefronts of a
+// workgroup = K splits, kDepth = steps in flight per wavefront.  A batch of a few dozen tokens
+// has a handful of work items and is bound by the chain of load round trips of one wavefront:
+// it takes 16 wavefronts x 8 steps, which puts a whole 4096-long row in flight at once.
+template <int NJ, int RB, int KW, int kDepth>
+__global__ __launch_bounds__(64 * KW) void shrink_kernel(
     const uint16_t *__restrict__ x, const uint16_t *__restrict__ A,
     const int32_t *__restrict__ offsets, const int32_t *__restrict__ perm,
     uint16_t *__restrict__ t2, int d_in, int C, int rank, Mix mix) {
@@ -42,8 +46,10 @@ __global__ __launch_bounds__(kShrinkThreads) void shrink_kernel(
     constexpr int RP = NJ * 16;                          // padded rank
     constexpr int ROWB = RP * 2 + (RP >= 64 ? 32 : 0);   // LDS bytes per slab row (bank shift)
     constexpr int SLABB = kStepK * ROWB;                 // one step's slab of one wavefront
-    constexpr int RED_FLOATS = 4 * kShrinkRows * RP;     // partial sums of the 4 wavefronts
-    constexpr int LDS_BYTES = (4 * 2 * SLABB > RED_FLOATS * 4) ? 4 * 2 * SLABB : RED_FLOATS * 4;
+    constexpr int kShrinkThreads = 64 * KW;
+    constexpr int RED_FLOATS = KW * kShrinkRows * RP;    // partial sums of the KW wavefronts
+    constexpr int LDS_BYTES = (KW * 2 * SLABB > RED_FLOATS * 4) ? KW * 2 * SLABB : RED_FLOATS * 4;
+    static_assert(LDS_BYTES <= 128 * 1024, "LDS");
     __shared__ __attribute__((aligned(16))) unsigned char lds[LDS_BYTES];
     __shared__ int32_t item[3];  // bucket, first sorted row, end row
 
@@ -93,7 +99,7 @@ __global__ __launch_bounds__(kShrinkThreads) void shrink_kernel(
     const int p_end = min(item[2], p_first + kShrinkRows);
 
     // ---- this wavefront's k range (a multiple of 32 long) and operand addresses ----
-    const int kq_len = ((d_in + 4 * kStepK - 1) / (4 * kStepK)) * kStepK;
+    const int kq_len = ((d_in + KW * kStepK - 1) / (KW * kStepK)) * kStepK;
     const int k_begin = wave * kq_len;
     const int k_end = min(d_in, k_begin + kq_len);
     const int nsteps = k_begin < k_end ? (k_end - k_begin + kStepK - 1) / kStepK : 0;
@@ -177,10 +183,10 @@ __global__ __launch_bounds__(kShrinkThreads) void shrink_kernel(
         }
     }
 
-    // ---- add the four partial sums in a fixed order, split into bf16 hi + lo, store ----
+    // ---- add the KW partial sums in a fixed order, split into bf16 hi + lo, store ----
     // acc[rb][jb][v] = t[row rb*16 + kg*4 + v][column jb*16 + l16]
     __syncthreads();  // all wavefronts are done with their slabs
-    float *red = (float *)lds;  // [4][rows][RP]
+    float *red = (float *)lds;  // [KW][rows][RP]
 #pragma unroll
     for (int rb = 0; rb < RB; ++rb)
 #pragma unroll
@@ -199,7 +205,7 @@ __global__ __launch_bounds__(kShrinkThreads) void shrink_kernel(
         for (int i = 0; i < 2; ++i) {
             float t = 0.f;
 #pragma unroll
-            for (int w = 0; w < 4; ++w) t += red[(w * kShrinkRows + row) * RP + col + i];
+            for (int w = 0; w < KW; ++w) t += red[(w * kShrinkRows + row) * RP + col + i];
             t *= wj;
             const uint32_t hi = f32_to_bf16_bits(t);
             const uint32_t lo = f32_to_bf16_bits(t - bf16_bits_to_f32(hi));
@@ -224,6 +230,18 @@ hipError_t launch_shrink(const uint16_t *x, const uint16_t *A, const int32_t *of
     // whose buckets fill its 64-row tiles (3.2-4.2 TB/s of x against 2.4-2.7 TB/s); the
     // row-item kernel below wins in between and when buckets are small.
     const int64_t R = (int64_t)mix.k * rank;
+    const int nj = (mix.k * rank + 15) / 16;
+    // a few work items only, narrow intermediate: 16 (8) wavefronts per 16-row item
+    if (N <= MOLORA_SHRINK_TINY_MAX && nj <= 2) {
+        const unsigned blocks = (unsigned)((N + 15) / 16 + C);
+        if (nj == 1)
+            hipLaunchKernelGGL((shrink_kernel<1, 1, 16, 8>), dim3(blocks), dim3(1024), 0, s, x, A,
+                               offsets, perm, t2, d_in, C, rank, mix);
+        else
+            hipLaunchKernelGGL((shrink_kernel<2, 1, 8, 8>), dim3(blocks), dim3(512), 0, s, x, A,
+                               offsets, perm, t2, d_in, C, rank, mix);
+        return hipGetLastError();
+    }
     const bool stream = N <= 64 || (N <= 2048 && d_in * R >= (1 << 17)) ||
                         (N * (int64_t)d_in >= (1 << 24) && N >= 128 * (int64_t)C &&
                          ((N + 63) / 64) * C <= 32768);  // its grid has a slot per (bucket, tile)
@@ -232,15 +250,14 @@ hipError_t launch_shrink(const uint16_t *x, const uint16_t *A, const int32_t *of
     const bool small_items = (N + 31) / 32 + C < 512;
     const int rows = small_items ? 16 : 32;
     const unsigned blocks = (unsigned)((N + rows - 1) / rows + C);
-    const int nj = (mix.k * rank + 15) / 16;
-#define MOLORA_SHRINK_CASE(NJ)                                                                   \
-    case NJ:                                                                                     \
-        if (small_items)                                                                         \
-            hipLaunchKernelGGL((shrink_kernel<NJ, 1>), dim3(blocks), dim3(kShrinkThreads), 0, s, \
-                               x, A, offsets, perm, t2, d_in, C, rank, mix);                     \
-        else                                                                                     \
-            hipLaunchKernelGGL((shrink_kernel<NJ, 2>), dim3(blocks), dim3(kShrinkThreads), 0, s, \
-                               x, A, offsets, perm, t2, d_in, C, rank, mix);                     \
+#define MOLORA_SHRINK_CASE(NJ)                                                                  \
+    case NJ:                                                                                    \
+        if (small_items)                                                                        \
+            hipLaunchKernelGGL((shrink_kernel<NJ, 1, 4, 4>), dim3(blocks), dim3(256), 0, s, x,  \
+                               A, offsets, perm, t2, d_in, C, rank, mix);                       \
+        else                                                                                    \
+            hipLaunchKernelGGL((shrink_kernel<NJ, 2, 4, 4>), dim3(blocks), dim3(256), 0, s, x,  \
+                               A, offsets, perm, t2, d_in, C, rank, mix);                       \
         break;
     switch (nj) {
         MOLORA_SHRINK_CASE(1)

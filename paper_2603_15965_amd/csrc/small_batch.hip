@@ -55,10 +55,11 @@ struct SbGeom {
 
 // one unit of a wavefront's work list: 4 steps of 16 k
 struct Unit {
-    int kind;  // 0: rows k0 .. k0+63 of W; 1: rows of [B_c; B_c]; 2: nothing (zeros)
-    int k0;    // kind 0: first k.  kind 1: first row of [B_c; B_c] (0 .. 2*rank)
-    int lo, hi;  // kind 1: the bucket's sorted-position range ...
-    int ad[4];   // ... and the pool positions of the adapters of its tuple
+    int kind;  // 0: rows k0 .. k0+63 of W; 1: an expand item; 2: nothing (zeros)
+    int k0;    // kind 0: first k
+    // kind 1: row kk of the unit is row vk0 + (kk & pmask) of [B_c; B_c] of the (sg0 + (kk >> psh))-th
+    // bucket that owns rows
+    int sg0, vk0;
     // fast: all 64 rows lie inside their matrix and follow one another in memory from `base`
     // (always so for W away from the K tail, and for B_c when rank is a multiple of 64); the
     // loads of such a unit are a scalar base plus a fixed per-lane offset, nothing to decide
@@ -83,9 +84,9 @@ __global__ __launch_bounds__(kSbWaves * 64) void small_batch_kernel(
                   kSbWaveLds = Geo::WAVE_LDS;
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
     int32_t *tile_perm = (int32_t *)(smem + kSbWaves * kSbWaveLds);  // [64] token per row, -1 = none
-    int32_t *seg_c = tile_perm + 64;                                 // buckets that own rows,
-    int32_t *seg_lo = seg_c + 64;                                    // ascending, with their
-    int32_t *seg_hi = seg_lo + 64;                                   // sorted-position ranges
+    int32_t *tile_pos = tile_perm + 64;                              // [64] sorted position per row
+    int32_t *seg_lo = tile_pos + 64;                                 // buckets that own rows, ascending:
+    int32_t *seg_hi = seg_lo + 64;                                   // their sorted-position ranges
     int32_t *nseg_p = seg_hi + 64;
     int32_t *seg_ad = nseg_p + 4;  // [64][4] pool positions of the adapters of a bucket's tuple
 
@@ -108,95 +109,70 @@ __global__ __launch_bounds__(kSbWaves * 64) void small_batch_kernel(
         row_base = blockIdx.y * 64;  // row tile of 64 sorted positions
         nrows = min(64, N - row_base);
     }
+    // A batch that fits one row tile keeps its rows in token order: x W then depends on nothing
+    // the dispatch step produced, so the stream starts at once, and only the expand units (the
+    // end of every wavefront's list) look up the sorted position of a row.
+    const bool direct = !SHRINK && gridDim.y == 1;
 
-    // ---- tables: row -> token, and the non-empty buckets in ascending order ----
-    if (tid < 64) tile_perm[tid] = tid < nrows ? perm[row_base + tid] : -1;
-    if (SHRINK && tid == 0) *nseg_p = 0;
-    if (!SHRINK && wave == kSbWaves - 1) {
-        const uint64_t lower = (lane == 0) ? 0ull : (~0ull >> (64 - lane));
-        int cnt = 0;
-        for (int c0 = 0; c0 < C; c0 += 64) {
-            const int c = min(c0 + lane, C - 1);
-            // the bucket's rows inside this row tile, relative to the tile
-            const int lo = max(offsets[c] - row_base, 0), hi = min(offsets[c + 1] - row_base, nrows);
-            const bool owns = (c0 + lane < C) && hi > lo;
-            const uint64_t m = __ballot(owns);
-            if (owns) {
-                const int idx = cnt + __popcll(m & lower);
-                seg_c[idx] = c;
-                seg_lo[idx] = lo;
-                seg_hi[idx] = hi;
-                // decoded here, once: a slot-table read inside the streaming loop would have to
-                // wait for every load in flight
-                for (int j = 0; j < 4; ++j) seg_ad[idx * 4 + j] = j < mix.k ? mix_adapter(mix, c, j) : 0;
-            }
-            cnt += __popcll(m);
-        }
-        if (lane == 0) *nseg_p = cnt;
-    }
-    __syncthreads();
-    const int nseg = __builtin_amdgcn_readfirstlane(*nseg_p);
-
-    // ---- this wavefront's share of the work list ----
-    // units 0 .. nub-1: W in pieces of 64 rows; then upb units per bucket: [B_c; B_c] in
-    // pieces of 64 rows (the last piece of either kind may be short)
+    // ---- this wavefront's work list ----
+    //   W units [wu0, wu1): its eighth of the nub pieces of 64 k-rows of W (the last piece may
+    //       be short) -- known at once;
+    //   expand items e = wave, wave + 8, ... < ne -- known once the table of buckets is built.
+    //       An item is 64 rows of the stacked [B_c; B_c] of a bucket that owns rows, or, when
+    //       2R is 16 or 32, the stacked matrices of 4 or 2 such buckets one after the other
+    //       (the t operand is zero outside a row's own bucket, so they do not mix).
     const int two_r = 2 * R;
-    const int nub = (d_in + 63) / 64, upb = (two_r + 63) / 64;
-    const int total = nub + nseg * upb;
-    const int u0 = total * wave / kSbWaves, u1 = total * (wave + 1) / kSbWaves;
+    const int nub = (d_in + 63) / 64;
+    const int wu0 = nub * wave / kSbWaves, wu1 = nub * (wave + 1) / kSbWaves;
+    const bool packed = two_r == 16 || two_r == 32;
+    const int pack = packed ? 64 / two_r : 1;       // buckets per expand item
+    const int psh = packed ? (two_r == 16 ? 4 : 5) : 31;  // unit row -> bucket of the item
+    const int pmask = packed ? two_r - 1 : 63;             // unit row -> row of [B_c; B_c]
+    const int upb = (two_r + 63) / 64;               // items per bucket when not packed
+    int nseg = 0, ne = 0;                            // set after the tables
 
     const int pitch = SHRINK ? rank : d_out;  // elements between consecutive k-rows of W (A)
-    bool fast_allowed = false;  // set below once the per-lane offsets are known to fit 32 bits
-    // a cursor walks the list one unit at a time (no division in the loop)
+    bool w_fast_ok = false, a_fast_ok = false;  // per-lane offsets fit 32 bits (set below)
     struct Cursor {
-        int u, sg, part;
-    };
-    auto cursor_at = [&](int u) {
-        Cursor cu;
-        cu.u = u;
-        const int e = max(u - nub, 0);
-        cu.sg = e / upb;
-        cu.part = e - cu.sg * upb;
-        return cu;
+        int u, e;
     };
     auto unit_of = [&](const Cursor &cu) {
         Unit un;
-        un.lo = un.hi = 0;
-        un.ad[0] = un.ad[1] = un.ad[2] = un.ad[3] = 0;
+        un.sg0 = un.vk0 = 0;
         un.fast = false;
         un.base = (const unsigned char *)zero;
-        if (cu.u >= u1) {
-            un.kind = 2;
-            un.k0 = 0;
-        } else if (cu.u < nub) {
+        if (cu.u < wu1) {
             un.kind = 0;
             un.k0 = cu.u * 64;
             un.fast = un.k0 + 64 <= d_in;
             un.base = (const unsigned char *)(W + (int64_t)un.k0 * pitch);
-        } else {
+        } else if (cu.e < ne) {
             un.kind = 1;
-            un.k0 = cu.part * 64;
-            un.lo = __builtin_amdgcn_readfirstlane(seg_lo[cu.sg]);
-            un.hi = __builtin_amdgcn_readfirstlane(seg_hi[cu.sg]);
-            const u32x4 ad4 = *(const u32x4 *)(seg_ad + cu.sg * 4);  // all four: no loop over mix.k here
-#pragma unroll
-            for (int j = 0; j < 4; ++j) un.ad[j] = __builtin_amdgcn_readfirstlane((int)ad4[j]);
+            un.k0 = 0;
+            if (packed) {
+                un.sg0 = cu.e * pack;
+            } else {
+                un.sg0 = upb == 1 ? cu.e : cu.e / upb;
+                un.vk0 = (cu.e - un.sg0 * upb) * 64;
+            }
             if ((rank & 63) == 0) {  // the unit is 64 consecutive rows of one adapter's B
-                const int jr = un.k0 < R ? un.k0 : un.k0 - R;
-                const int jj = jr / rank;
-                const int ad = jj == 0 ? un.ad[0] : jj == 1 ? un.ad[1] : jj == 2 ? un.ad[2] : un.ad[3];
+                const int jr = un.vk0 < R ? un.vk0 : un.vk0 - R;
+                const int jj = (jr >= rank) + (jr >= 2 * rank) + (jr >= 3 * rank);
+                const int ad = __builtin_amdgcn_readfirstlane(seg_ad[un.sg0 * 4 + jj]);
                 un.fast = true;
                 un.base = (const unsigned char *)(B + ((int64_t)ad * rank + (jr - jj * rank)) * d_out);
             }
+        } else {
+            un.kind = 2;
+            un.k0 = 0;
         }
         return un;
     };
     auto advance = [&](Cursor &cu) {
-        if (cu.u >= nub && cu.u < u1 && ++cu.part == upb) {
-            cu.part = 0;
-            ++cu.sg;
-        }
-        ++cu.u;
+        if (cu.u < wu1)
+            ++cu.u;
+        else
+            cu.e += kSbWaves;
     };
 
     // ---- slab loads: 1 KB per instruction = RPD k-rows x (2 * COLS) bytes ----
@@ -211,61 +187,48 @@ __global__ __launch_bounds__(kSbWaves * 64) void small_batch_kernel(
     };
     // SHRINK: the "matrix" is the tuple's A side by side, [d_in][R]; a group of 8 columns lies
     // inside one adapter, whose rows are rank elements apart
-    const uint16_t *w_lane[Geo::NR], *b_lane[Geo::NR];
+    const uint16_t *w_lane[Geo::NR];
     uint32_t w_off[Geo::NR];  // fast units: byte offset of this lane from the unit's base + row term
-    bool off32_ok = true;     // ... which must fit 32 bits in every lane for the fast form
     int w_colv[Geo::NR];
+    {
+        bool ok = true;  // ... which must fit 32 bits in every lane for the fast form
 #pragma unroll
-    for (int r = 0; r < Geo::NR; ++r) {
-        const int col = w_col_of(r);
-        w_colv[r] = col;
-        const int row = r * Geo::RPD + w_rr;
-        w_lane[r] = SHRINK
-            ? W + ((int64_t)mix_adapter(mix, bucket, col / rank) * d_in + row) * rank + col % rank
-            : W + (int64_t)row * d_out + col;
-        b_lane[r] = B + (int64_t)w_rr * d_out + col;  // + (row of the pool) * d_out
-        // the same lane offset serves W and B in the GEMM (both have d_out columns)
-        const int64_t off = ((const unsigned char *)w_lane[r] - (const unsigned char *)W) -
-                            (int64_t)r * Geo::RPD * pitch * 2;
-        w_off[r] = (uint32_t)off;
-        off32_ok = off32_ok && (off >> 32) == 0;
+        for (int r = 0; r < Geo::NR; ++r) {
+            const int col = w_col_of(r);
+            w_colv[r] = col;
+            const int row = r * Geo::RPD + w_rr;
+            w_lane[r] = SHRINK
+                ? W + ((int64_t)mix_adapter(mix, bucket, col / rank) * d_in + row) * rank + col % rank
+                : W + (int64_t)row * d_out + col;
+            // the same lane offset serves W and B in the GEMM (both have d_out columns)
+            const int64_t off = ((const unsigned char *)w_lane[r] - (const unsigned char *)W) -
+                                (int64_t)r * Geo::RPD * pitch * 2;
+            w_off[r] = (uint32_t)off;
+            ok = ok && (off >> 32) == 0;
+        }
+        w_fast_ok = __all(ok) != 0;
     }
     auto issue_slab = [&](const Unit &un, int j, int q) {  // step j of the unit, into slot q % ring
         unsigned char *slot = ring + (q % kSbRing) * kSbSlot;
 #pragma unroll
         for (int r = 0; r < Geo::NR; ++r) {
-            const int kk = un.k0 + j * 16;  // first row of the slab
-            if (un.fast && fast_allowed) {
+            if (un.fast && w_fast_ok) {
                 load_to_lds16(un.base + (int64_t)(j * 16 + r * Geo::RPD) * (pitch * 2), w_off[r],
                               slot + r * 1024);
                 continue;
             }
             const uint16_t *src = zero;
-            if constexpr (Geo::RPD == 8) {
-                // d_in and rank are multiples of 8: the 8 rows of a load are inside their matrix,
-                // and inside one adapter of the tuple, as a whole; nothing here is per lane
-                const int k8 = kk + r * 8;
-                if (un.kind == 0) {
-                    if (k8 < d_in) src = w_lane[r] + (int64_t)kk * pitch;
-                } else if (un.kind == 1) {
-                    if (k8 < two_r) {
-                        const int jr = k8 < R ? k8 : k8 - R;        // row of the tuple's stacked B
-                        const int jj = mix.k > 1 ? jr / rank : 0;   // which adapter of the tuple
-                        const int ad = jj == 0 ? un.ad[0] : jj == 1 ? un.ad[1] : jj == 2 ? un.ad[2] : un.ad[3];
-                        src = b_lane[r] + ((int64_t)ad * rank + (jr - jj * rank)) * d_out;
-                    }
-                }
-            } else {
-                const int row = kk + r * Geo::RPD + w_rr;  // this lane's row
-                if (un.kind == 0) {
-                    if (row < d_in) src = w_lane[r] + (int64_t)kk * pitch;
-                } else if (un.kind == 1) {
-                    if (row < two_r) {
-                        const int jr = row < R ? row : row - R;
-                        const int jj = mix.k > 1 ? jr / rank : 0;
-                        const int ad = jj == 0 ? un.ad[0] : jj == 1 ? un.ad[1] : jj == 2 ? un.ad[2] : un.ad[3];
-                        src = B + ((int64_t)ad * rank + (jr - jj * rank)) * d_out + w_colv[r];
-                    }
+            const int kk = j * 16 + r * Geo::RPD + w_rr;  // this lane's row of the unit
+            if (un.kind == 0) {
+                // d_in is a multiple of 8 and so is RPD: rows of a load leave the matrix together
+                if (un.k0 + kk < d_in) src = w_lane[r] + (int64_t)(un.k0 + j * 16) * pitch;
+            } else if (un.kind == 1) {
+                const int sg = un.sg0 + (kk >> psh), vk = un.vk0 + (kk & pmask);
+                if (sg < nseg && vk < two_r) {
+                    const int jr = vk < R ? vk : vk - R;  // row of the tuple's stacked B
+                    const int jj = mix.k > 1 ? (jr >= rank) + (jr >= 2 * rank) + (jr >= 3 * rank) : 0;
+                    const int ad = seg_ad[sg * 4 + jj];
+                    src = B + ((int64_t)ad * rank + (jr - jj * rank)) * d_out + w_colv[r];
                 }
             }
             load_to_lds16_ptr(src, slot + r * 1024);
@@ -278,23 +241,23 @@ __global__ __launch_bounds__(kSbWaves * 64) void small_batch_kernel(
     const int a_sub = lane >> 3, a_pos = lane & 7;
     const uint16_t *a_xrow[4 * TM];
     int a_ch8[4 * TM];
-#pragma unroll
-    for (int i = 0; i < 4 * TM; ++i) {
-        const int row = i * 8 + a_sub;
-        const int tok = perm[row_base + min(row, nrows - 1)];  // rows past the end repeat the last one; never stored
-        a_ch8[i] = (a_pos ^ ((row ^ (row >> 3)) & 7)) * 8;
-        a_xrow[i] = x + (int64_t)tok * d_in + a_ch8[i];
-    }
     uint32_t a_off[4 * TM];  // byte offset of this lane's chunk from x + k0
+    {
+        bool ok = true;
 #pragma unroll
-    for (int i = 0; i < 4 * TM; ++i) {
-        const int64_t off = (const unsigned char *)a_xrow[i] - (const unsigned char *)x;
-        a_off[i] = (uint32_t)off;
-        off32_ok = off32_ok && (off >> 32) == 0;
+        for (int i = 0; i < 4 * TM; ++i) {
+            const int row = min(i * 8 + a_sub, nrows - 1);  // rows past the end repeat the last one; never stored
+            const int tok = direct ? row : perm[row_base + row];
+            a_ch8[i] = (a_pos ^ (((i * 8 + a_sub) ^ ((i * 8 + a_sub) >> 3)) & 7)) * 8;
+            a_xrow[i] = x + (int64_t)tok * d_in + a_ch8[i];
+            const int64_t off = (const unsigned char *)a_xrow[i] - (const unsigned char *)x;
+            a_off[i] = (uint32_t)off;
+            ok = ok && (off >> 32) == 0;
+        }
+        a_fast_ok = __all(ok) != 0;
     }
-    fast_allowed = __all(off32_ok) != 0;
     auto issue_stage = [&](const Unit &un) {
-        if (un.kind == 0 && un.fast && fast_allowed) {  // 64 k of x, all inside d_in
+        if (un.kind == 0 && un.fast && a_fast_ok) {  // 64 k of x, all inside d_in
             const unsigned char *xb = (const unsigned char *)(x + un.k0);
 #pragma unroll
             for (int i = 0; i < 4 * TM; ++i) load_to_lds16(xb, a_off[i], stage + i * 1024);
@@ -303,13 +266,15 @@ __global__ __launch_bounds__(kSbWaves * 64) void small_batch_kernel(
 #pragma unroll
         for (int i = 0; i < 4 * TM; ++i) {
             const int row = i * 8 + a_sub;
-            const int kk = un.k0 + a_ch8[i];
             const uint16_t *src = zero;
             if (un.kind == 0) {
-                if (kk < d_in) src = a_xrow[i] + un.k0;
+                if (un.k0 + a_ch8[i] < d_in) src = a_xrow[i] + un.k0;
             } else if (un.kind == 1) {
-                if (row >= un.lo && row < un.hi && kk < two_r)
-                    src = t2 + (int64_t)(row_base + row) * two_r + kk;
+                const int sg = un.sg0 + (a_ch8[i] >> psh), vk = un.vk0 + (a_ch8[i] & pmask);
+                if (sg < nseg && vk < two_r) {
+                    const int p = tile_pos[row];  // sorted position of the row
+                    if (p >= seg_lo[sg] && p < seg_hi[sg]) src = t2 + (int64_t)p * two_r + vk;
+                }
             }
             load_to_lds16_ptr(src, stage + i * 1024);
         }
@@ -354,25 +319,66 @@ __global__ __launch_bounds__(kSbWaves * 64) void small_batch_kernel(
     constexpr int XD = 4 * TM;
     constexpr int AHEAD = kSbRing - 1;
     static_assert(AHEAD == 4, "the wait counts above assume slabs are issued 4 steps ahead");
-    Cursor cw = cursor_at(u0), cx = cursor_at(u0);  // slab stream, staged-operand stream
-    Unit uw = unit_of(cw);
+    Cursor cw = {wu0, wave}, cx = {wu0, wave};  // slab stream, staged-operand stream
+    Unit uw;
+    uw.kind = 2;
     int qw = 0;  // step index of the next slab to issue; its unit is uw, its step qw % 4
     auto next_slab = [&]() {
-        issue_slab(uw, qw & 3, qw);
-        if ((++qw & 3) == 0) {
-            advance(cw);
+        if ((qw & 3) == 0) {  // first slab of a unit: only now is the unit looked at
             uw = unit_of(cw);
+            advance(cw);
         }
+        issue_slab(uw, qw & 3, qw);
+        ++qw;
     };
-    // what iterations -4 .. -1 would have issued
-    next_slab();
-    issue_stage(unit_of(cx));
-    advance(cx);
-    next_slab();
-    next_slab();
-    next_slab();
+    auto first_issues = [&]() {  // what iterations -4 .. -1 would have issued
+        next_slab();
+        issue_stage(unit_of(cx));
+        advance(cx);
+        next_slab();
+        next_slab();
+        next_slab();
+    };
+    // a wavefront that owns rows of W starts on them before anything else is known
+    const bool has_w = wu0 < wu1;
+    if (has_w) first_issues();
 
-    const int nunits = u1 - u0;
+    // ---- tables: row -> token and sorted position; the buckets that own rows, ascending ----
+    if (wave == 0) {
+        tile_perm[lane] = lane < nrows ? (direct ? lane : perm[row_base + lane]) : -1;
+        tile_pos[lane] = direct ? 0x7fffffff : row_base + lane;
+        if (direct && lane < nrows) {
+            const int tok = perm[lane];
+            if ((unsigned)tok < 64u) tile_pos[tok] = lane;  // same wavefront: after the line above
+        }
+    }
+    if (wave == kSbWaves - 1) {
+        const uint64_t lower = (lane == 0) ? 0ull : (~0ull >> (64 - lane));
+        int cnt = 0;
+        for (int c0 = 0; !SHRINK && c0 < C; c0 += 64) {
+            const int c = min(c0 + lane, C - 1);
+            // the bucket's sorted positions inside this row tile
+            const int lo = max(offsets[c], row_base), hi = min(offsets[c + 1], row_base + nrows);
+            const bool owns = (c0 + lane < C) && hi > lo;
+            const uint64_t m = __ballot(owns);
+            if (owns) {
+                const int idx = cnt + __popcll(m & lower);
+                seg_lo[idx] = lo;
+                seg_hi[idx] = hi;
+                // decoded here, once: a slot-table read inside the streaming loop would have to
+                // wait for every load in flight
+                for (int j = 0; j < 4; ++j) seg_ad[idx * 4 + j] = j < mix.k ? mix_adapter(mix, c, j) : 0;
+            }
+            cnt += __popcll(m);
+        }
+        if (lane == 0) *nseg_p = cnt;
+    }
+    __syncthreads();
+    nseg = __builtin_amdgcn_readfirstlane(*nseg_p);
+    ne = packed ? (nseg + pack - 1) / pack : nseg * upb;
+    if (!has_w) first_issues();
+
+    const int nunits = (wu1 - wu0) + (ne > wave ? (ne - wave + kSbWaves - 1) / kSbWaves : 0);
     for (int ui = 0; ui < nunits; ++ui) {
         bf16x8 fa[4][TM];
 #pragma unroll
