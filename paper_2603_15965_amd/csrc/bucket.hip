@@ -100,9 +100,13 @@ __global__ __launch_bounds__(kBucketThreads) void bucket_kernel(const int32_t *_
     const int end = (int)(start64 + per < N ? start64 + per : N);
     const uint64_t lower = (lane == 0) ? 0ull : (~0ull >> (64 - lane));
 
+    // a range of at most 64 * kUnroll tokens is one pass of either sweep: the second then
+    // reuses the keys of the first instead of reading (and, with a gate, deriving) them again
+    const bool one_pass = per <= 64 * kUnroll;
+    int32_t key[kUnroll];
+
     // ---- sweep 1: histogram per (target, wavefront) ----
     for (int base = start; base < end; base += 64 * kUnroll) {
-        int32_t key[kUnroll];
 #pragma unroll
         for (int u = 0; u < kUnroll; ++u) {
             const int t = base + u * 64 + lane;
@@ -112,6 +116,7 @@ __global__ __launch_bounds__(kBucketThreads) void bucket_kernel(const int32_t *_
         }
 #pragma unroll
         for (int u = 0; u < kUnroll; ++u) {
+            if (base + u * 64 >= end) break;  // wave-uniform: no token in this group
             const int t = base + u * 64 + lane;
             const bool valid = t < end;
             const uint64_t same = match_lanes(key[u], valid, nbits);
@@ -150,15 +155,17 @@ __global__ __launch_bounds__(kBucketThreads) void bucket_kernel(const int32_t *_
 
     // ---- sweep 2: scatter token indices to their positions ----
     for (int base = start; base < end; base += 64 * kUnroll) {
-        int32_t key[kUnroll];
+        if (!one_pass) {
 #pragma unroll
-        for (int u = 0; u < kUnroll; ++u) {
-            const int t = base + u * 64 + lane;
-            const int32_t c = target_of<GATE>(r, gate, t < end ? t : end - 1);
-            key[u] = (c >= 0 && c < C) ? c : C;
+            for (int u = 0; u < kUnroll; ++u) {
+                const int t = base + u * 64 + lane;
+                const int32_t c = target_of<GATE>(r, gate, t < end ? t : end - 1);
+                key[u] = (c >= 0 && c < C) ? c : C;
+            }
         }
 #pragma unroll
         for (int u = 0; u < kUnroll; ++u) {
+            if (base + u * 64 >= end) break;  // wave-uniform
             const int t = base + u * 64 + lane;
             const bool valid = t < end;
             const uint64_t same = match_lanes(key[u], valid, nbits);

@@ -250,14 +250,21 @@ hipError_t launch_shrink(const uint16_t *x, const uint16_t *A, const int32_t *of
     const bool small_items = (N + 31) / 32 + C < 512;
     const int rows = small_items ? 16 : 32;
     const unsigned blocks = (unsigned)((N + rows - 1) / rows + C);
-#define MOLORA_SHRINK_CASE(NJ)                                                                  \
-    case NJ:                                                                                    \
-        if (small_items)                                                                        \
-            hipLaunchKernelGGL((shrink_kernel<NJ, 1, 4, 4>), dim3(blocks), dim3(256), 0, s, x,  \
-                               A, offsets, perm, t2, d_in, C, rank, mix);                       \
-        else                                                                                    \
-            hipLaunchKernelGGL((shrink_kernel<NJ, 2, 4, 4>), dim3(blocks), dim3(256), 0, s, x,  \
-                               A, offsets, perm, t2, d_in, C, rank, mix);                       \
+    // fewer items than compute units and a long K: 8 wavefronts split it (measured 11.3 us
+    // against 14.9 us at 2048 tokens x 4096, 64 adapters; no gain once every unit has an item)
+    const bool wide = blocks <= 256 && d_in >= 4096;
+#define MOLORA_SHRINK_CASE(NJ)                                                                      \
+    case NJ:                                                                                        \
+        if (small_items && wide)                                                                    \
+            hipLaunchKernelGGL((shrink_kernel<NJ, 1, (NJ <= 2 ? 8 : 4), 4>), dim3(blocks),          \
+                               dim3(64 * (NJ <= 2 ? 8 : 4)), 0, s, x, A, offsets, perm, t2, d_in,   \
+                               C, rank, mix);                                                       \
+        else if (small_items)                                                                       \
+            hipLaunchKernelGGL((shrink_kernel<NJ, 1, 4, 4>), dim3(blocks), dim3(256), 0, s, x, A,   \
+                               offsets, perm, t2, d_in, C, rank, mix);                              \
+        else                                                                                        \
+            hipLaunchKernelGGL((shrink_kernel<NJ, 2, 4, 4>), dim3(blocks), dim3(256), 0, s, x, A,   \
+                               offsets, perm, t2, d_in, C, rank, mix);                              \
         break;
     switch (nj) {
         MOLORA_SHRINK_CASE(1)

@@ -129,6 +129,9 @@ def mix_case(seed, N, d_in, d_out, C, rank, k, S=None, bad=False, weights=True):
     (64, 512, 264, 5, 8, 4, None, True),        # small-batch path, four per token, bad entries
     (500, 256, 256, 6, 16, 1, 9, False),        # one adapter per token through a slot table
     (48, 512, 256, 5, 16, 2, 8, False),         # small-batch path, slot table and tuples
+    (64, 384, 200, 6, 8, 2, None, False),       # small-batch path, 2R = 32: two tuples per expand item
+    (37, 256, 136, 4, 8, 3, 7, True),           # small-batch path, 2R = 48, slot table, bad entries
+    (60, 512, 264, 3, 64, 2, None, False),      # small-batch path, tuples of rank-64 adapters (fast B pieces)
     (2000, 512, 1024, 16, 32, 2, 20, False),    # 256 tuples, wide intermediate
 ])
 def test_apply_mix_matches_oracle(gpu, N, d_in, d_out, C, rank, k, S, bad):

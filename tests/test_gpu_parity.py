@@ -116,6 +116,11 @@ def test_route_gate_bit_exact_full_configs(gpu, name):
     (50, 1024, 520, 5, 16, "uniform"),      # small-batch path with the K range split, ragged
     (64, 2048, 1024, 16, 64, "zipf"),       # small-batch path, many buckets in the one row tile
     (7, 1096, 264, 3, 8, "uniform"),        # small-batch path, K tail
+    (64, 640, 200, 11, 8, "uniform"),       # small-batch path, four buckets per expand item (2R = 16), 3 items
+    (61, 512, 136, 37, 16, "uniform"),      # two buckets per expand item, more items than wavefronts
+    (33, 128, 72, 9, 24, "uniform"),        # fewer pieces of W than wavefronts; 2R = 48, one bucket per item
+    (64, 256, 328, 6, 128, "zipf"),         # four 64-row pieces of [B; B] per bucket
+    (16, 64, 64, 16, 40, "uniform"),        # one piece of W, 2R = 80: a full and a short piece per bucket
     (200, 520, 328, 9, 24, "zipf"),         # small-batch path, four row tiles, ragged everywhere
     (700, 2048, 136, 3, 64, "zipf"),        # buckets of several 64-row tiles in the small-batch shrink
     (600, 328, 1000, 7, 24, "zipf"),        # 128 x 128 tiles with three stages, K shorter than the ring
