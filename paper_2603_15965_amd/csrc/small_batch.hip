@@ -55,16 +55,12 @@ struct SbGeom {
     }
 };
 
-// one unit of a wavefront's work list: 4 steps of 16 k
+// one unit of a wavefront's work list: 64 k-rows of W, four steps of 16 k
 struct Unit {
-    int kind;  // 0: rows k0 .. k0+63 of W; 1: an expand item; 2: nothing (zeros)
-    int k0;    // kind 0: first k
-    // kind 1: row kk of the unit is row vk0 + (kk & pmask) of [B_c; B_c] of the (sg0 + (kk >> psh))-th
-    // bucket that owns rows
-    int sg0, vk0;
-    // fast: all 64 rows lie inside their matrix and follow one another in memory from `base`
-    // (always so for W away from the K tail, and for B_c when rank is a multiple of 64); the
-    // loads of such a unit are a scalar base plus a fixed per-lane offset, nothing to decide
+    bool real;  // false: past the end of the list, nothing (zeros)
+    int k0;     // first k
+    // fast: all 64 rows lie inside W and follow one another in memory from `base`; the loads
+    // are a scalar base plus a fixed per-lane offset, nothing to decide
     bool fast;
     const unsigned char *base;
 };
@@ -116,67 +112,31 @@ __global__ __launch_bounds__(kSbWaves * 64) void small_batch_kernel(
     // end of every wavefront's list) look up the sorted position of a row.
     const bool direct = !SHRINK && gridDim.y == 1;
 
-    // ---- this wavefront's work list ----
-    //   W units [wu0, wu1): of the nub pieces of 64 k-rows of W (the last piece may be short)
-    //       every 8th one, piece 8 * u + wave -- known at once.  Interleaved, so that the
-    //       workgroups together sweep W from top to bottom (measured 2% faster than giving
-    //       every wavefront one contiguous eighth);
-    //   expand items e = wave, wave + 8, ... < ne -- known once the table of buckets is built.
-    //       An item is 64 rows of the stacked [B_c; B_c] of a bucket that owns rows, or, when
-    //       2R is 16 or 32, the stacked matrices of 4 or 2 such buckets one after the other
-    //       (the t operand is zero outside a row's own bucket, so they do not mix).
+    // ---- this wavefront's share of W ----
+    // Of the nub pieces of 64 k-rows of W (the last piece may be short) every 8th one, piece
+    // 8 * u + wave.  Interleaved, so that the workgroups together sweep W from top to bottom
+    // (measured 2% faster than giving every wavefront one contiguous eighth).
     const int two_r = 2 * R;
     const int nub = (d_in + 63) / 64;
-    const int wu0 = 0, wu1 = nub > wave ? (nub - wave + kSbWaves - 1) / kSbWaves : 0;
-    const bool packed = two_r == 16 || two_r == 32;
-    const int pack = packed ? 64 / two_r : 1;       // buckets per expand item
-    const int psh = packed ? (two_r == 16 ? 4 : 5) : 31;  // unit row -> bucket of the item
-    const int pmask = packed ? two_r - 1 : 63;             // unit row -> row of [B_c; B_c]
-    const int upb = (two_r + 63) / 64;               // items per bucket when not packed
-    int nseg = 0, ne = 0;                            // set after the tables
+    const int nw = nub > wave ? (nub - wave + kSbWaves - 1) / kSbWaves : 0;
 
     const int pitch = SHRINK ? rank : d_out;  // elements between consecutive k-rows of W (A)
     bool w_fast_ok = false, a_fast_ok = false;  // per-lane offsets fit 32 bits (set below)
-    struct Cursor {
-        int u, e;
+    // wave-uniform by construction; says so to the compiler, which must keep them in scalar
+    // registers for the load instruction
+    auto uniform_ptr = [](const void *ptr) {
+        const uint64_t v = (uint64_t)(uintptr_t)ptr;
+        const uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)v);
+        const uint32_t hi = __builtin_amdgcn_readfirstlane((uint32_t)(v >> 32));
+        return (const unsigned char *)(uintptr_t)(((uint64_t)hi << 32) | lo);
     };
-    auto unit_of = [&](const Cursor &cu) {
+    auto unit_of = [&](int u) {  // u-th unit of this wavefront
         Unit un;
-        un.sg0 = un.vk0 = 0;
-        un.fast = false;
-        un.base = (const unsigned char *)zero;
-        if (cu.u < wu1) {
-            un.kind = 0;
-            un.k0 = (cu.u * kSbWaves + wave) * 64;
-            un.fast = un.k0 + 64 <= d_in;
-            un.base = (const unsigned char *)(W + (int64_t)un.k0 * pitch);
-        } else if (cu.e < ne) {
-            un.kind = 1;
-            un.k0 = 0;
-            if (packed) {
-                un.sg0 = cu.e * pack;
-            } else {
-                un.sg0 = upb == 1 ? cu.e : cu.e / upb;
-                un.vk0 = (cu.e - un.sg0 * upb) * 64;
-            }
-            if ((rank & 63) == 0) {  // the unit is 64 consecutive rows of one adapter's B
-                const int jr = un.vk0 < R ? un.vk0 : un.vk0 - R;
-                const int jj = (jr >= rank) + (jr >= 2 * rank) + (jr >= 3 * rank);
-                const int ad = __builtin_amdgcn_readfirstlane(seg_ad[un.sg0 * 4 + jj]);
-                un.fast = true;
-                un.base = (const unsigned char *)(B + ((int64_t)ad * rank + (jr - jj * rank)) * d_out);
-            }
-        } else {
-            un.kind = 2;
-            un.k0 = 0;
-        }
+        un.real = u < nw;
+        un.k0 = un.real ? (u * kSbWaves + wave) * 64 : 0;
+        un.fast = un.real && un.k0 + 64 <= d_in;
+        un.base = (const unsigned char *)(W + (int64_t)un.k0 * pitch);
         return un;
-    };
-    auto advance = [&](Cursor &cu) {
-        if (cu.u < wu1)
-            ++cu.u;
-        else
-            cu.e += kSbWaves;
     };
 
     // ---- slab loads: 1 KB per instruction = RPD k-rows x (2 * COLS) bytes ----
@@ -212,8 +172,7 @@ __global__ __launch_bounds__(kSbWaves * 64) void small_batch_kernel(
         }
         w_fast_ok = __all(ok) != 0;
     }
-    auto issue_slab = [&](const Unit &un, int j, int q) {  // step j of the unit, into slot q % ring
-        unsigned char *slot = ring + (q % kSbRing) * kSbSlot;
+    auto issue_slab = [&](const Unit &un, int j, unsigned char *slot) {  // step j of the unit
 #pragma unroll
         for (int r = 0; r < Geo::NR; ++r) {
             if (un.fast && w_fast_ok) {
@@ -221,25 +180,14 @@ __global__ __launch_bounds__(kSbWaves * 64) void small_batch_kernel(
                               slot + r * 1024);
                 continue;
             }
-            const uint16_t *src = zero;
-            const int kk = j * 16 + r * Geo::RPD + w_rr;  // this lane's row of the unit
-            if (un.kind == 0) {
-                // d_in is a multiple of 8 and so is RPD: rows of a load leave the matrix together
-                if (un.k0 + kk < d_in) src = w_lane[r] + (int64_t)(un.k0 + j * 16) * pitch;
-            } else if (un.kind == 1) {
-                const int sg = un.sg0 + (kk >> psh), vk = un.vk0 + (kk & pmask);
-                if (sg < nseg && vk < two_r) {
-                    const int jr = vk < R ? vk : vk - R;  // row of the tuple's stacked B
-                    const int jj = mix.k > 1 ? (jr >= rank) + (jr >= 2 * rank) + (jr >= 3 * rank) : 0;
-                    const int ad = seg_ad[sg * 4 + jj];
-                    src = B + ((int64_t)ad * rank + (jr - jj * rank)) * d_out + w_colv[r];
-                }
-            }
+            // d_in is a multiple of 8 and so is RPD: rows of a load leave the matrix together
+            const int kk = un.k0 + j * 16 + r * Geo::RPD + w_rr;  // this lane's row
+            const uint16_t *src = (un.real && kk < d_in) ? w_lane[r] + (int64_t)(un.k0 + j * 16) * pitch : zero;
             load_to_lds16_ptr(src, slot + r * 1024);
         }
     };
 
-    // ---- x / t loads: 8 rows x 128 bytes (64 k) per instruction, 4 * TM instructions a unit ----
+    // ---- x loads: 8 rows x 128 bytes (64 k) per instruction, 4 * TM instructions a unit ----
     // lane -> row i*8 + lane/8, 16-byte position lane%8 of the staged row, which holds the
     // 8-k chunk (position ^ swizzle(row)); the operand read below undoes the swizzle.
     const int a_sub = lane >> 3, a_pos = lane & 7;
@@ -261,7 +209,7 @@ __global__ __launch_bounds__(kSbWaves * 64) void small_batch_kernel(
         a_fast_ok = __all(ok) != 0;
     }
     auto issue_stage = [&](const Unit &un) {
-        if (un.kind == 0 && un.fast && a_fast_ok) {  // 64 k of x, all inside d_in
+        if (un.fast && a_fast_ok) {  // 64 k of x, all inside d_in
             const unsigned char *xb = (const unsigned char *)(x + un.k0);
 #pragma unroll
             for (int i = 0; i < 4 * TM; ++i) load_to_lds16(xb, a_off[i], stage + i * 1024);
@@ -269,17 +217,7 @@ __global__ __launch_bounds__(kSbWaves * 64) void small_batch_kernel(
         }
 #pragma unroll
         for (int i = 0; i < 4 * TM; ++i) {
-            const int row = i * 8 + a_sub;
-            const uint16_t *src = zero;
-            if (un.kind == 0) {
-                if (un.k0 + a_ch8[i] < d_in) src = a_xrow[i] + un.k0;
-            } else if (un.kind == 1) {
-                const int sg = un.sg0 + (a_ch8[i] >> psh), vk = un.vk0 + (a_ch8[i] & pmask);
-                if (sg < nseg && vk < two_r) {
-                    const int p = tile_pos[row];  // sorted position of the row
-                    if (p >= seg_lo[sg] && p < seg_hi[sg]) src = t2 + (int64_t)p * two_r + vk;
-                }
-            }
+            const uint16_t *src = (un.real && un.k0 + a_ch8[i] < d_in) ? a_xrow[i] + un.k0 : zero;
             load_to_lds16_ptr(src, stage + i * 1024);
         }
     };
@@ -312,7 +250,7 @@ __global__ __launch_bounds__(kSbWaves * 64) void small_batch_kernel(
         return __builtin_bit_cast(bf16x8, b8);
     };
 
-    // ---- streaming loop ----
+    // ---- streaming loop over W ----
     // Step s = 4 * unit + j.  Iteration s issues slab s + 4, and at j == 0 (after the staged
     // operand of its own unit has been moved to registers) the staged operand of the next
     // unit.  Loads return in order, so "at most n outstanding", n = the number of loads issued
@@ -320,32 +258,25 @@ __global__ __launch_bounds__(kSbWaves * 64) void small_batch_kernel(
     //   staged operand of the unit, at j == 0: the three slabs issued since         -> 3 NR
     //   slab s at j > 0: 4 slabs and one staged operand issued since                -> 4 NR + XD
     //   slab s at j == 0: older than the staged operand, already there.
+    // Nothing here depends on the dispatch step's output (in token order not even the rows),
+    // so the stream starts before the tables below are built.
     constexpr int XD = 4 * TM;
     constexpr int AHEAD = kSbRing - 1;
     static_assert(AHEAD == 4, "the wait counts above assume slabs are issued 4 steps ahead");
-    Cursor cw = {wu0, wave}, cx = {wu0, wave};  // slab stream, staged-operand stream
-    Unit uw;
-    uw.kind = 2;
+    int uw_i = 0, ux_i = 0;  // next unit of the slab stream, of the staged-operand stream
+    Unit uw = unit_of(0);
     int qw = 0;  // step index of the next slab to issue; its unit is uw, its step qw % 4
     auto next_slab = [&]() {
-        if ((qw & 3) == 0) {  // first slab of a unit: only now is the unit looked at
-            uw = unit_of(cw);
-            advance(cw);
-        }
-        issue_slab(uw, qw & 3, qw);
+        if ((qw & 3) == 0) uw = unit_of(uw_i++);
+        issue_slab(uw, qw & 3, ring + (qw % kSbRing) * kSbSlot);
         ++qw;
     };
-    auto first_issues = [&]() {  // what iterations -4 .. -1 would have issued
-        next_slab();
-        issue_stage(unit_of(cx));
-        advance(cx);
-        next_slab();
-        next_slab();
-        next_slab();
-    };
-    // a wavefront that owns rows of W starts on them before anything else is known
-    const bool has_w = wu0 < wu1;
-    if (has_w) first_issues();
+    // what iterations -4 .. -1 would have issued
+    next_slab();
+    issue_stage(unit_of(ux_i++));
+    next_slab();
+    next_slab();
+    next_slab();
 
     // ---- tables: row -> token and sorted position; the buckets that own rows, ascending ----
     if (wave == 0) {
@@ -369,8 +300,7 @@ __global__ __launch_bounds__(kSbWaves * 64) void small_batch_kernel(
                 const int idx = cnt + __popcll(m & lower);
                 seg_lo[idx] = lo;
                 seg_hi[idx] = hi;
-                // decoded here, once: a slot-table read inside the streaming loop would have to
-                // wait for every load in flight
+                // the tuple and the slot table are decoded here, once
                 for (int j = 0; j < 4; ++j) seg_ad[idx * 4 + j] = j < mix.k ? mix_adapter(mix, c, j) : 0;
             }
             cnt += __popcll(m);
@@ -378,12 +308,8 @@ __global__ __launch_bounds__(kSbWaves * 64) void small_batch_kernel(
         if (lane == 0) *nseg_p = cnt;
     }
     __syncthreads();
-    nseg = __builtin_amdgcn_readfirstlane(*nseg_p);
-    ne = packed ? (nseg + pack - 1) / pack : nseg * upb;
-    if (!has_w) first_issues();
 
-    const int nunits = (wu1 - wu0) + (ne > wave ? (ne - wave + kSbWaves - 1) / kSbWaves : 0);
-    for (int ui = 0; ui < nunits; ++ui) {
+    for (int ui = 0; ui < nw; ++ui) {
         bf16x8 fa[4][TM];
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
@@ -397,12 +323,10 @@ __global__ __launch_bounds__(kSbWaves * 64) void small_batch_kernel(
                 wait_lds();  // the staging tile is in registers before it is refilled
             }
             next_slab();
-            if (j == 0) {
-                issue_stage(unit_of(cx));
-                advance(cx);
-            } else {
+            if (j == 0)
+                issue_stage(unit_of(ux_i++));
+            else
                 wait_vmcnt<4 * Geo::NR + XD>();
-            }
             const unsigned char *slot = ring + (s % kSbRing) * kSbSlot;
             bf16x8 bfr[TN];
 #pragma unroll
@@ -416,7 +340,87 @@ __global__ __launch_bounds__(kSbWaves * 64) void small_batch_kernel(
             wait_lds();  // the slab has been read before its slot is refilled
         }
     }
-    wait_vmcnt<0>();  // the trailing loads (zeros) land before the memory is reused
+    wait_vmcnt<0>();  // the trailing loads (zeros) have landed: the ring is free
+
+    // ---- grouped expand: acc += t B for the buckets that own rows ----
+    // The stacked B (R = k * rank rows) of every such bucket is cut into slabs of 16 rows;
+    // wavefront w takes slabs w, w + 8, ... of that sequence, four at a time: their loads and
+    // the loads of the matching columns of t (both halves, [hi | lo]; zero for rows outside
+    // the bucket) are all issued before the first is waited for, so a round costs one trip to
+    // memory.  One read of a slab serves both halves of t.
+    if constexpr (!SHRINK) {
+        const int nseg = __builtin_amdgcn_readfirstlane(*nseg_p);
+        const int nsl = (R + 15) / 16;  // slabs per bucket
+        const int nq = nseg * nsl;
+        constexpr int G = 4;
+        int p_row[TM];  // sorted position of this lane's rows
+#pragma unroll
+        for (int tm = 0; tm < TM; ++tm) p_row[tm] = tile_pos[tm * 32 + m_lo];
+        for (int q0 = wave; q0 < nq; q0 += kSbWaves * G) {
+            bf16x8 ta[G][2][TM];
+#pragma unroll
+            for (int g = 0; g < G; ++g) {
+                const int q = q0 + kSbWaves * g;
+                if (q >= nq) break;
+                const int sg = nsl == 1 ? q : q / nsl;
+                const int part = q - sg * nsl;
+                unsigned char *slot = ring + g * kSbSlot;
+                // rows part*16 .. +15 of the stacked B of the sg-th bucket
+                const bool whole = (rank & 15) == 0 && w_fast_ok;  // 16 rows of one adapter, all there
+                const unsigned char *bb = nullptr;
+                if (whole) {
+                    const int col = part * 16;
+                    const int jj = (col >= rank) + (col >= 2 * rank) + (col >= 3 * rank);
+                    const int ad = __builtin_amdgcn_readfirstlane(seg_ad[sg * 4 + jj]);
+                    bb = uniform_ptr(B + ((int64_t)ad * rank + (col - jj * rank)) * d_out);
+                }
+#pragma unroll
+                for (int r = 0; r < Geo::NR; ++r) {
+                    if (whole) {
+                        load_to_lds16(bb + (int64_t)(r * Geo::RPD) * (d_out * 2), w_off[r], slot + r * 1024);
+                        continue;
+                    }
+                    const int col = part * 16 + r * Geo::RPD + w_rr;  // this lane's row of the stacked B
+                    const uint16_t *src = zero;
+                    if (col < R) {
+                        const int jj = mix.k > 1 ? (col >= rank) + (col >= 2 * rank) + (col >= 3 * rank) : 0;
+                        const int ad = seg_ad[sg * 4 + jj];
+                        src = B + ((int64_t)ad * rank + (col - jj * rank)) * d_out + w_colv[r];
+                    }
+                    load_to_lds16_ptr(src, slot + r * 1024);
+                }
+                const int lo = __builtin_amdgcn_readfirstlane(seg_lo[sg]);
+                const int hi = __builtin_amdgcn_readfirstlane(seg_hi[sg]);
+                const int col = part * 16 + kg * 8;  // this lane's 8 columns of t
+#pragma unroll
+                for (int hl = 0; hl < 2; ++hl)
+#pragma unroll
+                    for (int tm = 0; tm < TM; ++tm) {
+                        const int p = p_row[tm];
+                        const bool ok = col < R && p >= lo && p < hi;
+                        const uint16_t *src = ok ? t2 + (int64_t)p * two_r + hl * R + col : zero;
+                        ta[g][hl][tm] = *(const bf16x8 *)src;
+                    }
+            }
+            wait_vmcnt<0>();
+#pragma unroll
+            for (int g = 0; g < G; ++g) {
+                if (q0 + kSbWaves * g >= nq) break;
+                bf16x8 bfr[TN];
+#pragma unroll
+                for (int tn = 0; tn < TN; ++tn) bfr[tn] = load_b_frag(ring + g * kSbSlot, tn);
+#pragma unroll
+                for (int hl = 0; hl < 2; ++hl)
+#pragma unroll
+                    for (int tm = 0; tm < TM; ++tm)
+#pragma unroll
+                        for (int tn = 0; tn < TN; ++tn)
+                            acc[tm][tn] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
+                                ta[g][hl][tm], bfr[tn], acc[tm][tn], 0, 0, 0);
+            }
+            wait_lds();  // the slabs have been read before the next round refills them
+        }
+    }
 
     // ---- add the 8 partial tiles, every row to its original position ----
     // acc[tm][tn][v]: row tm*32 + (v/4)*8 + (lane/32)*4 + v%4, column tn*32 + lane%32
