@@ -7,20 +7,23 @@
 // so the kernel is built around keeping many bytes in flight per compute unit and around
 // spending few cache-line accesses per byte, with no workgroup barrier in the streaming loop:
 //   * a workgroup owns 64 (or 32, where that is needed to occupy the chip) output columns and
-//     up to 64 rows; its 8 wavefronts split the K range in units of 64 k -- every 8th piece
-//     of the d_in rows of W, then every 8th of the expand items (the 2*rank rows of
-//     [B_c; B_c] of the buckets that own rows) -- and add their partial tiles in LDS at the
-//     end, in wavefront order, so the result does not depend on timing and needs no scratch
-//     memory or atomics;
+//     up to 64 rows; its 8 wavefronts split the K range -- of the pieces of 64 rows of W every
+//     8th one, then of the 16-row slabs of the B_c of the buckets that own rows every 8th
+//     one -- and add their partial tiles in LDS at the end, in wavefront order, so the result
+//     does not depend on timing and needs no scratch memory or atomics;
 //   * every wavefront streams its 16 x 64 slabs of W straight from HBM into a private ring of
 //     LDS slots (global_load_lds_dwordx4), 4 slabs ahead of the one it multiplies; the LDS
 //     transpose read turns the K-major slab into the MFMA operand;
-//   * the x (or t) operand of 64 k travels the same way, as whole 128-byte lines of 8 rows per
+//   * the x operand of 64 k travels the same way, as whole 128-byte lines of 8 rows per
 //     load instruction, into a private staging tile, one unit ahead; it is moved to registers
 //     at the start of its unit, which frees the staging tile for the next one;
-//   * chunks that must read as zero (k past d_in, t rows of other buckets, padding of a
-//     wavefront's list) come from an all-zero page, so every step issues the same number of
-//     loads and the explicit vmcnt waits are compile-time constants.
+//   * chunks that must read as zero (k past d_in, padding of a wavefront's list) come from an
+//     all-zero page, so every step issues the same number of loads and the explicit vmcnt
+//     waits are compile-time constants;
+//   * the grouped expand follows as a phase of its own: a few trips to memory, each for four
+//     slabs of B and the matching columns of t per wavefront (as units of the streaming loop
+//     they cost a full memory latency each: 46 us against 38 us at 64 tokens, 14 adapters of
+//     rank 64).
 #include <type_traits>
 
 #include "common.h"
@@ -352,7 +355,8 @@ __global__ __launch_bounds__(kSbWaves * 64) void small_batch_kernel(
         const int nseg = __builtin_amdgcn_readfirstlane(*nseg_p);
         const int nsl = (R + 15) / 16;  // slabs per bucket
         const int nq = nseg * nsl;
-        constexpr int G = 4;
+        constexpr int G = 4;  // slabs per round (8 measured no faster: the phase is bound by reading B)
+        static_assert(G * kSbSlot <= kSbWaveLds, "a round's slabs fit the wavefront's LDS");
         int p_row[TM];  // sorted position of this lane's rows
 #pragma unroll
         for (int tm = 0; tm < TM; ++tm) p_row[tm] = tile_pos[tm * 32 + m_lo];
