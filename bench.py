@@ -49,6 +49,10 @@ def parse():
     ap.add_argument("--sets", type=int, default=0,
                     help="independent input copies to rotate through (0 = enough for > 600 MB)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--timed-only", action="store_true",
+                    help="stop after the timed region: no latency pass, no two-stream pass, no per-kernel "
+                         "breakdown (for profiler runs, whose per-kernel averages then cover the "
+                         "warm-up and the timed region only)")
     ap.add_argument("--no-kernel-events", action="store_true",
                     help="leave the per-kernel HIP events out of the timed region")
     ap.add_argument("--copy-calibration", action="store_true",
@@ -249,21 +253,24 @@ def main():
     if use_ev:
         gemm_us = sum(e[2 * j].elapsed_time(e[2 * j + 1]) for e in evs.values() for j in range(P)) / len(evs) * 1e3
 
-    ticks = [torch.cuda.Event(enable_timing=True) for _ in range(args.steps + 1)]
-    for i in range(args.steps):
-        ticks[i].record(run_stream)
-        run_step(i)
-    ticks[args.steps].record(run_stream)
-    torch.cuda.synchronize()
-    lat = np.array([ticks[i].elapsed_time(ticks[i + 1]) * 1e3 for i in range(args.steps)])
-    latency = None if extra else {"p50_us": float(np.percentile(lat, 50)), "p99_us": float(np.percentile(lat, 99)),
+    skip_passes = bool(extra) or args.timed_only
+    latency = None
+    if not skip_passes:
+        ticks = [torch.cuda.Event(enable_timing=True) for _ in range(args.steps + 1)]
+        for i in range(args.steps):
+            ticks[i].record(run_stream)
+            run_step(i)
+        ticks[args.steps].record(run_stream)
+        torch.cuda.synchronize()
+        lat = np.array([ticks[i].elapsed_time(ticks[i + 1]) * 1e3 for i in range(args.steps)])
+        latency = {"p50_us": float(np.percentile(lat, 50)), "p99_us": float(np.percentile(lat, 99)),
                "mean_us": float(lat.mean()), "cv": float(lat.std() / lat.mean()),
                "how": "HIP events between consecutive steps on the launch stream, in a second pass "
                       "after the timed region (one event per step adds ~3 us to each)"}
 
     # ---- same K steps with independent batches overlapping (reported beside `value`) ----
     pipelined = None
-    if graphs is None and not extra and sets % 2 == 0:
+    if graphs is None and not skip_passes and sets % 2 == 0:
         two = [torch.cuda.Stream(), torch.cuda.Stream()]
         for i in range(min(args.warmup, 4)):
             step(S[i % sets], None, stream=two[i % 2])
@@ -294,12 +301,13 @@ def main():
         return total
 
     breakdown = {}
-    if "G" in S[0][0] or "v" in S[0][0]:
-        breakdown["route_us"] = timed_calls(lambda d: route(d))
-    rsrc = (lambda d: d["r"]) if ("G" in S[0][0] or "v" in S[0][0]) else (lambda d: d["r_given"])
-    breakdown["bucket_us"] = timed_calls(lambda d: mb.molora_bucket(rsrc(d), d["shape"].C, d["offsets"], d["perm"]))
-    breakdown["shrink_us"] = timed_calls(lambda d: mb.molora_shrink(d["x"], d["A"], d["offsets"], d["perm"], d["t"]))
-    breakdown["gemm_us"] = timed_calls(lambda d: mb.molora_base_expand(d["x"], d["W"], d["B"], d["t"], d["offsets"], d["perm"], d["h"]))
+    if not (args.timed_only and gemm_us is not None):
+        if "G" in S[0][0] or "v" in S[0][0]:
+            breakdown["route_us"] = timed_calls(lambda d: route(d))
+        rsrc = (lambda d: d["r"]) if ("G" in S[0][0] or "v" in S[0][0]) else (lambda d: d["r_given"])
+        breakdown["bucket_us"] = timed_calls(lambda d: mb.molora_bucket(rsrc(d), d["shape"].C, d["offsets"], d["perm"]))
+        breakdown["shrink_us"] = timed_calls(lambda d: mb.molora_shrink(d["x"], d["A"], d["offsets"], d["perm"], d["t"]))
+        breakdown["gemm_us"] = timed_calls(lambda d: mb.molora_base_expand(d["x"], d["W"], d["B"], d["t"], d["offsets"], d["perm"], d["h"]))
 
     work = None
     n_routed_all, touched_all = [], []

@@ -3,11 +3,14 @@
 //
 // The paper's dispatch hands out list positions with atomicAdd, which leaves the order
 // inside a target's list to chance.  Here the lists are ordered by token index (a stable
-// counting sort), so the output is unique and no atomics are needed at all: one workgroup
-// of 16 wavefronts splits the tokens into 16 contiguous ranges, every wavefront finds the
-// lanes that share a target with wave-wide ballots, the per-(target, wavefront) counts are
-// prefix-summed in LDS in (target-major, wavefront-minor) order, and a second sweep writes
-// every token to  base[target][wavefront] + (number of lower lanes with the same target).
+// counting sort), so the output is unique: one workgroup of 16 wavefronts splits the tokens
+// into 16 contiguous ranges, every wavefront finds the lanes that share a target with
+// wave-wide ballots, the per-(target, wavefront) counts are prefix-summed in LDS in
+// (target-major, wavefront-minor) order, and a second sweep writes every token to
+// base[target][wavefront] + (number of lower lanes with the same target).  The only atomics
+// are LDS adds on counters that belong to one wavefront (used because they need no wait, not
+// for exclusion): they execute in issue order, which is token order, so nothing depends on
+// timing.
 //
 // The whole problem (N <= a few 10^4 tokens, <= 131 KB of traffic) is latency bound, which
 // is why it is one workgroup and one launch rather than a multi-pass device-wide sort.
@@ -85,6 +88,7 @@ __global__ __launch_bounds__(kBucketThreads) void bucket_kernel(const int32_t *_
     // cnt[b * 16 + w]: tokens of target b (b == C: out of range) in wavefront w's range
     extern __shared__ int32_t lds[];
     volatile int32_t *cnt = lds;
+    int32_t *cnt_rw = lds;  // the same counters, for the LDS atomics of the two sweeps
     __shared__ int32_t wave_tot[kBucketWaves];
 
     const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
@@ -117,12 +121,21 @@ __global__ __launch_bounds__(kBucketThreads) void bucket_kernel(const int32_t *_
 #pragma unroll
         for (int u = 0; u < kUnroll; ++u) {
             if (base + u * 64 >= end) break;  // wave-uniform: no token in this group
-            const int t = base + u * 64 + lane;
-            const bool valid = t < end;
-            const uint64_t same = match_lanes(key[u], valid, nbits);
-            if (valid && (same & lower) == 0)  // lowest lane of its group
-                cnt[key[u] * kBucketWaves + w] += __popcll(same);
-            __builtin_amdgcn_wave_barrier();
+            const bool valid = base + u * 64 + lane < end;
+            if (nbits <= 2) {
+                // few targets: group the lanes (three ballots), one add per group by its lowest lane
+                const uint64_t same = match_lanes(key[u], valid, nbits);
+                if (valid && (same & lower) == 0)
+                    __hip_atomic_fetch_add(&cnt_rw[key[u] * kBucketWaves + w], __popcll(same),
+                                           __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+            } else if (valid) {
+                // one LDS add per lane, without return value: nothing to wait for, and integer
+                // counts do not depend on the order in which the lanes are served (the sweep is
+                // bound by vector instructions on the one compute unit it runs on; grouping the
+                // lanes first costs more of them than the serialised adds to equal addresses)
+                __hip_atomic_fetch_add(&cnt_rw[key[u] * kBucketWaves + w], 1, __ATOMIC_RELAXED,
+                                       __HIP_MEMORY_SCOPE_WORKGROUP);
+            }
         }
     }
     __syncthreads();
@@ -170,14 +183,16 @@ __global__ __launch_bounds__(kBucketThreads) void bucket_kernel(const int32_t *_
             const bool valid = t < end;
             const uint64_t same = match_lanes(key[u], valid, nbits);
             const int slot = key[u] * kBucketWaves + w;
-            int32_t pos = 0;
-            if (valid) pos = cnt[slot] + __popcll(same & lower);
-            __builtin_amdgcn_wave_barrier();
-            if (valid) {
-                perm[pos] = t;
-                if ((same & lower) == 0) cnt[slot] += __popcll(same);
-            }
-            __builtin_amdgcn_wave_barrier();
+            // the group's lowest lane takes the group's positions with one returning LDS add
+            // (the adds of successive groups execute in issue order, which is token order) and
+            // hands the base to the other lanes of the group
+            int32_t got = 0;
+            if (valid && (same & lower) == 0)
+                got = __hip_atomic_fetch_add(&cnt_rw[slot], __popcll(same), __ATOMIC_RELAXED,
+                                             __HIP_MEMORY_SCOPE_WORKGROUP);
+            const int first = same ? __ffsll((long long)same) - 1 : 0;
+            const int32_t base_pos = __shfl(got, first, 64);
+            if (valid) perm[base_pos + __popcll(same & lower)] = t;
         }
     }
 }
