@@ -97,26 +97,27 @@ __global__ __launch_bounds__(TB * TGW * 64) void route_gate_kernel(
         constexpr int IPT = K::KS * K::CW / 8 / K::NT;  // 8-element items per thread and slab
         static_assert(IPT * K::NT * 8 == K::KS * K::CW, "slab staging split");
         u32x4 greg[IPT];
+        // geometry of staging item m of this thread: lanes of a wavefront cover 32 k (4 apart) x 2
+        // groups of 8 targets, so that the 64 lanes of each LDS store below hit 64 different
+        // banks (bank = 4c + k/4 mod 64)
+        auto g_item = [&](int m, int &kk, int &c8) {
+            const int item = tid + m * K::NT;
+            const int lq = item % 64, gq = item / 64;
+            kk = (gq / (4 * (K::CW / 16))) * 128 + 4 * (lq % 32) + gq % 4;
+            c8 = 8 * (lq / 32) + 16 * ((gq / 4) % (K::CW / 16));
+        };
         auto g_load = [&](int k0) {
 #pragma unroll
             for (int m = 0; m < IPT; ++m) {
-                const int item = tid + m * K::NT;
-                // lanes of a wavefront: 32 k (4 apart) x 2 groups of 8 targets, so that the 64
-                // lanes of each LDS store below hit 64 different banks (bank = 4c + k/4 mod 64)
-                const int lq = item % 64, gq = item / 64;
-                const int kk = (gq / (4 * (K::CW / 16))) * 128 + 4 * (lq % 32) + gq % 4;
-                const int c8 = 8 * (lq / 32) + 16 * ((gq / 4) % (K::CW / 16));
-                const int k = k0 + kk;
-                const int kc = min(k, d_in - 1);
-                const uint32_t km = (k < d_in) ? 0xFFFFFFFFu : 0u;
-                u32x4 v;
+                int kk, c8;
+                g_item(m, kk, c8);
+                const int kc = min(k0 + kk, d_in - 1);
                 if constexpr (VEC8) {
-                    const int cc = min(c0 + c8, C - 8);
-                    v = *(const u32x4 *)(G + (int64_t)kc * C + cc);
-                    asm volatile("" : "+v"(v));  // keep the load unconditional
-                    const uint32_t m8 = (c0 + c8 < C) ? km : 0u;
-                    v = u32x4{v[0] & m8, v[1] & m8, v[2] & m8, v[3] & m8};
+                    // raw: zeroing of what came from clamped addresses waits until the slab is
+                    // stored, one slab later, so that nothing here waits for the load
+                    greg[m] = *(const u32x4 *)(G + (int64_t)kc * C + min(c0 + c8, C - 8));
                 } else {
+                    const uint32_t km = (k0 + kk < d_in) ? 0xFFFFFFFFu : 0u;
                     uint32_t e[8];
 #pragma unroll
                     for (int i = 0; i < 8; ++i) {
@@ -124,25 +125,27 @@ __global__ __launch_bounds__(TB * TGW * 64) void route_gate_kernel(
                         asm volatile("" : "+v"(raw));
                         e[i] = raw & ((c0 + c8 + i < C) ? km : 0u);
                     }
-                    v = u32x4{e[0] | (e[1] << 16), e[2] | (e[3] << 16), e[4] | (e[5] << 16),
-                              e[6] | (e[7] << 16)};
+                    greg[m] = u32x4{e[0] | (e[1] << 16), e[2] | (e[3] << 16), e[4] | (e[5] << 16),
+                                    e[6] | (e[7] << 16)};
                 }
-                greg[m] = v;
             }
         };
-        auto g_store = [&](float *slab) {
+        // the slab that starts at k0 (loaded KS k ago) goes to LDS
+        auto g_store = [&](float *slab, int k0) {
 #pragma unroll
             for (int m = 0; m < IPT; ++m) {
-                const int item = tid + m * K::NT;
-                // lanes of a wavefront: 32 k (4 apart) x 2 groups of 8 targets, so that the 64
-                // lanes of each LDS store below hit 64 different banks (bank = 4c + k/4 mod 64)
-                const int lq = item % 64, gq = item / 64;
-                const int kk = (gq / (4 * (K::CW / 16))) * 128 + 4 * (lq % 32) + gq % 4;
-                const int c8 = 8 * (lq / 32) + 16 * ((gq / 4) % (K::CW / 16));
+                int kk, c8;
+                g_item(m, kk, c8);
+                u32x4 v = greg[m];
+                if constexpr (VEC8) {
+                    // rows past d_in and targets past C were fetched from clamped addresses: zero
+                    const uint32_t m8 = (k0 + kk < d_in && c0 + c8 < C) ? 0xFFFFFFFFu : 0u;
+                    v = u32x4{v[0] & m8, v[1] & m8, v[2] & m8, v[3] & m8};
+                }
                 float *dst = slab + c8 * K::LDG + (kk & 3) * (K::KS / 4) + (kk >> 2);
 #pragma unroll
                 for (int i = 0; i < 8; ++i) {
-                    const uint32_t w = greg[m][i >> 1];
+                    const uint32_t w = v[i >> 1];
                     dst[i * K::LDG] = __uint_as_float((i & 1) ? (w & 0xFFFF0000u) : (w << 16));
                 }
             }
@@ -160,7 +163,7 @@ __global__ __launch_bounds__(TB * TGW * 64) void route_gate_kernel(
         for (int j = 0; j < kRing; ++j) x_load(j, j * kXK);
         if (c0 > 0) route_barrier();  // the previous pass has finished reading the slabs
         g_load(0);
-        g_store(gs);
+        g_store(gs, 0);
         g_load(K::KS);
         route_barrier();
 
@@ -205,7 +208,7 @@ __global__ __launch_bounds__(TB * TGW * 64) void route_gate_kernel(
                 if (((j + 1) * kXK) % K::KS == 0) {
                     // the next chunk starts a G slab: it was loaded into registers one slab ago
                     ++slab_idx;
-                    g_store(gs + (slab_idx & 1) * K::SLAB_FLOATS);
+                    g_store(gs + (slab_idx & 1) * K::SLAB_FLOATS, slab_idx * K::KS);
                     g_load((slab_idx + 1) * K::KS);
                     route_barrier();
                 }
@@ -219,6 +222,9 @@ __global__ __launch_bounds__(TB * TGW * 64) void route_gate_kernel(
                         acc[b] = __builtin_amdgcn_mfma_f32_16x16x4f32(xa, g[cur][b][s >> 2][s & 3],
                                                                       acc[b], 0, 0, 0);
                 }
+                // nothing moves across a chunk boundary: left alone, the scheduler sinks all eight
+                // x loads of a round to its end and the next round starts by waiting for them
+                __builtin_amdgcn_sched_barrier(0);
             }
         }
 
@@ -339,6 +345,9 @@ hipError_t launch_route_gate(const uint16_t *x, const uint16_t *G, int32_t *r, f
                              int64_t N, int d_in, int C, hipStream_t s) {
     if (N == 0) return hipSuccess;
     if (C <= 16) return launch_tb<1, 1>(x, G, r, logits_out, N, d_in, C, s);
+#ifdef MOLORA_ROUTE_NB2
+    if (C <= 32) return launch_tb<2, 1>(x, G, r, logits_out, N, d_in, C, s);
+#endif
     if (C <= 32) return launch_tb<1, 2>(x, G, r, logits_out, N, d_in, C, s);
     if (C <= 64) return launch_tb<2, 2>(x, G, r, logits_out, N, d_in, C, s);
     return launch_tb<2, 4>(x, G, r, logits_out, N, d_in, C, s);  // 128 targets per pass
