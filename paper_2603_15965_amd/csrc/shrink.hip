@@ -126,6 +126,9 @@ __global__ __launch_bounds__(64 * KW) void shrink_kernel(
     unsigned char *slab0 = lds + wave * 2 * SLABB;
 
     u32x4 xg[kDepth][RB], ag[kDepth][NJ];
+    // Loads are never predicated (addresses are clamped; what came from a clamped address is
+    // zeroed when the slab is written, kDepth steps later) and nothing here touches the loaded
+    // registers, so that a whole ring of steps really is in flight.
     auto load_step = [&](int slot, int s) {  // step s of this wavefront into ring slot
         const int k0 = k_begin + s * kStepK;
         const int kx = min(k0 + kg * 8, d_in - 8);
@@ -134,12 +137,8 @@ __global__ __launch_bounds__(64 * KW) void shrink_kernel(
 #pragma unroll
         for (int m = 0; m < NJ; ++m) {
             const int id = lane + 64 * m;
-            const int kr = id / (RP / 8), u = id % (RP / 8);
-            const int k = k0 + kr;
-            u32x4 v = *(const u32x4 *)(acol[m] + (int64_t)min(k, d_in - 1) * rank);
-            asm volatile("" : "+v"(v));  // keep the load unconditional
-            const uint32_t ok = (k < k_end && u * 8 < R) ? 0xFFFFFFFFu : 0u;
-            ag[slot][m] = u32x4{v[0] & ok, v[1] & ok, v[2] & ok, v[3] & ok};
+            const int kr = id / (RP / 8);
+            ag[slot][m] = *(const u32x4 *)(acol[m] + (int64_t)min(k0 + kr, d_in - 1) * rank);
         }
     };
 
@@ -162,7 +161,10 @@ __global__ __launch_bounds__(64 * KW) void shrink_kernel(
                 for (int m = 0; m < NJ; ++m) {
                     const int id = lane + 64 * m;
                     const int kr = id / (RP / 8), u = id % (RP / 8);
-                    *(u32x4 *)(slab + kr * ROWB + u * 16) = ag[d][m];
+                    // rows past this wavefront's k range and columns past R read as zero
+                    const uint32_t ok = (k_begin + s * kStepK + kr < k_end && u * 8 < R) ? 0xFFFFFFFFu : 0u;
+                    const u32x4 v = ag[d][m];
+                    *(u32x4 *)(slab + kr * ROWB + u * 16) = u32x4{v[0] & ok, v[1] & ok, v[2] & ok, v[3] & ok};
                 }
 #pragma unroll
                 for (int jb = 0; jb < NJ; ++jb) {
@@ -179,6 +181,9 @@ __global__ __launch_bounds__(64 * KW) void shrink_kernel(
                             __builtin_bit_cast(bf16x8, xg[d][rb]), bfrag, acc[rb][jb], 0, 0, 0);
                 }
                 load_step(d, s + kDepth);  // refill the ring slot
+                // a step's loads stay where they are written: the scheduler must not gather the
+                // refills of a round at its end
+                __builtin_amdgcn_sched_barrier(0);
             }
         }
     }
