@@ -28,6 +28,19 @@ def _cases():
         S = None if rng.random() < 0.5 else C + int(rng.integers(0, 5))
         bad = bool(rng.random() < 0.3)
         out.append((i, N, d_in, d_out, C, rank, k, S, bad))
+    # small batches (one row tile in token order, and a few tiles of sorted rows): the expand
+    # phase with every rank / tuple width, many and few buckets per tile
+    for i in range(36, 64):
+        N = int(rng.integers(1, 65)) if i % 2 == 0 else int(rng.integers(65, 513))
+        d_in = int(rng.integers(1, 70)) * 8
+        d_out = int(rng.integers(1, 70)) * 8
+        k = int(rng.choice([1, 1, 2, 3, 4]))
+        rank = int(rng.choice([r for r in ranks if r * k <= 128]))
+        cmax = {1: 64, 2: 31, 3: 10, 4: 5}[k]
+        C = int(rng.integers(max(k, 1), cmax + 1))
+        S = None if rng.random() < 0.5 else C + int(rng.integers(0, 5))
+        bad = bool(rng.random() < 0.3)
+        out.append((i, N, d_in, d_out, C, rank, k, S, bad))
     return out
 
 
