@@ -348,9 +348,6 @@ hipError_t launch_route_gate(const uint16_t *x, const uint16_t *G, int32_t *r, f
                              int64_t N, int d_in, int C, hipStream_t s) {
     if (N == 0) return hipSuccess;
     if (C <= 16) return launch_tb<1, 1>(x, G, r, logits_out, N, d_in, C, s);
-#ifdef MOLORA_ROUTE_NB2
-    if (C <= 32) return launch_tb<2, 1>(x, G, r, logits_out, N, d_in, C, s);
-#endif
     if (C <= 32) return launch_tb<1, 2>(x, G, r, logits_out, N, d_in, C, s);
     if (C <= 64) return launch_tb<2, 2>(x, G, r, logits_out, N, d_in, C, s);
     return launch_tb<2, 4>(x, G, r, logits_out, N, d_in, C, s);  // 128 targets per pass
