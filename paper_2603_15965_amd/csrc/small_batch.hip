@@ -34,6 +34,7 @@ namespace molora {
 namespace {
 
 constexpr int kSbWaves = 8;                    // wavefronts per workgroup = K splits
+constexpr int kSbRing = 5;                     // slab slots per wavefront
 constexpr int kSbStage = 64 * 128;             // x / t staging tile: 64 rows x 64 k
 
 // TN = 32-column blocks per workgroup: 2 (64 columns, 128-byte pieces of W rows) where the
@@ -46,11 +47,7 @@ struct SbGeom {
     static constexpr int CPR = COLS / 8;                // 16-byte chunks per slab row
     static constexpr int RPD = 64 / CPR;                // slab rows per load instruction
     static constexpr int ROW_BYTES = COLS * 4 + 16;     // partial tile row in LDS (+16: bank shift)
-    // slab slots per wavefront: slabs are issued RING - 1 steps ahead.  A 32-column slab is
-    // 1 KB, and four of them in flight per wavefront (32 KB per workgroup, ~16 GB/s at 2 us of
-    // latency) made the narrow form latency bound; LDS has room for eight
-    static constexpr int RING = TN == 1 ? 9 : 5;
-    static constexpr int WAVE_LDS = RING * SLOT + kSbStage;  // per wavefront; partial tile reuses it
+    static constexpr int WAVE_LDS = kSbRing * SLOT + kSbStage;  // per wavefront; partial tile reuses it
     static constexpr size_t LDS_BYTES = (size_t)kSbWaves * WAVE_LDS + (8 * 64 + 4) * sizeof(int32_t);
     static_assert(64 * ROW_BYTES <= WAVE_LDS, "partial tile fits the wavefront's region");
     // 32-byte chunk position inside a slab row that holds column chunk cc of k-row `row`
@@ -98,7 +95,7 @@ __global__ __launch_bounds__(kSbWaves * 64) void small_batch_kernel(
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int n0 = blockIdx.x * kSbCols;
     unsigned char *ring = smem + wave * kSbWaveLds;
-    unsigned char *stage = ring + Geo::RING * kSbSlot;
+    unsigned char *stage = ring + kSbRing * kSbSlot;
     const uint16_t *zero = (const uint16_t *)g_zero_page;
 
     // ---- rows of this workgroup ----
@@ -257,35 +254,32 @@ __global__ __launch_bounds__(kSbWaves * 64) void small_batch_kernel(
     };
 
     // ---- streaming loop over W ----
-    // Step s = 4 * unit + j.  Iteration s issues slab s + AHEAD (AHEAD = 4 or 8 steps), and at
-    // j == 0 (after the staged operand of its own unit has been moved to registers) the staged
-    // operand of the next unit.  Loads return in order, so "at most n outstanding", n = the
-    // number of loads issued after the needed one, is exactly "the needed one has landed":
+    // Step s = 4 * unit + j.  Iteration s issues slab s + 4, and at j == 0 (after the staged
+    // operand of its own unit has been moved to registers) the staged operand of the next
+    // unit.  Loads return in order, so "at most n outstanding", n = the number of loads issued
+    // after the needed one, is exactly "the needed one has landed":
     //   staged operand of the unit, at j == 0: the three slabs issued since         -> 3 NR
-    //   slab s at j > 0: AHEAD slabs and the staged operands of the AHEAD / 4 units that began
-    //       since                                                    -> AHEAD NR + (AHEAD / 4) XD
+    //   slab s at j > 0: 4 slabs and one staged operand issued since                -> 4 NR + XD
     //   slab s at j == 0: older than the staged operand, already there.
     // Nothing here depends on the dispatch step's output (in token order not even the rows),
     // so the stream starts before the tables below are built.
     constexpr int XD = 4 * TM;
-    constexpr int AHEAD = Geo::RING - 1;
-    static_assert(AHEAD % 4 == 0 && AHEAD >= 4, "slabs are issued a whole number of units ahead");
+    constexpr int AHEAD = kSbRing - 1;
+    static_assert(AHEAD == 4, "the wait counts above assume slabs are issued 4 steps ahead");
     int uw_i = 0, ux_i = 0;  // next unit of the slab stream, of the staged-operand stream
     Unit uw = unit_of(0);
     int qw = 0;  // step index of the next slab to issue; its unit is uw, its step qw % 4
     auto next_slab = [&]() {
         if ((qw & 3) == 0) uw = unit_of(uw_i++);
-        issue_slab(uw, qw & 3, ring + (qw % Geo::RING) * kSbSlot);
+        issue_slab(uw, qw & 3, ring + (qw % kSbRing) * kSbSlot);
         ++qw;
     };
-    // what the iterations before the first would have issued, except that only one staged
-    // operand is among them (the first wait for a staged operand finds more slabs behind it
-    // than in steady state: stricter, not weaker; the slab waits of the first unit count one
-    // staged operand less)
+    // what iterations -4 .. -1 would have issued
     next_slab();
     issue_stage(unit_of(ux_i++));
-#pragma unroll
-    for (int i = 1; i < AHEAD; ++i) next_slab();
+    next_slab();
+    next_slab();
+    next_slab();
 
     // ---- tables: row -> token and sorted position; the buckets that own rows, ascending ----
     if (wave == 0) {
@@ -335,13 +329,8 @@ __global__ __launch_bounds__(kSbWaves * 64) void small_batch_kernel(
             if (j == 0)
                 issue_stage(unit_of(ux_i++));
             else
-                // (the first unit has one staged operand less behind its slabs: the loads before
-                // the loop issue only one)
-                if (ui == 0)
-                    wait_vmcnt<AHEAD * Geo::NR + (AHEAD / 4 - 1) * XD>();
-                else
-                    wait_vmcnt<AHEAD * Geo::NR + (AHEAD / 4) * XD>();
-            const unsigned char *slot = ring + (s % Geo::RING) * kSbSlot;
+                wait_vmcnt<4 * Geo::NR + XD>();
+            const unsigned char *slot = ring + (s % kSbRing) * kSbSlot;
             bf16x8 bfr[TN];
 #pragma unroll
             for (int tn = 0; tn < TN; ++tn) bfr[tn] = load_b_frag(slot, tn);
