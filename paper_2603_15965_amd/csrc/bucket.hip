@@ -64,17 +64,19 @@ struct GateArgs {
     int M, n_adapters;
     VocabBreaks br;
 };
+// my_b: break b[lane] in lane `lane` (lanes 0 .. 63), b_top = b[M]: read once per kernel; a
+// break is then a lane read, not a scalar load from the argument block per token group
 template <bool GATE>
-__device__ __forceinline__ int32_t target_of(const int32_t *__restrict__ r, const GateArgs &g, int t) {
+__device__ __forceinline__ int32_t target_of(const int32_t *__restrict__ r, const GateArgs &g,
+                                             int32_t my_b, int32_t b_top, int t) {
     if constexpr (!GATE) {
         return r[t];
     } else {
         const int32_t id = g.v[t];
         const int32_t a = g.adapter != nullptr ? g.adapter[t] : 0;
-        int32_t m = 0;
-        for (int j = 1; j < g.M; ++j)
-            if (id >= g.br.b[j]) m = j;
-        const bool ok = id >= g.br.b[0] && id < g.br.b[g.M] && a >= 0 && a < g.n_adapters;
+        int32_t m = 0;  // breaks ascend: the last j with id >= b[j] is the number of such j >= 1
+        for (int j = 1; j < g.M; ++j) m += id >= __builtin_amdgcn_readlane(my_b, j) ? 1 : 0;
+        const bool ok = id >= __builtin_amdgcn_readlane(my_b, 0) && id < b_top && a >= 0 && a < g.n_adapters;
         return ok ? a * g.M + m : -1;
     }
 }
@@ -108,13 +110,18 @@ __global__ __launch_bounds__(kBucketThreads) void bucket_kernel(const int32_t *_
     // reuses the keys of the first instead of reading (and, with a gate, deriving) them again
     const bool one_pass = per <= 64 * kUnroll;
     int32_t key[kUnroll];
+    int32_t my_b = 0, b_top = 0;
+    if constexpr (GATE) {
+        my_b = gate.br.b[lane];
+        b_top = gate.br.b[gate.M];
+    }
 
     // ---- sweep 1: histogram per (target, wavefront) ----
     for (int base = start; base < end; base += 64 * kUnroll) {
 #pragma unroll
         for (int u = 0; u < kUnroll; ++u) {
             const int t = base + u * 64 + lane;
-            const int32_t c = target_of<GATE>(r, gate, t < end ? t : end - 1);  // never predicated: all loads in flight
+            const int32_t c = target_of<GATE>(r, gate, my_b, b_top, t < end ? t : end - 1);  // never predicated: all loads in flight
             if (GATE && t < end) gate.r_out[t] = c;
             key[u] = (c >= 0 && c < C) ? c : C;
         }
@@ -172,7 +179,7 @@ __global__ __launch_bounds__(kBucketThreads) void bucket_kernel(const int32_t *_
 #pragma unroll
             for (int u = 0; u < kUnroll; ++u) {
                 const int t = base + u * 64 + lane;
-                const int32_t c = target_of<GATE>(r, gate, t < end ? t : end - 1);
+                const int32_t c = target_of<GATE>(r, gate, my_b, b_top, t < end ? t : end - 1);
                 key[u] = (c >= 0 && c < C) ? c : C;
             }
         }
