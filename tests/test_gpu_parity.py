@@ -69,6 +69,8 @@ def test_route_vocab_bit_exact(gpu):
 @pytest.mark.parametrize("N,d_in,C", [
     (1, 8, 1), (77, 136, 3), (300, 256, 4), (300, 264, 8), (129, 1000, 16), (513, 520, 32),
     (200, 320, 64), (100, 200, 100), (64, 64, 300), (40, 72, 1024),
+    # four token groups per workgroup, ragged token counts
+    (8200, 264, 8), (16390, 136, 24), (20000, 72, 33), (33000, 40, 64),
 ])
 def test_route_gate_bit_exact_small(gpu, N, d_in, C):
     import oracle
