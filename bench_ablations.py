@@ -32,6 +32,7 @@ def main():
 
     import numpy as np
     import torch
+    from paper_2603_15965_amd import baselines
     from paper_2603_15965_amd import binding as mb
     from paper_2603_15965_amd import workloads as wl
 
@@ -118,11 +119,12 @@ def main():
             h = torch.empty((N, d_out), dtype=torch.float32, device="cuda")
             ws = mb.new_workspace(N, d_in, d_out, K, rank)
             t_tok = timed(lambda: mb.molora_apply(x, W, A, B, r, h=h, workspace=ws))
-            r_c = [torch.full((N,), c, dtype=torch.int32, device="cuda") for c in range(K)]
+            r_pass = [torch.full((N,), c, dtype=torch.int32, device="cuda") for c in range(-1, K)]
+            h_pass = torch.empty_like(h)
 
-            def passes():
-                for c in range(K):  # one pass of the whole batch per adapter
-                    mb.molora_apply(x, W, A, B, r_c[c], h=h, workspace=ws)
+            def passes():  # one pass of the whole batch per adapter, rows selected afterwards
+                baselines.kpass_apply(x, W, A, B, r, h=h, h_pass=h_pass, workspace=ws, r_pass=r_pass,
+                                      base_pass=False)
 
             t_seq = timed(passes, reps=max(5, args.reps // K))
             rows.append({"adapters": K, "per_token_us": t_tok, "per_sequence_K_passes_us": t_seq,

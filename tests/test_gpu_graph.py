@@ -69,3 +69,69 @@ def test_captured_step_replays(N):
         torch.cuda.synchronize()
         assert np.array_equal(d["h"].cpu().numpy(), h_gpu), f"replay {replay} vs eager"
     g.destroy()
+
+
+def test_captured_seven_projection_layer():
+    """The whole Qwen3-8B-shaped layer of configuration 4 at full size (seven projections,
+    N = 16384, each route -> bucket -> apply) recorded as ONE launch sequence, the form the
+    benchmark replays with --graph.  Every replay (inputs refreshed in place, eager work and a
+    synchronisation in between) must reproduce the eager calls bit for bit (r, offsets, perm, h
+    of every projection), and h is compared with the oracle on every 64th token."""
+    import torch
+    import oracle
+    from paper_2603_15965_amd import binding as mb
+    import gpu_helpers as gpu
+    names = [f"prefill8_{p}" for p in ("q", "k", "v", "o", "gate", "up", "down")]
+    side = torch.cuda.Stream()
+    P = []
+    for name in names:
+        print(f"layer graph: inputs of {name}", flush=True)
+        w = wl.make(wl.shapes()[name])
+        d = _setup(w)
+        d["w"] = w
+        P.append(d)
+
+    def step(stream):
+        for d in P:
+            sh = d["w"].shape
+            mb.molora_route(d["x"], d["G"], d["r"], stream=stream)
+            mb.molora_bucket(d["r"], sh.C, d["offsets"], d["perm"], stream=stream)
+            mb.molora_apply_bucketed(d["x"], d["W"], d["A"], d["B"], d["offsets"], d["perm"], d["h"],
+                                     workspace=d["ws"], stream=stream)
+
+    step(None)  # eager reference of the first inputs (also: first launches outside capture)
+    torch.cuda.synchronize()
+    g = mb.Graph(side)
+    with g.capture():
+        step(side)
+    rows = np.arange(0, P[0]["w"].shape.N, 64, dtype=np.int64)
+    rows_d = torch.from_numpy(rows).cuda()
+    for replay in range(3):
+        print(f"layer graph: replay {replay}", flush=True)
+        if replay > 0:  # refresh every projection's x in place: rows rolled by a fixed amount
+            for d in P:
+                d["x"].copy_(torch.roll(d["x"], 1000 * replay + 1, dims=0))
+        step(None)
+        torch.cuda.synchronize()
+        eager = [{k: d[k].clone() for k in ("r", "offsets", "perm", "h")} for d in P]
+        for d in P:
+            d["h"].zero_()
+            d["r"].fill_(-7)
+            d["perm"].fill_(-1)
+        torch.cuda.synchronize()
+        g.launch()
+        side.synchronize()
+        for d, e, name in zip(P, eager, names):
+            for k in ("r", "offsets", "perm", "h"):
+                assert torch.equal(d[k], e[k]), f"replay {replay}: {k} of {name} differs from the eager call"
+        if replay != 1:
+            continue
+        for d, name in zip(P, names):  # one replay against the oracle, on sampled rows
+            w = d["w"]
+            x_bits = np.roll(w.x, 1001, axis=0)
+            r_gpu = d["r"].cpu().numpy()
+            ref = oracle.apply_rows(x_bits, w.W, w.A, w.B, r_gpu, rows)
+            gpu.assert_h_close(d["h"][rows_d].cpu().numpy(), ref, f"replayed {name}")
+            sample = rows[::8]
+            assert np.array_equal(r_gpu[sample], oracle.route_gate(x_bits[sample], w.G)), name
+    g.destroy()
