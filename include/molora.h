@@ -31,7 +31,9 @@
  *  - Data-dependent problems (a routing target outside [0, C)) cannot be seen by the
  *    host without a synchronisation; they are reported through an optional DEVICE flag
  *    and handled as "this token has no adapter" (see molora_bucket).
- *  - Inputs are expected to be finite.  A NaN gate logit never wins the argmax.
+ *  - Inputs are expected to be finite.  The argmax is a scan from target 0 that moves on a
+ *    strict ">": a NaN logit at a target above 0 is never selected, a NaN at target 0 is
+ *    kept unless a later logit compares greater (never, against NaN), so it yields r = 0.
  */
 #ifndef MOLORA_H
 #define MOLORA_H
@@ -127,7 +129,10 @@ size_t molora_apply_workspace_bytes(int64_t N, int32_t d_in, int32_t d_out,
  *   x, W, A, B, r DEVICE (read); h DEVICE fp32 [N][d_out] (every element written);
  *   workspace DEVICE, 256-byte aligned, workspace_bytes >= molora_apply_workspace_bytes.
  *   0 <= N < 2^31; d_in, d_out >= 8 and multiples of 8; rank a multiple of 8,
- *   8 <= rank <= MOLORA_MAX_RANK; 1 <= C <= MOLORA_MAX_TARGETS.
+ *   8 <= rank <= MOLORA_MAX_RANK; 1 <= C <= MOLORA_MAX_TARGETS.  For N > 512 (the tiled
+ *   kernel) x and W must each be smaller than 4 GiB (N * d_in < 2^31 and d_in * d_out < 2^31
+ *   elements): larger ones are MOLORA_EINVAL, here and in molora_apply_bucketed,
+ *   molora_base_expand and molora_apply_mix.
  */
 molora_status molora_apply(const void *x, const void *W, const void *A, const void *B,
                            const int32_t *r, float *h,
@@ -164,6 +169,18 @@ molora_status molora_base_expand(const void *x, const void *W, const void *B, co
                                  const int32_t *offsets, const int32_t *perm, float *h,
                                  int64_t N, int32_t d_in, int32_t d_out, int32_t C, int32_t rank,
                                  void *stream);
+
+/*
+ * molora_base_expand with the height of the row tiles forced, for the tiling ablation (App.
+ * "Adaptive Tiling", Table "tab:adaptive_tiling": tile shape chosen from the load against one
+ * fixed shape).  tile_rows = 64 (the streaming kernel, W read once per 64-row tile), 128
+ * (128 x 128 output tiles) or 256 (256 x 256 tiles); anything else is MOLORA_EINVAL.  Same
+ * result as molora_base_expand up to the order of the fp32 additions.
+ */
+molora_status molora_base_expand_fixed(const void *x, const void *W, const void *B, const void *t,
+                                       const int32_t *offsets, const int32_t *perm, float *h,
+                                       int64_t N, int32_t d_in, int32_t d_out, int32_t C,
+                                       int32_t rank, int32_t tile_rows, void *stream);
 
 /*
  * Learned router with top-k selection (Sec. "Router Architecture"):
@@ -240,7 +257,9 @@ molora_status molora_apply_mix(const void *x, const void *W, const void *A, cons
  * molora_graph_begin puts `stream` (a hipStream_t other than the null stream) into capture
  * mode; every molora_* call issued on that stream until molora_graph_end is recorded instead
  * of executed (all of them are capturable: no allocation, no synchronisation, no host read of
- * device memory).  molora_graph_end stops the capture and returns an executable graph, owned
+ * device memory).  The once-per-device set-up of molora_init is not a stream operation and
+ * must not happen inside a capture: molora_graph_begin runs it before the capture starts; a
+ * caller that captures with the HIP API itself calls molora_init() first.  molora_graph_end stops the capture and returns an executable graph, owned
  * by the caller, in *graph (NULL on error).  molora_graph_launch replays it on `stream`
  * (asynchronous, any stream of the same device); the recorded calls read and write the same
  * device addresses as at capture time, so the caller refreshes inputs in place.
@@ -252,6 +271,14 @@ molora_status molora_graph_begin(void *stream);
 molora_status molora_graph_end(void *stream, molora_graph **graph);
 molora_status molora_graph_launch(molora_graph *graph, void *stream);
 void molora_graph_destroy(molora_graph *graph);
+
+/*
+ * Once-per-device set-up on the current device: tells the runtime which kernels use more than
+ * 64 KB of LDS.  Every entry point does this by itself the first time it runs on a device, so
+ * the call is only needed before the caller's own stream capture (see above).  Enqueues
+ * nothing, allocates nothing; thread safe.  MOLORA_EHIP if the runtime refuses (no device).
+ */
+molora_status molora_init(void);
 
 /* Human-readable name of a status code (static storage, never NULL). */
 const char *molora_status_string(molora_status status);

@@ -54,7 +54,8 @@ static float *widen(const uint16_t *src, size_t n)
  * mixture collapses to Eq. "pertok").  The gate is the linear, bias-free MoE
  * form of Table "tab:moe_adapter": logits_i = x_i G, G is [d_in][C] row-major.
  * r[i] = argmax_c logits_i[c]; ties go to the lowest index (strict '>' scan).
- * A NaN logit never wins; if logit 0 is NaN and nothing compares greater, 0.
+ * A NaN logit above index 0 is never selected; logit 0 is the scan's starting point and
+ * stays selected if it is NaN (nothing compares greater than a NaN).
  * Returns 0, or -1 on allocation failure.
  */
 int oracle_route_gate(const uint16_t *x, const uint16_t *G, int32_t *r,

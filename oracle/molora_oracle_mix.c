@@ -19,7 +19,9 @@
  * exp(y) = 2^n exp(r), n = rint(y / ln 2), with a degree-7 Taylor polynomial in r; both are
  * written out below in plain fp32 operations whose order is part of the definition.  The
  * softmax weights use the same exp.  Selection: k times the largest remaining logit, the
- * lowest index among equals (strict '>' scan); a NaN never wins.
+ * lowest index among equals (strict '>' scan).  Inputs are expected to be finite: a NaN
+ * logit is never selected over an earlier candidate, but the first remaining candidate of a
+ * scan is its starting point and stays selected if it is NaN (nothing compares greater).
  *
  * Pins (tests/test_oracle_mix.py): float64 numpy MLP with math.erf, numpy argsort for the
  * selection, k = 1 reducing bit-exactly to the single-adapter oracle, equal logits giving

@@ -15,6 +15,7 @@ LIB_PATH = os.path.join(_HERE, "libmolora.so")
 MOLORA_OK = 0
 EXPORTS = ["molora_route", "molora_route_vocab", "molora_bucket", "molora_apply_workspace_bytes",
            "molora_apply", "molora_apply_bucketed", "molora_shrink", "molora_base_expand",
+           "molora_base_expand_fixed", "molora_init",
            "molora_route_mlp_workspace_bytes", "molora_route_mlp", "molora_route_compose",
            "molora_gate_dispatch",
            "molora_apply_mix_workspace_bytes", "molora_apply_mix",
@@ -57,6 +58,10 @@ def load():
     lib.molora_shrink.restype = ctypes.c_int
     lib.molora_base_expand.argtypes = [vp, vp, vp, vp, vp, vp, vp, i64, i32, i32, i32, i32, vp]
     lib.molora_base_expand.restype = ctypes.c_int
+    lib.molora_base_expand_fixed.argtypes = [vp, vp, vp, vp, vp, vp, vp, i64, i32, i32, i32, i32, i32, vp]
+    lib.molora_base_expand_fixed.restype = ctypes.c_int
+    lib.molora_init.argtypes = []
+    lib.molora_init.restype = ctypes.c_int
     lib.molora_route_mlp_workspace_bytes.argtypes = [i64, i32]
     lib.molora_route_mlp_workspace_bytes.restype = sz
     lib.molora_route_mlp.argtypes = [vp, vp, vp, vp, vp, vp, vp, i64, i32, i32, i32, i32, vp, sz, vp]
@@ -222,20 +227,29 @@ def molora_shrink(x, A, offsets, perm, t=None, stream=None):
     return t
 
 
-def molora_base_expand(x, W, B, t, offsets, perm, h=None, stream=None):
-    """h[perm[p]] = x[perm[p]] W + t_p B_c, every row written once."""
+def molora_base_expand(x, W, B, t, offsets, perm, h=None, stream=None, tile_rows=None):
+    """h[perm[p]] = x[perm[p]] W + t_p B_c, every row written once.  tile_rows (64, 128 or
+    256) forces the row-tile height (molora_base_expand_fixed, for the tiling ablation)."""
     N, d_in = x.shape
     d_out = W.shape[1]
     C, rank, _ = B.shape
     if h is None:
         h = torch.empty((N, d_out), dtype=torch.float32, device=x.device)
     bf = torch.bfloat16
-    st = load().molora_base_expand(_dev(x, bf, "x"), _dev(W, bf, "W"), _dev(B, bf, "B"),
-                                   _dev(t, bf, "t"), _dev(offsets, torch.int32, "offsets"),
-                                   _dev(perm, torch.int32, "perm"), _dev(h, torch.float32, "h"),
-                                   N, d_in, d_out, C, rank, _stream(stream))
+    args = [_dev(x, bf, "x"), _dev(W, bf, "W"), _dev(B, bf, "B"), _dev(t, bf, "t"),
+            _dev(offsets, torch.int32, "offsets"), _dev(perm, torch.int32, "perm"),
+            _dev(h, torch.float32, "h"), N, d_in, d_out, C, rank]
+    if tile_rows is None:
+        st = load().molora_base_expand(*args, _stream(stream))
+    else:
+        st = load().molora_base_expand_fixed(*args, int(tile_rows), _stream(stream))
     _check(st, "molora_base_expand")
     return h
+
+
+def molora_init():
+    """Once-per-device set-up (needed only before a stream capture made with the HIP API)."""
+    _check(load().molora_init(), "molora_init")
 
 
 def bf16_tensor(bits, device="cuda"):

@@ -3,6 +3,43 @@
 
 #include "common.h"
 
+#include <mutex>
+
+namespace molora {
+
+namespace {
+constexpr int kMaxDevices = 64;
+std::mutex g_init_mutex;
+bool g_device_ready[kMaxDevices];
+KernelLdsNeed *&lds_list() {
+    static KernelLdsNeed *head = nullptr;
+    return head;
+}
+}  // namespace
+
+void register_kernel_lds(KernelLdsNeed *node) {  // from static initialisers: no HIP call here
+    node->next = lds_list();
+    lds_list() = node;
+}
+
+hipError_t ensure_device_ready() {
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    if (dev < 0 || dev >= kMaxDevices) return hipErrorInvalidDevice;
+    std::lock_guard<std::mutex> lock(g_init_mutex);
+    if (g_device_ready[dev]) return hipSuccess;
+    for (KernelLdsNeed *n = lds_list(); n != nullptr; n = n->next) {
+        if (n->bytes <= 64 * 1024) continue;
+        e = hipFuncSetAttribute(n->fn, hipFuncAttributeMaxDynamicSharedMemorySize, n->bytes);
+        if (e != hipSuccess) return e;
+    }
+    g_device_ready[dev] = true;
+    return hipSuccess;
+}
+
+}  // namespace molora
+
 namespace {
 
 inline bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
@@ -42,7 +79,8 @@ molora_status apply_common(const void *x, const void *W, const void *A, const vo
                            const int32_t *r, const int32_t *offsets, const int32_t *perm, float *h,
                            int64_t N, int32_t d_in, int32_t d_out, int32_t C, int32_t rank,
                            void *workspace, size_t workspace_bytes, void *stream) {
-    if (!apply_sizes_ok(N, d_in, d_out, C, rank)) return MOLORA_EINVAL;
+    if (!apply_sizes_ok(N, d_in, d_out, C, rank) || !molora::fused_gemm_sizes_ok(N, d_in, d_out))
+        return MOLORA_EINVAL;
     if (N == 0) return MOLORA_OK;
     if (!x || !W || !A || !B || !h || !workspace) return MOLORA_EINVAL;
     if (r == nullptr && (offsets == nullptr || perm == nullptr)) return MOLORA_EINVAL;
@@ -52,6 +90,7 @@ molora_status apply_common(const void *x, const void *W, const void *A, const vo
         return MOLORA_EALIGN;
     const Workspace ws = carve(workspace, N, C, rank);
     if (workspace_bytes < ws.bytes) return MOLORA_EWORKSPACE;
+    if (molora::ensure_device_ready() != hipSuccess) return MOLORA_EHIP;
 
     hipStream_t s = static_cast<hipStream_t>(stream);
     const uint16_t *xb = static_cast<const uint16_t *>(x);
@@ -84,6 +123,7 @@ molora_status molora_route(const void *x, const void *G, int32_t *r, int64_t N, 
     if (N == 0) return MOLORA_OK;
     if (!x || !G || !r) return MOLORA_EINVAL;
     if (!aligned16(x) || !aligned16(G) || !aligned16(r)) return MOLORA_EALIGN;
+    if (molora::ensure_device_ready() != hipSuccess) return MOLORA_EHIP;
     return from_hip(molora::launch_route_gate(static_cast<const uint16_t *>(x),
                                               static_cast<const uint16_t *>(G), r, nullptr, N, d_in, C,
                                               static_cast<hipStream_t>(stream)));
@@ -106,6 +146,7 @@ molora_status molora_bucket(const int32_t *r, int32_t *offsets, int32_t *perm, i
     if (N < 0 || N >= (int64_t(1) << 31) || C < 1 || C > MOLORA_MAX_TARGETS) return MOLORA_EINVAL;
     if (!offsets || (N > 0 && (!r || !perm))) return MOLORA_EINVAL;
     if (!aligned16(offsets) || (N > 0 && (!aligned16(r) || !aligned16(perm)))) return MOLORA_EALIGN;
+    if (molora::ensure_device_ready() != hipSuccess) return MOLORA_EHIP;
     return from_hip(molora::launch_bucket(r, offsets, perm, N, C, err_flag,
                                           static_cast<hipStream_t>(stream)));
 }
@@ -122,6 +163,7 @@ molora_status molora_gate_dispatch(const int32_t *v, const int32_t *adapter, con
     if (!aligned16(offsets) ||
         (N > 0 && (!aligned16(v) || !aligned16(r) || !aligned16(perm) || (adapter && !aligned16(adapter)))))
         return MOLORA_EALIGN;
+    if (molora::ensure_device_ready() != hipSuccess) return MOLORA_EHIP;
     return from_hip(molora::launch_gate_bucket(v, adapter, breaks, M, n_adapters, r, offsets, perm, N,
                                                err_flag, static_cast<hipStream_t>(stream)));
 }
@@ -158,6 +200,7 @@ molora_status molora_shrink(const void *x, const void *A, const int32_t *offsets
     if (!x || !A || !offsets || !perm || !t) return MOLORA_EINVAL;
     if (!aligned16(x) || !aligned16(A) || !aligned16(offsets) || !aligned16(perm) || !aligned16(t))
         return MOLORA_EALIGN;
+    if (molora::ensure_device_ready() != hipSuccess) return MOLORA_EHIP;
     return from_hip(molora::launch_shrink(static_cast<const uint16_t *>(x),
                                           static_cast<const uint16_t *>(A), offsets, perm,
                                           static_cast<uint16_t *>(t), N, d_in, C, rank,
@@ -165,20 +208,41 @@ molora_status molora_shrink(const void *x, const void *A, const int32_t *offsets
                                           static_cast<hipStream_t>(stream)));
 }
 
-molora_status molora_base_expand(const void *x, const void *W, const void *B, const void *t,
-                                 const int32_t *offsets, const int32_t *perm, float *h,
-                                 int64_t N, int32_t d_in, int32_t d_out, int32_t C, int32_t rank,
+namespace {
+molora_status base_expand_common(const void *x, const void *W, const void *B, const void *t,
+                                 const int32_t *offsets, const int32_t *perm, float *h, int64_t N,
+                                 int32_t d_in, int32_t d_out, int32_t C, int32_t rank, int tile,
                                  void *stream) {
     if (!apply_sizes_ok(N, d_in, d_out, C, rank)) return MOLORA_EINVAL;
+    if (!molora::fused_gemm_sizes_ok(N, d_in, d_out, tile)) return MOLORA_EINVAL;
     if (N == 0) return MOLORA_OK;
     if (!x || !W || !B || !t || !offsets || !perm || !h) return MOLORA_EINVAL;
     if (!aligned16(x) || !aligned16(W) || !aligned16(B) || !aligned16(t) || !aligned16(offsets) ||
         !aligned16(perm) || !aligned16(h))
         return MOLORA_EALIGN;
+    if (molora::ensure_device_ready() != hipSuccess) return MOLORA_EHIP;
     return from_hip(molora::launch_fused_gemm(
         static_cast<const uint16_t *>(x), static_cast<const uint16_t *>(W),
         static_cast<const uint16_t *>(B), static_cast<const uint16_t *>(t), offsets, perm, h, N,
-        d_in, d_out, C, rank, molora::Mix{1, C, nullptr, nullptr}, static_cast<hipStream_t>(stream)));
+        d_in, d_out, C, rank, molora::Mix{1, C, nullptr, nullptr}, static_cast<hipStream_t>(stream),
+        tile));
+}
+}  // namespace
+
+molora_status molora_base_expand(const void *x, const void *W, const void *B, const void *t,
+                                 const int32_t *offsets, const int32_t *perm, float *h,
+                                 int64_t N, int32_t d_in, int32_t d_out, int32_t C, int32_t rank,
+                                 void *stream) {
+    return base_expand_common(x, W, B, t, offsets, perm, h, N, d_in, d_out, C, rank, 0, stream);
+}
+
+molora_status molora_base_expand_fixed(const void *x, const void *W, const void *B, const void *t,
+                                       const int32_t *offsets, const int32_t *perm, float *h,
+                                       int64_t N, int32_t d_in, int32_t d_out, int32_t C,
+                                       int32_t rank, int32_t tile_rows, void *stream) {
+    if (tile_rows != 64 && tile_rows != 128 && tile_rows != 256) return MOLORA_EINVAL;
+    return base_expand_common(x, W, B, t, offsets, perm, h, N, d_in, d_out, C, rank, tile_rows,
+                              stream);
 }
 
 size_t molora_route_mlp_workspace_bytes(int64_t N, int32_t H) {
@@ -200,6 +264,7 @@ molora_status molora_route_mlp(const void *x, const void *W1, const float *b1, c
         !aligned16(idx) || !aligned16(w) || !aligned256(workspace))
         return MOLORA_EALIGN;
     if (workspace_bytes < molora_route_mlp_workspace_bytes(N, H)) return MOLORA_EWORKSPACE;
+    if (molora::ensure_device_ready() != hipSuccess) return MOLORA_EHIP;
     hipStream_t s = static_cast<hipStream_t>(stream);
     float *u = static_cast<float *>(workspace);
     hipError_t e = molora::launch_route_gate(static_cast<const uint16_t *>(x),
@@ -281,7 +346,8 @@ molora_status molora_apply_mix(const void *x, const void *W, const void *A, cons
                                const int32_t *idx, const float *w, const int32_t *slots, float *h,
                                int64_t N, int32_t d_in, int32_t d_out, int32_t C, int32_t rank,
                                int32_t k, void *workspace, size_t workspace_bytes, void *stream) {
-    if (!mix_sizes_ok(N, d_in, d_out, C, rank, k)) return MOLORA_EINVAL;
+    if (!mix_sizes_ok(N, d_in, d_out, C, rank, k) || !molora::fused_gemm_sizes_ok(N, d_in, d_out))
+        return MOLORA_EINVAL;
     if (N == 0) return MOLORA_OK;
     if (!x || !W || !A || !B || !idx || !h || !workspace) return MOLORA_EINVAL;
     if (!aligned16(x) || !aligned16(W) || !aligned16(A) || !aligned16(B) || !aligned16(idx) ||
@@ -290,6 +356,7 @@ molora_status molora_apply_mix(const void *x, const void *W, const void *A, cons
         return MOLORA_EALIGN;
     const MixWorkspace ws = carve_mix(workspace, N, C, rank, k);
     if (workspace_bytes < ws.bytes) return MOLORA_EWORKSPACE;
+    if (molora::ensure_device_ready() != hipSuccess) return MOLORA_EHIP;
     const int Cb = (int)mix_buckets(C, k);
     hipStream_t s = static_cast<hipStream_t>(stream);
     const uint16_t *xb = static_cast<const uint16_t *>(x);
@@ -316,6 +383,10 @@ const char *molora_status_string(molora_status status) {
     }
 }
 
-const char *molora_version(void) { return "molora-gfx950 0.1"; }
+const char *molora_version(void) { return "molora-gfx950 0.2"; }
+
+molora_status molora_init(void) {
+    return molora::ensure_device_ready() == hipSuccess ? MOLORA_OK : MOLORA_EHIP;
+}
 
 }  // extern "C"

@@ -53,6 +53,28 @@ __device__ __forceinline__ int mix_adapter(const Mix &m, int b, int j) {
     return m.slots != nullptr ? m.slots[c] : c;
 }
 
+// ---- once-per-device set-up ----
+// A kernel that uses more than 64 KB of dynamic LDS has to be told so once (a function
+// attribute).  Every such kernel registers itself in a list when the library is loaded (no HIP
+// call happens then); ensure_device_ready() walks the list the first time any entry point runs
+// on a device, and molora_init() / molora_graph_begin() call it eagerly, so that no attribute
+// call ever falls inside a stream capture.
+struct KernelLdsNeed {
+    const void *fn;
+    int bytes;
+    KernelLdsNeed *next;
+};
+void register_kernel_lds(KernelLdsNeed *node);
+struct LdsRegistrar {
+    KernelLdsNeed node;
+    LdsRegistrar(const void *fn, size_t bytes) : node{fn, (int)bytes, nullptr} { register_kernel_lds(&node); }
+};
+hipError_t ensure_device_ready();
+
+// the tiled GEMM keeps per-lane byte offsets into x and W in 32 bits: false when the kernel
+// that launch_fused_gemm would pick for these sizes (force_tile as there) cannot address them
+bool fused_gemm_sizes_ok(int64_t N, int d_in, int d_out, int force_tile = 0);
+
 // ---- launchers implemented in the kernel translation units (all asynchronous) ----
 // rank is the rank of one adapter; buckets number C (the tuples, when mix.k > 1)
 // r and logits_out (fp32 [N][C], the chains themselves) are each optional
@@ -81,7 +103,7 @@ hipError_t launch_shrink(const uint16_t *x, const uint16_t *A, const int32_t *of
 hipError_t launch_fused_gemm(const uint16_t *x, const uint16_t *W, const uint16_t *B,
                              const uint16_t *t2, const int32_t *offsets, const int32_t *perm,
                              float *h, int64_t N, int d_in, int d_out, int C, int rank, Mix mix,
-                             hipStream_t s);
+                             hipStream_t s, int force_tile = 0);
 
 // same contract, N <= 64 (the fused GEMM launcher routes such batches here)
 hipError_t launch_small_batch_gemm(const uint16_t *x, const uint16_t *W, const uint16_t *B,

@@ -402,16 +402,18 @@ __global__ __launch_bounds__(Cfg::NT) void fused_gemm_kernel(
     }
 }
 
+// more than 64 KB of dynamic LDS has to be asked for, once per device (see common.h)
+template <class Cfg>
+struct GemmKernel {
+    static inline LdsRegistrar lds{(const void *)fused_gemm_kernel<Cfg>, Cfg::LDS_BYTES};
+};
+
 template <class Cfg>
 hipError_t launch_cfg(const uint16_t *x, const uint16_t *W, const uint16_t *B, const uint16_t *t2,
                       const int32_t *offsets, const int32_t *perm, float *h, int64_t N, int d_in,
                       int d_out, int C, int rank, Mix mix, hipStream_t s) {
     auto kern = fused_gemm_kernel<Cfg>;
-    // once per kernel: more than 64 KB of dynamic LDS has to be asked for
-    static const hipError_t e = hipFuncSetAttribute((const void *)kern,
-                                                    hipFuncAttributeMaxDynamicSharedMemorySize,
-                                                    (int)Cfg::LDS_BYTES);
-    if (e != hipSuccess) return e;
+    (void)&GemmKernel<Cfg>::lds;  // instantiates the registration
     const int tiles_m = (int)((N + Cfg::BM - 1) / Cfg::BM);
     const int tiles_n = (d_out + Cfg::BN - 1) / Cfg::BN;
     const int total = tiles_m * tiles_n;
@@ -423,41 +425,42 @@ hipError_t launch_cfg(const uint16_t *x, const uint16_t *W, const uint16_t *B, c
 
 }  // namespace
 
-#ifndef MOLORA_SMALL_BATCH_MAX
-#define MOLORA_SMALL_BATCH_MAX 512  // up to here W is streamed once per 64-row tile instead (measured crossover)
-#endif
-#ifndef MOLORA_BIG_MIN_TILES
-#define MOLORA_BIG_MIN_TILES 256
-#endif
-#ifndef MOLORA_GEMM_BIG
-#define MOLORA_GEMM_BIG 256, 256, 2, 4, 64, 2
-#endif
-#ifndef MOLORA_GEMM_SMALL
-#define MOLORA_GEMM_SMALL 128, 128, 2, 2, 64, 2
-#endif
-#ifndef MOLORA_GEMM_MID
-#define MOLORA_GEMM_MID 128, 128, 2, 2, 64, 3
-#endif
+// Kernel and tile choice from static shapes only (no host read of the histogram); the
+// thresholds are measured crossovers.
+constexpr int kSmallBatchMax = 512;  // up to here W is streamed once per 64-row tile by the small-batch kernel
+constexpr int kBigMinTiles = 256;    // 256 x 256 tiles as soon as they number one per compute unit
+using GemmBig = GemmCfg<256, 256, 2, 4, 64, 2>;
+using GemmSmall = GemmCfg<128, 128, 2, 2, 64, 2>;
+// 128 x 128 tiles with at most one workgroup per compute unit: a third stage replaces the
+// second resident workgroup as the way to cover the load latency
+using GemmMid = GemmCfg<128, 128, 2, 2, 64, 3>;
 
+bool fused_gemm_sizes_ok(int64_t N, int d_in, int d_out, int force_tile) {
+    const bool tiled = force_tile == 128 || force_tile == 256 || (force_tile == 0 && N > kSmallBatchMax);
+    if (!tiled) return true;  // the small-batch kernel checks its own offsets
+    const uint64_t lim = uint64_t(1) << 32;
+    return (uint64_t)N * (uint64_t)d_in * 2 < lim && (uint64_t)d_in * (uint64_t)d_out * 2 < lim;
+}
+
+// force_tile: 0 = the choice below; 64 / 128 / 256 = that row-tile height whatever the shape
+// (the tiling ablation compares the choice with fixed tiles).
 hipError_t launch_fused_gemm(const uint16_t *x, const uint16_t *W, const uint16_t *B,
                              const uint16_t *t2, const int32_t *offsets, const int32_t *perm,
                              float *h, int64_t N, int d_in, int d_out, int C, int rank, Mix mix,
-                             hipStream_t s) {
+                             hipStream_t s, int force_tile) {
     if (N == 0) return hipSuccess;
-    // Kernel and tile choice from static shapes only (no host read of the histogram); the
-    // thresholds are measured crossovers.  Up to 512 tokens W is streamed once per 64-row tile
-    // by the small-batch kernel; 256 x 256 tiles as soon as they number one per compute unit
-    // (with fewer, 128 x 128 tiles keep more of the chip busy).
-    if (N <= MOLORA_SMALL_BATCH_MAX) return launch_small_batch_gemm(x, W, B, t2, offsets, perm, h, N, d_in, d_out, C, rank, mix, s);
+#define MOLORA_GEMM_ARGS x, W, B, t2, offsets, perm, h, N, d_in, d_out, C, rank, mix, s
+    if (force_tile == 64) return launch_small_batch_gemm(MOLORA_GEMM_ARGS);
+    if (force_tile == 128) return launch_cfg<GemmSmall>(MOLORA_GEMM_ARGS);
+    if (force_tile == 256) return launch_cfg<GemmBig>(MOLORA_GEMM_ARGS);
+    if (N <= kSmallBatchMax) return launch_small_batch_gemm(MOLORA_GEMM_ARGS);
     const int64_t t256 = ((N + 255) / 256) * ((d_out + 255) / 256);
-    if (t256 >= MOLORA_BIG_MIN_TILES)
-        return launch_cfg<GemmCfg<MOLORA_GEMM_BIG>>(x, W, B, t2, offsets, perm, h, N, d_in, d_out, C, rank, mix, s);
-    // 128 x 128 tiles: with at most one workgroup per compute unit a third stage replaces the
-    // second resident workgroup as the way to cover the load latency
+    if (t256 >= kBigMinTiles) return launch_cfg<GemmBig>(MOLORA_GEMM_ARGS);
+    // with fewer, 128 x 128 tiles keep more of the chip busy
     const int64_t t128 = ((N + 127) / 128) * ((d_out + 127) / 128);
-    if (t128 <= 256)
-        return launch_cfg<GemmCfg<MOLORA_GEMM_MID>>(x, W, B, t2, offsets, perm, h, N, d_in, d_out, C, rank, mix, s);
-    return launch_cfg<GemmCfg<MOLORA_GEMM_SMALL>>(x, W, B, t2, offsets, perm, h, N, d_in, d_out, C, rank, mix, s);
+    if (t128 <= 256) return launch_cfg<GemmMid>(MOLORA_GEMM_ARGS);
+    return launch_cfg<GemmSmall>(MOLORA_GEMM_ARGS);
+#undef MOLORA_GEMM_ARGS
 }
 
 }  // namespace molora

@@ -2,10 +2,11 @@
 // shape; Sec. "CUDA Graph Compatibility"): a thin layer over HIP stream capture, so that a
 // caller without HIP bindings can record any sequence of molora_* calls once and replay it
 // with a single launch.  All molora_* launches are capturable: they allocate nothing, never
-// synchronise, read no device memory on the host and clear memory with kernels only.
+// synchronise, read no device memory on the host and clear memory with kernels only; the one
+// thing that is not a launch, the once-per-device set-up, is done before the capture begins.
 #include "../../include/molora.h"
 
-#include <hip/hip_runtime.h>
+#include "common.h"
 
 #include <new>
 
@@ -18,6 +19,8 @@ extern "C" {
 
 molora_status molora_graph_begin(void *stream) {
     if (stream == nullptr) return MOLORA_EINVAL;  // the null stream cannot be captured
+    // the once-per-device set-up (function attributes) must not fall inside the capture
+    if (molora::ensure_device_ready() != hipSuccess) return MOLORA_EHIP;
     const hipError_t e =
         hipStreamBeginCapture(static_cast<hipStream_t>(stream), hipStreamCaptureModeThreadLocal);
     return e == hipSuccess ? MOLORA_OK : MOLORA_EHIP;

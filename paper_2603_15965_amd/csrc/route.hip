@@ -307,16 +307,19 @@ __global__ __launch_bounds__(TB * TGW * 64) void route_gate_kernel(
     }
 }
 
+// more than 64 KB of dynamic LDS has to be asked for, once per device (see common.h)
+template <int NB, int TB, int TGW, bool VEC8>
+struct RouteKernel {
+    static inline LdsRegistrar lds{(const void *)route_gate_kernel<NB, TB, TGW, VEC8>,
+                                   RouteCfg<NB, TB, TGW>::LDS_BYTES};
+};
+
 template <int NB, int TB, int TGW, bool VEC8>
 hipError_t launch_cfg(const uint16_t *x, const uint16_t *G, int32_t *r, float *lo, int64_t N,
                       int d_in, int C, hipStream_t s) {
     using K = RouteCfg<NB, TB, TGW>;
     auto kern = route_gate_kernel<NB, TB, TGW, VEC8>;
-    if (K::LDS_BYTES > 64 * 1024) {  // once per kernel
-        static const hipError_t e = hipFuncSetAttribute(
-            (const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)K::LDS_BYTES);
-        if (e != hipSuccess) return e;
-    }
+    (void)&RouteKernel<NB, TB, TGW, VEC8>::lds;  // instantiates the registration
     const unsigned blocks = (unsigned)((N + K::TOK_WG - 1) / K::TOK_WG);
     hipLaunchKernelGGL(kern, dim3(blocks), dim3(K::NT), K::LDS_BYTES, s, x, G, r, lo, N, d_in, C);
     return hipGetLastError();

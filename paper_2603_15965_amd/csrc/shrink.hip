@@ -25,9 +25,7 @@ namespace molora {
 namespace {
 
 constexpr int kStepK = 32;       // k per MFMA step
-#ifndef MOLORA_SHRINK_TINY_MAX
-#define MOLORA_SHRINK_TINY_MAX 64  // batches up to this size take the many-wavefront form
-#endif
+constexpr int kShrinkTinyMax = 64;  // batches up to this size take the many-wavefront form
 
 // R = mix.k * rank is the width of a bucket's intermediate: piece j of it is x A of the j-th
 // adapter of the bucket's tuple, scaled by the token's j-th mixture weight.
@@ -237,7 +235,7 @@ hipError_t launch_shrink(const uint16_t *x, const uint16_t *A, const int32_t *of
     const int64_t R = (int64_t)mix.k * rank;
     const int nj = (mix.k * rank + 15) / 16;
     // a few work items only, narrow intermediate: 16 (8) wavefronts per 16-row item
-    if (N <= MOLORA_SHRINK_TINY_MAX && nj <= 2) {
+    if (N <= kShrinkTinyMax && nj <= 2) {
         const unsigned blocks = (unsigned)((N + 15) / 16 + C);
         if (nj == 1)
             hipLaunchKernelGGL((shrink_kernel<1, 1, 16, 8>), dim3(blocks), dim3(1024), 0, s, x, A,

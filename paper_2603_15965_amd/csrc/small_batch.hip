@@ -469,17 +469,19 @@ __global__ __launch_bounds__(kSbWaves * 64) void small_batch_kernel(
     }
 }
 
+// more than 64 KB of dynamic LDS has to be asked for, once per device (see common.h)
+template <int TM, int TN, bool SHRINK>
+struct SmallBatchKernel {
+    static inline LdsRegistrar lds{(const void *)small_batch_kernel<TM, TN, SHRINK>, SbGeom<TN>::LDS_BYTES};
+};
+
 template <int TM, int TN, bool SHRINK>
 hipError_t launch_small(const uint16_t *x, const uint16_t *W, const uint16_t *B, const uint16_t *t2,
                         const int32_t *offsets, const int32_t *perm, float *h, uint16_t *t_out, int N,
                         int d_in, int d_out, int C, int rank, Mix mix, hipStream_t s) {
     using Geo = SbGeom<TN>;
     auto kern = small_batch_kernel<TM, TN, SHRINK>;
-    // once per kernel: more than 64 KB of dynamic LDS has to be asked for
-    static const hipError_t e = hipFuncSetAttribute((const void *)kern,
-                                                    hipFuncAttributeMaxDynamicSharedMemorySize,
-                                                    (int)Geo::LDS_BYTES);
-    if (e != hipSuccess) return e;
+    (void)&SmallBatchKernel<TM, TN, SHRINK>::lds;  // instantiates the registration
     const unsigned groups = (unsigned)((d_out + Geo::COLS - 1) / Geo::COLS);
     const unsigned row_tiles = (unsigned)((N + 63) / 64);
     // GEMM: row tiles of the batch.  SHRINK: buckets x row tiles a bucket can have at most

@@ -125,3 +125,27 @@ def test_widened_entry_points_reject_bad_arguments(lib):
     assert lib.molora_graph_end(None, ctypes.byref(h)) == EINVAL
     assert lib.molora_graph_launch(None, None) == EINVAL
     lib.molora_graph_destroy(None)
+
+
+def test_operands_of_4_gib_are_rejected_for_the_tiled_kernel(lib):
+    """The tiled GEMM (N > 512) keeps per-lane byte offsets into x and W in 32 bits; sizes
+    beyond that are an error before launch, not silently wrapped addresses."""
+    EINVAL, EWORKSPACE = -1, -3
+    p = ctypes.c_void_p
+    buf = (ctypes.c_char * 4096)()
+    a = ctypes.addressof(buf)
+    a += (-a) % 256
+    f = lib.molora_apply
+    call = lambda N, di, do: f(p(a), p(a), p(a), p(a), p(a), p(a), N, di, do, 4, 8, p(a), 16, None)
+    assert call(1 << 20, 4096, 64) == EINVAL          # x = 8 GiB
+    assert call(1 << 19, 4096, 64) == EINVAL          # x = 4 GiB exactly
+    assert call((1 << 19) - 8, 4096, 64) == EWORKSPACE  # just below: passes the size check
+    assert call(1024, 65536, 32768) == EINVAL         # W = 4 GiB
+    assert call(1024, 65536, 32760) == EWORKSPACE
+    assert call(512, 65536, 32768) == EWORKSPACE      # the small-batch kernel has no such limit
+    be = lib.molora_base_expand
+    assert be(p(a), p(a), p(a), p(a), p(a), p(a), p(a), 1 << 20, 4096, 64, 4, 8, None) == EINVAL
+    fx = lib.molora_base_expand_fixed
+    assert fx(p(a), p(a), p(a), p(a), p(a), p(a), p(a), 64, 65536, 32768, 4, 8, 256, None) == EINVAL
+    assert fx(p(a), p(a), p(a), p(a), p(a), p(a), p(a), 64, 64, 64, 4, 8, 100, None) == EINVAL  # no such tile
+    assert fx(None, None, None, None, None, None, None, 0, 64, 64, 4, 8, 128, None) == 0

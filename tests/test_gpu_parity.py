@@ -96,6 +96,22 @@ def test_route_gate_exact_ties_pick_lowest_index(gpu):
     assert not np.any((r == 7) | (r == 11))
 
 
+@pytest.mark.parametrize("nan_col", [0, 3])
+def test_route_gate_nan_logits_follow_the_scan(gpu, nan_col):
+    """Unsupported input with a defined result: a NaN logit above target 0 is never selected,
+    a NaN at target 0 (the scan's starting point) yields 0."""
+    import oracle
+    say(f"route with NaN logits in column {nan_col}")
+    w = wl.custom("nan", 300, 128, 16, 9, 8, 9100, route="gate")
+    G = w.G.copy()
+    G[5, nan_col] = 0x7FC0  # bf16 quiet NaN: every token's logit for this target is NaN
+    w.G = G
+    r = gpu.gpu_route(w).cpu().numpy()
+    ref = oracle.route_gate(w.x, w.G)
+    assert np.array_equal(r, ref)
+    assert np.all(r == 0) if nan_col == 0 else not np.any(r == nan_col)
+
+
 @pytest.mark.parametrize("name", ["gate_up17", "prefill8_q", "prefill8_down"])
 def test_route_gate_bit_exact_full_configs(gpu, name):
     import oracle
