@@ -3,17 +3,32 @@
 //
 // The paper's dispatch hands out list positions with atomicAdd, which leaves the order
 // inside a target's list to chance.  Here the lists are ordered by token index (a stable
-// counting sort), so the output is unique: one workgroup of 16 wavefronts splits the tokens
-// into 16 contiguous ranges, every wavefront finds the lanes that share a target with
-// wave-wide ballots, the per-(target, wavefront) counts are prefix-summed in LDS in
-// (target-major, wavefront-minor) order, and a second sweep writes every token to
-// base[target][wavefront] + (number of lower lanes with the same target).  The only atomics
-// are LDS adds on counters that belong to one wavefront (used because they need no wait, not
-// for exclusion): they execute in issue order, which is token order, so nothing depends on
-// timing.
+// counting sort), so the output is unique, and it is unique BY CONSTRUCTION: nothing in the
+// kernel depends on the order in which the hardware serves the lanes of an atomic
+// instruction or on timing between wavefronts.
+//
+//   * The tokens are cut into contiguous ranges, one per wavefront (16 wavefronts per
+//     workgroup, 1 to 8 workgroups).  Sweep 1 counts, per target, the tokens of every range of
+//     the workgroup's own part (cnt[target][wavefront]) and the tokens before and after the
+//     workgroup's part (pre[target], post[target]; every workgroup reads all of r for this,
+//     <= 64 KB from L2, instead of waiting for the other workgroups' counts).  Counts are sums
+//     of ones: LDS adds whose order does not matter.
+//   * offsets[c] is the exclusive prefix of the totals; the first position of wavefront w's
+//     tokens of target c is offsets[c] + pre[c] + sum_{w' < w} cnt[c][w'].
+//   * Sweep 2: a wavefront walks its range in token order, 64 tokens per step.  Inside a step,
+//     a token's place among the lanes with the same target is the number of LOWER lanes with
+//     that target, read off a bit mask of those lanes: for up to three targets the mask comes
+//     from wave ballots; for up to 255 from an LDS word per (wavefront, target) into which
+//     every lane ORs its own bit (OR is commutative: the mask does not depend on the order of
+//     service) and which every lane then reads and clears its bit from again; above that from
+//     one ballot per bit of the target index.  LDS operations of one wavefront execute in the
+//     order they are issued, so the running base of a (wavefront, target) pair, read by all
+//     lanes and then advanced, needs no wait either.
 //
 // The whole problem (N <= a few 10^4 tokens, <= 131 KB of traffic) is latency bound, which
-// is why it is one workgroup and one launch rather than a multi-pass device-wide sort.
+// is why it is one launch of a few workgroups that each recount rather than a multi-pass
+// device-wide sort.
+#include "../../include/molora.h"
 #include "common.h"
 
 namespace molora {
@@ -81,27 +96,56 @@ __device__ __forceinline__ int32_t target_of(const int32_t *__restrict__ r, cons
     }
 }
 
+constexpr int kMaskMaxKeys = 256;  // keys (targets + 1) up to which sweep 2 uses LDS lane masks
+
+// LDS layout for `keys` = C + 1 keys (key C: target out of range)
+struct BucketLds {
+    int keys;
+    bool masks;
+    __host__ __device__ explicit BucketLds(int C) : keys(C + 1), masks(C + 1 > 4 && C + 1 <= kMaskMaxKeys) {}
+    __host__ __device__ size_t cnt_off() const { return 0; }                                    // [keys][16]
+    __host__ __device__ size_t pre_off() const { return (size_t)keys * kBucketWaves * 4; }     // [keys]
+    __host__ __device__ size_t post_off() const { return pre_off() + (size_t)keys * 4; }       // [keys]
+    __host__ __device__ size_t tot_off() const { return post_off() + (size_t)keys * 4; }       // [keys]
+    __host__ __device__ size_t mask_off() const { return (tot_off() + (size_t)keys * 4 + 7) & ~size_t(7); }
+    __host__ __device__ size_t bytes() const {
+        return mask_off() + (masks ? (size_t)keys * kBucketWaves * 8 : 0);
+    }
+};
+
 template <bool GATE>
 __global__ __launch_bounds__(kBucketThreads) void bucket_kernel(const int32_t *__restrict__ r,
                                                                 int32_t *__restrict__ offsets,
                                                                 int32_t *__restrict__ perm, int N,
                                                                 int C, int32_t *err_flag,
                                                                 GateArgs gate) {
-    // cnt[b * 16 + w]: tokens of target b (b == C: out of range) in wavefront w's range
-    extern __shared__ int32_t lds[];
-    volatile int32_t *cnt = lds;
-    int32_t *cnt_rw = lds;  // the same counters, for the LDS atomics of the two sweeps
+    extern __shared__ __attribute__((aligned(16))) unsigned char lds_raw[];
+    const BucketLds L(C);
+    int32_t *cnt = (int32_t *)(lds_raw + L.cnt_off());    // cnt[b * 16 + w]: own part, by wavefront
+    int32_t *pre = (int32_t *)(lds_raw + L.pre_off());    // tokens of target b before the own part
+    int32_t *post = (int32_t *)(lds_raw + L.post_off());  // ... after it
+    int32_t *tot = (int32_t *)(lds_raw + L.tot_off());    // per-target totals, then their prefix
+    uint64_t *mask = (uint64_t *)(lds_raw + L.mask_off());  // mask[w * keys + b]: lanes of the step with target b
     __shared__ int32_t wave_tot[kBucketWaves];
 
     const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
-    const int E = (C + 1) * kBucketWaves;
+    const int keys = C + 1;
     const int nbits = 32 - __clz(C);  // keys are 0..C
-    for (int i = tid; i < E; i += kBucketThreads) cnt[i] = 0;
+    {
+        int32_t *z = (int32_t *)lds_raw;
+        const int words = (int)(L.bytes() / 4);
+        for (int i = tid; i < words; i += kBucketThreads) z[i] = 0;
+    }
     __syncthreads();
 
-    // contiguous token range of this wavefront, a multiple of 64 long
-    const int per = (int)((((int64_t)N + kBucketWaves * 64 - 1) / (kBucketWaves * 64)) * 64);
-    const int64_t start64 = (int64_t)w * per;
+    // contiguous token range of this wavefront, a multiple of 64 long; the workgroup's own part
+    // is the 16 ranges of its wavefronts
+    const int G = gridDim.x, g = blockIdx.x;
+    const int per = (int)((((int64_t)N + (int64_t)G * kBucketWaves * 64 - 1) / ((int64_t)G * kBucketWaves * 64)) * 64);
+    const int64_t own64 = (int64_t)g * kBucketWaves * per;
+    const int own_lo = (int)(own64 < N ? own64 : N);
+    const int own_hi = (int)(own64 + (int64_t)kBucketWaves * per < N ? own64 + (int64_t)kBucketWaves * per : N);
+    const int64_t start64 = own64 + (int64_t)w * per;
     const int start = (int)(start64 < N ? start64 : N);
     const int end = (int)(start64 + per < N ? start64 + per : N);
     const uint64_t lower = (lane == 0) ? 0ull : (~0ull >> (64 - lane));
@@ -116,7 +160,7 @@ __global__ __launch_bounds__(kBucketThreads) void bucket_kernel(const int32_t *_
         b_top = gate.br.b[gate.M];
     }
 
-    // ---- sweep 1: histogram per (target, wavefront) ----
+    // ---- sweep 1a: histogram of the own part per (target, wavefront) ----
     for (int base = start; base < end; base += 64 * kUnroll) {
 #pragma unroll
         for (int u = 0; u < kUnroll; ++u) {
@@ -133,26 +177,52 @@ __global__ __launch_bounds__(kBucketThreads) void bucket_kernel(const int32_t *_
                 // few targets: group the lanes (three ballots), one add per group by its lowest lane
                 const uint64_t same = match_lanes(key[u], valid, nbits);
                 if (valid && (same & lower) == 0)
-                    __hip_atomic_fetch_add(&cnt_rw[key[u] * kBucketWaves + w], __popcll(same),
+                    __hip_atomic_fetch_add(&cnt[key[u] * kBucketWaves + w], __popcll(same),
                                            __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
             } else if (valid) {
-                // one LDS add per lane, without return value: nothing to wait for, and integer
-                // counts do not depend on the order in which the lanes are served (the sweep is
-                // bound by vector instructions on the one compute unit it runs on; grouping the
-                // lanes first costs more of them than the serialised adds to equal addresses)
-                __hip_atomic_fetch_add(&cnt_rw[key[u] * kBucketWaves + w], 1, __ATOMIC_RELAXED,
+                // one LDS add per lane, without return value: nothing to wait for, and a count
+                // does not depend on the order in which the lanes are served
+                __hip_atomic_fetch_add(&cnt[key[u] * kBucketWaves + w], 1, __ATOMIC_RELAXED,
                                        __HIP_MEMORY_SCOPE_WORKGROUP);
+            }
+        }
+    }
+    // ---- sweep 1b: the tokens of the other workgroups' parts, before / after the own part ----
+    if (G > 1) {
+        const int n_other = N - (own_hi - own_lo);
+        for (int base = 0; base < n_other; base += kBucketThreads * kUnroll) {
+            int32_t k2[kUnroll];
+#pragma unroll
+            for (int u = 0; u < kUnroll; ++u) {
+                int i = base + u * kBucketThreads + tid;
+                i = i < n_other ? i : n_other - 1;
+                const int t = i < own_lo ? i : i + (own_hi - own_lo);
+                const int32_t c = target_of<GATE>(r, gate, my_b, b_top, t);
+                k2[u] = (c >= 0 && c < C) ? c : C;
+            }
+#pragma unroll
+            for (int u = 0; u < kUnroll; ++u) {
+                const int i = base + u * kBucketThreads + tid;
+                if (i < n_other)
+                    __hip_atomic_fetch_add(i < own_lo ? &pre[k2[u]] : &post[k2[u]], 1, __ATOMIC_RELAXED,
+                                           __HIP_MEMORY_SCOPE_WORKGROUP);
             }
         }
     }
     __syncthreads();
 
-    // ---- exclusive prefix sum over cnt[0 .. E) ----
-    const int chunk = (E + kBucketThreads - 1) / kBucketThreads;
-    const int lo = tid * chunk < E ? tid * chunk : E;
-    const int hi = lo + chunk < E ? lo + chunk : E;
+    // ---- totals per target, their exclusive prefix (= offsets), first positions ----
+    const int chunk = (keys + kBucketThreads - 1) / kBucketThreads;
+    const int lo = tid * chunk < keys ? tid * chunk : keys;
+    const int hi = lo + chunk < keys ? lo + chunk : keys;
     int32_t mine = 0;
-    for (int i = lo; i < hi; ++i) mine += cnt[i];
+    for (int b = lo; b < hi; ++b) {
+        int32_t sum = pre[b] + post[b];
+#pragma unroll
+        for (int j = 0; j < kBucketWaves; ++j) sum += cnt[b * kBucketWaves + j];
+        tot[b] = sum;
+        mine += sum;
+    }
     int32_t incl = mine;
 #pragma unroll
     for (int d = 1; d < 64; d <<= 1) {
@@ -163,14 +233,21 @@ __global__ __launch_bounds__(kBucketThreads) void bucket_kernel(const int32_t *_
     __syncthreads();
     int32_t before = incl - mine;
     for (int j = 0; j < w; ++j) before += wave_tot[j];
-    for (int i = lo; i < hi; ++i) {
-        const int32_t c = cnt[i];
-        cnt[i] = before;
-        before += c;
+    for (int b = lo; b < hi; ++b) {
+        const int32_t total = tot[b];
+        if (g == 0) offsets[b] = before;
+        // cnt[b][j] becomes the first position of wavefront j's tokens of target b
+        int32_t run = before + pre[b];
+#pragma unroll
+        for (int j = 0; j < kBucketWaves; ++j) {
+            const int32_t c = cnt[b * kBucketWaves + j];
+            cnt[b * kBucketWaves + j] = run;
+            run += c;
+        }
+        // offsets[C] counts the routed tokens: fewer than N means some target was out of range
+        if (b == C && g == 0 && err_flag != nullptr && before != N) *err_flag = 1;
+        before += total;
     }
-    __syncthreads();
-    for (int c = tid; c <= C; c += kBucketThreads) offsets[c] = cnt[c * kBucketWaves];
-    if (tid == 0 && err_flag != nullptr && cnt[C * kBucketWaves] != N) *err_flag = 1;
     __syncthreads();
 
     // ---- sweep 2: scatter token indices to their positions ----
@@ -183,36 +260,63 @@ __global__ __launch_bounds__(kBucketThreads) void bucket_kernel(const int32_t *_
                 key[u] = (c >= 0 && c < C) ? c : C;
             }
         }
+        if (L.masks) {
+            // every step: OR the own bit into the (wavefront, target) word, read the word, clear
+            // the bit again; read the running base, advance it by one per lane.  All of one
+            // wavefront, executed in issue order, so the steps can be issued back to back.
+            uint64_t m[kUnroll];
+            int32_t first[kUnroll];
+            uint64_t *my_mask = mask + w * keys;
+            const uint64_t bit = 1ull << lane;
+#pragma unroll
+            for (int u = 0; u < kUnroll; ++u) {
+                m[u] = 0;
+                first[u] = 0;
+                if (base + u * 64 + lane < end) {
+                    uint64_t *mp = my_mask + key[u];
+                    int32_t *cp = &cnt[key[u] * kBucketWaves + w];
+                    __hip_atomic_fetch_or(mp, bit, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+                    m[u] = __hip_atomic_load(mp, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+                    __hip_atomic_fetch_and(mp, ~bit, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+                    first[u] = __hip_atomic_load(cp, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+                    __hip_atomic_fetch_add(cp, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+                }
+            }
+#pragma unroll
+            for (int u = 0; u < kUnroll; ++u) {
+                const int t = base + u * 64 + lane;
+                if (t < end) perm[first[u] + __popcll(m[u] & lower)] = t;
+            }
+            continue;
+        }
 #pragma unroll
         for (int u = 0; u < kUnroll; ++u) {
             if (base + u * 64 >= end) break;  // wave-uniform
             const int t = base + u * 64 + lane;
             const bool valid = t < end;
-            const int slot = key[u] * kBucketWaves + w;
-            if (nbits <= 2) {
-                // few targets: the group's lowest lane takes the group's positions with one
-                // returning LDS add and hands the base to the other lanes of the group
-                const uint64_t same = match_lanes(key[u], valid, nbits);
-                int32_t got = 0;
-                if (valid && (same & lower) == 0)
-                    got = __hip_atomic_fetch_add(&cnt_rw[slot], __popcll(same), __ATOMIC_RELAXED,
-                                                 __HIP_MEMORY_SCOPE_WORKGROUP);
-                const int first = same ? __ffsll((long long)same) - 1 : 0;
-                const int32_t base_pos = __shfl(got, first, 64);
-                if (valid) perm[base_pos + __popcll(same & lower)] = t;
-            } else if (valid) {
-                // one returning LDS add per lane.  Lanes of one instruction that add to the same
-                // address are served in ascending lane order on this hardware (measured: no
-                // exception in 6e7 wave-wide adds with random targets and random inactive lanes),
-                // and successive instructions execute in issue order, so the positions come out
-                // in token order; the bit-exact comparison with a stable sort in the parity tests
-                // checks exactly this on every run.
-                const int32_t pos = __hip_atomic_fetch_add(&cnt_rw[slot], 1, __ATOMIC_RELAXED,
-                                                           __HIP_MEMORY_SCOPE_WORKGROUP);
-                perm[pos] = t;
-            }
+            // lanes with the same target from ballots; the group's lowest lane takes the group's
+            // positions with one returning LDS add and hands the base to the other lanes
+            const uint64_t same = match_lanes(key[u], valid, nbits);
+            int32_t got = 0;
+            if (valid && (same & lower) == 0)
+                got = __hip_atomic_fetch_add(&cnt[key[u] * kBucketWaves + w], __popcll(same),
+                                             __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+            const int first = same ? __ffsll((long long)same) - 1 : 0;
+            const int32_t base_pos = __shfl(got, first, 64);
+            if (valid) perm[base_pos + __popcll(same & lower)] = t;
         }
     }
+}
+
+// more than 64 KB of dynamic LDS has to be asked for, once per device (see common.h)
+LdsRegistrar g_bucket_lds{(const void *)bucket_kernel<false>, BucketLds(MOLORA_MAX_TARGETS).bytes()};
+LdsRegistrar g_gate_bucket_lds{(const void *)bucket_kernel<true>, BucketLds(MOLORA_MAX_TARGETS).bytes()};
+
+// workgroups: every one recounts all tokens and scatters its own part, so more of them pay
+// only when the scatter dominates
+inline unsigned bucket_workgroups(int64_t N) {
+    const int64_t g = (N + 2047) / 2048;
+    return (unsigned)(g < 1 ? 1 : (g > 8 ? 8 : g));
 }
 
 }  // namespace
@@ -230,9 +334,8 @@ hipError_t launch_route_vocab(const int32_t *v, const int32_t *breaks_host, int 
 
 hipError_t launch_bucket(const int32_t *r, int32_t *offsets, int32_t *perm, int64_t N, int C,
                          int32_t *err_flag, hipStream_t s) {
-    const size_t lds_bytes = (size_t)(C + 1) * kBucketWaves * sizeof(int32_t);
-    hipLaunchKernelGGL(bucket_kernel<false>, dim3(1), dim3(kBucketThreads), lds_bytes, s, r, offsets,
-                       perm, (int)N, C, err_flag, GateArgs{});
+    hipLaunchKernelGGL(bucket_kernel<false>, dim3(bucket_workgroups(N)), dim3(kBucketThreads),
+                       BucketLds(C).bytes(), s, r, offsets, perm, (int)N, C, err_flag, GateArgs{});
     return hipGetLastError();
 }
 
@@ -248,9 +351,8 @@ hipError_t launch_gate_bucket(const int32_t *v, const int32_t *adapter, const in
     g.n_adapters = n_adapters;
     for (int j = 0; j <= M; ++j) g.br.b[j] = breaks_host[j];
     for (int j = M + 1; j < 65; ++j) g.br.b[j] = 0;
-    const size_t lds_bytes = (size_t)(C + 1) * kBucketWaves * sizeof(int32_t);
-    hipLaunchKernelGGL(bucket_kernel<true>, dim3(1), dim3(kBucketThreads), lds_bytes, s, nullptr,
-                       offsets, perm, (int)N, C, err_flag, g);
+    hipLaunchKernelGGL(bucket_kernel<true>, dim3(bucket_workgroups(N)), dim3(kBucketThreads),
+                       BucketLds(C).bytes(), s, nullptr, offsets, perm, (int)N, C, err_flag, g);
     return hipGetLastError();
 }
 
