@@ -61,6 +61,7 @@ enum {
 #define MOLORA_MAX_BREAKS 64    /* M of molora_route_vocab             */
 #define MOLORA_MAX_HIDDEN 256   /* H of molora_route_mlp, a multiple of 8 */
 #define MOLORA_MAX_TOPK 4       /* k of molora_route_mlp / molora_apply_mix */
+#define MOLORA_STATIC_WORKSPACE_BYTES (8u << 20) /* scratch of molora_apply_static, per GPU */
 
 /*
  * Learned routing with one selected adapter per token (Sec. "Router Architecture"
@@ -138,6 +139,25 @@ molora_status molora_apply(const void *x, const void *W, const void *A, const vo
                            const int32_t *r, float *h,
                            int64_t N, int32_t d_in, int32_t d_out, int32_t C, int32_t rank,
                            void *workspace, size_t workspace_bytes, void *stream);
+
+/*
+ * molora_apply for callers that cannot allocate device memory and have no workspace to hand
+ * in: code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.
+ * Same arguments, same kernels and bit-identical h; the workspace is a fixed array of
+ * MOLORA_STATIC_WORKSPACE_BYTES (8 MiB) inside the library, one copy per GPU, held until the
+ * process ends.  Sizes whose molora_apply_workspace_bytes exceeds it are refused with
+ * MOLORA_EWORKSPACE before anything is enqueued (8 MiB covers N = 16384 tokens at rank 32, or
+ * 8192 at rank 64, ...).  The call allocates nothing (no hipMalloc / hipFree, no allocating
+ * library routine).  All calls on one GPU share that GPU's array: calls that overlap in time
+ * on one GPU (two streams, two threads) race on it and must be serialised by the caller;
+ * successive calls on one stream are safe.  The array keeps the last call's contents; nothing
+ * in it needs to start at zero.  molora_static_workspace_bytes returns the limit.
+ */
+size_t molora_static_workspace_bytes(void);
+molora_status molora_apply_static(const void *x, const void *W, const void *A, const void *B,
+                                  const int32_t *r, float *h,
+                                  int64_t N, int32_t d_in, int32_t d_out, int32_t C, int32_t rank,
+                                  void *stream);
 
 /*
  * Same as molora_apply for a caller that already holds molora_bucket's output for r

@@ -15,7 +15,7 @@ LIB_PATH = os.path.join(_HERE, "libmolora.so")
 MOLORA_OK = 0
 EXPORTS = ["molora_route", "molora_route_vocab", "molora_bucket", "molora_apply_workspace_bytes",
            "molora_apply", "molora_apply_bucketed", "molora_shrink", "molora_base_expand",
-           "molora_base_expand_fixed", "molora_init",
+           "molora_base_expand_fixed", "molora_init", "molora_apply_static", "molora_static_workspace_bytes",
            "molora_route_mlp_workspace_bytes", "molora_route_mlp", "molora_route_compose",
            "molora_gate_dispatch",
            "molora_apply_mix_workspace_bytes", "molora_apply_mix",
@@ -60,6 +60,10 @@ def load():
     lib.molora_base_expand.restype = ctypes.c_int
     lib.molora_base_expand_fixed.argtypes = [vp, vp, vp, vp, vp, vp, vp, i64, i32, i32, i32, i32, i32, vp]
     lib.molora_base_expand_fixed.restype = ctypes.c_int
+    lib.molora_apply_static.argtypes = [vp, vp, vp, vp, vp, vp, i64, i32, i32, i32, i32, vp]
+    lib.molora_apply_static.restype = ctypes.c_int
+    lib.molora_static_workspace_bytes.argtypes = []
+    lib.molora_static_workspace_bytes.restype = sz
     lib.molora_init.argtypes = []
     lib.molora_init.restype = ctypes.c_int
     lib.molora_route_mlp_workspace_bytes.argtypes = [i64, i32]
@@ -193,6 +197,19 @@ def molora_apply(x, W, A, B, r, h=None, workspace=None, stream=None):
                              N, d_in, d_out, C, rank, _dev(workspace, torch.uint8, "workspace"),
                              workspace.numel(), _stream(stream))
     _check(st, "molora_apply")
+    return h
+
+
+def molora_apply_static(x, W, A, B, r, h, stream=None):
+    """molora_apply on the library's own fixed scratch array: no workspace argument and no
+    allocation anywhere in the call, so h must be supplied."""
+    N, d_in, d_out, C, rank = _shapes(x, W, A, B)
+    bf = torch.bfloat16
+    st = load().molora_apply_static(_dev(x, bf, "x"), _dev(W, bf, "W"), _dev(A, bf, "A"),
+                                    _dev(B, bf, "B"), _dev(r, torch.int32, "r"),
+                                    _dev(h, torch.float32, "h"), N, d_in, d_out, C, rank,
+                                    _stream(stream))
+    _check(st, "molora_apply_static")
     return h
 
 

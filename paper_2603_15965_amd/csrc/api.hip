@@ -5,12 +5,19 @@
 
 #include <mutex>
 
+// Scratch of molora_apply_static: one copy per GPU the library runs on, held until the process
+// ends.  In host code this name is only a handle for hipGetSymbolAddress, never an address to
+// pass on: the device address is resolved once per device in ensure_device_ready() and kept
+// in g_scratch_ptr.
+static __device__ __align__(256) unsigned char scratch[MOLORA_STATIC_WORKSPACE_BYTES];
+
 namespace molora {
 
 namespace {
 constexpr int kMaxDevices = 64;
 std::mutex g_init_mutex;
 bool g_device_ready[kMaxDevices];
+void *g_scratch_ptr[kMaxDevices];  // device address of `scratch` on each device
 KernelLdsNeed *&lds_list() {
     static KernelLdsNeed *head = nullptr;
     return head;
@@ -34,9 +41,24 @@ hipError_t ensure_device_ready() {
         e = hipFuncSetAttribute(n->fn, hipFuncAttributeMaxDynamicSharedMemorySize, n->bytes);
         if (e != hipSuccess) return e;
     }
+    void *ptr = nullptr;
+    e = hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch));
+    if (e != hipSuccess) return e;
+    if (ptr == nullptr) return hipErrorInvalidSymbol;
+    g_scratch_ptr[dev] = ptr;
     g_device_ready[dev] = true;
     return hipSuccess;
 }
+
+namespace {
+// the current device's copy of `scratch` (nullptr before ensure_device_ready() succeeded there)
+void *static_scratch_of_current_device() {
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return nullptr;
+    std::lock_guard<std::mutex> lock(g_init_mutex);
+    return g_device_ready[dev] ? g_scratch_ptr[dev] : nullptr;
+}
+}  // namespace
 
 }  // namespace molora
 
@@ -181,6 +203,24 @@ molora_status molora_apply(const void *x, const void *W, const void *A, const vo
     if (N > 0 && !r) return MOLORA_EINVAL;
     return apply_common(x, W, A, B, r, nullptr, nullptr, h, N, d_in, d_out, C, rank, workspace,
                         workspace_bytes, stream);
+}
+
+size_t molora_static_workspace_bytes(void) { return MOLORA_STATIC_WORKSPACE_BYTES; }
+
+molora_status molora_apply_static(const void *x, const void *W, const void *A, const void *B,
+                                  const int32_t *r, float *h, int64_t N, int32_t d_in,
+                                  int32_t d_out, int32_t C, int32_t rank, void *stream) {
+    if (N > 0 && !r) return MOLORA_EINVAL;
+    const size_t need = molora_apply_workspace_bytes(N, d_in, d_out, C, rank);
+    if (need == 0) return MOLORA_EINVAL;
+    if (need > MOLORA_STATIC_WORKSPACE_BYTES) return MOLORA_EWORKSPACE;
+    if (molora::ensure_device_ready() != hipSuccess) return MOLORA_EHIP;
+    void *ws = molora::static_scratch_of_current_device();
+    if (ws == nullptr) return MOLORA_EHIP;
+    // nothing in the workspace has to start at zero: every word the kernels read (offsets,
+    // perm, t) is written earlier in the same call
+    return apply_common(x, W, A, B, r, nullptr, nullptr, h, N, d_in, d_out, C, rank, ws,
+                        MOLORA_STATIC_WORKSPACE_BYTES, stream);
 }
 
 molora_status molora_apply_bucketed(const void *x, const void *W, const void *A, const void *B,
