@@ -15,6 +15,11 @@ latency distribution (median, P99, coefficient of variation) and the CPU oracle 
 host cores.  Inputs rotate through several independent copies so that consecutive steps do
 not find their operands in the 256 MB Infinity Cache.
 
+The default run (configuration 1 as `value`) also times the other configurations briefly
+(gate_up17, decode_up8 and the seven-projection layer of configuration 4) and reports them
+in a `configs` object of the same JSON line: step time, tokens/s, roofline fraction of the
+dominant kernel and of the whole step.
+
 --workload prefill8_layer runs all seven projections of configuration 4 in one step;
 --graph replays the step from a recorded launch sequence (one per input copy) instead of
 launching the kernels one by one.
@@ -55,6 +60,8 @@ def parse():
                          "warm-up and the timed region only)")
     ap.add_argument("--no-kernel-events", action="store_true",
                     help="leave the per-kernel HIP events out of the timed region")
+    ap.add_argument("--no-other-configs", action="store_true",
+                    help="leave out the short runs of the other configurations (the `configs` object)")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run one 256 MiB device copy (reference for rocprofv3 --pmc FETCH_SIZE/WRITE_SIZE)")
     return ap.parse_args()
@@ -116,29 +123,20 @@ def cpu_baseline(wl_mod, shape, budget_flops=1.5e12):
                       f"median of {reps} run(s)"}
 
 
-def main():
-    args = parse()
-    if args.gpus != 1:
-        print("bench.py: this build runs on one GPU only (the path needs no exchange between "
-              "GPUs: token ranges are independent); use --gpus 1", file=sys.stderr)
-        sys.exit(2)
-
+def run_workload(args, workload, steps, warmup, full):
+    """One workload: resident inputs, warm-up, the timed region, and (full=True) the latency,
+    two-stream and per-kernel passes plus the CPU baseline.  Returns the JSON object."""
     import numpy as np
     import torch
     from paper_2603_15965_amd import binding as mb
     from paper_2603_15965_amd import workloads as wl_mod
 
-    if not torch.cuda.is_available():
-        print("bench.py: no GPU visible", file=sys.stderr)
-        sys.exit(1)
-    torch.cuda.set_device(0)
-    mb.load()
     all_shapes = wl_mod.shapes()
-    if args.workload in ("prefill8_layer", "prefill8_layer_deg"):
-        suffix = "_deg" if args.workload.endswith("_deg") else ""
+    if workload in ("prefill8_layer", "prefill8_layer_deg"):
+        suffix = "_deg" if workload.endswith("_deg") else ""
         shapes = [all_shapes[f"prefill8_{p}{suffix}"] for p in LAYER]
     else:
-        shapes = [all_shapes[args.workload]]
+        shapes = [all_shapes[workload]]
     N = shapes[0].N
 
     # ---- resident inputs: `sets` independent copies (different seeds for x), rotated ----
@@ -197,7 +195,7 @@ def main():
             if ev is not None:
                 ev[2 * j + 1].record()
 
-    if args.copy_calibration:
+    if args.copy_calibration and full:
         a = torch.empty(256 << 20, dtype=torch.uint8, device="cuda")
         b = torch.empty_like(a)
         b.copy_(a)
@@ -208,7 +206,7 @@ def main():
     graphs = None
     if args.graph:
         run_stream = torch.cuda.Stream()
-        step(S[0], stream=run_stream)  # first launches (module load, attributes) outside capture
+        step(S[0], stream=run_stream)  # module load and first-touch costs outside the recorded region
         run_stream.synchronize()
         graphs = []
         for s in range(sets):
@@ -234,7 +232,7 @@ def main():
         else:
             step(S[i % sets], ev)
 
-    for i in range(args.warmup):
+    for i in range(warmup):
         run_step(i)
     torch.cuda.synchronize()
 
@@ -244,30 +242,30 @@ def main():
     # after the timed region.
     use_ev = not args.no_kernel_events and graphs is None and not extra
     P = len(shapes)
-    EV_EVERY = 8
-    ev_steps = [i for i in range(args.steps) if i % EV_EVERY == EV_EVERY - 1] or [args.steps - 1]
+    EV_EVERY = 4 if steps >= 16 else 1
+    ev_steps = [i for i in range(steps) if i % EV_EVERY == EV_EVERY - 1] or [steps - 1]
     evs = {i: [torch.cuda.Event(enable_timing=True) for _ in range(2 * P)] for i in ev_steps} if use_ev else {}
     torch.cuda.synchronize()
     t0 = time.perf_counter()
-    for i in range(args.steps):
+    for i in range(steps):
         run_step(i, evs.get(i))
     torch.cuda.synchronize()
     elapsed = time.perf_counter() - t0
-    ms_per_step = 1e3 * elapsed / args.steps
+    ms_per_step = 1e3 * elapsed / steps
     gemm_us = None
     if use_ev:
         gemm_us = sum(e[2 * j].elapsed_time(e[2 * j + 1]) for e in evs.values() for j in range(P)) / len(evs) * 1e3
 
-    skip_passes = bool(extra) or args.timed_only
+    skip_passes = bool(extra) or args.timed_only or not full
     latency = None
     if not skip_passes:
-        ticks = [torch.cuda.Event(enable_timing=True) for _ in range(args.steps + 1)]
-        for i in range(args.steps):
+        ticks = [torch.cuda.Event(enable_timing=True) for _ in range(steps + 1)]
+        for i in range(steps):
             ticks[i].record(run_stream)
             run_step(i)
-        ticks[args.steps].record(run_stream)
+        ticks[steps].record(run_stream)
         torch.cuda.synchronize()
-        lat = np.array([ticks[i].elapsed_time(ticks[i + 1]) * 1e3 for i in range(args.steps)])
+        lat = np.array([ticks[i].elapsed_time(ticks[i + 1]) * 1e3 for i in range(steps)])
         latency = {"p50_us": float(np.percentile(lat, 50)), "p99_us": float(np.percentile(lat, 99)),
                "mean_us": float(lat.mean()), "cv": float(lat.std() / lat.mean()),
                "how": "HIP events between consecutive steps on the launch stream, in a second pass "
@@ -277,16 +275,16 @@ def main():
     pipelined = None
     if graphs is None and not skip_passes and sets % 2 == 0:
         two = [torch.cuda.Stream(), torch.cuda.Stream()]
-        for i in range(min(args.warmup, 4)):
+        for i in range(min(warmup, 4)):
             step(S[i % sets], None, stream=two[i % 2])
         torch.cuda.synchronize()
         t1 = time.perf_counter()
-        for i in range(args.steps):
+        for i in range(steps):
             step(S[i % sets], None, stream=two[i % 2])
         torch.cuda.synchronize()
         el2 = time.perf_counter() - t1
-        pipelined = {"streams": 2, "value": N * args.steps / el2, "unit": "tokens/s",
-                     "ms_per_step": 1e3 * el2 / args.steps,
+        pipelined = {"streams": 2, "value": N * steps / el2, "unit": "tokens/s",
+                     "ms_per_step": 1e3 * el2 / steps,
                      "what": "the same steps launched round-robin on two streams, so that the "
                              "latency-bound dispatch and shrink of one batch overlap the GEMM of "
                              "the previous one (every input copy belongs to one stream)"}
@@ -306,7 +304,7 @@ def main():
         return total
 
     breakdown = {}
-    if not (args.timed_only and gemm_us is not None):
+    if full and not (args.timed_only and gemm_us is not None):
         if "G" in S[0][0] or "v" in S[0][0]:
             breakdown["route_us"] = timed_calls(lambda d: route(d))
         rsrc = (lambda d: d["r"]) if ("G" in S[0][0] or "v" in S[0][0]) else (lambda d: d["r_given"])
@@ -334,37 +332,56 @@ def main():
         ach = work["gemm_bytes"] / t_gemm / 1e9
         roof = {"bound": "hbm", "achieved": ach, "peak": PEAK_HBM_GBS, "unit": "GB/s",
                 "frac": ach / PEAK_HBM_GBS}
-    traffic = None
-    try:  # measured with rocprofv3 --pmc in a separate run (see profiles/)
+    # HBM-side bytes per launch are counter readings of separate rocprofv3 --pmc runs of this
+    # command, kept under profiles/; they are quoted here (never measured by this run) and only
+    # for the library version they were taken on
+    traffic, traffic_from = None, None
+    try:
         with open(os.path.join(ROOT, "profiles", "traffic.json")) as f:
-            tj = json.load(f).get(args.workload)
-        if tj:
+            tj_all = json.load(f)
+        tj = tj_all.get(workload)
+        if tj and tj_all.get("_library_version") == mb.version():
             traffic = tj["read_bytes"] + tj["write_bytes"]
+            traffic_from = (f"profiles/traffic.json: rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE of {tj['kernel']} "
+                            f"on {tj_all['_library_version']} (a constant of that profile, not of this run)")
     except (OSError, ValueError, KeyError):
-        traffic = None
+        traffic, traffic_from = None, None
     kname = ("small_batch_kernel" if N <= 64 else "fused_gemm_kernel") + \
         " (base x.W + grouped expand, unpermuting fp32 store)"
     if P > 1:
         kname += f", {P} launches per step summed"
-    roof.update({"kernel": kname, "kernel_us": t_gemm * 1e6, "traffic": traffic,
+    roof.update({"kernel": kname, "kernel_us": t_gemm * 1e6, "traffic": traffic, "traffic_from": traffic_from,
+                 "kernel_event_samples": len(evs) if gemm_us is not None else 0,
                  "kernel_us_from": f"HIP events around the launch on every {EV_EVERY}th step of the timed region"
                  if gemm_us is not None
                  else "HIP events around the call, outside the timed region",
                  "algorithmic_flops": work["gemm_flops"], "algorithmic_bytes": work["gemm_bytes"]})
+
+    # the whole step against the roofline that binds the whole step's algorithmic work
+    step_s = elapsed / steps
+    if work["layer_flops"] / work["layer_bytes"] >= PEAK_BF16_TFLOPS * 1e12 / (PEAK_HBM_GBS * 1e9):
+        step_roof = {"bound": "mfma", "achieved": work["layer_flops"] / step_s / 1e12, "peak": PEAK_BF16_TFLOPS,
+                     "unit": "TFLOP/s"}
+    else:
+        step_roof = {"bound": "hbm", "achieved": work["layer_bytes"] / step_s / 1e9, "peak": PEAK_HBM_GBS,
+                     "unit": "GB/s"}
+    step_roof["frac"] = step_roof["achieved"] / step_roof["peak"]
+    step_roof["what"] = ("algorithmic flops (bytes) of route + shrink + base + expand of one step over the "
+                         "wall time of a step, launch gaps included")
 
     if P == 1:
         sh = shapes[0]
         wname = (f"{sh.name}: N={sh.N} tokens, {sh.d_in}->{sh.d_out}, C={sh.C} adapters of rank {sh.rank}, "
                  f"route={sh.route}")
     else:
-        wname = (f"{args.workload}: N={N} tokens through the seven projections of a Qwen3-8B-shaped layer "
+        wname = (f"{workload}: N={N} tokens through the seven projections of a Qwen3-8B-shaped layer "
                  f"(q, o 4096->4096; k, v 4096->1024; gate, up 4096->12288; down 12288->4096), "
                  f"C={shapes[0].C} adapters of rank {shapes[0].rank}, route={shapes[0].route} per projection")
     out = {
         "metric": "routed-LoRA layer tokens/s",
-        "value": N * args.steps / elapsed,
+        "value": N * steps / elapsed,
         "unit": "tokens/s",
-        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "n_gpus": 1, "steps": steps, "warmup": warmup,
         "ms_per_step": ms_per_step,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16", "data": "synthetic",
@@ -373,15 +390,16 @@ def main():
                    else "kernel by kernel" + (f", steps round-robin on {args.streams} streams" if extra else ""),
                    "kernel_events_in_timed_region": (f"every {EV_EVERY}th step" if use_ev else False)},
         "roofline": roof,
+        "step_roofline": step_roof,
         "latency": latency,
         "pipelined": pipelined,
-        "layer": {"tflops": work["layer_flops"] / (elapsed / args.steps) / 1e12,
-                  "gbs": work["layer_bytes"] / (elapsed / args.steps) / 1e9,
+        "layer": {"tflops": work["layer_flops"] / (elapsed / steps) / 1e12,
+                  "gbs": work["layer_bytes"] / (elapsed / steps) / 1e9,
                   "routed_tokens": n_routed_all if P > 1 else n_routed_all[0],
                   "touched_adapters": touched_all if P > 1 else touched_all[0]},
         "breakdown_us": breakdown,
     }
-    if not args.no_cpu_baseline:
+    if full and not args.no_cpu_baseline:
         if P == 1:
             out["cpu_baseline"] = cpu_baseline(wl_mod, shapes[0])
         else:  # the same bounded sample of tokens through every projection
@@ -392,6 +410,43 @@ def main():
                                    "kind": "oracle", "seconds": secs,
                                    "sample": f"{n_s} tokens per projection (rates of the per-projection "
                                              f"samples combined), route+bucket+apply, seven projections"}
+    del S
+    torch.cuda.empty_cache()
+    return out
+
+
+
+OTHER_CONFIGS = [  # (workload, steps, warm-up) of the short runs reported under `configs`
+    ("gate_up17", 50, 5), ("decode_up8", 100, 10), ("prefill8_layer", 10, 2)]
+
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (the path needs no exchange between "
+              "GPUs: token ranges are independent); use --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    from paper_2603_15965_amd import binding as mb
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(1)
+    torch.cuda.set_device(0)
+    mb.load()
+    out = run_workload(args, args.workload, args.steps, args.warmup, full=True)
+    if args.workload == "vocab_q17" and not (args.timed_only or args.no_other_configs or args.graph
+                                             or args.streams > 1):
+        others = {}
+        for name, st, wu in OTHER_CONFIGS:
+            o = run_workload(args, name, min(st, args.steps), min(wu, args.warmup), full=False)
+            others[name] = {"workload": o["config"]["workload"], "steps": o["steps"], "warmup": o["warmup"],
+                            "ms_per_step": o["ms_per_step"], "tokens_per_s": o["value"],
+                            "kernel": {k: o["roofline"][k] for k in ("kernel", "bound", "achieved", "peak",
+                                                                      "unit", "frac", "kernel_us")},
+                            "step": o["step_roofline"]}
+        out["configs"] = others
     print(json.dumps(out))
 
 
