@@ -114,8 +114,9 @@ molora_status molora_bucket(const int32_t *r, int32_t *offsets, int32_t *perm,
 /*
  * Bytes of DEVICE workspace molora_apply / molora_apply_bucketed need for these sizes
  * (0 if the sizes are invalid).  The workspace holds the bucketing (molora_apply only),
- * the low-rank intermediate t = x A_r in sorted order and small tile tables; its
- * contents are scratch and need no initialisation.
+ * the low-rank intermediate t = x A_r in sorted order and, for small batches, the partial
+ * sums of a shrink whose K range is split over workgroups; its contents are scratch and
+ * need no initialisation.
  */
 size_t molora_apply_workspace_bytes(int64_t N, int32_t d_in, int32_t d_out,
                                     int32_t C, int32_t rank);
@@ -181,10 +182,18 @@ molora_status molora_apply_bucketed(const void *x, const void *W, const void *A,
  * molora_base_expand:  h[perm[p]][:] = x[perm[p]] W + t_p B_c  (rows without adapter:
  * x W only), every row of h written once.
  * offsets and perm must be molora_bucket's output for this N and C.
+ * molora_shrink's workspace is optional DEVICE scratch (256-byte aligned, contents need no
+ * initialisation) of molora_shrink_workspace_bytes(...) bytes, which is 0 for most sizes: a
+ * batch of a few dozen tokens has too few (adapter, row tile) pairs to occupy the chip, so
+ * the K range of t = x A_c is then cut into slices over more workgroups, whose fp32 partial
+ * sums pass through the scratch and are added in a fixed order by a second kernel.  With
+ * workspace NULL (or smaller than that) K is not split: same t up to the order of the fp32
+ * additions, more slowly.
  */
+size_t molora_shrink_workspace_bytes(int64_t N, int32_t d_in, int32_t C, int32_t rank);
 molora_status molora_shrink(const void *x, const void *A, const int32_t *offsets,
                             const int32_t *perm, void *t, int64_t N, int32_t d_in, int32_t C,
-                            int32_t rank, void *stream);
+                            int32_t rank, void *workspace, size_t workspace_bytes, void *stream);
 molora_status molora_base_expand(const void *x, const void *W, const void *B, const void *t,
                                  const int32_t *offsets, const int32_t *perm, float *h,
                                  int64_t N, int32_t d_in, int32_t d_out, int32_t C, int32_t rank,

@@ -14,7 +14,8 @@ LIB_PATH = os.path.join(_HERE, "libmolora.so")
 
 MOLORA_OK = 0
 EXPORTS = ["molora_route", "molora_route_vocab", "molora_bucket", "molora_apply_workspace_bytes",
-           "molora_apply", "molora_apply_bucketed", "molora_shrink", "molora_base_expand",
+           "molora_apply", "molora_apply_bucketed", "molora_shrink", "molora_shrink_workspace_bytes",
+           "molora_base_expand",
            "molora_base_expand_fixed", "molora_init", "molora_apply_static", "molora_static_workspace_bytes",
            "molora_route_mlp_workspace_bytes", "molora_route_mlp", "molora_route_compose",
            "molora_gate_dispatch",
@@ -54,8 +55,10 @@ def load():
     lib.molora_apply.restype = ctypes.c_int
     lib.molora_apply_bucketed.argtypes = [vp, vp, vp, vp, vp, vp, vp, i64, i32, i32, i32, i32, vp, sz, vp]
     lib.molora_apply_bucketed.restype = ctypes.c_int
-    lib.molora_shrink.argtypes = [vp, vp, vp, vp, vp, i64, i32, i32, i32, vp]
+    lib.molora_shrink.argtypes = [vp, vp, vp, vp, vp, i64, i32, i32, i32, vp, sz, vp]
     lib.molora_shrink.restype = ctypes.c_int
+    lib.molora_shrink_workspace_bytes.argtypes = [i64, i32, i32, i32]
+    lib.molora_shrink_workspace_bytes.restype = sz
     lib.molora_base_expand.argtypes = [vp, vp, vp, vp, vp, vp, vp, i64, i32, i32, i32, i32, vp]
     lib.molora_base_expand.restype = ctypes.c_int
     lib.molora_base_expand_fixed.argtypes = [vp, vp, vp, vp, vp, vp, vp, i64, i32, i32, i32, i32, i32, vp]
@@ -230,16 +233,26 @@ def molora_apply_bucketed(x, W, A, B, offsets, perm, h=None, workspace=None, str
     return h
 
 
-def molora_shrink(x, A, offsets, perm, t=None, stream=None):
-    """t[p] = x[perm[p]] A_c as [hi | lo] bf16 halves, [N][2*rank]."""
+def molora_shrink_workspace(N, d_in, C, rank, device="cuda"):
+    """Scratch for molora_shrink (None when these sizes need none)."""
+    nbytes = int(load().molora_shrink_workspace_bytes(N, d_in, C, rank))
+    return torch.empty(nbytes, dtype=torch.uint8, device=device) if nbytes else None
+
+
+def molora_shrink(x, A, offsets, perm, t=None, workspace="auto", stream=None):
+    """t[p] = x[perm[p]] A_c as [hi | lo] bf16 halves, [N][2*rank].  workspace: a tensor from
+    molora_shrink_workspace, None (never split K over workgroups) or "auto" (allocate)."""
     N, d_in = x.shape
     C, _, rank = A.shape
     if t is None:
         t = torch.empty((N, 2 * rank), dtype=torch.bfloat16, device=x.device)
+    if isinstance(workspace, str):
+        workspace = molora_shrink_workspace(N, d_in, C, rank, x.device)
     bf = torch.bfloat16
     st = load().molora_shrink(_dev(x, bf, "x"), _dev(A, bf, "A"), _dev(offsets, torch.int32, "offsets"),
                               _dev(perm, torch.int32, "perm"), _dev(t, bf, "t"), N, d_in, C, rank,
-                              _stream(stream))
+                              None if workspace is None else _dev(workspace, torch.uint8, "workspace"),
+                              0 if workspace is None else workspace.numel(), _stream(stream))
     _check(st, "molora_shrink")
     return t
 

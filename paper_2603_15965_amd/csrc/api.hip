@@ -78,10 +78,11 @@ struct Workspace {
     int32_t *offsets;
     int32_t *perm;
     uint16_t *t2;
+    float *shrink_scratch;  // partial sums of a K-split shrink (nullptr: these sizes never split)
     size_t bytes;
 };
 
-inline Workspace carve(void *base, int64_t N, int32_t C, int32_t rank) {
+inline Workspace carve(void *base, int64_t N, int32_t d_in, int32_t C, int32_t rank) {
     Workspace w;
     unsigned char *p = static_cast<unsigned char *>(base);
     size_t off = 0;
@@ -91,6 +92,9 @@ inline Workspace carve(void *base, int64_t N, int32_t C, int32_t rank) {
     off += round256(size_t(N) * sizeof(int32_t));
     w.t2 = reinterpret_cast<uint16_t *>(p + off);
     off += round256(size_t(N) * 2 * size_t(rank) * sizeof(uint16_t));
+    const size_t sb = molora::shrink_scratch_bytes(N, d_in, C, rank);
+    w.shrink_scratch = sb ? reinterpret_cast<float *>(p + off) : nullptr;
+    off += round256(sb);
     w.bytes = off;
     return w;
 }
@@ -110,7 +114,7 @@ molora_status apply_common(const void *x, const void *W, const void *A, const vo
         (r && !aligned16(r)) || (offsets && !aligned16(offsets)) || (perm && !aligned16(perm)) ||
         !aligned256(workspace))
         return MOLORA_EALIGN;
-    const Workspace ws = carve(workspace, N, C, rank);
+    const Workspace ws = carve(workspace, N, d_in, C, rank);
     if (workspace_bytes < ws.bytes) return MOLORA_EWORKSPACE;
     if (molora::ensure_device_ready() != hipSuccess) return MOLORA_EHIP;
 
@@ -125,7 +129,7 @@ molora_status apply_common(const void *x, const void *W, const void *A, const vo
     }
     const molora::Mix plain{1, C, nullptr, nullptr};
     e = molora::launch_shrink(xb, static_cast<const uint16_t *>(A), offsets, perm, ws.t2, N, d_in,
-                              C, rank, plain, s);
+                              C, rank, plain, s, ws.shrink_scratch);
     if (e != hipSuccess) return MOLORA_EHIP;
     e = molora::launch_fused_gemm(xb, static_cast<const uint16_t *>(W),
                                   static_cast<const uint16_t *>(B), ws.t2, offsets, perm, h, N,
@@ -193,7 +197,7 @@ molora_status molora_gate_dispatch(const int32_t *v, const int32_t *adapter, con
 size_t molora_apply_workspace_bytes(int64_t N, int32_t d_in, int32_t d_out, int32_t C,
                                     int32_t rank) {
     if (!apply_sizes_ok(N, d_in, d_out, C, rank)) return 0;
-    return carve(nullptr, N, C, rank).bytes;
+    return carve(nullptr, N, d_in, C, rank).bytes;
 }
 
 molora_status molora_apply(const void *x, const void *W, const void *A, const void *B,
@@ -232,20 +236,32 @@ molora_status molora_apply_bucketed(const void *x, const void *W, const void *A,
                         workspace_bytes, stream);
 }
 
+size_t molora_shrink_workspace_bytes(int64_t N, int32_t d_in, int32_t C, int32_t rank) {
+    if (!apply_sizes_ok(N, d_in, 8, C, rank)) return 0;
+    return round256(molora::shrink_scratch_bytes(N, d_in, C, rank));
+}
+
 molora_status molora_shrink(const void *x, const void *A, const int32_t *offsets,
                             const int32_t *perm, void *t, int64_t N, int32_t d_in, int32_t C,
-                            int32_t rank, void *stream) {
+                            int32_t rank, void *workspace, size_t workspace_bytes, void *stream) {
     if (!apply_sizes_ok(N, d_in, 8, C, rank)) return MOLORA_EINVAL;
     if (N == 0) return MOLORA_OK;
     if (!x || !A || !offsets || !perm || !t) return MOLORA_EINVAL;
     if (!aligned16(x) || !aligned16(A) || !aligned16(offsets) || !aligned16(perm) || !aligned16(t))
         return MOLORA_EALIGN;
+    // the scratch is optional: without it (NULL, or too small) K is never split over workgroups
+    float *scratch = nullptr;
+    const size_t need = molora::shrink_scratch_bytes(N, d_in, C, rank);
+    if (workspace != nullptr && need > 0 && workspace_bytes >= need) {
+        if (!aligned256(workspace)) return MOLORA_EALIGN;
+        scratch = static_cast<float *>(workspace);
+    }
     if (molora::ensure_device_ready() != hipSuccess) return MOLORA_EHIP;
     return from_hip(molora::launch_shrink(static_cast<const uint16_t *>(x),
                                           static_cast<const uint16_t *>(A), offsets, perm,
                                           static_cast<uint16_t *>(t), N, d_in, C, rank,
                                           molora::Mix{1, C, nullptr, nullptr},
-                                          static_cast<hipStream_t>(stream)));
+                                          static_cast<hipStream_t>(stream), scratch));
 }
 
 namespace {
@@ -353,10 +369,11 @@ struct MixWorkspace {
     int32_t *offsets;
     int32_t *perm;
     uint16_t *t2;
+    float *shrink_scratch;
     size_t bytes;
 };
 
-inline MixWorkspace carve_mix(void *base, int64_t N, int32_t C, int32_t rank, int32_t k) {
+inline MixWorkspace carve_mix(void *base, int64_t N, int32_t d_in, int32_t C, int32_t rank, int32_t k) {
     MixWorkspace w;
     unsigned char *p = static_cast<unsigned char *>(base);
     size_t off = 0;
@@ -370,6 +387,9 @@ inline MixWorkspace carve_mix(void *base, int64_t N, int32_t C, int32_t rank, in
     off += round256(size_t(N) * sizeof(int32_t));
     w.t2 = reinterpret_cast<uint16_t *>(p + off);
     off += round256(size_t(N) * 2 * size_t(k) * size_t(rank) * sizeof(uint16_t));
+    const size_t sb = molora::shrink_scratch_bytes(N, d_in, (int)mix_buckets(C, k), k * rank);
+    w.shrink_scratch = sb ? reinterpret_cast<float *>(p + off) : nullptr;
+    off += round256(sb);
     w.bytes = off;
     return w;
 }
@@ -379,7 +399,7 @@ inline MixWorkspace carve_mix(void *base, int64_t N, int32_t C, int32_t rank, in
 size_t molora_apply_mix_workspace_bytes(int64_t N, int32_t d_in, int32_t d_out, int32_t C,
                                         int32_t rank, int32_t k) {
     if (!mix_sizes_ok(N, d_in, d_out, C, rank, k)) return 0;
-    return carve_mix(nullptr, N, C, rank, k).bytes;
+    return carve_mix(nullptr, N, d_in, C, rank, k).bytes;
 }
 
 molora_status molora_apply_mix(const void *x, const void *W, const void *A, const void *B,
@@ -394,7 +414,7 @@ molora_status molora_apply_mix(const void *x, const void *W, const void *A, cons
         (w && !aligned16(w)) || (slots && !aligned16(slots)) || !aligned16(h) ||
         !aligned256(workspace))
         return MOLORA_EALIGN;
-    const MixWorkspace ws = carve_mix(workspace, N, C, rank, k);
+    const MixWorkspace ws = carve_mix(workspace, N, d_in, C, rank, k);
     if (workspace_bytes < ws.bytes) return MOLORA_EWORKSPACE;
     if (molora::ensure_device_ready() != hipSuccess) return MOLORA_EHIP;
     const int Cb = (int)mix_buckets(C, k);
@@ -405,7 +425,7 @@ molora_status molora_apply_mix(const void *x, const void *W, const void *A, cons
         return MOLORA_EHIP;
     const molora::Mix mix{k, C, slots, ws.wq};
     if (molora::launch_shrink(xb, static_cast<const uint16_t *>(A), ws.offsets, ws.perm, ws.t2, N,
-                              d_in, Cb, rank, mix, s) != hipSuccess)
+                              d_in, Cb, rank, mix, s, ws.shrink_scratch) != hipSuccess)
         return MOLORA_EHIP;
     return from_hip(molora::launch_fused_gemm(xb, static_cast<const uint16_t *>(W),
                                               static_cast<const uint16_t *>(B), ws.t2, ws.offsets,

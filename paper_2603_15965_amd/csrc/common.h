@@ -97,9 +97,12 @@ hipError_t launch_bucket(const int32_t *r, int32_t *offsets, int32_t *perm, int6
 hipError_t launch_gate_bucket(const int32_t *v, const int32_t *adapter, const int32_t *breaks_host,
                               int M, int n_adapters, int32_t *r, int32_t *offsets, int32_t *perm,
                               int64_t N, int32_t *err_flag, hipStream_t s);
+// scratch: fp32 scratch of shrink_scratch_bytes(...) bytes or nullptr (then K is never split
+// over workgroups); contents need no initialisation
+size_t shrink_scratch_bytes(int64_t N, int d_in, int C, int R);
 hipError_t launch_shrink(const uint16_t *x, const uint16_t *A, const int32_t *offsets,
                          const int32_t *perm, uint16_t *t2, int64_t N, int d_in, int C, int rank,
-                         Mix mix, hipStream_t s);
+                         Mix mix, hipStream_t s, float *scratch = nullptr);
 hipError_t launch_fused_gemm(const uint16_t *x, const uint16_t *W, const uint16_t *B,
                              const uint16_t *t2, const int32_t *offsets, const int32_t *perm,
                              float *h, int64_t N, int d_in, int d_out, int C, int rank, Mix mix,
@@ -110,8 +113,11 @@ hipError_t launch_small_batch_gemm(const uint16_t *x, const uint16_t *W, const u
                                    const uint16_t *t2, const int32_t *offsets, const int32_t *perm,
                                    float *h, int64_t N, int d_in, int d_out, int C, int rank, Mix mix,
                                    hipStream_t s);
+// ksplit > 1 (with planes, fp32 [ksplit][N][R]): K cut into slices over workgroups, second pass adds them
+int small_batch_shrink_ksplit(int64_t N, int d_in, int C, int R);
 hipError_t launch_small_batch_shrink(const uint16_t *x, const uint16_t *A, const int32_t *offsets,
                                      const int32_t *perm, uint16_t *t2, int64_t N, int d_in, int C,
-                                     int rank, Mix mix, hipStream_t s);
+                                     int rank, Mix mix, hipStream_t s, float *planes = nullptr,
+                                     int ksplit = 1);
 
 }  // namespace molora

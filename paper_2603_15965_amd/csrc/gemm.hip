@@ -51,7 +51,7 @@ struct GemmCfg {
     static constexpr int A_PIECES = BM / A_RPI, B_PIECES = BK / B_RPI;
     static constexpr int LPW = (A_PIECES + B_PIECES) / NW;  // pieces (loads) per wavefront and tile
     static constexpr int A_BYTES = BM * A_RB, B_BYTES = BK * B_RB, STAGE = A_BYTES + B_BYTES;
-    static constexpr size_t LDS_BYTES = (size_t)STAGES * STAGE + 8 * BM * sizeof(int32_t) + 16;
+    static constexpr size_t LDS_BYTES = (size_t)STAGES * STAGE + 7 * BM * sizeof(int32_t) + 16;
     static_assert(BK == 32 || BK == 64, "BK");
     static_assert(LPW * NW == A_PIECES + B_PIECES && LPW >= 1, "pieces split evenly over wavefronts");
     static_assert(STAGES >= 2 && STAGES <= 4, "stages");
@@ -74,8 +74,7 @@ __global__ __launch_bounds__(Cfg::NT) void fused_gemm_kernel(
                   TN = Cfg::TN, STAGES = Cfg::STAGES;
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
     int32_t *tile_perm = (int32_t *)(smem + STAGES * Cfg::STAGE);  // [BM] token per row, -1 = none
-    int32_t *seg_c = tile_perm + BM;                               // buckets intersecting the tile
-    int32_t *seg_lo = seg_c + BM;
+    int32_t *seg_lo = tile_perm + BM;  // buckets intersecting the tile: their sorted-position ranges
     int32_t *seg_hi = seg_lo + BM;
     int32_t *nseg_p = seg_hi + BM;
     int32_t *seg_ad = nseg_p + 4;  // [BM][4] pool positions of the adapters of a bucket's tuple
@@ -105,7 +104,6 @@ __global__ __launch_bounds__(Cfg::NT) void fused_gemm_kernel(
         const int lo = max(offsets[c], p0), hi = min(offsets[c + 1], p0 + BM);
         if (lo < hi) {
             const int idx = atomicAdd(nseg_p, 1);
-            seg_c[idx] = c;
             seg_lo[idx] = lo;
             seg_hi[idx] = hi;
             // slot table and tuple decoded once here, not inside the K loop

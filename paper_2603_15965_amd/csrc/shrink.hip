@@ -223,9 +223,25 @@ __global__ __launch_bounds__(64 * KW) void shrink_kernel(
 
 }  // namespace
 
+namespace {
+// which of the two kernels: see launch_shrink
+bool shrink_streams(int64_t N, int d_in, int C, int64_t R) {
+    return N <= 64 || (N <= 2048 && d_in * R >= (1 << 17)) ||
+           (N * (int64_t)d_in >= (1 << 24) && N >= 128 * (int64_t)C &&
+            ((N + 63) / 64) * C <= 32768);  // its grid has a slot per (bucket, tile)
+}
+bool shrink_tiny(int64_t N, int64_t R) { return N <= kShrinkTinyMax && (R + 15) / 16 <= 2; }
+}  // namespace
+
+size_t shrink_scratch_bytes(int64_t N, int d_in, int C, int R) {
+    if (N == 0 || shrink_tiny(N, R) || !shrink_streams(N, d_in, C, R)) return 0;
+    const int ks = small_batch_shrink_ksplit(N, d_in, C, R);
+    return ks > 1 ? (size_t)ks * (size_t)N * (size_t)R * sizeof(float) : 0;
+}
+
 hipError_t launch_shrink(const uint16_t *x, const uint16_t *A, const int32_t *offsets,
                          const int32_t *perm, uint16_t *t2, int64_t N, int d_in, int C, int rank,
-                         Mix mix, hipStream_t s) {
+                         Mix mix, hipStream_t s, float *scratch) {
     if (N == 0) return hipSuccess;
     // Two kernels (measured crossovers).  The streaming kernel (one workgroup per 64 rows of a
     // bucket, K split over its 8 wavefronts, x staged as whole 128-byte lines) wins for small
@@ -235,7 +251,7 @@ hipError_t launch_shrink(const uint16_t *x, const uint16_t *A, const int32_t *of
     const int64_t R = (int64_t)mix.k * rank;
     const int nj = (mix.k * rank + 15) / 16;
     // a few work items only, narrow intermediate: 16 (8) wavefronts per 16-row item
-    if (N <= kShrinkTinyMax && nj <= 2) {
+    if (shrink_tiny(N, R)) {
         const unsigned blocks = (unsigned)((N + 15) / 16 + C);
         if (nj == 1)
             hipLaunchKernelGGL((shrink_kernel<1, 1, 16, 8>), dim3(blocks), dim3(1024), 0, s, x, A,
@@ -245,10 +261,11 @@ hipError_t launch_shrink(const uint16_t *x, const uint16_t *A, const int32_t *of
                                offsets, perm, t2, d_in, C, rank, mix);
         return hipGetLastError();
     }
-    const bool stream = N <= 64 || (N <= 2048 && d_in * R >= (1 << 17)) ||
-                        (N * (int64_t)d_in >= (1 << 24) && N >= 128 * (int64_t)C &&
-                         ((N + 63) / 64) * C <= 32768);  // its grid has a slot per (bucket, tile)
-    if (stream) return launch_small_batch_shrink(x, A, offsets, perm, t2, N, d_in, C, rank, mix, s);
+    if (shrink_streams(N, d_in, C, R)) {
+        // few (bucket, tile) pairs and a long K: K split over workgroups, when scratch is there
+        const int ks = scratch != nullptr ? small_batch_shrink_ksplit(N, d_in, C, (int)R) : 1;
+        return launch_small_batch_shrink(x, A, offsets, perm, t2, N, d_in, C, rank, mix, s, scratch, ks);
+    }
     // 32-row items when they still cover the chip twice, 16-row items otherwise
     const bool small_items = (N + 31) / 32 + C < 512;
     const int rows = small_items ? 16 : 32;

@@ -58,6 +58,22 @@ struct SbGeom {
     }
 };
 
+// four values of a row of the low-rank intermediate, scaled by the token's mixture weight, as
+// t = hi + lo with hi = bf16(t), lo = bf16(t - hi); row of t = [hi | lo], R values each
+__device__ __forceinline__ void store_t_hi_lo(uint16_t *row_dst, int R, int col, f32x4 sum, float wj) {
+    u32x2 hi2 = {0, 0}, lo2 = {0, 0};
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const float tv = sum[i] * wj;
+        const uint32_t hi = f32_to_bf16_bits(tv);
+        const uint32_t lo = f32_to_bf16_bits(tv - bf16_bits_to_f32(hi));
+        hi2[i >> 1] |= hi << (16 * (i & 1));
+        lo2[i >> 1] |= lo << (16 * (i & 1));
+    }
+    *(u32x2 *)(row_dst + col) = hi2;
+    *(u32x2 *)(row_dst + R + col) = lo2;
+}
+
 // one unit of a wavefront's work list: 64 k-rows of W, four steps of 16 k
 struct Unit {
     bool real;  // false: past the end of the list, nothing (zeros)
@@ -73,13 +89,18 @@ struct Unit {
 // SHRINK = true:  the shrink step t_p = x[perm[p]] A_c for the rows of bucket c = blockIdx.y
 //                 (grid: column groups of the rank x buckets x 64-row tiles of a bucket); W is
 //                 A, d_out is rank, there are no expand units and the result goes to t_out as
-//                 [hi | lo] bf16 halves.
+//                 [hi | lo] bf16 halves.  With ksplit > 1 the K range is cut into ksplit
+//                 slices, one workgroup each (blockIdx.z = tile * ksplit + slice): a batch of
+//                 a few dozen tokens has too few (bucket, tile) pairs to draw the touched A_c
+//                 from HBM at speed, a workgroup draws ~50 GB/s.  A slice's sums then go, in
+//                 fp32, to plane `slice` of h [ksplit][N][R]; shrink_reduce_kernel adds the
+//                 planes in ascending order (a fixed order: no atomics) and writes t_out.
 template <int TM, int TN, bool SHRINK>  // TM: 32-row blocks, 1 (N <= 32) or 2
 __global__ __launch_bounds__(kSbWaves * 64) void small_batch_kernel(
     const uint16_t *__restrict__ x, const uint16_t *__restrict__ W, const uint16_t *__restrict__ B,
     const uint16_t *__restrict__ t2, const int32_t *__restrict__ offsets,
     const int32_t *__restrict__ perm, float *__restrict__ h, uint16_t *__restrict__ t_out, int N,
-    int d_in, int d_out, int C, int rank, Mix mix) {
+    int d_in, int d_out, int C, int rank, Mix mix, int ksplit) {
     using Geo = SbGeom<TN>;
     constexpr int kSbCols = Geo::COLS, kSbSlot = Geo::SLOT, kSbRowBytes = Geo::ROW_BYTES,
                   kSbWaveLds = Geo::WAVE_LDS;
@@ -103,7 +124,7 @@ __global__ __launch_bounds__(kSbWaves * 64) void small_batch_kernel(
     int row_base = 0, nrows = N, bucket = 0;
     if constexpr (SHRINK) {
         bucket = blockIdx.y;
-        row_base = offsets[bucket] + 64 * blockIdx.z;  // 64-row tile of the bucket
+        row_base = offsets[bucket] + 64 * (blockIdx.z / ksplit);  // 64-row tile of the bucket
         nrows = min(64, offsets[bucket + 1] - row_base);
         if (nrows <= 0) return;  // nothing (left) in this bucket: its adapters are not touched
     } else {
@@ -120,7 +141,12 @@ __global__ __launch_bounds__(kSbWaves * 64) void small_batch_kernel(
     // 8 * u + wave.  Interleaved, so that the workgroups together sweep W from top to bottom
     // (measured 2% faster than giving every wavefront one contiguous eighth).
     const int two_r = 2 * R;
-    const int nub = (d_in + 63) / 64;
+    const int nub_all = (d_in + 63) / 64;
+    // K slice of this workgroup (SHRINK with ksplit > 1): pieces [u_lo, u_lo + nub)
+    const int slice = SHRINK ? (int)(blockIdx.z % ksplit) : 0;
+    const int per_slice = SHRINK ? (nub_all + ksplit - 1) / ksplit : nub_all;
+    const int u_lo = slice * per_slice;
+    const int nub = max(0, min(nub_all, u_lo + per_slice) - u_lo);
     const int nw = nub > wave ? (nub - wave + kSbWaves - 1) / kSbWaves : 0;
 
     const int pitch = SHRINK ? rank : d_out;  // elements between consecutive k-rows of W (A)
@@ -136,7 +162,7 @@ __global__ __launch_bounds__(kSbWaves * 64) void small_batch_kernel(
     auto unit_of = [&](int u) {  // u-th unit of this wavefront
         Unit un;
         un.real = u < nw;
-        un.k0 = un.real ? (u * kSbWaves + wave) * 64 : 0;
+        un.k0 = un.real ? (u_lo + u * kSbWaves + wave) * 64 : 0;
         un.fast = un.real && un.k0 + 64 <= d_in;
         un.base = (const unsigned char *)(W + (int64_t)un.k0 * pitch);
         return un;
@@ -447,26 +473,47 @@ __global__ __launch_bounds__(kSbWaves * 64) void small_batch_kernel(
 #pragma unroll
         for (int w = 1; w < kSbWaves; ++w)
             sum += *(const f32x4 *)(smem + w * kSbWaveLds + row * kSbRowBytes + ch * 16);
-        if constexpr (SHRINK) {
+        if (SHRINK && ksplit > 1) {
+            // partial sums of this K slice; weights and the bf16 split wait for the reduction
+            *(f32x4 *)(h + ((int64_t)slice * N + row_base + row) * R + col) = sum;
+        } else if constexpr (SHRINK) {
             // piece j of the row is scaled by the token's j-th mixture weight; then
             // t = hi + lo with hi = bf16(t), lo = bf16(t - hi); row of t_out = [hi | lo]
             const float wj = mix.w != nullptr ? mix.w[(int64_t)tok * mix.k + col / rank] : 1.f;
-            u32x2 hi2 = {0, 0}, lo2 = {0, 0};
-#pragma unroll
-            for (int i = 0; i < 4; ++i) {
-                const float tv = sum[i] * wj;
-                const uint32_t hi = f32_to_bf16_bits(tv);
-                const uint32_t lo = f32_to_bf16_bits(tv - bf16_bits_to_f32(hi));
-                hi2[i >> 1] |= hi << (16 * (i & 1));
-                lo2[i >> 1] |= lo << (16 * (i & 1));
-            }
-            uint16_t *dst = t_out + (int64_t)(row_base + row) * 2 * R;
-            *(u32x2 *)(dst + col) = hi2;
-            *(u32x2 *)(dst + R + col) = lo2;
+            store_t_hi_lo(t_out + (int64_t)(row_base + row) * 2 * R, R, col, sum, wj);
         } else {
             *(f32x4 *)(h + (int64_t)tok * d_out + col) = sum;
         }
     }
+}
+
+// Second pass of a K-split shrink: t_p = (sum over the slices, ascending, of plane[s][p]) * w,
+// split into bf16 halves.  Four columns of one routed sorted position per thread.
+__global__ __launch_bounds__(256) void shrink_reduce_kernel(const float *__restrict__ planes,
+                                                            const int32_t *__restrict__ offsets,
+                                                            const int32_t *__restrict__ perm,
+                                                            uint16_t *__restrict__ t_out, int N, int C,
+                                                            int R, int rank, int ksplit, Mix mix) {
+    const int per_row = R / 4;
+    const int64_t e = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (e >= (int64_t)N * per_row) return;
+    const int p = (int)(e / per_row), col = (int)(e % per_row) * 4;
+    // all loads issued before any is used: one trip to memory (a row past the routed ones holds
+    // whatever the scratch held: read, never stored)
+    const int n_routed = offsets[C];
+    const int tok = perm[p];
+    f32x4 part[4];
+#pragma unroll
+    for (int s = 0; s < 4; ++s)
+        part[s] = *(const f32x4 *)(planes + ((int64_t)(s < ksplit ? s : 0) * N + p) * R + col);
+    f32x4 sum = part[0];
+#pragma unroll
+    for (int s = 1; s < 4; ++s)
+        if (s < ksplit) sum += part[s];
+    for (int s = 4; s < ksplit; ++s) sum += *(const f32x4 *)(planes + ((int64_t)s * N + p) * R + col);
+    if (p >= n_routed) return;  // rows past the routed ones belong to no bucket
+    const float wj = mix.w != nullptr ? mix.w[(int64_t)tok * mix.k + col / rank] : 1.f;
+    store_t_hi_lo(t_out + (int64_t)p * 2 * R, R, col, sum, wj);
 }
 
 // more than 64 KB of dynamic LDS has to be asked for, once per device (see common.h)
@@ -478,7 +525,7 @@ struct SmallBatchKernel {
 template <int TM, int TN, bool SHRINK>
 hipError_t launch_small(const uint16_t *x, const uint16_t *W, const uint16_t *B, const uint16_t *t2,
                         const int32_t *offsets, const int32_t *perm, float *h, uint16_t *t_out, int N,
-                        int d_in, int d_out, int C, int rank, Mix mix, hipStream_t s) {
+                        int d_in, int d_out, int C, int rank, Mix mix, hipStream_t s, int ksplit) {
     using Geo = SbGeom<TN>;
     auto kern = small_batch_kernel<TM, TN, SHRINK>;
     (void)&SmallBatchKernel<TM, TN, SHRINK>::lds;  // instantiates the registration
@@ -486,23 +533,25 @@ hipError_t launch_small(const uint16_t *x, const uint16_t *W, const uint16_t *B,
     const unsigned row_tiles = (unsigned)((N + 63) / 64);
     // GEMM: row tiles of the batch.  SHRINK: buckets x row tiles a bucket can have at most
     // (workgroups past a bucket's end leave at once)
-    const dim3 grid = SHRINK ? dim3(groups, (unsigned)C, row_tiles) : dim3(groups, row_tiles);
+    // (a K-split shrink: one workgroup per K slice of each of them)
+    const dim3 grid = SHRINK ? dim3(groups, (unsigned)C, row_tiles * (unsigned)ksplit) : dim3(groups, row_tiles);
     hipLaunchKernelGGL(kern, grid, dim3(kSbWaves * 64), Geo::LDS_BYTES, s, x, W, B, t2, offsets, perm,
-                       h, t_out, N, d_in, d_out, C, rank, mix);
+                       h, t_out, N, d_in, d_out, C, rank, mix, ksplit);
     return hipGetLastError();
 }
 
 template <bool SHRINK>
 hipError_t launch_small_tn(const uint16_t *x, const uint16_t *W, const uint16_t *B, const uint16_t *t2,
                            const int32_t *offsets, const int32_t *perm, float *h, uint16_t *t_out,
-                           int N, int d_in, int d_out, int C, int rank, Mix mix, hipStream_t s) {
+                           int N, int d_in, int d_out, int C, int rank, Mix mix, hipStream_t s,
+                           int ksplit = 1) {
     // 32-column groups when 64-column groups would occupy at most half of the compute units:
     // a workgroup draws ~40 GB/s from HBM whatever its width, so more, narrower ones win there.
     // The shrink has at most a few workgroups per bucket and always takes the narrow form.
     const int64_t wgs64 = (int64_t)((d_out + 63) / 64) * ((N + 63) / 64);
     const bool narrow = SHRINK || wgs64 <= 128;
 #define MOLORA_SB_LAUNCH(TM, TN) \
-    launch_small<TM, TN, SHRINK>(x, W, B, t2, offsets, perm, h, t_out, N, d_in, d_out, C, rank, mix, s)
+    launch_small<TM, TN, SHRINK>(x, W, B, t2, offsets, perm, h, t_out, N, d_in, d_out, C, rank, mix, s, ksplit)
     if (N <= 32) return narrow ? MOLORA_SB_LAUNCH(1, 1) : MOLORA_SB_LAUNCH(1, 2);
     return narrow ? MOLORA_SB_LAUNCH(2, 1) : MOLORA_SB_LAUNCH(2, 2);
 #undef MOLORA_SB_LAUNCH
@@ -518,12 +567,30 @@ hipError_t launch_small_batch_gemm(const uint16_t *x, const uint16_t *W, const u
                                   mix, s);
 }
 
+int small_batch_shrink_ksplit(int64_t N, int d_in, int C, int R) {
+    // an upper bound of the workgroups a plain launch would have (32-column groups x (bucket,
+    // 64-row tile) pairs): K is split when they would occupy at most a quarter / half of the
+    // compute units and K is long enough for every slice to keep its wavefronts busy
+    const int64_t groups = (R + 31) / 32;
+    const int64_t pairs = (N < C ? N : C) + N / 64;
+    const int64_t wgs = groups * pairs;
+    if (wgs <= 64 && d_in >= 2048) return 4;
+    if (wgs <= 128 && d_in >= 1024) return 2;
+    return 1;
+}
+
 hipError_t launch_small_batch_shrink(const uint16_t *x, const uint16_t *A, const int32_t *offsets,
                                      const int32_t *perm, uint16_t *t_out, int64_t N, int d_in, int C,
-                                     int rank, Mix mix, hipStream_t s) {
+                                     int rank, Mix mix, hipStream_t s, float *planes, int ksplit) {
     const int R = mix.k * rank;  // the kernel's "d_out" is the width of the intermediate
-    return launch_small_tn<true>(x, A, nullptr, nullptr, offsets, perm, nullptr, t_out, (int)N, d_in, R,
-                                 C, rank, mix, s);
+    if (planes == nullptr) ksplit = 1;
+    hipError_t e = launch_small_tn<true>(x, A, nullptr, nullptr, offsets, perm, planes, t_out, (int)N, d_in,
+                                         R, C, rank, mix, s, ksplit);
+    if (e != hipSuccess || ksplit <= 1) return e;
+    const int64_t items = N * (R / 4);
+    hipLaunchKernelGGL(shrink_reduce_kernel, dim3((unsigned)((items + 255) / 256)), dim3(256), 0, s, planes,
+                       offsets, perm, t_out, (int)N, C, R, rank, ksplit, mix);
+    return hipGetLastError();
 }
 
 }  // namespace molora

@@ -39,10 +39,16 @@ def test_status_strings(lib):
 
 def test_workspace_size_formula(lib):
     f = lib.molora_apply_workspace_bytes
-    # offsets + perm + t as [hi | lo] bf16, each rounded up to 256 bytes
+    # offsets + perm + t as [hi | lo] bf16 (+ the scratch of a K-split shrink), each rounded up
+    # to 256 bytes
     r256 = lambda b: (b + 255) // 256 * 256
+    g = lib.molora_shrink_workspace_bytes
     for (N, di, do, C, rk) in [(256, 256, 256, 4, 8), (16384, 4096, 12288, 32, 32), (64, 4096, 12288, 16, 64)]:
-        assert f(N, di, do, C, rk) == r256(4 * (C + 1)) + r256(4 * N) + r256(N * 2 * rk * 2)
+        assert f(N, di, do, C, rk) == r256(4 * (C + 1)) + r256(4 * N) + r256(N * 2 * rk * 2) + g(N, di, C, rk)
+    # a few dozen tokens, long K, wide intermediate: four K slices of fp32 partial sums
+    assert g(64, 4096, 16, 64) == 4 * 64 * 64 * 4
+    assert g(16384, 4096, 32, 32) == 0 and g(256, 256, 4, 8) == 0 and g(0, 4096, 16, 64) == 0
+    assert g(64, 4096, 16, 60) == 0          # rank not a multiple of 8
     assert f(16, 10, 64, 4, 8) == 0          # d_in not a multiple of 8
     assert f(16, 64, 64, 4, 12) == 0         # rank not a multiple of 8
     assert f(16, 64, 64, 4, 256) == 0        # rank above the limit
@@ -109,7 +115,7 @@ def test_widened_entry_points_reject_bad_arguments(lib):
     g = lib.molora_apply_mix_workspace_bytes
     N, C, rk, k = 300, 8, 16, 2
     assert g(N, 64, 64, C, rk, k) == (r256(4 * N) + r256(4 * N * k) + r256(4 * (C ** k + 1)) + r256(4 * N)
-                                      + r256(N * 2 * k * rk * 2))
+                                      + r256(N * 2 * k * rk * 2))   # no K split at these sizes
     assert g(N, 64, 64, 40, rk, 2) == 0          # 1600 tuples
     assert g(N, 64, 64, 4, 64, 4) == 0           # stacked rank 256
     assert g(N, 64, 64, 4, 8, 5) == 0            # k above the limit
