@@ -96,28 +96,11 @@ __global__ __launch_bounds__(Cfg::NT) void fused_gemm_kernel(
     const int tile_n = (logical % group_size) / gm;
     const int p0 = tile_m * BM, n0 = tile_n * BN;
 
-    // ---- per-tile tables ----
-    if (tid == 0) *nseg_p = 0;
-    for (int i = tid; i < BM; i += NT) tile_perm[i] = (p0 + i < N) ? perm[p0 + i] : -1;
-    __syncthreads();
-    for (int c = tid; c < C; c += NT) {
-        const int lo = max(offsets[c], p0), hi = min(offsets[c + 1], p0 + BM);
-        if (lo < hi) {
-            const int idx = atomicAdd(nseg_p, 1);
-            seg_lo[idx] = lo;
-            seg_hi[idx] = hi;
-            // slot table and tuple decoded once here, not inside the K loop
-            for (int j = 0; j < mix.k; ++j) seg_ad[idx * 4 + j] = mix_adapter(mix, c, j);
-        }
-    }
-    __syncthreads();
-    const int nseg = *nseg_p;
     const int R = mix.k * rank;  // width of a bucket's intermediate (k adapters side by side)
     const int two_r = 2 * R;
     const int tps = (two_r + BK - 1) / BK;  // extra K tiles per bucket
     const int nkf = d_in / BK;              // full K tiles
     const int nkb = (d_in + BK - 1) / BK;   // K tiles of x.W, the last one possibly partial
-    const int nk = nkb + nseg * tps;        // all K tiles of this output tile
 
     // ---- per-lane sources of this wavefront's load instructions ----
     // A stage is A_PIECES + B_PIECES pieces of 1 KB, x pieces (A_RPI rows each) first, then W
@@ -146,15 +129,10 @@ __global__ __launch_bounds__(Cfg::NT) void fused_gemm_kernel(
     };
     uint32_t off_g[Cfg::LPW];  // full tiles: byte offset from the scalar base
 #pragma unroll
-    for (int i = 0; i < Cfg::LPW; ++i) {
+    for (int i = 0; i < Cfg::LPW; ++i) {  // W pieces (the x pieces need the row table, below)
         int row, col;
         slot_geom(i, row, col);
-        if (slot_is_a(i)) {
-            const int tok = tile_perm[row];
-            off_g[i] = (uint32_t)(((int64_t)(tok >= 0 ? tok : 0) * d_in + col * 8) * 2);
-        } else {
-            off_g[i] = (uint32_t)(((int64_t)row * d_out + col) * 2);
-        }
+        off_g[i] = slot_is_a(i) ? 0u : (uint32_t)(((int64_t)row * d_out + col) * 2);
     }
     // scalar bases of the full tiles, advanced per tile (x and W are < 4 GiB each)
     const unsigned char *a_base = (const unsigned char *)x;
@@ -164,39 +142,88 @@ __global__ __launch_bounds__(Cfg::NT) void fused_gemm_kernel(
     auto issue_one = [&](unsigned char *stage, int i) {  // i-th load of a full tile
         load_to_lds16(slot_is_a(i) ? a_base : b_base, off_g[i], stage + piece_of(i) * 1024);
     };
-    auto advance_full = [&]() {
-        a_base += BK * 2;
-        b_base += b_step;
-    };
-    // Any K tile T, full tiles through the fast form.  A partial last tile of x.W and the
-    // expand tiles compute a source per lane; chunks that must read as zero come from the
-    // zero page.  Tiles must be issued in ascending order (the fast form advances its base).
-    auto issue_tile = [&](unsigned char *stage, int T) {
+    // The x part (want_a) and / or the W part (want_b) of base tile T < nkb; a partial last
+    // tile computes a source per lane, k past d_in reads from the zero page.  Each part must
+    // be issued in ascending tile order (the fast form advances its base).
+    auto issue_base_parts = [&](unsigned char *stage, int T, bool want_a, bool want_b) {
         if (T < nkf) {
 #pragma unroll
-            for (int i = 0; i < Cfg::LPW; ++i) issue_one(stage, i);
-            advance_full();
+            for (int i = 0; i < Cfg::LPW; ++i)
+                if (slot_is_a(i) ? want_a : want_b) issue_one(stage, i);
+            if (want_a) a_base += BK * 2;
+            if (want_b) b_base += b_step;
             return;
         }
         const uint16_t *zero = (const uint16_t *)g_zero_page;
-        if (T < nkb) {  // partial tile of x.W: k past d_in reads zero
 #pragma unroll
-            for (int i = 0; i < Cfg::LPW; ++i) {
-                const uint16_t *src;
-                int row, col;
-                slot_geom(i, row, col);
-                if (slot_is_a(i)) {
-                    const int k = T * BK + col * 8;
-                    const int tok = tile_perm[row];
-                    src = (k < d_in) ? x + (int64_t)(tok >= 0 ? tok : 0) * d_in + k : zero;
-                } else {
-                    const int k = T * BK + row;
-                    src = (k < d_in) ? W + (int64_t)k * d_out + col : zero;
-                }
-                load_to_lds16_ptr(src, stage + piece_of(i) * 1024);
+        for (int i = 0; i < Cfg::LPW; ++i) {
+            if (!(slot_is_a(i) ? want_a : want_b)) continue;
+            const uint16_t *src;
+            int row, col;
+            slot_geom(i, row, col);
+            if (slot_is_a(i)) {
+                const int k = T * BK + col * 8;
+                const int tok = tile_perm[row];
+                src = (k < d_in) ? x + (int64_t)(tok >= 0 ? tok : 0) * d_in + k : zero;
+            } else {
+                const int k = T * BK + row;
+                src = (k < d_in) ? W + (int64_t)k * d_out + col : zero;
             }
-            return;
+            load_to_lds16_ptr(src, stage + piece_of(i) * 1024);
         }
+    };
+    // With two stages every wait of the main loop is for all outstanding loads, so the order in
+    // which the first tiles' pieces are issued is free: their W pieces, which depend on nothing
+    // the dispatch step produced, go out before the tables are even read.
+    const bool early_w = STAGES == 2 && nkb >= STAGES;
+    if (early_w) {
+#pragma unroll
+        for (int T = 0; T < STAGES; ++T) issue_base_parts(smem + T * Cfg::STAGE, T, false, true);
+    }
+
+    // ---- per-tile tables: the rows' tokens and the buckets that own rows, both global reads
+    // in flight together ----
+    if (tid == 0) *nseg_p = 0;
+    int32_t my_tok = -1, o_lo = 0, o_hi = 0;
+    if (tid < BM && p0 + tid < N) my_tok = perm[p0 + tid];
+    if (tid < C) {
+        o_lo = offsets[tid];
+        o_hi = offsets[tid + 1];
+    }
+    __syncthreads();  // the segment counter is zero
+    if (tid < BM) tile_perm[tid] = my_tok;
+    for (int i = tid + NT; i < BM; i += NT) tile_perm[i] = (p0 + i < N) ? perm[p0 + i] : -1;
+    for (int c = tid; c < C; c += NT) {
+        if (c != tid) {
+            o_lo = offsets[c];
+            o_hi = offsets[c + 1];
+        }
+        const int lo = max(o_lo, p0), hi = min(o_hi, p0 + BM);
+        if (lo < hi) {
+            const int idx = atomicAdd(nseg_p, 1);
+            seg_lo[idx] = lo;
+            seg_hi[idx] = hi;
+            // slot table and tuple decoded once here, not inside the K loop
+            for (int j = 0; j < mix.k; ++j) seg_ad[idx * 4 + j] = mix_adapter(mix, c, j);
+        }
+    }
+    __syncthreads();
+    const int nseg = *nseg_p;
+    const int nk = nkb + nseg * tps;  // all K tiles of this output tile
+#pragma unroll
+    for (int i = 0; i < Cfg::LPW; ++i) {  // x pieces: the gathered row of every lane
+        if (!slot_is_a(i)) continue;
+        int row, col;
+        slot_geom(i, row, col);
+        const int tok = tile_perm[row];
+        off_g[i] = (uint32_t)(((int64_t)(tok >= 0 ? tok : 0) * d_in + col * 8) * 2);
+    }
+
+    // Any K tile T.  The expand tiles compute a source per lane; chunks that must read as zero
+    // come from the zero page.  Tiles must be issued in ascending order.
+    auto issue_tile = [&](unsigned char *stage, int T) {
+        if (T < nkb) return issue_base_parts(stage, T, true, true);
+        const uint16_t *zero = (const uint16_t *)g_zero_page;
         // expand tile: A operand = t rows of one bucket (others zero), B operand = [B_c; B_c]
         const int e = T - nkb;
         const int sg = e / tps, sub = e % tps;
@@ -294,8 +321,12 @@ __global__ __launch_bounds__(Cfg::NT) void fused_gemm_kernel(
     };
     auto stage_of = [&](int T) { return smem + (T % STAGES) * Cfg::STAGE; };
 #pragma unroll
-    for (int T = 0; T < STAGES; ++T)
-        if (T < nk) issue_tile(smem + T * Cfg::STAGE, T);
+    for (int T = 0; T < STAGES; ++T) {
+        if (early_w)
+            issue_base_parts(smem + T * Cfg::STAGE, T, true, false);  // the W part is on its way
+        else if (T < nk)
+            issue_tile(smem + T * Cfg::STAGE, T);
+    }
     wait_tiles(min(nk, STAGES) - 1);
     wg_barrier();
 #pragma unroll
@@ -349,7 +380,8 @@ __global__ __launch_bounds__(Cfg::NT) void fused_gemm_kernel(
         if constexpr (REFILL == 1) {
 #pragma unroll
             for (int i = TM * TN; i < Cfg::LPW; ++i) issue_one(as, i);
-            advance_full();
+            a_base += BK * 2;
+            b_base += b_step;
         }
     };
     using I0 = std::integral_constant<int, 0>;
