@@ -56,6 +56,18 @@ struct GemmCfg {
     static_assert(LPW * NW == A_PIECES + B_PIECES && LPW >= 1, "pieces split evenly over wavefronts");
     static_assert(STAGES >= 2 && STAGES <= 4, "stages");
 
+    // Where the 32-byte chunk `chunk` (16 columns) of k-row `row` of the W tile lies in its LDS
+    // row: XORed with row & 3, so that the four consecutive k-rows a group of 16 lanes takes in
+    // a transpose read land in four different chunks of a 128-byte window.  (All rows start at
+    // bank 0, and lanes 0-31 of a read, which the hardware serves together, take adjacent chunks
+    // of the SAME window: SQ_LDS_BANK_CONFLICT counts 2 extra cycles on every such read and on
+    // nothing else in the kernel.  Sending the two groups to different halves of the banks --
+    // chunk bits 0 and 2 swapped -- brings the counter to zero and the LDS busy cycles down by
+    // 24 %, and makes the kernel 1.5 % slower: the LDS-direct loads then fetch alternating
+    // 32-byte pieces of two cache lines per 8 lanes, and the LDS, a third busy, is not what
+    // the kernel waits for.  Measured, not kept.)
+    __device__ static __forceinline__ int swz_b(int chunk, int row) { return chunk ^ (row & 3); }
+    __device__ static __forceinline__ int swz_b_inv(int pos, int row) { return pos ^ (row & 3); }
     // XOR applied to the 16-byte chunk index of an x-tile row
     __device__ static __forceinline__ int swz_a(int row) {
         if constexpr (BK == 64) return (row ^ (row >> 3)) & 7;
@@ -72,7 +84,8 @@ __global__ __launch_bounds__(Cfg::NT) void fused_gemm_kernel(
     int rank, int tiles_m, int tiles_n, Mix mix) {
     constexpr int BM = Cfg::BM, BN = Cfg::BN, BK = Cfg::BK, NT = Cfg::NT, TM = Cfg::TM,
                   TN = Cfg::TN, STAGES = Cfg::STAGES;
-    extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+    // (1 KB alignment: the operand reads XOR k-step bits into addresses relative to this base)
+    extern __shared__ __attribute__((aligned(1024))) unsigned char smem[];
     int32_t *tile_perm = (int32_t *)(smem + STAGES * Cfg::STAGE);  // [BM] token per row, -1 = none
     int32_t *seg_lo = tile_perm + BM;  // buckets intersecting the tile: their sorted-position ranges
     int32_t *seg_hi = seg_lo + BM;
@@ -123,7 +136,9 @@ __global__ __launch_bounds__(Cfg::NT) void fused_gemm_kernel(
         } else {
             row = (piece_of(i) - Cfg::A_PIECES) * Cfg::B_RPI + lane / Cfg::B_CPR;
             const int pos = lane % Cfg::B_CPR;
-            const int u16 = ((((pos >> 1) ^ (row & 3))) << 1) | (pos & 1);
+            // this lane fills 16-byte position pos of the LDS row, i.e. half pos & 1 of physical
+            // 32-byte chunk pos >> 1, which holds the logical chunk given by swz_b's inverse
+            const int u16 = (Cfg::swz_b_inv(pos >> 1, row) << 1) | (pos & 1);
             col = min(n0 + u16 * 8, d_out - 8);
         }
     };
@@ -262,31 +277,57 @@ __global__ __launch_bounds__(Cfg::NT) void fused_gemm_kernel(
     const int b_kr0 = (blk >> 1) * 8 + (a16 >> 2);            // + ks*16 (+4 for the upper half)
     const int b_col0 = wn * (BN / Cfg::WN) + 16 * (blk & 1);  // + tn*32 ; column of lane = +a16
     const int b_in = (a16 & 3) * 8;                           // byte inside the 32-byte chunk
-    int a_off[TM], a_swz[TM];
+    // Per-lane LDS addresses of the operand fragments in stage 0, k-step 0:
+    //   x fragment tm: row a_row0 + tm*32, 16-byte chunk (2*ks + a_kg) ^ swizzle(row).  The
+    //     chunk index is XORed, and 2*ks touches bits the rest of the address never carries into
+    //     (rows are A_RB = 32*KS bytes long and so aligned), so k-step ks is the k-step-0
+    //     address XOR ks*32: one operation per read;
+    //   W fragment tn: k-row b_kr0 (+4), the swizzled position of 32-byte chunk
+    //     (b_col0 + tn*32) / 16, which is the same for every k-step (the swizzle looks at bits
+    //     0 and 1 of the row): k-step ks is a constant added, i.e. the read's immediate offset.
+    // A tile's addresses are these plus its stage's offset, added once per tile.
+    static_assert(Cfg::A_RB == 32 * (BK / 16), "the XOR form of the x fragment address");
+    const uint32_t smem0 = (uint32_t)(uintptr_t)(MOLORA_LDS unsigned char *)smem;
+    uint32_t pa[TM], pb[TN];
 #pragma unroll
     for (int tm = 0; tm < TM; ++tm) {
-        a_off[tm] = (a_row0 + tm * 32) * Cfg::A_RB;
-        a_swz[tm] = Cfg::swz_a(a_row0 + tm * 32);
+        const int row = a_row0 + tm * 32;
+        pa[tm] = smem0 + row * Cfg::A_RB + ((a_kg ^ Cfg::swz_a(row)) << 4);
     }
+#pragma unroll
+    for (int tn = 0; tn < TN; ++tn)
+        pb[tn] = smem0 + Cfg::A_BYTES + b_kr0 * Cfg::B_RB + (Cfg::swz_b((b_col0 + tn * 32) >> 4, b_kr0) << 5) + b_in;
 
-    // The LDS addresses are recomputed at every use from a few per-lane constants (two or three
-    // VALU operations per read, which ride along with the MFMAs for free); `opaque` keeps the
-    // compiler from hoisting one address register per (stage, k-step, fragment) out of the
-    // loop, which costs far more registers than it saves.
-    auto opaque = [](int v) {
+    // `opaque` keeps the compiler from precomputing one address register per (stage, k-step,
+    // fragment) outside the loop, which costs far more registers than it saves.
+    auto opaque = [](uint32_t v) {
         asm volatile("" : "+v"(v));
         return v;
     };
-    auto load_a_frag = [&](const unsigned char *as, int ks, int tm) -> bf16x8 {
-        const int sw = opaque(a_swz[tm]);
-        return *(const bf16x8 *)(as + a_off[tm] + (((ks * 2 + a_kg) ^ sw) << 4));
+    // Addresses of the tile being multiplied (ca, cb) and of the next one (na, nb).  With two
+    // stages the hot loop is unrolled by two, so each copy knows its stage: it reads through the
+    // constant arrays p?0 / p?1 and spends nothing on addresses but the XOR; elsewhere the
+    // stage offset is added once per tile.
+    uint32_t ca_rt[TM], cb_rt[TN], na_rt[TM], nb_rt[TN];
+    uint32_t pa1[TM], pb1[TN];  // stage 1
+#pragma unroll
+    for (int tm = 0; tm < TM; ++tm) pa1[tm] = pa[tm] + Cfg::STAGE;
+#pragma unroll
+    for (int tn = 0; tn < TN; ++tn) pb1[tn] = pb[tn] + Cfg::STAGE;
+    auto stage_addresses = [&](uint32_t (&a)[TM], uint32_t (&b)[TN], int T) {
+        const uint32_t so = (uint32_t)(T % STAGES) * Cfg::STAGE;
+#pragma unroll
+        for (int tm = 0; tm < TM; ++tm) a[tm] = opaque(pa[tm] + so);
+#pragma unroll
+        for (int tn = 0; tn < TN; ++tn) b[tn] = opaque(pb[tn] + so);
     };
-    auto load_b_frag = [&](const unsigned char *as, int ks, int tn) -> bf16x8 {
-        const int k3 = opaque(b_kr0 & 3);
-        const int cc = (b_col0 + tn * 32) >> 4;
-        const unsigned char *p = as + Cfg::A_BYTES + (ks * 16 + b_kr0) * Cfg::B_RB + ((cc ^ k3) << 5) + b_in;
-        const i16x4 lo = lds_read_tr16((const MOLORA_LDS void *)p);
-        const i16x4 hi = lds_read_tr16((const MOLORA_LDS void *)(p + 4 * Cfg::B_RB));
+    auto load_a_frag = [&](const uint32_t (&a)[TM], int ks, int tm) -> bf16x8 {
+        return *(const MOLORA_LDS bf16x8 *)(uintptr_t)(a[tm] ^ (uint32_t)(ks * 32));
+    };
+    auto load_b_frag = [&](const uint32_t (&b)[TN], int ks, int tn) -> bf16x8 {
+        const uint32_t p = b[tn] + (uint32_t)(ks * 16 * Cfg::B_RB);
+        const i16x4 lo = lds_read_tr16((const MOLORA_LDS void *)(uintptr_t)p);
+        const i16x4 hi = lds_read_tr16((const MOLORA_LDS void *)(uintptr_t)(p + 4 * Cfg::B_RB));
         const i16x8 b8 = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
         return __builtin_bit_cast(bf16x8, b8);
     };
@@ -304,11 +345,11 @@ __global__ __launch_bounds__(Cfg::NT) void fused_gemm_kernel(
     // further ahead.
     static_assert(KS % 2 == 0, "two fragment register sets");
     bf16x8 fa[2][TM], fb[2][TN];
-    auto fetch_one = [&](const unsigned char *as, int ks, int set, int i) {  // i-th fragment
+    auto fetch_one = [&](const uint32_t (&a)[TM], const uint32_t (&b)[TN], int ks, int set, int i) {  // i-th fragment
         if (i < TM)
-            fa[set][i] = load_a_frag(as, ks, i);
+            fa[set][i] = load_a_frag(a, ks, i);
         else if (i < TM + TN)
-            fb[set][i - TM] = load_b_frag(as, ks, i - TM);
+            fb[set][i - TM] = load_b_frag(b, ks, i - TM);
     };
     // loads return in order: tile T has landed once at most the loads of the `younger` tiles
     // issued after it are outstanding
@@ -330,16 +371,22 @@ __global__ __launch_bounds__(Cfg::NT) void fused_gemm_kernel(
     wait_tiles(min(nk, STAGES) - 1);
     wg_barrier();
 #pragma unroll
-    for (int i = 0; i < TM + TN; ++i) fetch_one(smem, 0, 0, i);
+    for (int i = 0; i < TM + TN; ++i) fetch_one(pa, pb, 0, 0, i);
 
     // one K tile: KS-1 ordinary k-steps, then the last one.  MORE: another tile follows.
     // REFILL: 0 = nothing to load, 1 = tile kt+STAGES is a full tile and its loads are
     // interleaved with the MFMAs, 2 = tile kt+STAGES is of any kind, loaded in one go.
-    auto k_tile = [&](int kt, auto more_c, auto refill_c) {
+    // SP: the tile's stage when the caller knows it (two stages, hot loop), -1 otherwise.
+    auto k_tile = [&](int kt, auto more_c, auto refill_c, auto sp_c) {
         constexpr bool MORE = decltype(more_c)::value;
         constexpr int REFILL = decltype(refill_c)::value;
-        unsigned char *as = stage_of(kt);
-        unsigned char *as_next = stage_of(kt + 1);
+        constexpr int SP = decltype(sp_c)::value;
+        unsigned char *as = SP >= 0 ? smem + SP * Cfg::STAGE : stage_of(kt);
+        const uint32_t (&ca)[TM] = SP < 0 ? ca_rt : (SP == 0 ? pa : pa1);
+        const uint32_t (&cb)[TN] = SP < 0 ? cb_rt : (SP == 0 ? pb : pb1);
+        const uint32_t (&na)[TM] = SP < 0 ? na_rt : (SP == 0 ? pa1 : pa);
+        const uint32_t (&nb)[TN] = SP < 0 ? nb_rt : (SP == 0 ? pb1 : pb);
+        if constexpr (MORE && SP < 0) stage_addresses(na_rt, nb_rt, kt + 1);
 #pragma unroll
         for (int ks = 0; ks < KS - 1; ++ks) {
             const int cur = ks & 1, nxt = cur ^ 1;
@@ -347,11 +394,11 @@ __global__ __launch_bounds__(Cfg::NT) void fused_gemm_kernel(
             for (int i = 0; i < TM * TN; ++i) {
                 acc[i / TN][i % TN] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
                     fa[cur][i / TN], fb[cur][i % TN], acc[i / TN][i % TN], 0, 0, 0);
-                fetch_one(as, ks + 1, nxt, i);
+                fetch_one(ca, cb, ks + 1, nxt, i);
                 __builtin_amdgcn_sched_barrier(0);
             }
 #pragma unroll
-            for (int i = TM * TN; i < TM + TN; ++i) fetch_one(as, ks + 1, nxt, i);
+            for (int i = TM * TN; i < TM + TN; ++i) fetch_one(ca, cb, ks + 1, nxt, i);
         }
         constexpr int cur = (KS - 1) & 1, nxt = cur ^ 1;
         if constexpr (MORE) {
@@ -368,14 +415,14 @@ __global__ __launch_bounds__(Cfg::NT) void fused_gemm_kernel(
         for (int i = 0; i < TM * TN; ++i) {
             acc[i / TN][i % TN] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
                 fa[cur][i / TN], fb[cur][i % TN], acc[i / TN][i % TN], 0, 0, 0);
-            if constexpr (MORE) fetch_one(as_next, 0, nxt, i);
+            if constexpr (MORE) fetch_one(na, nb, 0, nxt, i);
             if constexpr (REFILL == 1)
                 if (i < Cfg::LPW) issue_one(as, i);
             __builtin_amdgcn_sched_barrier(0);
         }
         if constexpr (MORE) {
 #pragma unroll
-            for (int i = TM * TN; i < TM + TN; ++i) fetch_one(as_next, 0, nxt, i);
+            for (int i = TM * TN; i < TM + TN; ++i) fetch_one(na, nb, 0, nxt, i);
         }
         if constexpr (REFILL == 1) {
 #pragma unroll
@@ -383,15 +430,29 @@ __global__ __launch_bounds__(Cfg::NT) void fused_gemm_kernel(
             a_base += BK * 2;
             b_base += b_step;
         }
+        if constexpr (MORE && SP < 0) {  // the next tile becomes the current one
+#pragma unroll
+            for (int tm = 0; tm < TM; ++tm) ca_rt[tm] = na_rt[tm];
+#pragma unroll
+            for (int tn = 0; tn < TN; ++tn) cb_rt[tn] = nb_rt[tn];
+        }
     };
     using I0 = std::integral_constant<int, 0>;
     using I1 = std::integral_constant<int, 1>;
     using I2 = std::integral_constant<int, 2>;
+    using RT = std::integral_constant<int, -1>;
     int kt = 0;
-    for (; kt + STAGES < nkf; ++kt) k_tile(kt, std::true_type{}, I1{});  // the hot loop
-    for (; kt + STAGES < nk; ++kt) k_tile(kt, std::true_type{}, I2{});   // last base + expand tiles
-    for (; kt + 1 < nk; ++kt) k_tile(kt, std::true_type{}, I0{});        // nothing left to load
-    k_tile(kt, std::false_type{}, I0{});
+    if constexpr (STAGES == 2) {  // the hot loop, two tiles per round: every copy knows its stage
+        for (; kt + 1 + STAGES < nkf; kt += 2) {
+            k_tile(kt, std::true_type{}, I1{}, I0{});
+            k_tile(kt + 1, std::true_type{}, I1{}, I1{});
+        }
+    }
+    stage_addresses(ca_rt, cb_rt, kt);
+    for (; kt + STAGES < nkf; ++kt) k_tile(kt, std::true_type{}, I1{}, RT{});  // the hot loop
+    for (; kt + STAGES < nk; ++kt) k_tile(kt, std::true_type{}, I2{}, RT{});   // last base + expand tiles
+    for (; kt + 1 < nk; ++kt) k_tile(kt, std::true_type{}, I0{}, RT{});        // nothing left to load
+    k_tile(kt, std::false_type{}, I0{}, RT{});
 
     // ---- epilogue: every row to its original position ----
     // acc[tm][tn][v]: row tm*32 + (v/4)*8 + (lane/32)*4 + v%4, column tn*32 + lane%32.
