@@ -4,8 +4,8 @@
 A step is one pass of the whole path over one batch of synthetic input that is already
 resident in HBM:  route (vocabulary or learned gate; skipped when r is given) -> bucket ->
 shrink -> fused base GEMM + expand, every call through the C ABI of libmolora.so (vocabulary
-routing and bucketing share one launch, molora_gate_dispatch, as in the paper's gating
-kernel).  The
+routing and bucketing share one launch, as in the paper's gating kernel; with a few narrow
+adapters, C * rank <= 64, the shrink shares that launch too: molora_gate_dispatch_shrink).  The
 default workload is configuration 1 (N = 4096 tokens, Qwen3-1.7B q_proj 2048 -> 2048, two
 adapters of rank 16, vocabulary-routed interleaved text/image runs).
 
@@ -168,7 +168,10 @@ def run_workload(args, workload, steps, warmup, full):
             d["r"] = torch.empty(sh.N, dtype=torch.int32, device="cuda")
             d["offsets"] = torch.empty(C + 1, dtype=torch.int32, device="cuda")
             d["perm"] = torch.empty(sh.N, dtype=torch.int32, device="cuda")
-            d["t"] = torch.empty((sh.N, 2 * rk), dtype=torch.bfloat16, device="cuda")
+            # a few narrow adapters: dispatch and shrink share one launch and the intermediate is
+            # in token order, all adapters side by side
+            d["dense"] = mb.molora_dense_shrink_supported(sh.N, sh.d_in, C, rk)
+            d["t"] = torch.empty((sh.N, 2 * rk * (C if d["dense"] else 1)), dtype=torch.bfloat16, device="cuda")
             d["sws"] = mb.molora_shrink_workspace(sh.N, sh.d_in, C, rk)  # None for most sizes
             d["h"] = torch.empty((sh.N, sh.d_out), dtype=torch.float32, device="cuda")
             S[s].append(d)
@@ -181,19 +184,31 @@ def run_workload(args, workload, steps, warmup, full):
             return mb.molora_route_vocab(d["v"], d["breaks"], d["r"], stream=stream)
         return d["r_given"]
 
+    def dispatch_and_shrink(d, stream=None):
+        if d["dense"]:  # gating / dispatch and the token-order shrink in ONE launch
+            if "v" in d:
+                mb.molora_gate_dispatch_shrink(d["v"], d["breaks"], d["x"], d["A"], None, 1, d["r"], d["offsets"],
+                                               d["perm"], d["t"], stream=stream)
+            else:
+                mb.molora_bucket_shrink(route(d, stream), d["x"], d["A"], d["offsets"], d["perm"], d["t"],
+                                        stream=stream)
+            return
+        if "v" in d:  # integer routing: gating inside the dispatch kernel (one launch)
+            mb.molora_gate_dispatch(d["v"], d["breaks"], None, 1, d["r"], d["offsets"], d["perm"], stream=stream)
+        else:
+            mb.molora_bucket(route(d, stream), d["shape"].C, d["offsets"], d["perm"], stream=stream)
+        mb.molora_shrink(d["x"], d["A"], d["offsets"], d["perm"], d["t"], workspace=d["sws"], stream=stream)
+
+    def gemm(d, stream=None):
+        f = mb.molora_base_expand_dense if d["dense"] else mb.molora_base_expand
+        f(d["x"], d["W"], d["B"], d["t"], d["offsets"], d["perm"], d["h"], stream=stream)
+
     def step(projs, ev=None, stream=None):
         for j, d in enumerate(projs):
-            if "v" in d:  # integer routing: gating inside the dispatch kernel (one launch)
-                mb.molora_gate_dispatch(d["v"], d["breaks"], None, 1, d["r"], d["offsets"], d["perm"],
-                                        stream=stream)
-            else:
-                r = route(d, stream)
-                mb.molora_bucket(r, d["shape"].C, d["offsets"], d["perm"], stream=stream)
-            mb.molora_shrink(d["x"], d["A"], d["offsets"], d["perm"], d["t"], workspace=d["sws"], stream=stream)
+            dispatch_and_shrink(d, stream)
             if ev is not None:
                 ev[2 * j].record()
-            mb.molora_base_expand(d["x"], d["W"], d["B"], d["t"], d["offsets"], d["perm"], d["h"],
-                                  stream=stream)
+            gemm(d, stream)
             if ev is not None:
                 ev[2 * j + 1].record()
 
@@ -317,12 +332,15 @@ def run_workload(args, workload, steps, warmup, full):
 
     breakdown = {}
     if full and not (args.timed_only and gemm_us is not None):
-        if "G" in S[0][0] or "v" in S[0][0]:
-            breakdown["route_us"] = timed_calls(lambda d: route(d))
-        rsrc = (lambda d: d["r"]) if ("G" in S[0][0] or "v" in S[0][0]) else (lambda d: d["r_given"])
-        breakdown["bucket_us"] = timed_calls(lambda d: mb.molora_bucket(rsrc(d), d["shape"].C, d["offsets"], d["perm"]))
-        breakdown["shrink_us"] = timed_calls(lambda d: mb.molora_shrink(d["x"], d["A"], d["offsets"], d["perm"], d["t"], workspace=d["sws"]))
-        breakdown["gemm_us"] = timed_calls(lambda d: mb.molora_base_expand(d["x"], d["W"], d["B"], d["t"], d["offsets"], d["perm"], d["h"]))
+        if S[0][0]["dense"]:
+            breakdown["dispatch_and_shrink_us"] = timed_calls(lambda d: dispatch_and_shrink(d))
+        else:
+            if "G" in S[0][0] or "v" in S[0][0]:
+                breakdown["route_us"] = timed_calls(lambda d: route(d))
+            rsrc = (lambda d: d["r"]) if ("G" in S[0][0] or "v" in S[0][0]) else (lambda d: d["r_given"])
+            breakdown["bucket_us"] = timed_calls(lambda d: mb.molora_bucket(rsrc(d), d["shape"].C, d["offsets"], d["perm"]))
+            breakdown["shrink_us"] = timed_calls(lambda d: mb.molora_shrink(d["x"], d["A"], d["offsets"], d["perm"], d["t"], workspace=d["sws"]))
+        breakdown["gemm_us"] = timed_calls(lambda d: gemm(d))
 
     work = None
     n_routed_all, touched_all = [], []

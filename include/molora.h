@@ -200,6 +200,42 @@ molora_status molora_base_expand(const void *x, const void *W, const void *B, co
                                  void *stream);
 
 /*
+ * Dispatch and shrink in ONE launch, for layers with a few narrow adapters (Alg. "Unified
+ * Dispatch Kernel" / Alg. "Compositional Gating Kernel" beside the shrink of Eq. "pertok").
+ * The grouped shrink needs the dispatch step's permutation, so the two normally run one after
+ * the other, each bound by latency on a batch of a few thousand tokens.  When C * rank <= 64
+ * (and N > 512) the shrink can do without the permutation: it computes x_i A_c for EVERY c in
+ * token order (the step is bound by reading x; the extra arithmetic costs nothing) and the
+ * expand step picks the row's adapter, so both steps fit one launch in which no workgroup
+ * waits for another.  molora_dense_shrink_supported says (1 / 0) whether the sizes qualify;
+ * the calls below return MOLORA_EINVAL when they do not.  molora_apply takes this path by
+ * itself.
+ *
+ *   molora_bucket_shrink:         r given -> offsets, perm as molora_bucket, and t
+ *   molora_gate_dispatch_shrink:  token ids (and request adapters) -> r, offsets, perm as
+ *                                 molora_gate_dispatch (C = n_adapters * M), and t
+ *   molora_base_expand_dense:     molora_base_expand reading that t
+ *
+ * t DEVICE bf16 [N][2 * C * rank], the TOKEN-ORDER intermediate: row i =
+ * [hi(x_i A_0) .. hi(x_i A_{C-1}) | lo(x_i A_0) .. lo(x_i A_{C-1})], hi = bf16(value),
+ * lo = bf16(value - hi).  Other arguments, ordering, err_flag and errors as in molora_bucket /
+ * molora_gate_dispatch / molora_shrink / molora_base_expand.
+ */
+int32_t molora_dense_shrink_supported(int64_t N, int32_t d_in, int32_t C, int32_t rank);
+molora_status molora_bucket_shrink(const int32_t *r, const void *x, const void *A, int32_t *offsets,
+                                   int32_t *perm, void *t, int64_t N, int32_t d_in, int32_t C,
+                                   int32_t rank, int32_t *err_flag, void *stream);
+molora_status molora_gate_dispatch_shrink(const int32_t *v, const int32_t *adapter,
+                                          const int32_t *breaks, int32_t M, int32_t n_adapters,
+                                          const void *x, const void *A, int32_t *r, int32_t *offsets,
+                                          int32_t *perm, void *t, int64_t N, int32_t d_in,
+                                          int32_t rank, int32_t *err_flag, void *stream);
+molora_status molora_base_expand_dense(const void *x, const void *W, const void *B, const void *t,
+                                       const int32_t *offsets, const int32_t *perm, float *h,
+                                       int64_t N, int32_t d_in, int32_t d_out, int32_t C,
+                                       int32_t rank, void *stream);
+
+/*
  * molora_base_expand with the height of the row tiles forced, for the tiling ablation (App.
  * "Adaptive Tiling", Table "tab:adaptive_tiling": tile shape chosen from the load against one
  * fixed shape).  tile_rows = 64 (the streaming kernel, W read once per 64-row tile), 128

@@ -16,7 +16,8 @@ MOLORA_OK = 0
 EXPORTS = ["molora_route", "molora_route_vocab", "molora_bucket", "molora_apply_workspace_bytes",
            "molora_apply", "molora_apply_bucketed", "molora_shrink", "molora_shrink_workspace_bytes",
            "molora_base_expand",
-           "molora_base_expand_fixed", "molora_init", "molora_apply_static", "molora_static_workspace_bytes",
+           "molora_base_expand_fixed", "molora_init", "molora_dense_shrink_supported", "molora_bucket_shrink",
+           "molora_gate_dispatch_shrink", "molora_base_expand_dense", "molora_apply_static", "molora_static_workspace_bytes",
            "molora_route_mlp_workspace_bytes", "molora_route_mlp", "molora_route_compose",
            "molora_gate_dispatch",
            "molora_apply_mix_workspace_bytes", "molora_apply_mix",
@@ -67,6 +68,15 @@ def load():
     lib.molora_apply_static.restype = ctypes.c_int
     lib.molora_static_workspace_bytes.argtypes = []
     lib.molora_static_workspace_bytes.restype = sz
+    lib.molora_dense_shrink_supported.argtypes = [i64, i32, i32, i32]
+    lib.molora_dense_shrink_supported.restype = ctypes.c_int32
+    lib.molora_bucket_shrink.argtypes = [vp, vp, vp, vp, vp, vp, i64, i32, i32, i32, vp, vp]
+    lib.molora_bucket_shrink.restype = ctypes.c_int
+    lib.molora_gate_dispatch_shrink.argtypes = [vp, vp, ctypes.POINTER(i32), i32, i32, vp, vp, vp, vp, vp, vp,
+                                                i64, i32, i32, vp, vp]
+    lib.molora_gate_dispatch_shrink.restype = ctypes.c_int
+    lib.molora_base_expand_dense.argtypes = [vp, vp, vp, vp, vp, vp, vp, i64, i32, i32, i32, i32, vp]
+    lib.molora_base_expand_dense.restype = ctypes.c_int
     lib.molora_init.argtypes = []
     lib.molora_init.restype = ctypes.c_int
     lib.molora_route_mlp_workspace_bytes.argtypes = [i64, i32]
@@ -274,6 +284,75 @@ def molora_base_expand(x, W, B, t, offsets, perm, h=None, stream=None, tile_rows
     else:
         st = load().molora_base_expand_fixed(*args, int(tile_rows), _stream(stream))
     _check(st, "molora_base_expand")
+    return h
+
+
+def molora_dense_shrink_supported(N, d_in, C, rank):
+    """Whether dispatch and shrink can run in one launch for these sizes (C * rank <= 64, N > 512)."""
+    return bool(load().molora_dense_shrink_supported(N, d_in, C, rank))
+
+
+def molora_bucket_shrink(r, x, A, offsets=None, perm=None, t=None, err_flag=None, stream=None):
+    """Dispatch (r given) and token-order shrink in one launch: (offsets, perm, t [N][2*C*rank])."""
+    N, d_in = x.shape
+    C, _, rank = A.shape
+    if offsets is None:
+        offsets = torch.empty(C + 1, dtype=torch.int32, device=x.device)
+    if perm is None:
+        perm = torch.empty(N, dtype=torch.int32, device=x.device)
+    if t is None:
+        t = torch.empty((N, 2 * C * rank), dtype=torch.bfloat16, device=x.device)
+    bf = torch.bfloat16
+    st = load().molora_bucket_shrink(_dev(r, torch.int32, "r"), _dev(x, bf, "x"), _dev(A, bf, "A"),
+                                     _dev(offsets, torch.int32, "offsets"), _dev(perm, torch.int32, "perm"),
+                                     _dev(t, bf, "t"), N, d_in, C, rank,
+                                     None if err_flag is None else _dev(err_flag, torch.int32, "err_flag"),
+                                     _stream(stream))
+    _check(st, "molora_bucket_shrink")
+    return offsets, perm, t
+
+
+def molora_gate_dispatch_shrink(v, breaks, x, A, adapter=None, n_adapters=1, r=None, offsets=None, perm=None,
+                                t=None, err_flag=None, stream=None):
+    """Vocabulary / compositional gating, dispatch and token-order shrink in one launch:
+    (r, offsets, perm, t [N][2*C*rank]) with C = n_adapters * M."""
+    N, d_in = x.shape
+    C, _, rank = A.shape
+    b = [int(q) for q in breaks]
+    M = len(b) - 1
+    if C != n_adapters * M:
+        raise ValueError("A must hold n_adapters * M adapters")
+    arr = (ctypes.c_int32 * len(b))(*b)
+    if r is None:
+        r = torch.empty(N, dtype=torch.int32, device=x.device)
+    if offsets is None:
+        offsets = torch.empty(C + 1, dtype=torch.int32, device=x.device)
+    if perm is None:
+        perm = torch.empty(N, dtype=torch.int32, device=x.device)
+    if t is None:
+        t = torch.empty((N, 2 * C * rank), dtype=torch.bfloat16, device=x.device)
+    bf = torch.bfloat16
+    st = load().molora_gate_dispatch_shrink(
+        _dev(v, torch.int32, "v"), None if adapter is None else _dev(adapter, torch.int32, "adapter"), arr, M,
+        n_adapters, _dev(x, bf, "x"), _dev(A, bf, "A"), _dev(r, torch.int32, "r"),
+        _dev(offsets, torch.int32, "offsets"), _dev(perm, torch.int32, "perm"), _dev(t, bf, "t"), N, d_in, rank,
+        None if err_flag is None else _dev(err_flag, torch.int32, "err_flag"), _stream(stream))
+    _check(st, "molora_gate_dispatch_shrink")
+    return r, offsets, perm, t
+
+
+def molora_base_expand_dense(x, W, B, t, offsets, perm, h=None, stream=None):
+    """molora_base_expand reading the token-order intermediate of the two calls above."""
+    N, d_in = x.shape
+    d_out = W.shape[1]
+    C, rank, _ = B.shape
+    if h is None:
+        h = torch.empty((N, d_out), dtype=torch.float32, device=x.device)
+    bf = torch.bfloat16
+    st = load().molora_base_expand_dense(_dev(x, bf, "x"), _dev(W, bf, "W"), _dev(B, bf, "B"), _dev(t, bf, "t"),
+                                         _dev(offsets, torch.int32, "offsets"), _dev(perm, torch.int32, "perm"),
+                                         _dev(h, torch.float32, "h"), N, d_in, d_out, C, rank, _stream(stream))
+    _check(st, "molora_base_expand_dense")
     return h
 
 

@@ -91,7 +91,9 @@ inline Workspace carve(void *base, int64_t N, int32_t d_in, int32_t C, int32_t r
     w.perm = reinterpret_cast<int32_t *>(p + off);
     off += round256(size_t(N) * sizeof(int32_t));
     w.t2 = reinterpret_cast<uint16_t *>(p + off);
-    off += round256(size_t(N) * 2 * size_t(rank) * sizeof(uint16_t));
+    // token-order form (dispatch and shrink in one launch): a row holds x A_c for every c
+    const size_t t_cols = molora::dense_shrink_ok(N, d_in, C, rank) ? size_t(C) * size_t(rank) : size_t(rank);
+    off += round256(size_t(N) * 2 * t_cols * sizeof(uint16_t));
     const size_t sb = molora::shrink_scratch_bytes(N, d_in, C, rank);
     w.shrink_scratch = sb ? reinterpret_cast<float *>(p + off) : nullptr;
     off += round256(sb);
@@ -120,7 +122,25 @@ molora_status apply_common(const void *x, const void *W, const void *A, const vo
 
     hipStream_t s = static_cast<hipStream_t>(stream);
     const uint16_t *xb = static_cast<const uint16_t *>(x);
+    const uint16_t *Ab = static_cast<const uint16_t *>(A);
     hipError_t e;
+    if (molora::dense_shrink_ok(N, d_in, C, rank)) {
+        // a few narrow adapters: dispatch and token-order shrink beside each other in one
+        // launch (the shrink alone when the bucketing is given), then the fused GEMM
+        const bool disp = r != nullptr;
+        e = molora::launch_dispatch_shrink(nullptr, nullptr, nullptr, 0, 0, const_cast<int32_t *>(r), xb, Ab,
+                                           disp ? ws.offsets : nullptr, disp ? ws.perm : nullptr, ws.t2, N,
+                                           d_in, C, rank, nullptr, s, disp);
+        if (e != hipSuccess) return MOLORA_EHIP;
+        if (disp) {
+            offsets = ws.offsets;
+            perm = ws.perm;
+        }
+        e = molora::launch_fused_gemm(xb, static_cast<const uint16_t *>(W),
+                                      static_cast<const uint16_t *>(B), ws.t2, offsets, perm, h, N,
+                                      d_in, d_out, C, rank, molora::Mix{1, C, nullptr, nullptr, 1}, s);
+        return from_hip(e);
+    }
     if (r != nullptr) {
         e = molora::launch_bucket(r, ws.offsets, ws.perm, N, C, nullptr, s);
         if (e != hipSuccess) return MOLORA_EHIP;
@@ -128,7 +148,7 @@ molora_status apply_common(const void *x, const void *W, const void *A, const vo
         perm = ws.perm;
     }
     const molora::Mix plain{1, C, nullptr, nullptr};
-    e = molora::launch_shrink(xb, static_cast<const uint16_t *>(A), offsets, perm, ws.t2, N, d_in,
+    e = molora::launch_shrink(xb, Ab, offsets, perm, ws.t2, N, d_in,
                               C, rank, plain, s, ws.shrink_scratch);
     if (e != hipSuccess) return MOLORA_EHIP;
     e = molora::launch_fused_gemm(xb, static_cast<const uint16_t *>(W),
@@ -268,8 +288,9 @@ namespace {
 molora_status base_expand_common(const void *x, const void *W, const void *B, const void *t,
                                  const int32_t *offsets, const int32_t *perm, float *h, int64_t N,
                                  int32_t d_in, int32_t d_out, int32_t C, int32_t rank, int tile,
-                                 void *stream) {
+                                 void *stream, bool t_dense = false) {
     if (!apply_sizes_ok(N, d_in, d_out, C, rank)) return MOLORA_EINVAL;
+    if (t_dense && !molora::dense_shrink_ok(N, d_in, C, rank)) return MOLORA_EINVAL;
     if (!molora::fused_gemm_sizes_ok(N, d_in, d_out, tile)) return MOLORA_EINVAL;
     if (N == 0) return MOLORA_OK;
     if (!x || !W || !B || !t || !offsets || !perm || !h) return MOLORA_EINVAL;
@@ -280,8 +301,8 @@ molora_status base_expand_common(const void *x, const void *W, const void *B, co
     return from_hip(molora::launch_fused_gemm(
         static_cast<const uint16_t *>(x), static_cast<const uint16_t *>(W),
         static_cast<const uint16_t *>(B), static_cast<const uint16_t *>(t), offsets, perm, h, N,
-        d_in, d_out, C, rank, molora::Mix{1, C, nullptr, nullptr}, static_cast<hipStream_t>(stream),
-        tile));
+        d_in, d_out, C, rank, molora::Mix{1, C, nullptr, nullptr, t_dense ? 1 : 0},
+        static_cast<hipStream_t>(stream), tile));
 }
 }  // namespace
 
@@ -299,6 +320,57 @@ molora_status molora_base_expand_fixed(const void *x, const void *W, const void 
     if (tile_rows != 64 && tile_rows != 128 && tile_rows != 256) return MOLORA_EINVAL;
     return base_expand_common(x, W, B, t, offsets, perm, h, N, d_in, d_out, C, rank, tile_rows,
                               stream);
+}
+
+int32_t molora_dense_shrink_supported(int64_t N, int32_t d_in, int32_t C, int32_t rank) {
+    return apply_sizes_ok(N, d_in, 8, C, rank) && molora::dense_shrink_ok(N, d_in, C, rank) ? 1 : 0;
+}
+
+molora_status molora_bucket_shrink(const int32_t *r, const void *x, const void *A, int32_t *offsets,
+                                   int32_t *perm, void *t, int64_t N, int32_t d_in, int32_t C,
+                                   int32_t rank, int32_t *err_flag, void *stream) {
+    if (!apply_sizes_ok(N, d_in, 8, C, rank) || !molora::dense_shrink_ok(N, d_in, C, rank))
+        return MOLORA_EINVAL;
+    if (!r || !x || !A || !offsets || !perm || !t) return MOLORA_EINVAL;
+    if (!aligned16(r) || !aligned16(x) || !aligned16(A) || !aligned16(offsets) || !aligned16(perm) ||
+        !aligned16(t))
+        return MOLORA_EALIGN;
+    if (molora::ensure_device_ready() != hipSuccess) return MOLORA_EHIP;
+    return from_hip(molora::launch_dispatch_shrink(
+        nullptr, nullptr, nullptr, 0, 0, const_cast<int32_t *>(r), static_cast<const uint16_t *>(x),
+        static_cast<const uint16_t *>(A), offsets, perm, static_cast<uint16_t *>(t), N, d_in, C, rank,
+        err_flag, static_cast<hipStream_t>(stream)));
+}
+
+molora_status molora_gate_dispatch_shrink(const int32_t *v, const int32_t *adapter,
+                                          const int32_t *breaks, int32_t M, int32_t n_adapters,
+                                          const void *x, const void *A, int32_t *r, int32_t *offsets,
+                                          int32_t *perm, void *t, int64_t N, int32_t d_in,
+                                          int32_t rank, int32_t *err_flag, void *stream) {
+    if (M < 1 || M > MOLORA_MAX_BREAKS || !breaks || n_adapters < 1 ||
+        int64_t(n_adapters) * M > MOLORA_MAX_TARGETS)
+        return MOLORA_EINVAL;
+    const int32_t C = n_adapters * M;
+    if (!apply_sizes_ok(N, d_in, 8, C, rank) || !molora::dense_shrink_ok(N, d_in, C, rank))
+        return MOLORA_EINVAL;
+    for (int j = 0; j < M; ++j)
+        if (breaks[j] >= breaks[j + 1]) return MOLORA_EINVAL;
+    if (!v || !x || !A || !r || !offsets || !perm || !t) return MOLORA_EINVAL;
+    if (!aligned16(v) || (adapter && !aligned16(adapter)) || !aligned16(x) || !aligned16(A) ||
+        !aligned16(r) || !aligned16(offsets) || !aligned16(perm) || !aligned16(t))
+        return MOLORA_EALIGN;
+    if (molora::ensure_device_ready() != hipSuccess) return MOLORA_EHIP;
+    return from_hip(molora::launch_dispatch_shrink(
+        v, adapter, breaks, M, n_adapters, r, static_cast<const uint16_t *>(x),
+        static_cast<const uint16_t *>(A), offsets, perm, static_cast<uint16_t *>(t), N, d_in, C, rank,
+        err_flag, static_cast<hipStream_t>(stream)));
+}
+
+molora_status molora_base_expand_dense(const void *x, const void *W, const void *B, const void *t,
+                                       const int32_t *offsets, const int32_t *perm, float *h,
+                                       int64_t N, int32_t d_in, int32_t d_out, int32_t C,
+                                       int32_t rank, void *stream) {
+    return base_expand_common(x, W, B, t, offsets, perm, h, N, d_in, d_out, C, rank, 0, stream, true);
 }
 
 size_t molora_route_mlp_workspace_bytes(int64_t N, int32_t H) {

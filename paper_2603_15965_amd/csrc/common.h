@@ -43,6 +43,10 @@ struct Mix {
     int C;
     const int32_t *slots;
     const float *w;
+    // 1: the low-rank intermediate is in the token-order form of the dense shrink, row of token
+    // i = [x_i A_0 .. x_i A_{C-1} as bf16 high parts | the same as remainders], 2 * C * rank
+    // values (k = 1, no slot table); 0: one row of 2 * k * rank values per sorted position
+    int t_dense;
 };
 __device__ __forceinline__ int mix_adapter(const Mix &m, int b, int j) {
     int c = b;
@@ -74,6 +78,19 @@ hipError_t ensure_device_ready();
 // the tiled GEMM keeps per-lane byte offsets into x and W in 32 bits: false when the kernel
 // that launch_fused_gemm would pick for these sizes (force_tile as there) cannot address them
 bool fused_gemm_sizes_ok(int64_t N, int d_in, int d_out, int force_tile = 0);
+
+// Sizes for which the dispatch step and the shrink run beside each other in one launch
+// (launch_dispatch_shrink) and the fused GEMM reads the token-order intermediate: a few narrow
+// adapters (C * rank <= 64, so that computing x A_c for every c costs the memory-bound shrink
+// nothing) and a batch that takes the tiled GEMM.
+bool dense_shrink_ok(int64_t N, int d_in, int C, int rank);
+// Gating (v != nullptr: vocabulary / composite target as launch_gate_bucket, r is then an
+// output; else r is the input) + dispatch + token-order shrink in one launch.
+hipError_t launch_dispatch_shrink(const int32_t *v, const int32_t *adapter, const int32_t *breaks_host,
+                                  int M, int n_adapters, int32_t *r, const uint16_t *x,
+                                  const uint16_t *A, int32_t *offsets, int32_t *perm, uint16_t *t_dense,
+                                  int64_t N, int d_in, int C, int rank, int32_t *err_flag, hipStream_t s,
+                                  bool with_dispatch = true);  // false: the token-order shrink alone
 
 // ---- launchers implemented in the kernel translation units (all asynchronous) ----
 // rank is the rank of one adapter; buckets number C (the tuples, when mix.k > 1)

@@ -51,7 +51,7 @@ struct GemmCfg {
     static constexpr int A_PIECES = BM / A_RPI, B_PIECES = BK / B_RPI;
     static constexpr int LPW = (A_PIECES + B_PIECES) / NW;  // pieces (loads) per wavefront and tile
     static constexpr int A_BYTES = BM * A_RB, B_BYTES = BK * B_RB, STAGE = A_BYTES + B_BYTES;
-    static constexpr size_t LDS_BYTES = (size_t)STAGES * STAGE + 7 * BM * sizeof(int32_t) + 16;
+    static constexpr size_t LDS_BYTES = (size_t)STAGES * STAGE + 8 * BM * sizeof(int32_t) + 16;
     static_assert(BK == 32 || BK == 64, "BK");
     static_assert(LPW * NW == A_PIECES + B_PIECES && LPW >= 1, "pieces split evenly over wavefronts");
     static_assert(STAGES >= 2 && STAGES <= 4, "stages");
@@ -91,6 +91,7 @@ __global__ __launch_bounds__(Cfg::NT) void fused_gemm_kernel(
     int32_t *seg_hi = seg_lo + BM;
     int32_t *nseg_p = seg_hi + BM;
     int32_t *seg_ad = nseg_p + 4;  // [BM][4] pool positions of the adapters of a bucket's tuple
+    int32_t *seg_c = seg_ad + 4 * BM;  // [BM] the buckets' indices (the token-order intermediate is addressed by them)
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -218,6 +219,7 @@ __global__ __launch_bounds__(Cfg::NT) void fused_gemm_kernel(
             const int idx = atomicAdd(nseg_p, 1);
             seg_lo[idx] = lo;
             seg_hi[idx] = hi;
+            seg_c[idx] = c;
             // slot table and tuple decoded once here, not inside the K loop
             for (int j = 0; j < mix.k; ++j) seg_ad[idx * 4 + j] = mix_adapter(mix, c, j);
         }
@@ -250,7 +252,16 @@ __global__ __launch_bounds__(Cfg::NT) void fused_gemm_kernel(
             slot_geom(i, row, col);
             if (slot_is_a(i)) {
                 const int p = p0 + row, vk = sub * BK + col * 8;
-                src = (p >= lo && p < hi && vk < two_r) ? t2 + (int64_t)p * two_r + vk : zero;
+                const bool own = p >= lo && p < hi && vk < two_r;
+                if (mix.t_dense) {
+                    // token-order intermediate: the row of this token, the bucket's adapter;
+                    // high parts in the first C * rank values, remainders in the second
+                    const int64_t trow = (int64_t)max(tile_perm[row], 0) * (2 * mix.C * rank);
+                    const int in_half = vk < rank ? vk : vk - rank;
+                    src = own ? t2 + trow + (vk < rank ? 0 : mix.C * rank) + seg_c[sg] * rank + in_half : zero;
+                } else {
+                    src = own ? t2 + (int64_t)p * two_r + vk : zero;
+                }
             } else {
                 const int vk = sub * BK + row;
                 const int j = vk < R ? vk : vk - R;        // row of the tuple's stacked B
@@ -540,6 +551,9 @@ hipError_t launch_fused_gemm(const uint16_t *x, const uint16_t *W, const uint16_
                              float *h, int64_t N, int d_in, int d_out, int C, int rank, Mix mix,
                              hipStream_t s, int force_tile) {
     if (N == 0) return hipSuccess;
+    // the token-order intermediate is read by the tiled kernel only
+    if (mix.t_dense && (force_tile == 64 || (force_tile == 0 && N <= kSmallBatchMax) || mix.k != 1))
+        return hipErrorInvalidValue;
 #define MOLORA_GEMM_ARGS x, W, B, t2, offsets, perm, h, N, d_in, d_out, C, rank, mix, s
     if (force_tile == 64) return launch_small_batch_gemm(MOLORA_GEMM_ARGS);
     if (force_tile == 128) return launch_cfg<GemmSmall>(MOLORA_GEMM_ARGS);

@@ -155,6 +155,90 @@ def test_apply_small_shapes(gpu, N, d_in, d_out, C, rank, structure):
     gpu.assert_h_close(h, oracle.apply(w.x, w.W, w.A, w.B, w.r), "apply")
 
 
+@pytest.mark.parametrize("N,d_in,d_out,C,rank,structure", [
+    (1500, 520, 392, 4, 16, "uniform"),     # C * rank = 64, ragged K tail, 128 x 128 tiles
+    (700, 256, 264, 2, 32, "zipf"),         # two wide adapters, three-stage tiles
+    (3000, 264, 520, 8, 8, "uniform"),      # eight rank-8 adapters
+    (600, 1096, 136, 1, 64, "uniform"),     # one adapter of rank 64
+    (2500, 128, 4000, 3, 8, "zipf"),        # 256 x 256 tiles, C * rank = 24 (padded to 32 columns)
+    (5000, 328, 264, 5, 8, "uniform"),      # five dispatch workgroups, 40 columns
+    (20000, 136, 136, 2, 16, "uniform"),    # sixteen dispatch workgroups, 32-row shrink items
+])
+def test_apply_few_narrow_adapters_one_launch_dispatch_and_shrink(gpu, N, d_in, d_out, C, rank, structure):
+    """C * rank <= 64 and N > 512: molora_apply runs dispatch and token-order shrink in one
+    launch.  The pieces are checked one by one (offsets and perm bit for bit, also with targets
+    out of range; t against the float64 product) and the whole against the oracle."""
+    import oracle
+    import torch
+    from paper_2603_15965_amd import binding as mb
+    say(f"dense shrink path N={N} {d_in}->{d_out} C={C} rank={rank} {structure}")
+    assert mb.molora_dense_shrink_supported(N, d_in, C, rank)
+    w = wl.custom("d", N, d_in, d_out, C, rank, 7300 + N, structure=structure)
+    r = w.r.copy()
+    r[5::23] = -1
+    r[7::31] = C
+    x, W, A, B = (gpu.dev_bf16(t) for t in (w.x, w.W, w.A, w.B))
+    flag = torch.zeros(1, dtype=torch.int32, device="cuda")
+    offsets, perm, t = mb.molora_bucket_shrink(gpu.dev_i32(r), x, A, err_flag=flag)
+    torch.cuda.synchronize()
+    o_ref, p_ref, bad = oracle.bucket(r, C)
+    assert np.array_equal(offsets.cpu().numpy(), o_ref) and np.array_equal(perm.cpu().numpy(), p_ref)
+    assert int(flag.item()) == 1 and bad > 0
+    # t = hi + lo against x A_c in float64, every token and every adapter (two bf16 halves carry
+    # 16 significant bits: 2^-17 |t| = 3e-5 at |t| = 4, plus the fp32 sum's ~1e-6)
+    tt = t.float().cpu().numpy().astype(np.float64).reshape(N, 2, C, rank)
+    x64 = wl.bf16_bits_to_f32(w.x).astype(np.float64)
+    for c in range(C):
+        ref_t = x64 @ wl.bf16_bits_to_f32(w.A[c]).astype(np.float64)
+        got_t = tt[:, 0, c, :] + tt[:, 1, c, :]
+        assert np.max(np.abs(got_t - ref_t) / np.maximum(1.0, np.abs(ref_t))) <= 2e-5, f"t of adapter {c}"
+    h = mb.molora_base_expand_dense(x, W, B, t, offsets, perm)
+    torch.cuda.synchronize()
+    ref = oracle.apply(w.x, w.W, w.A, w.B, r)
+    gpu.assert_h_close(h.cpu().numpy(), ref, "dispatch+shrink, then expand")
+    h2 = gpu.gpu_apply(w, r)
+    assert torch.equal(h, h2), "molora_apply takes the same path"
+    h3 = gpu.gpu_apply(w, r, bucketed=True)
+    assert torch.equal(h, h3), "molora_apply_bucketed: the token-order shrink alone, same bits"
+
+
+def test_gate_dispatch_shrink_matches_separate_calls(gpu):
+    """Gating + dispatch + shrink in one launch on configuration 1's shape and on composite
+    targets: r, offsets, perm bit for bit as the oracle's, h as the oracle's."""
+    import oracle
+    import torch
+    from paper_2603_15965_amd import binding as mb
+    say("gate_dispatch_shrink")
+    w = wl.make(wl.shapes()["vocab_q17"])
+    x, W, A, B = (gpu.dev_bf16(t) for t in (w.x, w.W, w.A, w.B))
+    r, offsets, perm, t = mb.molora_gate_dispatch_shrink(gpu.dev_i32(w.v), w.breaks, x, A)
+    h = mb.molora_base_expand_dense(x, W, B, t, offsets, perm)
+    torch.cuda.synchronize()
+    r_ref = oracle.route_vocab(w.v, w.breaks)
+    o_ref, p_ref, _ = oracle.bucket(r_ref, 2)
+    assert np.array_equal(r.cpu().numpy(), r_ref)
+    assert np.array_equal(offsets.cpu().numpy(), o_ref) and np.array_equal(perm.cpu().numpy(), p_ref)
+    gpu.assert_h_close(h.cpu().numpy(), oracle.apply(w.x, w.W, w.A, w.B, r_ref), "config 1, one-launch dispatch")
+    # composite targets a * M + m, some invalid
+    rng = np.random.default_rng(77)
+    N, n_ad, breaks = 3001, 3, (0, 1000, 5000)
+    wc = wl.custom("dc", N, 264, 200, n_ad * 2, 8, 7400)
+    v = rng.integers(-50, 5100, size=N).astype(np.int32)
+    a = rng.integers(-1, n_ad + 1, size=N).astype(np.int32)
+    xc, Wc, Ac, Bc = (gpu.dev_bf16(q) for q in (wc.x, wc.W, wc.A, wc.B))
+    flag = torch.zeros(1, dtype=torch.int32, device="cuda")
+    r, offsets, perm, t = mb.molora_gate_dispatch_shrink(gpu.dev_i32(v), breaks, xc, Ac, adapter=gpu.dev_i32(a),
+                                                         n_adapters=n_ad, err_flag=flag)
+    h = mb.molora_base_expand_dense(xc, Wc, Bc, t, offsets, perm)
+    torch.cuda.synchronize()
+    r_ref = oracle.route_compose(v, a, np.array(breaks, dtype=np.int32), n_ad)
+    o_ref, p_ref, bad = oracle.bucket(r_ref, n_ad * 2)
+    assert np.array_equal(r.cpu().numpy(), r_ref)
+    assert np.array_equal(offsets.cpu().numpy(), o_ref) and np.array_equal(perm.cpu().numpy(), p_ref)
+    assert int(flag.item()) == (1 if bad else 0)
+    gpu.assert_h_close(h.cpu().numpy(), oracle.apply(wc.x, wc.W, wc.A, wc.B, r_ref), "composite targets")
+
+
 def test_apply_tokens_without_adapter_get_base_only(gpu):
     import oracle
     say("apply with out-of-range targets")
