@@ -120,62 +120,117 @@ def _check(status, what):
         raise MoloraError(status, what)
 
 
-def _dev(t, dtype, name):
-    if not isinstance(t, torch.Tensor) or not t.is_cuda:
-        raise TypeError(f"{name} must be a device tensor")
-    if t.dtype != dtype:
-        raise TypeError(f"{name} must be {dtype}, got {t.dtype}")
-    if not t.is_contiguous():
-        raise ValueError(f"{name} must be contiguous")
-    return t.data_ptr()
+class _T:
+    """A tensor argument: what the library will take it for (dtype, shape), checked by _call."""
+
+    def __init__(self, t, dtype, name, shape=None):
+        self.t, self.dtype, self.name = t, dtype, name
+        self.shape = None if shape is None else tuple(int(q) for q in shape)
 
 
-def _stream(stream):
+def _dev(t, dtype, name, shape=None):
+    return _T(t, dtype, name, shape)
+
+
+def _call(fn, *args):
+    """Call the library function `fn` with tensors given as _T.  The C ABI gets plain pointers
+    and sizes: a tensor smaller than the sizes passed beside it would be read or written past
+    its end by the kernels, so every tensor's type, shape and layout is checked first, for all
+    arguments (host tensors included: shape errors come before the complaint that a tensor is
+    not on the device), and nothing is launched unless all of them pass."""
+    specs = [a for a in args if isinstance(a, _T)]
+    for a in specs:
+        if not isinstance(a.t, torch.Tensor):
+            raise TypeError(f"{a.name} must be a tensor")
+        if a.shape is not None and tuple(a.t.shape) != a.shape:
+            raise ValueError(f"{a.name} must have shape {a.shape}, got {tuple(a.t.shape)}")
+        if a.t.dtype != a.dtype:
+            raise TypeError(f"{a.name} must be {a.dtype}, got {a.t.dtype}")
+        if not a.t.is_contiguous():
+            raise ValueError(f"{a.name} must be contiguous")
+    for a in specs:
+        if not a.t.is_cuda:
+            raise TypeError(f"{a.name} must be a device tensor")
+    raw = [a.t.data_ptr() if isinstance(a, _T) else _stream_now(a.stream) if isinstance(a, _S) else a
+           for a in args]
+    st = getattr(load(), fn)(*raw)
+    if st != MOLORA_OK:
+        raise MoloraError(st, fn)
+
+
+def _stream_now(stream):
     if stream is None:
         return torch.cuda.current_stream().cuda_stream
     return stream.cuda_stream if hasattr(stream, "cuda_stream") else int(stream)
 
 
+class _S:
+    """The stream argument of a _call, resolved after the tensors have been checked."""
+
+    def __init__(self, stream):
+        self.stream = stream
+
+
+def _stream(stream):
+    return _S(stream)
+
+
+def _two(t, name):
+    if not isinstance(t, torch.Tensor) or t.dim() != 2:
+        raise ValueError(f"{name} must be a 2-D tensor")
+    return int(t.shape[0]), int(t.shape[1])
+
+
+def _three(t, name):
+    if not isinstance(t, torch.Tensor) or t.dim() != 3:
+        raise ValueError(f"{name} must be a 3-D tensor")
+    return int(t.shape[0]), int(t.shape[1]), int(t.shape[2])
+
+
+def _breaks(breaks):
+    b = [int(q) for q in breaks]
+    if len(b) < 2:
+        raise ValueError("breaks must hold at least two boundaries")
+    return (ctypes.c_int32 * len(b))(*b), len(b) - 1
+
+
+def _opt(t, dtype, name, shape=None):
+    return None if t is None else _dev(t, dtype, name, shape)
+
+
 def molora_route(x, G, r=None, stream=None):
     """r[i] = argmax_c x[i] . G[:, c] (fp32 ascending-k chain, lowest index on ties)."""
-    N, d_in = x.shape
-    C = G.shape[1]
-    if G.shape[0] != d_in:
-        raise ValueError("G must be [d_in][C]")
+    N, d_in = _two(x, "x")
+    C = _two(G, "G")[1]
     if r is None:
         r = torch.empty(N, dtype=torch.int32, device=x.device)
-    st = load().molora_route(_dev(x, torch.bfloat16, "x"), _dev(G, torch.bfloat16, "G"),
-                             _dev(r, torch.int32, "r"), N, d_in, C, _stream(stream))
-    _check(st, "molora_route")
+    _call("molora_route", _dev(x, torch.bfloat16, "x"), _dev(G, torch.bfloat16, "G", (d_in, C)),
+                             _dev(r, torch.int32, "r", (N,)), N, d_in, C, _stream(stream))
     return r
 
 
 def molora_route_vocab(v, breaks, r=None, stream=None):
     """r[i] = m with breaks[m] <= v[i] < breaks[m+1], else -1.  breaks: host ints."""
-    N = v.shape[0]
-    b = [int(t) for t in breaks]
-    M = len(b) - 1
-    arr = (ctypes.c_int32 * len(b))(*b)
+    N = int(v.shape[0])
+    arr, M = _breaks(breaks)
     if r is None:
         r = torch.empty(N, dtype=torch.int32, device=v.device)
-    st = load().molora_route_vocab(_dev(v, torch.int32, "v"), arr, M, _dev(r, torch.int32, "r"), N,
+    _call("molora_route_vocab", _dev(v, torch.int32, "v", (N,)), arr, M, _dev(r, torch.int32, "r", (N,)), N,
                                    _stream(stream))
-    _check(st, "molora_route_vocab")
     return r
 
 
 def molora_bucket(r, C, offsets=None, perm=None, err_flag=None, stream=None):
     """Stable grouping of tokens by target: returns (offsets[C+1], perm[N])."""
-    N = r.shape[0]
+    N = int(r.shape[0])
+    C = int(C)
     if offsets is None:
         offsets = torch.empty(C + 1, dtype=torch.int32, device=r.device)
     if perm is None:
         perm = torch.empty(max(N, 1), dtype=torch.int32, device=r.device)[:N]
-    st = load().molora_bucket(_dev(r, torch.int32, "r"), _dev(offsets, torch.int32, "offsets"),
-                              _dev(perm, torch.int32, "perm"), N, C,
-                              None if err_flag is None else _dev(err_flag, torch.int32, "err_flag"),
-                              _stream(stream))
-    _check(st, "molora_bucket")
+    _call("molora_bucket", _dev(r, torch.int32, "r", (N,)), _dev(offsets, torch.int32, "offsets", (C + 1,)),
+                              _dev(perm, torch.int32, "perm", (N,)), N, C,
+                              _opt(err_flag, torch.int32, "err_flag"), _stream(stream))
     return offsets, perm
 
 
@@ -184,9 +239,10 @@ def molora_apply_workspace_bytes(N, d_in, d_out, C, rank):
 
 
 def _shapes(x, W, A, B):
-    N, d_in = x.shape
-    d_out = W.shape[1]
-    C, _, rank = A.shape
+    N, d_in = _two(x, "x")
+    d_out = _two(W, "W")[1]
+    C, _, rank = _three(A, "A")
+    _three(B, "B")
     if W.shape[0] != d_in or A.shape[1] != d_in or tuple(B.shape) != (C, rank, d_out):
         raise ValueError("expected W [d_in][d_out], A [C][d_in][rank], B [C][rank][d_out]")
     return N, d_in, d_out, C, rank
@@ -197,6 +253,12 @@ def new_workspace(N, d_in, d_out, C, rank, device="cuda"):
     return torch.empty(max(nbytes, 256), dtype=torch.uint8, device=device)
 
 
+def _flat_bytes(t, name):
+    if not isinstance(t, torch.Tensor) or t.dim() != 1:
+        raise ValueError(f"{name} must be a 1-D uint8 tensor")
+    return _dev(t, torch.uint8, name), t.numel()
+
+
 def molora_apply(x, W, A, B, r, h=None, workspace=None, stream=None):
     """h[i] = x[i] W + (x[i] A[r[i]]) B[r[i]]  (fp32 [N][d_out])."""
     N, d_in, d_out, C, rank = _shapes(x, W, A, B)
@@ -205,11 +267,10 @@ def molora_apply(x, W, A, B, r, h=None, workspace=None, stream=None):
     if workspace is None:
         workspace = new_workspace(N, d_in, d_out, C, rank, x.device)
     bf = torch.bfloat16
-    st = load().molora_apply(_dev(x, bf, "x"), _dev(W, bf, "W"), _dev(A, bf, "A"), _dev(B, bf, "B"),
-                             _dev(r, torch.int32, "r"), _dev(h, torch.float32, "h"),
-                             N, d_in, d_out, C, rank, _dev(workspace, torch.uint8, "workspace"),
-                             workspace.numel(), _stream(stream))
-    _check(st, "molora_apply")
+    ws, ws_bytes = _flat_bytes(workspace, "workspace")
+    _call("molora_apply", _dev(x, bf, "x"), _dev(W, bf, "W"), _dev(A, bf, "A"), _dev(B, bf, "B"),
+                             _dev(r, torch.int32, "r", (N,)), _dev(h, torch.float32, "h", (N, d_out)),
+                             N, d_in, d_out, C, rank, ws, ws_bytes, _stream(stream))
     return h
 
 
@@ -218,11 +279,10 @@ def molora_apply_static(x, W, A, B, r, h, stream=None):
     allocation anywhere in the call, so h must be supplied."""
     N, d_in, d_out, C, rank = _shapes(x, W, A, B)
     bf = torch.bfloat16
-    st = load().molora_apply_static(_dev(x, bf, "x"), _dev(W, bf, "W"), _dev(A, bf, "A"),
-                                    _dev(B, bf, "B"), _dev(r, torch.int32, "r"),
-                                    _dev(h, torch.float32, "h"), N, d_in, d_out, C, rank,
+    _call("molora_apply_static", _dev(x, bf, "x"), _dev(W, bf, "W"), _dev(A, bf, "A"),
+                                    _dev(B, bf, "B"), _dev(r, torch.int32, "r", (N,)),
+                                    _dev(h, torch.float32, "h", (N, d_out)), N, d_in, d_out, C, rank,
                                     _stream(stream))
-    _check(st, "molora_apply_static")
     return h
 
 
@@ -234,12 +294,11 @@ def molora_apply_bucketed(x, W, A, B, offsets, perm, h=None, workspace=None, str
     if workspace is None:
         workspace = new_workspace(N, d_in, d_out, C, rank, x.device)
     bf = torch.bfloat16
-    st = load().molora_apply_bucketed(
+    ws, ws_bytes = _flat_bytes(workspace, "workspace")
+    _call("molora_apply_bucketed", 
         _dev(x, bf, "x"), _dev(W, bf, "W"), _dev(A, bf, "A"), _dev(B, bf, "B"),
-        _dev(offsets, torch.int32, "offsets"), _dev(perm, torch.int32, "perm"),
-        _dev(h, torch.float32, "h"), N, d_in, d_out, C, rank,
-        _dev(workspace, torch.uint8, "workspace"), workspace.numel(), _stream(stream))
-    _check(st, "molora_apply_bucketed")
+        _dev(offsets, torch.int32, "offsets", (C + 1,)), _dev(perm, torch.int32, "perm", (N,)),
+        _dev(h, torch.float32, "h", (N, d_out)), N, d_in, d_out, C, rank, ws, ws_bytes, _stream(stream))
     return h
 
 
@@ -252,38 +311,43 @@ def molora_shrink_workspace(N, d_in, C, rank, device="cuda"):
 def molora_shrink(x, A, offsets, perm, t=None, workspace="auto", stream=None):
     """t[p] = x[perm[p]] A_c as [hi | lo] bf16 halves, [N][2*rank].  workspace: a tensor from
     molora_shrink_workspace, None (never split K over workgroups) or "auto" (allocate)."""
-    N, d_in = x.shape
-    C, _, rank = A.shape
+    N, d_in = _two(x, "x")
+    C, _, rank = _three(A, "A")
     if t is None:
         t = torch.empty((N, 2 * rank), dtype=torch.bfloat16, device=x.device)
     if isinstance(workspace, str):
         workspace = molora_shrink_workspace(N, d_in, C, rank, x.device)
     bf = torch.bfloat16
-    st = load().molora_shrink(_dev(x, bf, "x"), _dev(A, bf, "A"), _dev(offsets, torch.int32, "offsets"),
-                              _dev(perm, torch.int32, "perm"), _dev(t, bf, "t"), N, d_in, C, rank,
-                              None if workspace is None else _dev(workspace, torch.uint8, "workspace"),
-                              0 if workspace is None else workspace.numel(), _stream(stream))
-    _check(st, "molora_shrink")
+    ws, ws_bytes = (None, 0) if workspace is None else _flat_bytes(workspace, "workspace")
+    _call("molora_shrink", _dev(x, bf, "x"), _dev(A, bf, "A", (C, d_in, rank)),
+                              _dev(offsets, torch.int32, "offsets", (C + 1,)),
+                              _dev(perm, torch.int32, "perm", (N,)), _dev(t, bf, "t", (N, 2 * rank)),
+                              N, d_in, C, rank, ws, ws_bytes, _stream(stream))
     return t
+
+
+def _base_expand_args(x, W, B, t, offsets, perm, h, t_cols):
+    N, d_in = _two(x, "x")
+    d_out = _two(W, "W")[1]
+    C, rank, _ = _three(B, "B")
+    if h is None:
+        h = torch.empty((N, d_out), dtype=torch.float32, device=x.device)
+    bf = torch.bfloat16
+    args = [_dev(x, bf, "x"), _dev(W, bf, "W", (d_in, d_out)), _dev(B, bf, "B", (C, rank, d_out)),
+            _dev(t, bf, "t", (N, t_cols(C, rank))), _dev(offsets, torch.int32, "offsets", (C + 1,)),
+            _dev(perm, torch.int32, "perm", (N,)), _dev(h, torch.float32, "h", (N, d_out)),
+            N, d_in, d_out, C, rank]
+    return args, h
 
 
 def molora_base_expand(x, W, B, t, offsets, perm, h=None, stream=None, tile_rows=None):
     """h[perm[p]] = x[perm[p]] W + t_p B_c, every row written once.  tile_rows (64, 128 or
     256) forces the row-tile height (molora_base_expand_fixed, for the tiling ablation)."""
-    N, d_in = x.shape
-    d_out = W.shape[1]
-    C, rank, _ = B.shape
-    if h is None:
-        h = torch.empty((N, d_out), dtype=torch.float32, device=x.device)
-    bf = torch.bfloat16
-    args = [_dev(x, bf, "x"), _dev(W, bf, "W"), _dev(B, bf, "B"), _dev(t, bf, "t"),
-            _dev(offsets, torch.int32, "offsets"), _dev(perm, torch.int32, "perm"),
-            _dev(h, torch.float32, "h"), N, d_in, d_out, C, rank]
+    args, h = _base_expand_args(x, W, B, t, offsets, perm, h, lambda C, rank: 2 * rank)
     if tile_rows is None:
-        st = load().molora_base_expand(*args, _stream(stream))
+        _call("molora_base_expand", *args, _stream(stream))
     else:
-        st = load().molora_base_expand_fixed(*args, int(tile_rows), _stream(stream))
-    _check(st, "molora_base_expand")
+        _call("molora_base_expand_fixed", *args, int(tile_rows), _stream(stream))
     return h
 
 
@@ -292,23 +356,28 @@ def molora_dense_shrink_supported(N, d_in, C, rank):
     return bool(load().molora_dense_shrink_supported(N, d_in, C, rank))
 
 
+def _dense_outputs(N, C, rank, offsets, perm, t, device):
+    if offsets is None:
+        offsets = torch.empty(C + 1, dtype=torch.int32, device=device)
+    if perm is None:
+        perm = torch.empty(N, dtype=torch.int32, device=device)
+    if t is None:
+        t = torch.empty((N, 2 * C * rank), dtype=torch.bfloat16, device=device)
+    return offsets, perm, t
+
+
 def molora_bucket_shrink(r, x, A, offsets=None, perm=None, t=None, err_flag=None, stream=None):
     """Dispatch (r given) and token-order shrink in one launch: (offsets, perm, t [N][2*C*rank])."""
-    N, d_in = x.shape
-    C, _, rank = A.shape
-    if offsets is None:
-        offsets = torch.empty(C + 1, dtype=torch.int32, device=x.device)
-    if perm is None:
-        perm = torch.empty(N, dtype=torch.int32, device=x.device)
-    if t is None:
-        t = torch.empty((N, 2 * C * rank), dtype=torch.bfloat16, device=x.device)
+    N, d_in = _two(x, "x")
+    C, _, rank = _three(A, "A")
+    offsets, perm, t = _dense_outputs(N, C, rank, offsets, perm, t, x.device)
     bf = torch.bfloat16
-    st = load().molora_bucket_shrink(_dev(r, torch.int32, "r"), _dev(x, bf, "x"), _dev(A, bf, "A"),
-                                     _dev(offsets, torch.int32, "offsets"), _dev(perm, torch.int32, "perm"),
-                                     _dev(t, bf, "t"), N, d_in, C, rank,
-                                     None if err_flag is None else _dev(err_flag, torch.int32, "err_flag"),
-                                     _stream(stream))
-    _check(st, "molora_bucket_shrink")
+    _call("molora_bucket_shrink", _dev(r, torch.int32, "r", (N,)), _dev(x, bf, "x"),
+                                     _dev(A, bf, "A", (C, d_in, rank)),
+                                     _dev(offsets, torch.int32, "offsets", (C + 1,)),
+                                     _dev(perm, torch.int32, "perm", (N,)),
+                                     _dev(t, bf, "t", (N, 2 * C * rank)), N, d_in, C, rank,
+                                     _opt(err_flag, torch.int32, "err_flag"), _stream(stream))
     return offsets, perm, t
 
 
@@ -316,43 +385,28 @@ def molora_gate_dispatch_shrink(v, breaks, x, A, adapter=None, n_adapters=1, r=N
                                 t=None, err_flag=None, stream=None):
     """Vocabulary / compositional gating, dispatch and token-order shrink in one launch:
     (r, offsets, perm, t [N][2*C*rank]) with C = n_adapters * M."""
-    N, d_in = x.shape
-    C, _, rank = A.shape
-    b = [int(q) for q in breaks]
-    M = len(b) - 1
+    N, d_in = _two(x, "x")
+    C, _, rank = _three(A, "A")
+    arr, M = _breaks(breaks)
     if C != n_adapters * M:
         raise ValueError("A must hold n_adapters * M adapters")
-    arr = (ctypes.c_int32 * len(b))(*b)
     if r is None:
         r = torch.empty(N, dtype=torch.int32, device=x.device)
-    if offsets is None:
-        offsets = torch.empty(C + 1, dtype=torch.int32, device=x.device)
-    if perm is None:
-        perm = torch.empty(N, dtype=torch.int32, device=x.device)
-    if t is None:
-        t = torch.empty((N, 2 * C * rank), dtype=torch.bfloat16, device=x.device)
+    offsets, perm, t = _dense_outputs(N, C, rank, offsets, perm, t, x.device)
     bf = torch.bfloat16
-    st = load().molora_gate_dispatch_shrink(
-        _dev(v, torch.int32, "v"), None if adapter is None else _dev(adapter, torch.int32, "adapter"), arr, M,
-        n_adapters, _dev(x, bf, "x"), _dev(A, bf, "A"), _dev(r, torch.int32, "r"),
-        _dev(offsets, torch.int32, "offsets"), _dev(perm, torch.int32, "perm"), _dev(t, bf, "t"), N, d_in, rank,
-        None if err_flag is None else _dev(err_flag, torch.int32, "err_flag"), _stream(stream))
-    _check(st, "molora_gate_dispatch_shrink")
+    _call("molora_gate_dispatch_shrink", 
+        _dev(v, torch.int32, "v", (N,)), _opt(adapter, torch.int32, "adapter", (N,)), arr, M,
+        n_adapters, _dev(x, bf, "x"), _dev(A, bf, "A", (C, d_in, rank)), _dev(r, torch.int32, "r", (N,)),
+        _dev(offsets, torch.int32, "offsets", (C + 1,)), _dev(perm, torch.int32, "perm", (N,)),
+        _dev(t, bf, "t", (N, 2 * C * rank)), N, d_in, rank,
+        _opt(err_flag, torch.int32, "err_flag"), _stream(stream))
     return r, offsets, perm, t
 
 
 def molora_base_expand_dense(x, W, B, t, offsets, perm, h=None, stream=None):
     """molora_base_expand reading the token-order intermediate of the two calls above."""
-    N, d_in = x.shape
-    d_out = W.shape[1]
-    C, rank, _ = B.shape
-    if h is None:
-        h = torch.empty((N, d_out), dtype=torch.float32, device=x.device)
-    bf = torch.bfloat16
-    st = load().molora_base_expand_dense(_dev(x, bf, "x"), _dev(W, bf, "W"), _dev(B, bf, "B"), _dev(t, bf, "t"),
-                                         _dev(offsets, torch.int32, "offsets"), _dev(perm, torch.int32, "perm"),
-                                         _dev(h, torch.float32, "h"), N, d_in, d_out, C, rank, _stream(stream))
-    _check(st, "molora_base_expand_dense")
+    args, h = _base_expand_args(x, W, B, t, offsets, perm, h, lambda C, rank: 2 * C * rank)
+    _call("molora_base_expand_dense", *args, _stream(stream))
     return h
 
 
@@ -362,18 +416,21 @@ def molora_init():
 
 
 def bf16_tensor(bits, device="cuda"):
-    """numpy uint16 bit patterns -> torch.bfloat16 tensor on the device (same bits)."""
+    """numpy uint16 bit patterns -> torch.bfloat16 tensor on the device (same bits).  Anything
+    but uint16 is refused: reinterpreting wider elements would silently change the shape."""
     import numpy as np
-    t = torch.from_numpy(np.ascontiguousarray(bits).view(np.int16))
+    bits = np.ascontiguousarray(bits)
+    if bits.dtype != np.uint16:
+        raise TypeError(f"bf16_tensor takes uint16 bit patterns, got {bits.dtype}")
+    t = torch.from_numpy(bits.view(np.int16))
     return t.to(device).view(torch.bfloat16)
 
 
 def molora_route_mlp(x, W1, b1, W2, b2, k, idx=None, w=None, workspace=None, stream=None):
     """Router MLP + top-k + softmax: returns (idx [N][k] int32, w [N][k] fp32)."""
-    N, d_in = x.shape
-    H, K = W2.shape
-    if W1.shape != (d_in, H):
-        raise ValueError("W1 must be [d_in][H]")
+    N, d_in = _two(x, "x")
+    H, K = _two(W2, "W2")
+    k = int(k)
     if idx is None:
         idx = torch.empty((N, k), dtype=torch.int32, device=x.device)
     if w is None:
@@ -382,36 +439,31 @@ def molora_route_mlp(x, W1, b1, W2, b2, k, idx=None, w=None, workspace=None, str
         nbytes = int(load().molora_route_mlp_workspace_bytes(N, H))
         workspace = torch.empty(max(nbytes, 256), dtype=torch.uint8, device=x.device)
     bf = torch.bfloat16
-    st = load().molora_route_mlp(_dev(x, bf, "x"), _dev(W1, bf, "W1"), _dev(b1, torch.float32, "b1"),
-                                 _dev(W2, bf, "W2"), _dev(b2, torch.float32, "b2"),
-                                 _dev(idx, torch.int32, "idx"), _dev(w, torch.float32, "w"),
-                                 N, d_in, H, K, k, _dev(workspace, torch.uint8, "workspace"),
-                                 workspace.numel(), _stream(stream))
-    _check(st, "molora_route_mlp")
+    ws, ws_bytes = _flat_bytes(workspace, "workspace")
+    _call("molora_route_mlp", _dev(x, bf, "x"), _dev(W1, bf, "W1", (d_in, H)),
+                                 _dev(b1, torch.float32, "b1", (H,)), _dev(W2, bf, "W2"),
+                                 _dev(b2, torch.float32, "b2", (K,)), _dev(idx, torch.int32, "idx", (N, k)),
+                                 _dev(w, torch.float32, "w", (N, k)), N, d_in, H, K, k, ws, ws_bytes,
+                                 _stream(stream))
     return idx, w
 
 
 def molora_route_compose(v, adapter, breaks, n_adapters, r=None, stream=None):
     """r[i] = adapter[i] * M + modality(v[i]), -1 when either part is out of range."""
-    N = v.shape[0]
-    b = [int(t) for t in breaks]
-    M = len(b) - 1
-    arr = (ctypes.c_int32 * len(b))(*b)
+    N = int(v.shape[0])
+    arr, M = _breaks(breaks)
     if r is None:
         r = torch.empty(N, dtype=torch.int32, device=v.device)
-    st = load().molora_route_compose(_dev(v, torch.int32, "v"), _dev(adapter, torch.int32, "adapter"),
-                                     arr, M, n_adapters, _dev(r, torch.int32, "r"), N, _stream(stream))
-    _check(st, "molora_route_compose")
+    _call("molora_route_compose", _dev(v, torch.int32, "v", (N,)), _dev(adapter, torch.int32, "adapter", (N,)),
+                                     arr, M, n_adapters, _dev(r, torch.int32, "r", (N,)), N, _stream(stream))
     return r
 
 
 def molora_gate_dispatch(v, breaks, adapter=None, n_adapters=1, r=None, offsets=None, perm=None,
                          err_flag=None, stream=None):
     """Vocabulary / compositional gating and bucketing in one launch: (r, offsets, perm)."""
-    N = v.shape[0]
-    b = [int(t) for t in breaks]
-    M = len(b) - 1
-    arr = (ctypes.c_int32 * len(b))(*b)
+    N = int(v.shape[0])
+    arr, M = _breaks(breaks)
     C = n_adapters * M
     if r is None:
         r = torch.empty(N, dtype=torch.int32, device=v.device)
@@ -419,12 +471,11 @@ def molora_gate_dispatch(v, breaks, adapter=None, n_adapters=1, r=None, offsets=
         offsets = torch.empty(C + 1, dtype=torch.int32, device=v.device)
     if perm is None:
         perm = torch.empty(max(N, 1), dtype=torch.int32, device=v.device)[:N]
-    st = load().molora_gate_dispatch(
-        _dev(v, torch.int32, "v"), None if adapter is None else _dev(adapter, torch.int32, "adapter"),
-        arr, M, n_adapters, _dev(r, torch.int32, "r"), _dev(offsets, torch.int32, "offsets"),
-        _dev(perm, torch.int32, "perm"), N,
-        None if err_flag is None else _dev(err_flag, torch.int32, "err_flag"), _stream(stream))
-    _check(st, "molora_gate_dispatch")
+    _call("molora_gate_dispatch", 
+        _dev(v, torch.int32, "v", (N,)), _opt(adapter, torch.int32, "adapter", (N,)),
+        arr, M, n_adapters, _dev(r, torch.int32, "r", (N,)), _dev(offsets, torch.int32, "offsets", (C + 1,)),
+        _dev(perm, torch.int32, "perm", (N,)), N,
+        _opt(err_flag, torch.int32, "err_flag"), _stream(stream))
     return r, offsets, perm
 
 
@@ -433,22 +484,23 @@ def molora_apply_mix(x, W, A, B, idx, w=None, slots=None, C=None, h=None, worksp
     N, d_in, d_out, S, rank = _shapes(x, W, A, B)
     if idx.dim() == 1:
         idx = idx.reshape(N, 1)
-    k = idx.shape[1]
+    k = int(idx.shape[1])
     if C is None:
-        C = S if slots is None else slots.shape[0]
+        C = S if slots is None else int(slots.shape[0])
+    if slots is None and C > S:
+        raise ValueError("without a slot table the adapter indices address the pool: C <= pool size")
     if h is None:
         h = torch.empty((N, d_out), dtype=torch.float32, device=x.device)
     if workspace is None:
         nbytes = int(load().molora_apply_mix_workspace_bytes(N, d_in, d_out, C, rank, k))
         workspace = torch.empty(max(nbytes, 256), dtype=torch.uint8, device=x.device)
     bf = torch.bfloat16
-    st = load().molora_apply_mix(
+    ws, ws_bytes = _flat_bytes(workspace, "workspace")
+    _call("molora_apply_mix", 
         _dev(x, bf, "x"), _dev(W, bf, "W"), _dev(A, bf, "A"), _dev(B, bf, "B"),
-        _dev(idx, torch.int32, "idx"), None if w is None else _dev(w, torch.float32, "w"),
-        None if slots is None else _dev(slots, torch.int32, "slots"), _dev(h, torch.float32, "h"),
-        N, d_in, d_out, C, rank, k, _dev(workspace, torch.uint8, "workspace"), workspace.numel(),
-        _stream(stream))
-    _check(st, "molora_apply_mix")
+        _dev(idx, torch.int32, "idx", (N, k)), _opt(w, torch.float32, "w", (N, k)),
+        _opt(slots, torch.int32, "slots", (C,)), _dev(h, torch.float32, "h", (N, d_out)),
+        N, d_in, d_out, C, rank, k, ws, ws_bytes, _stream(stream))
     return h
 
 
@@ -470,11 +522,11 @@ class Graph:
 
         class _Capture:
             def __enter__(self):
-                _check(load().molora_graph_begin(_stream(graph.stream)), "molora_graph_begin")
+                _check(load().molora_graph_begin(_stream_now(graph.stream)), "molora_graph_begin")
 
             def __exit__(self, et, ev, tb):
                 h = ctypes.c_void_p()
-                st = load().molora_graph_end(_stream(graph.stream), ctypes.byref(h))
+                st = load().molora_graph_end(_stream_now(graph.stream), ctypes.byref(h))
                 if et is None:
                     _check(st, "molora_graph_end")
                     graph._handle = h
@@ -487,7 +539,7 @@ class Graph:
     def launch(self, stream=None):
         if self._handle is None:
             raise RuntimeError("nothing captured")
-        _check(load().molora_graph_launch(self._handle, _stream(stream or self.stream)),
+        _check(load().molora_graph_launch(self._handle, _stream_now(stream or self.stream)),
                "molora_graph_launch")
 
     def destroy(self):
