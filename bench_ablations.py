@@ -20,6 +20,7 @@ with the headline table.
           "kernel_benchmark")
 """
 import argparse
+import time
 import json
 import math
 import os
@@ -49,12 +50,17 @@ def main():
     mb.load()
     rng = np.random.default_rng(2026)
 
-    def timed(fn, copies, reps=args.reps, warm=24, rounds=3):
+    def timed(fn, copies, reps=args.reps, warm_s=0.08, rounds=3):
         """fn(copy) launched back to back, copy i % len(copies) at launch i; us per launch, the
-        best of `rounds` rounds after a warm-up long enough for the clocks to settle (what is
-        measured first must not look slower for that alone)."""
-        for i in range(warm):
-            fn(copies[i % len(copies)])
+        best of `rounds` rounds after a warm-up of warm_s seconds of the same launches: the chip
+        takes 30-50 ms of load to reach the clocks it then holds, and what is measured first
+        must not look slower for that alone."""
+        t0, i = time.time(), 0
+        while time.time() - t0 < warm_s:
+            for _ in range(8):
+                fn(copies[i % len(copies)])
+                i += 1
+            torch.cuda.synchronize()
         best = None
         for _ in range(rounds):
             a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
