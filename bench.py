@@ -5,7 +5,8 @@ A step is one pass of the whole path over one batch of synthetic input that is a
 resident in HBM:  route (vocabulary or learned gate; skipped when r is given) -> bucket ->
 shrink -> fused base GEMM + expand, every call through the C ABI of libmolora.so (vocabulary
 routing and bucketing share one launch, as in the paper's gating kernel; with a few narrow
-adapters, C * rank <= 64, the shrink shares that launch too: molora_gate_dispatch_shrink).  The
+adapters, C * rank <= 64, the shrink shares that launch too: molora_gate_dispatch_shrink; a
+batch of at most 64 tokens is dispatched inside its shrink launch: molora_bucket_shrink_small).  The
 default workload is configuration 1 (N = 4096 tokens, Qwen3-1.7B q_proj 2048 -> 2048, two
 adapters of rank 16, vocabulary-routed interleaved text/image runs).
 
@@ -171,6 +172,8 @@ def run_workload(args, workload, steps, warmup, full):
             # a few narrow adapters: dispatch and shrink share one launch and the intermediate is
             # in token order, all adapters side by side
             d["dense"] = mb.molora_dense_shrink_supported(sh.N, sh.d_in, C, rk)
+            # a batch of at most 64 tokens: the dispatch runs inside the shrink launch
+            d["small"] = mb.molora_bucket_shrink_small_supported(sh.N, sh.d_in, C, rk)
             d["t"] = torch.empty((sh.N, 2 * rk * (C if d["dense"] else 1)), dtype=torch.bfloat16, device="cuda")
             d["sws"] = mb.molora_shrink_workspace(sh.N, sh.d_in, C, rk)  # None for most sizes
             d["h"] = torch.empty((sh.N, sh.d_out), dtype=torch.float32, device="cuda")
@@ -192,6 +195,10 @@ def run_workload(args, workload, steps, warmup, full):
             else:
                 mb.molora_bucket_shrink(route(d, stream), d["x"], d["A"], d["offsets"], d["perm"], d["t"],
                                         stream=stream)
+            return
+        if d["small"] and "v" not in d:
+            mb.molora_bucket_shrink_small(route(d, stream), d["x"], d["A"], d["offsets"], d["perm"], d["t"],
+                                          workspace=d["sws"], stream=stream)
             return
         if "v" in d:  # integer routing: gating inside the dispatch kernel (one launch)
             mb.molora_gate_dispatch(d["v"], d["breaks"], None, 1, d["r"], d["offsets"], d["perm"], stream=stream)
@@ -332,7 +339,7 @@ def run_workload(args, workload, steps, warmup, full):
 
     breakdown = {}
     if full and not (args.timed_only and gemm_us is not None):
-        if S[0][0]["dense"]:
+        if S[0][0]["dense"] or (S[0][0]["small"] and "v" not in S[0][0]):
             breakdown["dispatch_and_shrink_us"] = timed_calls(lambda d: dispatch_and_shrink(d))
         else:
             if "G" in S[0][0] or "v" in S[0][0]:

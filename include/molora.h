@@ -236,6 +236,24 @@ molora_status molora_base_expand_dense(const void *x, const void *W, const void 
                                        int32_t rank, void *stream);
 
 /*
+ * Dispatch and shrink in one launch for a batch of at most 64 tokens (a decode step): the
+ * targets of the whole batch are one wavefront of keys, so every workgroup of the shrink
+ * derives the rows of its adapter from r itself (ascending token index: the stable order of
+ * Alg. "Unified Dispatch Kernel") instead of waiting for a dispatch launch, and offsets and perm
+ * are written on the side for molora_base_expand.  Same outputs as molora_bucket followed by
+ * molora_shrink (offsets, perm bit for bit; t in the bucket-order layout of molora_shrink,
+ * [N][2*rank]), same optional workspace as molora_shrink, err_flag as molora_bucket.
+ * molora_bucket_shrink_small_supported says (1 / 0) whether the sizes qualify (N <= 64 and a
+ * rank above 32, where the shrink is the K-streaming kernel); otherwise MOLORA_EINVAL.
+ * molora_apply takes this path by itself.
+ */
+int32_t molora_bucket_shrink_small_supported(int64_t N, int32_t d_in, int32_t C, int32_t rank);
+molora_status molora_bucket_shrink_small(const int32_t *r, const void *x, const void *A,
+                                         int32_t *offsets, int32_t *perm, void *t, int64_t N,
+                                         int32_t d_in, int32_t C, int32_t rank, void *workspace,
+                                         size_t workspace_bytes, int32_t *err_flag, void *stream);
+
+/*
  * molora_base_expand with the height of the row tiles forced, for the tiling ablation (App.
  * "Adaptive Tiling", Table "tab:adaptive_tiling": tile shape chosen from the load against one
  * fixed shape).  tile_rows = 64 (the streaming kernel, W read once per 64-row tile), 128

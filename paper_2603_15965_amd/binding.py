@@ -17,7 +17,8 @@ EXPORTS = ["molora_route", "molora_route_vocab", "molora_bucket", "molora_apply_
            "molora_apply", "molora_apply_bucketed", "molora_shrink", "molora_shrink_workspace_bytes",
            "molora_base_expand",
            "molora_base_expand_fixed", "molora_init", "molora_dense_shrink_supported", "molora_bucket_shrink",
-           "molora_gate_dispatch_shrink", "molora_base_expand_dense", "molora_apply_static", "molora_static_workspace_bytes",
+           "molora_gate_dispatch_shrink", "molora_base_expand_dense", "molora_bucket_shrink_small_supported",
+           "molora_bucket_shrink_small", "molora_apply_static", "molora_static_workspace_bytes",
            "molora_route_mlp_workspace_bytes", "molora_route_mlp", "molora_route_compose",
            "molora_gate_dispatch",
            "molora_apply_mix_workspace_bytes", "molora_apply_mix",
@@ -75,6 +76,10 @@ def load():
     lib.molora_gate_dispatch_shrink.argtypes = [vp, vp, ctypes.POINTER(i32), i32, i32, vp, vp, vp, vp, vp, vp,
                                                 i64, i32, i32, vp, vp]
     lib.molora_gate_dispatch_shrink.restype = ctypes.c_int
+    lib.molora_bucket_shrink_small_supported.argtypes = [i64, i32, i32, i32]
+    lib.molora_bucket_shrink_small_supported.restype = ctypes.c_int32
+    lib.molora_bucket_shrink_small.argtypes = [vp, vp, vp, vp, vp, vp, i64, i32, i32, i32, vp, sz, vp, vp]
+    lib.molora_bucket_shrink_small.restype = ctypes.c_int
     lib.molora_base_expand_dense.argtypes = [vp, vp, vp, vp, vp, vp, vp, i64, i32, i32, i32, i32, vp]
     lib.molora_base_expand_dense.restype = ctypes.c_int
     lib.molora_init.argtypes = []
@@ -378,6 +383,34 @@ def molora_bucket_shrink(r, x, A, offsets=None, perm=None, t=None, err_flag=None
                                      _dev(perm, torch.int32, "perm", (N,)),
                                      _dev(t, bf, "t", (N, 2 * C * rank)), N, d_in, C, rank,
                                      _opt(err_flag, torch.int32, "err_flag"), _stream(stream))
+    return offsets, perm, t
+
+
+def molora_bucket_shrink_small_supported(N, d_in, C, rank):
+    """Whether dispatch and shrink of a batch can run in one launch (N <= 64, rank above 32)."""
+    return bool(load().molora_bucket_shrink_small_supported(N, d_in, C, rank))
+
+
+def molora_bucket_shrink_small(r, x, A, offsets=None, perm=None, t=None, workspace="auto", err_flag=None,
+                               stream=None):
+    """molora_bucket + molora_shrink of a batch of at most 64 tokens in one launch:
+    (offsets, perm, t [N][2*rank] in bucket order, as molora_shrink writes it)."""
+    N, d_in = _two(x, "x")
+    C, _, rank = _three(A, "A")
+    if offsets is None:
+        offsets = torch.empty(C + 1, dtype=torch.int32, device=x.device)
+    if perm is None:
+        perm = torch.empty(N, dtype=torch.int32, device=x.device)
+    if t is None:
+        t = torch.empty((N, 2 * rank), dtype=torch.bfloat16, device=x.device)
+    if isinstance(workspace, str):
+        workspace = molora_shrink_workspace(N, d_in, C, rank, x.device)
+    bf = torch.bfloat16
+    ws, ws_bytes = (None, 0) if workspace is None else _flat_bytes(workspace, "workspace")
+    _call("molora_bucket_shrink_small", _dev(r, torch.int32, "r", (N,)), _dev(x, bf, "x"),
+          _dev(A, bf, "A", (C, d_in, rank)), _dev(offsets, torch.int32, "offsets", (C + 1,)),
+          _dev(perm, torch.int32, "perm", (N,)), _dev(t, bf, "t", (N, 2 * rank)), N, d_in, C, rank,
+          ws, ws_bytes, _opt(err_flag, torch.int32, "err_flag"), _stream(stream))
     return offsets, perm, t
 
 

@@ -141,7 +141,13 @@ molora_status apply_common(const void *x, const void *W, const void *A, const vo
                                       d_in, d_out, C, rank, molora::Mix{1, C, nullptr, nullptr, 1}, s);
         return from_hip(e);
     }
-    if (r != nullptr) {
+    // a batch of at most 64 tokens: the dispatch step runs inside the shrink launch
+    molora::SortArgs sort{};
+    if (r != nullptr && molora::sort_in_shrink_ok(N, d_in, C, rank)) {
+        sort = molora::SortArgs{r, ws.offsets, ws.perm, nullptr};
+        offsets = ws.offsets;
+        perm = ws.perm;
+    } else if (r != nullptr) {
         e = molora::launch_bucket(r, ws.offsets, ws.perm, N, C, nullptr, s);
         if (e != hipSuccess) return MOLORA_EHIP;
         offsets = ws.offsets;
@@ -149,7 +155,7 @@ molora_status apply_common(const void *x, const void *W, const void *A, const vo
     }
     const molora::Mix plain{1, C, nullptr, nullptr};
     e = molora::launch_shrink(xb, Ab, offsets, perm, ws.t2, N, d_in,
-                              C, rank, plain, s, ws.shrink_scratch);
+                              C, rank, plain, s, ws.shrink_scratch, sort);
     if (e != hipSuccess) return MOLORA_EHIP;
     e = molora::launch_fused_gemm(xb, static_cast<const uint16_t *>(W),
                                   static_cast<const uint16_t *>(B), ws.t2, offsets, perm, h, N,
@@ -340,6 +346,35 @@ molora_status molora_bucket_shrink(const int32_t *r, const void *x, const void *
         nullptr, nullptr, nullptr, 0, 0, const_cast<int32_t *>(r), static_cast<const uint16_t *>(x),
         static_cast<const uint16_t *>(A), offsets, perm, static_cast<uint16_t *>(t), N, d_in, C, rank,
         err_flag, static_cast<hipStream_t>(stream)));
+}
+
+int32_t molora_bucket_shrink_small_supported(int64_t N, int32_t d_in, int32_t C, int32_t rank) {
+    return apply_sizes_ok(N, d_in, 8, C, rank) && molora::sort_in_shrink_ok(N, d_in, C, rank) ? 1 : 0;
+}
+
+molora_status molora_bucket_shrink_small(const int32_t *r, const void *x, const void *A,
+                                         int32_t *offsets, int32_t *perm, void *t, int64_t N,
+                                         int32_t d_in, int32_t C, int32_t rank, void *workspace,
+                                         size_t workspace_bytes, int32_t *err_flag, void *stream) {
+    if (!apply_sizes_ok(N, d_in, 8, C, rank) || !molora::sort_in_shrink_ok(N, d_in, C, rank))
+        return MOLORA_EINVAL;
+    if (!r || !x || !A || !offsets || !perm || !t) return MOLORA_EINVAL;
+    if (!aligned16(r) || !aligned16(x) || !aligned16(A) || !aligned16(offsets) || !aligned16(perm) ||
+        !aligned16(t))
+        return MOLORA_EALIGN;
+    float *scratch = nullptr;  // optional, as in molora_shrink
+    const size_t need = molora::shrink_scratch_bytes(N, d_in, C, rank);
+    if (workspace != nullptr && need > 0 && workspace_bytes >= need) {
+        if (!aligned256(workspace)) return MOLORA_EALIGN;
+        scratch = static_cast<float *>(workspace);
+    }
+    if (molora::ensure_device_ready() != hipSuccess) return MOLORA_EHIP;
+    return from_hip(molora::launch_shrink(static_cast<const uint16_t *>(x),
+                                          static_cast<const uint16_t *>(A), nullptr, nullptr,
+                                          static_cast<uint16_t *>(t), N, d_in, C, rank,
+                                          molora::Mix{1, C, nullptr, nullptr},
+                                          static_cast<hipStream_t>(stream), scratch,
+                                          molora::SortArgs{r, offsets, perm, err_flag}));
 }
 
 molora_status molora_gate_dispatch_shrink(const int32_t *v, const int32_t *adapter,

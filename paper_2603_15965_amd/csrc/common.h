@@ -117,9 +117,23 @@ hipError_t launch_gate_bucket(const int32_t *v, const int32_t *adapter, const in
 // scratch: fp32 scratch of shrink_scratch_bytes(...) bytes or nullptr (then K is never split
 // over workgroups); contents need no initialisation
 size_t shrink_scratch_bytes(int64_t N, int d_in, int C, int R);
+// The dispatch step inside the shrink launch, for a batch of at most 64 tokens (one wavefront
+// of targets): r != nullptr makes every workgroup of the shrink derive its bucket's rows from r
+// itself, and the workgroups of column group 0 write offsets and perm (molora_bucket's output:
+// stable, tokens without adapter listed last, err_flag set if there are any) for the step
+// that follows.  One launch and two dependent trips to memory less than bucket, then shrink.
+struct SortArgs {
+    const int32_t *r = nullptr;
+    int32_t *offsets = nullptr;
+    int32_t *perm = nullptr;
+    int32_t *err_flag = nullptr;
+};
+// sizes for which launch_shrink takes SortArgs (its streaming kernel, N <= 64)
+bool sort_in_shrink_ok(int64_t N, int d_in, int C, int rank);
+// sort.r != nullptr: offsets and perm are ignored (sort.offsets / sort.perm are written)
 hipError_t launch_shrink(const uint16_t *x, const uint16_t *A, const int32_t *offsets,
                          const int32_t *perm, uint16_t *t2, int64_t N, int d_in, int C, int rank,
-                         Mix mix, hipStream_t s, float *scratch = nullptr);
+                         Mix mix, hipStream_t s, float *scratch = nullptr, SortArgs sort = SortArgs{});
 hipError_t launch_fused_gemm(const uint16_t *x, const uint16_t *W, const uint16_t *B,
                              const uint16_t *t2, const int32_t *offsets, const int32_t *perm,
                              float *h, int64_t N, int d_in, int d_out, int C, int rank, Mix mix,
@@ -135,6 +149,6 @@ int small_batch_shrink_ksplit(int64_t N, int d_in, int C, int R);
 hipError_t launch_small_batch_shrink(const uint16_t *x, const uint16_t *A, const int32_t *offsets,
                                      const int32_t *perm, uint16_t *t2, int64_t N, int d_in, int C,
                                      int rank, Mix mix, hipStream_t s, float *planes = nullptr,
-                                     int ksplit = 1);
+                                     int ksplit = 1, SortArgs sort = SortArgs{});
 
 }  // namespace molora

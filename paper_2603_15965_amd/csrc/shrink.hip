@@ -50,10 +50,20 @@ size_t shrink_scratch_bytes(int64_t N, int d_in, int C, int R) {
     return ks > 1 ? (size_t)ks * (size_t)N * (size_t)R * sizeof(float) : 0;
 }
 
+bool sort_in_shrink_ok(int64_t N, int d_in, int C, int rank) {
+    return N > 0 && N <= 64 && !shrink_tiny(N, rank) && shrink_streams(N, d_in, C, rank);
+}
+
 hipError_t launch_shrink(const uint16_t *x, const uint16_t *A, const int32_t *offsets,
                          const int32_t *perm, uint16_t *t2, int64_t N, int d_in, int C, int rank,
-                         Mix mix, hipStream_t s, float *scratch) {
+                         Mix mix, hipStream_t s, float *scratch, SortArgs sort) {
     if (N == 0) return hipSuccess;
+    if (sort.r != nullptr) {
+        if (mix.k != 1 || !sort_in_shrink_ok(N, d_in, C, rank) || !sort.offsets || !sort.perm)
+            return hipErrorInvalidValue;
+        offsets = sort.offsets;  // what the reduction pass of a K-split shrink reads afterwards
+        perm = sort.perm;
+    }
     // Two kernels (measured crossovers).  The streaming kernel (one workgroup per 64 rows of a
     // bucket, K split over its 8 wavefronts, x staged as whole 128-byte lines) wins for small
     // batches, which are bound by the latency of streaming the touched A_c, and for large ones
@@ -75,7 +85,7 @@ hipError_t launch_shrink(const uint16_t *x, const uint16_t *A, const int32_t *of
     if (shrink_streams(N, d_in, C, R)) {
         // few (bucket, tile) pairs and a long K: K split over workgroups, when scratch is there
         const int ks = scratch != nullptr ? small_batch_shrink_ksplit(N, d_in, C, (int)R) : 1;
-        return launch_small_batch_shrink(x, A, offsets, perm, t2, N, d_in, C, rank, mix, s, scratch, ks);
+        return launch_small_batch_shrink(x, A, offsets, perm, t2, N, d_in, C, rank, mix, s, scratch, ks, sort);
     }
     // 32-row items when they still cover the chip twice, 16-row items otherwise
     const bool small_items = (N + 31) / 32 + C < 512;

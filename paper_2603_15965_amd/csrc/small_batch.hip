@@ -100,7 +100,7 @@ __global__ __launch_bounds__(kSbWaves * 64) void small_batch_kernel(
     const uint16_t *__restrict__ x, const uint16_t *__restrict__ W, const uint16_t *__restrict__ B,
     const uint16_t *__restrict__ t2, const int32_t *__restrict__ offsets,
     const int32_t *__restrict__ perm, float *__restrict__ h, uint16_t *__restrict__ t_out, int N,
-    int d_in, int d_out, int C, int rank, Mix mix, int ksplit) {
+    int d_in, int d_out, int C, int rank, Mix mix, int ksplit, SortArgs sort) {
     using Geo = SbGeom<TN>;
     constexpr int kSbCols = Geo::COLS, kSbSlot = Geo::SLOT, kSbRowBytes = Geo::ROW_BYTES,
                   kSbWaveLds = Geo::WAVE_LDS;
@@ -122,11 +122,54 @@ __global__ __launch_bounds__(kSbWaves * 64) void small_batch_kernel(
     // ---- rows of this workgroup ----
     const int R = mix.k * rank;  // width of a bucket's intermediate (k adapters side by side)
     int row_base = 0, nrows = N, bucket = 0;
+    // SHRINK with the dispatch step inside (sort.r given; N <= 64, so the targets of the whole
+    // batch are one wavefront of keys): every wavefront derives the rows of its bucket from r
+    // itself -- the tokens with that target in ascending order, which is the stable order of
+    // the dispatch step -- instead of reading offsets and perm, and the workgroups of column
+    // group 0 write offsets and perm for the step that follows (Alg. "Unified Dispatch Kernel").
+    const bool sorting = SHRINK && sort.r != nullptr;
+    int sort_tok = 0;  // sorting: token of row `lane` of the bucket (lanes past its rows: 0)
     if constexpr (SHRINK) {
         bucket = blockIdx.y;
-        row_base = offsets[bucket] + 64 * (blockIdx.z / ksplit);  // 64-row tile of the bucket
-        nrows = min(64, offsets[bucket + 1] - row_base);
-        if (nrows <= 0) return;  // nothing (left) in this bucket: its adapters are not touched
+        if (sorting) {
+            if (blockIdx.z >= (unsigned)ksplit) return;  // a batch of one wavefront is one row tile
+            int key = C + 1;  // lanes past the batch: no key at all
+            if (lane < N) {
+                const int c = sort.r[lane];
+                key = (c >= 0 && c < C) ? c : C;  // C: no adapter
+            }
+            // lane j <- the j-th lane (ascending) of a ballot mask
+            auto nth_lane = [&](uint64_t m) {
+                int tok = 0, cnt = 0;
+                while (m) {  // wave-uniform, at most 64 rounds
+                    if (cnt == lane) tok = __builtin_ctzll(m);
+                    ++cnt;
+                    m &= m - 1;
+                }
+                return tok;
+            };
+            const uint64_t mine = __ballot(key == bucket);
+            row_base = __popcll(__ballot(key < bucket));  // sorted position of the bucket's first row
+            nrows = __popcll(mine);
+            sort_tok = nth_lane(mine);
+            if (blockIdx.x == 0 && blockIdx.z == 0 && wave == 0) {
+                if (lane == 0) sort.offsets[bucket] = row_base;
+                if (lane < nrows) sort.perm[row_base + lane] = sort_tok;
+                if (bucket == C - 1) {  // ... and once: the end of the lists, the tokens without adapter
+                    const uint64_t none = __ballot(key == C);
+                    const int n_routed = __popcll(__ballot(key < C));
+                    const int tok = nth_lane(none);
+                    if (lane == 0) sort.offsets[C] = n_routed;
+                    if (lane < __popcll(none)) sort.perm[n_routed + lane] = tok;
+                    if (none != 0 && lane == 0 && sort.err_flag != nullptr) *sort.err_flag = 1;
+                }
+            }
+            if (nrows <= 0) return;  // an empty bucket: its adapters are not touched
+        } else {
+            row_base = offsets[bucket] + 64 * (blockIdx.z / ksplit);  // 64-row tile of the bucket
+            nrows = min(64, offsets[bucket + 1] - row_base);
+            if (nrows <= 0) return;  // nothing (left) in this bucket: its adapters are not touched
+        }
     } else {
         row_base = blockIdx.y * 64;  // row tile of 64 sorted positions
         nrows = min(64, N - row_base);
@@ -228,7 +271,7 @@ __global__ __launch_bounds__(kSbWaves * 64) void small_batch_kernel(
 #pragma unroll
         for (int i = 0; i < 4 * TM; ++i) {
             const int row = min(i * 8 + a_sub, nrows - 1);  // rows past the end repeat the last one; never stored
-            const int tok = direct ? row : perm[row_base + row];
+            const int tok = sorting ? __shfl(sort_tok, row, 64) : (direct ? row : perm[row_base + row]);
             a_ch8[i] = (a_pos ^ (((i * 8 + a_sub) ^ ((i * 8 + a_sub) >> 3)) & 7)) * 8;
             a_xrow[i] = x + (int64_t)tok * d_in + a_ch8[i];
             const int64_t off = (const unsigned char *)a_xrow[i] - (const unsigned char *)x;
@@ -309,7 +352,7 @@ __global__ __launch_bounds__(kSbWaves * 64) void small_batch_kernel(
 
     // ---- tables: row -> token and sorted position; the buckets that own rows, ascending ----
     if (wave == 0) {
-        tile_perm[lane] = lane < nrows ? (direct ? lane : perm[row_base + lane]) : -1;
+        tile_perm[lane] = lane < nrows ? (sorting ? sort_tok : (direct ? lane : perm[row_base + lane])) : -1;
         tile_pos[lane] = direct ? 0x7fffffff : row_base + lane;
         if (direct && lane < nrows) {
             const int tok = perm[lane];
@@ -525,7 +568,8 @@ struct SmallBatchKernel {
 template <int TM, int TN, bool SHRINK>
 hipError_t launch_small(const uint16_t *x, const uint16_t *W, const uint16_t *B, const uint16_t *t2,
                         const int32_t *offsets, const int32_t *perm, float *h, uint16_t *t_out, int N,
-                        int d_in, int d_out, int C, int rank, Mix mix, hipStream_t s, int ksplit) {
+                        int d_in, int d_out, int C, int rank, Mix mix, hipStream_t s, int ksplit,
+                        SortArgs sort) {
     using Geo = SbGeom<TN>;
     auto kern = small_batch_kernel<TM, TN, SHRINK>;
     (void)&SmallBatchKernel<TM, TN, SHRINK>::lds;  // instantiates the registration
@@ -536,7 +580,7 @@ hipError_t launch_small(const uint16_t *x, const uint16_t *W, const uint16_t *B,
     // (a K-split shrink: one workgroup per K slice of each of them)
     const dim3 grid = SHRINK ? dim3(groups, (unsigned)C, row_tiles * (unsigned)ksplit) : dim3(groups, row_tiles);
     hipLaunchKernelGGL(kern, grid, dim3(kSbWaves * 64), Geo::LDS_BYTES, s, x, W, B, t2, offsets, perm,
-                       h, t_out, N, d_in, d_out, C, rank, mix, ksplit);
+                       h, t_out, N, d_in, d_out, C, rank, mix, ksplit, sort);
     return hipGetLastError();
 }
 
@@ -544,14 +588,14 @@ template <bool SHRINK>
 hipError_t launch_small_tn(const uint16_t *x, const uint16_t *W, const uint16_t *B, const uint16_t *t2,
                            const int32_t *offsets, const int32_t *perm, float *h, uint16_t *t_out,
                            int N, int d_in, int d_out, int C, int rank, Mix mix, hipStream_t s,
-                           int ksplit = 1) {
+                           int ksplit = 1, SortArgs sort = SortArgs{}) {
     // 32-column groups when 64-column groups would occupy at most half of the compute units:
     // a workgroup draws ~40 GB/s from HBM whatever its width, so more, narrower ones win there.
     // The shrink has at most a few workgroups per bucket and always takes the narrow form.
     const int64_t wgs64 = (int64_t)((d_out + 63) / 64) * ((N + 63) / 64);
     const bool narrow = SHRINK || wgs64 <= 128;
 #define MOLORA_SB_LAUNCH(TM, TN) \
-    launch_small<TM, TN, SHRINK>(x, W, B, t2, offsets, perm, h, t_out, N, d_in, d_out, C, rank, mix, s, ksplit)
+    launch_small<TM, TN, SHRINK>(x, W, B, t2, offsets, perm, h, t_out, N, d_in, d_out, C, rank, mix, s, ksplit, sort)
     if (N <= 32) return narrow ? MOLORA_SB_LAUNCH(1, 1) : MOLORA_SB_LAUNCH(1, 2);
     return narrow ? MOLORA_SB_LAUNCH(2, 1) : MOLORA_SB_LAUNCH(2, 2);
 #undef MOLORA_SB_LAUNCH
@@ -581,11 +625,13 @@ int small_batch_shrink_ksplit(int64_t N, int d_in, int C, int R) {
 
 hipError_t launch_small_batch_shrink(const uint16_t *x, const uint16_t *A, const int32_t *offsets,
                                      const int32_t *perm, uint16_t *t_out, int64_t N, int d_in, int C,
-                                     int rank, Mix mix, hipStream_t s, float *planes, int ksplit) {
+                                     int rank, Mix mix, hipStream_t s, float *planes, int ksplit,
+                                     SortArgs sort) {
     const int R = mix.k * rank;  // the kernel's "d_out" is the width of the intermediate
     if (planes == nullptr) ksplit = 1;
+    if (sort.r != nullptr && N > 64) return hipErrorInvalidValue;  // one wavefront of targets
     hipError_t e = launch_small_tn<true>(x, A, nullptr, nullptr, offsets, perm, planes, t_out, (int)N, d_in,
-                                         R, C, rank, mix, s, ksplit);
+                                         R, C, rank, mix, s, ksplit, sort);
     if (e != hipSuccess || ksplit <= 1) return e;
     const int64_t items = N * (R / 4);
     hipLaunchKernelGGL(shrink_reduce_kernel, dim3((unsigned)((items + 255) / 256)), dim3(256), 0, s, planes,

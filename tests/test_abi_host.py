@@ -133,6 +133,30 @@ def test_widened_entry_points_reject_bad_arguments(lib):
     lib.molora_graph_destroy(None)
 
 
+def test_one_launch_dispatch_and_shrink_reject_bad_arguments(lib):
+    EINVAL, EALIGN = -1, -2
+    p = ctypes.c_void_p
+    buf = (ctypes.c_char * 4096)()
+    a = ctypes.addressof(buf)
+    a += (-a) % 256
+    small, dense = lib.molora_bucket_shrink_small_supported, lib.molora_dense_shrink_supported
+    assert small(64, 4096, 16, 64) == 1 and small(1, 64, 4, 40) == 1
+    assert small(65, 4096, 16, 64) == 0      # more than one wavefront of targets
+    assert small(64, 4096, 16, 32) == 0      # narrow ranks take another shrink kernel
+    assert small(0, 4096, 16, 64) == 0 and small(64, 4096, 16, 60) == 0
+    assert dense(4096, 2048, 2, 16) == 1 and dense(4096, 2048, 4, 16) == 1
+    assert dense(512, 2048, 2, 16) == 0 and dense(4096, 2048, 8, 16) == 0
+    f = lib.molora_bucket_shrink_small
+    call = lambda N=64, rank=64, r=a, t=a, ws=None: f(p(r), p(a), p(a), p(a), p(a), p(t), N, 4096, 16, rank,
+                                                      ws, 0, None, None)
+    assert call(N=65) == EINVAL and call(rank=32) == EINVAL and call(r=0) == EINVAL
+    assert call(t=a + 8) == EALIGN
+    g = lib.molora_bucket_shrink
+    assert g(p(a), p(a), p(a), p(a), p(a), p(a), 64, 4096, 2, 16, None, None) == EINVAL   # N <= 512
+    assert g(p(a), p(a), p(a), p(a), p(a), p(a), 4096, 2048, 8, 16, None, None) == EINVAL  # C * rank > 64
+    assert g(None, p(a), p(a), p(a), p(a), p(a), 4096, 2048, 2, 16, None, None) == EINVAL
+
+
 def test_operands_of_4_gib_are_rejected_for_the_tiled_kernel(lib):
     """The tiled GEMM (N > 512) keeps per-lane byte offsets into x and W in 32 bits; sizes
     beyond that are an error before launch, not silently wrapped addresses."""

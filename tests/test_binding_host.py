@@ -116,6 +116,12 @@ def test_one_launch_dispatch_and_shrink_reject_mismatched_shapes():
         mb.molora_gate_dispatch_shrink(v, [0, 10, 20], g["x"], g["A"], adapter=tens((N - 1,), i32))
     with pytest.raises(ValueError):
         mb.molora_gate_dispatch(v, [0], None, 1)
+    with pytest.raises(ValueError):   # the small-batch form writes the bucket-order t
+        mb.molora_bucket_shrink_small(g["r"], g["x"], g["A"], g["offsets"], g["perm"], g["td"], workspace=None)
+    with pytest.raises(ValueError):
+        mb.molora_bucket_shrink_small(g["r"], g["x"], g["A"], tens((C,), i32), g["perm"], g["t"], workspace=None)
+    with pytest.raises(TypeError, match="device tensor"):
+        mb.molora_bucket_shrink_small(g["r"], g["x"], g["A"], g["offsets"], g["perm"], g["t"], workspace=None)
 
 
 def test_routes_and_mixture_reject_mismatched_shapes():

@@ -202,6 +202,57 @@ def test_apply_few_narrow_adapters_one_launch_dispatch_and_shrink(gpu, N, d_in, 
     assert torch.equal(h, h3), "molora_apply_bucketed: the token-order shrink alone, same bits"
 
 
+@pytest.mark.parametrize("N,d_in,d_out,C,rank,structure,invalid", [
+    (64, 4096, 1024, 16, 64, "zipf", False),    # configuration 3's shape class: K split over 4 slices
+    (64, 1024, 264, 16, 64, "uniform", True),   # K split over 2 slices, targets out of range
+    (1, 256, 72, 4, 64, "uniform", False),      # one token
+    (37, 520, 136, 8, 40, "zipf", True),        # ragged everything, rank not a multiple of 16
+    (33, 2048, 64, 3, 128, "uniform", True),    # the widest intermediate
+    (50, 264, 64, 1024, 64, "uniform", False),  # as many adapters as the dispatch step allows: most buckets empty
+    (64, 512, 128, 2, 48, "all0", False),       # every token in one bucket
+])
+def test_bucket_shrink_small_one_launch(gpu, N, d_in, d_out, C, rank, structure, invalid):
+    """A batch of at most 64 tokens: the dispatch step inside the shrink launch.  offsets and
+    perm bit for bit as the oracle's, t bit for bit as molora_bucket followed by molora_shrink
+    (with and without the K-split workspace), h as the oracle's and as molora_apply's."""
+    import oracle
+    import torch
+    from paper_2603_15965_amd import binding as mb
+    say(f"dispatch inside the shrink N={N} {d_in}->{d_out} C={C} rank={rank} {structure}")
+    assert mb.molora_bucket_shrink_small_supported(N, d_in, C, rank)
+    w = wl.custom("s", N, d_in, d_out, C, rank, 7500 + N + C, structure=structure)
+    r = w.r.copy()
+    if invalid:
+        r[3::7] = -1
+        r[5::11] = C
+    x, W, A, B = (gpu.dev_bf16(q) for q in (w.x, w.W, w.A, w.B))
+    rd = gpu.dev_i32(r)
+    o_ref, p_ref, bad = oracle.bucket(r, C)
+    o2, p2 = mb.molora_bucket(rd, C)
+    for workspace in (None, "auto"):  # the last t is the one molora_apply computes too
+        flag = torch.zeros(1, dtype=torch.int32, device="cuda")
+        offsets, perm, t = mb.molora_bucket_shrink_small(rd, x, A, workspace=workspace, err_flag=flag)
+        torch.cuda.synchronize()
+        assert np.array_equal(offsets.cpu().numpy(), o_ref) and np.array_equal(perm.cpu().numpy(), p_ref)
+        assert int(flag.item()) == (1 if bad else 0)
+        t2 = mb.molora_shrink(x, A, o2, p2, workspace=workspace)
+        torch.cuda.synchronize()
+        n_routed = int(o_ref[C])
+        assert torch.equal(t[:n_routed], t2[:n_routed]), f"t, workspace={workspace}"
+    # t against its definition (reading: two bf16 halves carry 16 significant bits)
+    tt = t.float().cpu().numpy().astype(np.float64)
+    x64 = wl.bf16_bits_to_f32(w.x).astype(np.float64)
+    for p in range(n_routed):
+        c = int(np.searchsorted(o_ref, p, side="right") - 1)
+        ref_t = x64[p_ref[p]] @ wl.bf16_bits_to_f32(w.A[c]).astype(np.float64)
+        got = tt[p, :rank] + tt[p, rank:]
+        assert np.max(np.abs(got - ref_t) / np.maximum(1.0, np.abs(ref_t))) <= 2e-5, f"t of sorted position {p}"
+    h = mb.molora_base_expand(x, W, B, t, offsets, perm)
+    torch.cuda.synchronize()
+    gpu.assert_h_close(h.cpu().numpy(), oracle.apply(w.x, w.W, w.A, w.B, r), "dispatch inside the shrink, then expand")
+    assert torch.equal(h, gpu.gpu_apply(w, r)), "molora_apply takes the same path"
+
+
 def test_gate_dispatch_shrink_matches_separate_calls(gpu):
     """Gating + dispatch + shrink in one launch on configuration 1's shape and on composite
     targets: r, offsets, perm bit for bit as the oracle's, h as the oracle's."""
