@@ -476,6 +476,8 @@ __global__ __launch_bounds__(Cfg::NT) void fused_gemm_kernel(
     {
         constexpr int EP_ROWS = Cfg::WM * 32;
         static_assert(EP_ROWS * EP_STRIDE <= STAGES * Cfg::STAGE, "epilogue staging fits the stages");
+        static_assert(EP_ROWS * EP_CPR % NT == 0, "every thread stores the same number of chunks of a band");
+        constexpr int EP_IT = EP_ROWS * EP_CPR / NT;
 #pragma unroll
         for (int tm = 0; tm < TM; ++tm) {
             __syncthreads();  // operand stages (or the previous band) are no longer read
@@ -489,16 +491,26 @@ __global__ __launch_bounds__(Cfg::NT) void fused_gemm_kernel(
                 }
             }
             __syncthreads();
-            for (int it = tid; it < EP_ROWS * EP_CPR; it += NT) {
+            // All of a thread's staged chunks and their rows' tokens are read before the first
+            // store is issued: as a loop that reads one token, waits, reads one chunk, waits and
+            // stores, the band took two LDS round trips per chunk, eight chunks in a row.
+            int tok[EP_IT];
+            f32x4 val[EP_IT];
+#pragma unroll
+            for (int j = 0; j < EP_IT; ++j) {
+                const int it = tid + j * NT;
                 const int r = it / EP_CPR, ch = it % EP_CPR;
                 const int row = (r >> 5) * (BM / Cfg::WM) + tm * 32 + (r & 31);
-                const int tok = tile_perm[row];
-                const int col = n0 + ch * 4;
-                if (tok >= 0 && col < d_out)
+                tok[j] = tile_perm[row];
+                val[j] = *(const f32x4 *)(smem + r * EP_STRIDE + ch * 16);
+            }
+#pragma unroll
+            for (int j = 0; j < EP_IT; ++j) {
+                const int col = n0 + ((tid + j * NT) % EP_CPR) * 4;
+                if (tok[j] >= 0 && col < d_out)
                     // h is written once and not read again here: a streaming store keeps it
                     // from displacing x and W tiles in L2 (measured: -11 % at config 1)
-                    __builtin_nontemporal_store(*(const f32x4 *)(smem + r * EP_STRIDE + ch * 16),
-                                                (f32x4 *)(h + (int64_t)tok * d_out + col));
+                    __builtin_nontemporal_store(val[j], (f32x4 *)(h + (int64_t)tok[j] * d_out + col));
             }
         }
     }
