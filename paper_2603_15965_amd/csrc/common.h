@@ -46,7 +46,7 @@ struct Mix {
     // 1: the low-rank intermediate is in the token-order form of the dense shrink, row of token
     // i = [x_i A_0 .. x_i A_{C-1} as bf16 high parts | the same as remainders], 2 * C * rank
     // values (k = 1, no slot table); 0: one row of 2 * k * rank values per sorted position
-    int t_dense;
+    int t_dense = 0;
 };
 __device__ __forceinline__ int mix_adapter(const Mix &m, int b, int j) {
     int c = b;

@@ -149,18 +149,18 @@ __global__ __launch_bounds__(kSbWaves * 64) void small_batch_kernel(
                 return tok;
             };
             const uint64_t mine = __ballot(key == bucket);
-            row_base = __popcll(__ballot(key < bucket));  // sorted position of the bucket's first row
-            nrows = __popcll(mine);
+            row_base = (int)__popcll(__ballot(key < bucket));  // sorted position of the bucket's first row
+            nrows = (int)__popcll(mine);
             sort_tok = nth_lane(mine);
             if (blockIdx.x == 0 && blockIdx.z == 0 && wave == 0) {
                 if (lane == 0) sort.offsets[bucket] = row_base;
                 if (lane < nrows) sort.perm[row_base + lane] = sort_tok;
                 if (bucket == C - 1) {  // ... and once: the end of the lists, the tokens without adapter
                     const uint64_t none = __ballot(key == C);
-                    const int n_routed = __popcll(__ballot(key < C));
+                    const int n_routed = (int)__popcll(__ballot(key < C));
                     const int tok = nth_lane(none);
                     if (lane == 0) sort.offsets[C] = n_routed;
-                    if (lane < __popcll(none)) sort.perm[n_routed + lane] = tok;
+                    if (lane < (int)__popcll(none)) sort.perm[n_routed + lane] = tok;
                     if (none != 0 && lane == 0 && sort.err_flag != nullptr) *sort.err_flag = 1;
                 }
             }
