@@ -71,6 +71,49 @@ def test_captured_step_replays(N):
     g.destroy()
 
 
+def test_captured_decode_step_replays():
+    """A decode-sized batch (64 tokens, rank 64) through molora_apply: the dispatch runs inside
+    the shrink launch, K is split over workgroups with a second pass, then the streaming GEMM.
+    Recorded once, replayed with targets and inputs refreshed in place: every replay as the
+    oracle's and bit for bit as the eager call."""
+    import torch
+    import oracle
+    from paper_2603_15965_amd import binding as mb
+    import gpu_helpers as gpu
+    N, d_in, d_out, C, rank = 64, 1024, 392, 16, 64
+    print("graph replay, decode-sized batch", flush=True)
+    assert mb.molora_bucket_shrink_small_supported(N, d_in, C, rank)
+    w = wl.custom("graph_decode", N, d_in, d_out, C, rank, wl.BASE_SEED + 7800, structure="zipf")
+    x, W, A, B = (mb.bf16_tensor(q) for q in (w.x, w.W, w.A, w.B))
+    r = gpu.dev_i32(w.r)
+    h = torch.empty((N, d_out), dtype=torch.float32, device="cuda")
+    ws = mb.new_workspace(N, d_in, d_out, C, rank)
+    side = torch.cuda.Stream()
+    torch.cuda.synchronize()
+    g = mb.Graph(side)
+    with g.capture():
+        mb.molora_apply(x, W, A, B, r, h, ws, stream=side)
+    rng = np.random.default_rng(9)
+    x_bits, r_np = w.x, w.r
+    for replay in range(4):
+        if replay > 0:
+            x_bits = w.x[rng.permutation(N)]
+            r_np = rng.integers(-1, C + 1, size=N).astype(np.int32)  # some tokens without adapter
+            x.copy_(mb.bf16_tensor(x_bits))
+            r.copy_(gpu.dev_i32(r_np))
+        h.zero_()
+        torch.cuda.synchronize()
+        g.launch()
+        side.synchronize()
+        h_gpu = h.cpu().numpy()
+        gpu.assert_h_close(h_gpu, oracle.apply(x_bits, w.W, w.A, w.B, r_np), f"replay {replay}")
+        h.zero_()
+        mb.molora_apply(x, W, A, B, r, h, ws)
+        torch.cuda.synchronize()
+        assert np.array_equal(h.cpu().numpy(), h_gpu), f"replay {replay} vs eager"
+    g.destroy()
+
+
 def test_captured_seven_projection_layer():
     """The whole Qwen3-8B-shaped layer of configuration 4 at full size (seven projections,
     N = 16384, each route -> bucket -> apply) recorded as ONE launch sequence, the form the
