@@ -254,6 +254,31 @@ molora_status molora_bucket_shrink_small(const int32_t *r, const void *x, const 
                                          size_t workspace_bytes, int32_t *err_flag, void *stream);
 
 /*
+ * A batch of at most 64 tokens in two launches (sizes as molora_bucket_shrink_small_supported):
+ *
+ *   molora_shrink_base_small:  offsets, perm, t as molora_bucket_shrink_small (K never split)
+ *                              AND h = x W, all in one launch.  The base projection of a batch
+ *                              of one row tile runs in token order and needs nothing from the
+ *                              dispatch step, so the latency-bound shrink (a dozen workgroups,
+ *                              each reading one A_c) hides behind the stream of W instead of
+ *                              preceding it.
+ *   molora_expand_small:       h[perm[p]] += t_p B_c for every routed sorted position p: the
+ *                              expand of Eq. "pertok" alone, added to what h holds.
+ *
+ * One after the other they give what molora_bucket, molora_shrink and molora_base_expand give,
+ * up to the order of the fp32 additions.  molora_apply takes this path by itself.  Arguments,
+ * layouts and errors as in those calls; h is written by the first call and read and
+ * written by the second.
+ */
+molora_status molora_shrink_base_small(const int32_t *r, const void *x, const void *W, const void *A,
+                                       int32_t *offsets, int32_t *perm, void *t, float *h, int64_t N,
+                                       int32_t d_in, int32_t d_out, int32_t C, int32_t rank,
+                                       int32_t *err_flag, void *stream);
+molora_status molora_expand_small(const void *B, const void *t, const int32_t *offsets,
+                                  const int32_t *perm, float *h, int64_t N, int32_t d_out, int32_t C,
+                                  int32_t rank, void *stream);
+
+/*
  * molora_base_expand with the height of the row tiles forced, for the tiling ablation (App.
  * "Adaptive Tiling", Table "tab:adaptive_tiling": tile shape chosen from the load against one
  * fixed shape).  tile_rows = 64 (the streaming kernel, W read once per 64-row tile), 128

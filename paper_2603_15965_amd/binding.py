@@ -18,7 +18,7 @@ EXPORTS = ["molora_route", "molora_route_vocab", "molora_bucket", "molora_apply_
            "molora_base_expand",
            "molora_base_expand_fixed", "molora_init", "molora_dense_shrink_supported", "molora_bucket_shrink",
            "molora_gate_dispatch_shrink", "molora_base_expand_dense", "molora_bucket_shrink_small_supported",
-           "molora_bucket_shrink_small", "molora_apply_static", "molora_static_workspace_bytes",
+           "molora_bucket_shrink_small", "molora_shrink_base_small", "molora_expand_small", "molora_apply_static", "molora_static_workspace_bytes",
            "molora_route_mlp_workspace_bytes", "molora_route_mlp", "molora_route_compose",
            "molora_gate_dispatch",
            "molora_apply_mix_workspace_bytes", "molora_apply_mix",
@@ -80,6 +80,10 @@ def load():
     lib.molora_bucket_shrink_small_supported.restype = ctypes.c_int32
     lib.molora_bucket_shrink_small.argtypes = [vp, vp, vp, vp, vp, vp, i64, i32, i32, i32, vp, sz, vp, vp]
     lib.molora_bucket_shrink_small.restype = ctypes.c_int
+    lib.molora_shrink_base_small.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, i64, i32, i32, i32, i32, vp, vp]
+    lib.molora_shrink_base_small.restype = ctypes.c_int
+    lib.molora_expand_small.argtypes = [vp, vp, vp, vp, vp, i64, i32, i32, i32, vp]
+    lib.molora_expand_small.restype = ctypes.c_int
     lib.molora_base_expand_dense.argtypes = [vp, vp, vp, vp, vp, vp, vp, i64, i32, i32, i32, i32, vp]
     lib.molora_base_expand_dense.restype = ctypes.c_int
     lib.molora_init.argtypes = []
@@ -412,6 +416,40 @@ def molora_bucket_shrink_small(r, x, A, offsets=None, perm=None, t=None, workspa
           _dev(perm, torch.int32, "perm", (N,)), _dev(t, bf, "t", (N, 2 * rank)), N, d_in, C, rank,
           ws, ws_bytes, _opt(err_flag, torch.int32, "err_flag"), _stream(stream))
     return offsets, perm, t
+
+
+def molora_shrink_base_small(r, x, W, A, offsets=None, perm=None, t=None, h=None, err_flag=None, stream=None):
+    """A batch of at most 64 tokens: dispatch, shrink and h = x W in one launch:
+    (offsets, perm, t [N][2*rank] in bucket order, h [N][d_out] holding the base projection)."""
+    N, d_in = _two(x, "x")
+    d_out = _two(W, "W")[1]
+    C, _, rank = _three(A, "A")
+    if offsets is None:
+        offsets = torch.empty(C + 1, dtype=torch.int32, device=x.device)
+    if perm is None:
+        perm = torch.empty(N, dtype=torch.int32, device=x.device)
+    if t is None:
+        t = torch.empty((N, 2 * rank), dtype=torch.bfloat16, device=x.device)
+    if h is None:
+        h = torch.empty((N, d_out), dtype=torch.float32, device=x.device)
+    bf = torch.bfloat16
+    _call("molora_shrink_base_small", _dev(r, torch.int32, "r", (N,)), _dev(x, bf, "x"),
+          _dev(W, bf, "W", (d_in, d_out)), _dev(A, bf, "A", (C, d_in, rank)),
+          _dev(offsets, torch.int32, "offsets", (C + 1,)), _dev(perm, torch.int32, "perm", (N,)),
+          _dev(t, bf, "t", (N, 2 * rank)), _dev(h, torch.float32, "h", (N, d_out)), N, d_in, d_out, C, rank,
+          _opt(err_flag, torch.int32, "err_flag"), _stream(stream))
+    return offsets, perm, t, h
+
+
+def molora_expand_small(B, t, offsets, perm, h, stream=None):
+    """h[perm[p]] += t_p B_c (a batch of at most 64 tokens; after molora_shrink_base_small)."""
+    C, rank, d_out = _three(B, "B")
+    N = int(h.shape[0])
+    bf = torch.bfloat16
+    _call("molora_expand_small", _dev(B, bf, "B"), _dev(t, bf, "t", (N, 2 * rank)),
+          _dev(offsets, torch.int32, "offsets", (C + 1,)), _dev(perm, torch.int32, "perm", (N,)),
+          _dev(h, torch.float32, "h", (N, d_out)), N, d_out, C, rank, _stream(stream))
+    return h
 
 
 def molora_gate_dispatch_shrink(v, breaks, x, A, adapter=None, n_adapters=1, r=None, offsets=None, perm=None,

@@ -141,12 +141,17 @@ molora_status apply_common(const void *x, const void *W, const void *A, const vo
                                       d_in, d_out, C, rank, molora::Mix{1, C, nullptr, nullptr, 1}, s);
         return from_hip(e);
     }
-    // a batch of at most 64 tokens: the dispatch step runs inside the shrink launch
+    // a batch of at most 64 tokens: dispatch, shrink and the base projection in one launch (the
+    // latency-bound shrink hides behind the stream of W), then the expand added to h
     molora::SortArgs sort{};
     if (r != nullptr && molora::sort_in_shrink_ok(N, d_in, C, rank)) {
-        sort = molora::SortArgs{r, ws.offsets, ws.perm, nullptr};
-        offsets = ws.offsets;
-        perm = ws.perm;
+        const molora::Mix one{1, C, nullptr, nullptr};
+        e = molora::launch_small_shrink_base(xb, static_cast<const uint16_t *>(W), Ab, h, ws.t2, N, d_in,
+                                             d_out, C, rank, one,
+                                             molora::SortArgs{r, ws.offsets, ws.perm, nullptr}, s);
+        if (e != hipSuccess) return MOLORA_EHIP;
+        return from_hip(molora::launch_small_expand(static_cast<const uint16_t *>(B), ws.t2, ws.offsets,
+                                                    ws.perm, h, N, d_in, d_out, C, rank, one, s));
     } else if (r != nullptr) {
         e = molora::launch_bucket(r, ws.offsets, ws.perm, N, C, nullptr, s);
         if (e != hipSuccess) return MOLORA_EHIP;
@@ -375,6 +380,40 @@ molora_status molora_bucket_shrink_small(const int32_t *r, const void *x, const 
                                           molora::Mix{1, C, nullptr, nullptr},
                                           static_cast<hipStream_t>(stream), scratch,
                                           molora::SortArgs{r, offsets, perm, err_flag}));
+}
+
+molora_status molora_shrink_base_small(const int32_t *r, const void *x, const void *W, const void *A,
+                                       int32_t *offsets, int32_t *perm, void *t, float *h, int64_t N,
+                                       int32_t d_in, int32_t d_out, int32_t C, int32_t rank,
+                                       int32_t *err_flag, void *stream) {
+    if (!apply_sizes_ok(N, d_in, d_out, C, rank) || !molora::sort_in_shrink_ok(N, d_in, C, rank))
+        return MOLORA_EINVAL;
+    if (!r || !x || !W || !A || !offsets || !perm || !t || !h) return MOLORA_EINVAL;
+    if (!aligned16(r) || !aligned16(x) || !aligned16(W) || !aligned16(A) || !aligned16(offsets) ||
+        !aligned16(perm) || !aligned16(t) || !aligned16(h))
+        return MOLORA_EALIGN;
+    if (molora::ensure_device_ready() != hipSuccess) return MOLORA_EHIP;
+    return from_hip(molora::launch_small_shrink_base(
+        static_cast<const uint16_t *>(x), static_cast<const uint16_t *>(W),
+        static_cast<const uint16_t *>(A), h, static_cast<uint16_t *>(t), N, d_in, d_out, C, rank,
+        molora::Mix{1, C, nullptr, nullptr}, molora::SortArgs{r, offsets, perm, err_flag},
+        static_cast<hipStream_t>(stream)));
+}
+
+molora_status molora_expand_small(const void *B, const void *t, const int32_t *offsets,
+                                  const int32_t *perm, float *h, int64_t N, int32_t d_out, int32_t C,
+                                  int32_t rank, void *stream) {
+    const int32_t d_in = 8;  // the step does not touch x or W
+    if (!apply_sizes_ok(N, d_in, d_out, C, rank) || N > 64) return MOLORA_EINVAL;
+    if (N == 0) return MOLORA_OK;
+    if (!B || !t || !offsets || !perm || !h) return MOLORA_EINVAL;
+    if (!aligned16(B) || !aligned16(t) || !aligned16(offsets) || !aligned16(perm) || !aligned16(h))
+        return MOLORA_EALIGN;
+    if (molora::ensure_device_ready() != hipSuccess) return MOLORA_EHIP;
+    return from_hip(molora::launch_small_expand(static_cast<const uint16_t *>(B),
+                                                static_cast<const uint16_t *>(t), offsets, perm, h, N, d_in,
+                                                d_out, C, rank, molora::Mix{1, C, nullptr, nullptr},
+                                                static_cast<hipStream_t>(stream)));
 }
 
 molora_status molora_gate_dispatch_shrink(const int32_t *v, const int32_t *adapter,

@@ -144,6 +144,15 @@ hipError_t launch_small_batch_gemm(const uint16_t *x, const uint16_t *W, const u
                                    const uint16_t *t2, const int32_t *offsets, const int32_t *perm,
                                    float *h, int64_t N, int d_in, int d_out, int C, int rank, Mix mix,
                                    hipStream_t s);
+// A batch of at most 64 tokens in two launches instead of four: (1) the dispatch step, the shrink
+// and the base projection h = x W side by side (the latency-bound shrink hides behind the
+// stream of W), (2) the expand added to h.
+hipError_t launch_small_shrink_base(const uint16_t *x, const uint16_t *W, const uint16_t *A, float *h,
+                                    uint16_t *t_out, int64_t N, int d_in, int d_out, int C, int rank,
+                                    Mix mix, SortArgs sort, hipStream_t s);
+hipError_t launch_small_expand(const uint16_t *B, const uint16_t *t2, const int32_t *offsets,
+                               const int32_t *perm, float *h, int64_t N, int d_in, int d_out, int C,
+                               int rank, Mix mix, hipStream_t s);
 // ksplit > 1 (with planes, fp32 [ksplit][N][R]): K cut into slices over workgroups, second pass adds them
 int small_batch_shrink_ksplit(int64_t N, int d_in, int C, int R);
 hipError_t launch_small_batch_shrink(const uint16_t *x, const uint16_t *A, const int32_t *offsets,

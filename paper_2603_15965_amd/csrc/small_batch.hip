@@ -95,12 +95,25 @@ struct Unit {
 //                 from HBM at speed, a workgroup draws ~50 GB/s.  A slice's sums then go, in
 //                 fp32, to plane `slice` of h [ksplit][N][R]; shrink_reduce_kernel adds the
 //                 planes in ascending order (a fixed order: no atomics) and writes t_out.
-template <int TM, int TN, bool SHRINK>  // TM: 32-row blocks, 1 (N <= 32) or 2
-__global__ __launch_bounds__(kSbWaves * 64) void small_batch_kernel(
+//
+// The body is a device function of the workgroup's place in its grid (wg) so that two grids
+// can share one launch (shrink_base_small_kernel below).  GEMM modes (SHRINK = false, a batch
+// of one row tile): kSbBaseOnly leaves the expand phase out and reads neither offsets nor perm
+// (h = x W: nothing the dispatch step produces is needed); kSbExpandOnly leaves the W stream
+// out and ADDS the expand to h (h += t B_c).  One after the other they give what mode 0 gives
+// up to the order of the fp32 additions.
+struct SbBlock {
+    int x, y, z;  // the workgroup's index in its grid
+    int gy;       // the grid's extent in y
+};
+constexpr int kSbBaseOnly = 1, kSbExpandOnly = 2;
+
+template <int TM, int TN, bool SHRINK, int MODE = 0>  // TM: 32-row blocks, 1 (N <= 32) or 2
+__device__ __forceinline__ void small_batch_body(
     const uint16_t *__restrict__ x, const uint16_t *__restrict__ W, const uint16_t *__restrict__ B,
     const uint16_t *__restrict__ t2, const int32_t *__restrict__ offsets,
     const int32_t *__restrict__ perm, float *__restrict__ h, uint16_t *__restrict__ t_out, int N,
-    int d_in, int d_out, int C, int rank, Mix mix, int ksplit, SortArgs sort) {
+    int d_in, int d_out, int C, int rank, Mix mix, int ksplit, SortArgs sort, SbBlock wg) {
     using Geo = SbGeom<TN>;
     constexpr int kSbCols = Geo::COLS, kSbSlot = Geo::SLOT, kSbRowBytes = Geo::ROW_BYTES,
                   kSbWaveLds = Geo::WAVE_LDS;
@@ -114,7 +127,7 @@ __global__ __launch_bounds__(kSbWaves * 64) void small_batch_kernel(
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int n0 = blockIdx.x * kSbCols;
+    const int n0 = wg.x * kSbCols;
     unsigned char *ring = smem + wave * kSbWaveLds;
     unsigned char *stage = ring + kSbRing * kSbSlot;
     const uint16_t *zero = (const uint16_t *)g_zero_page;
@@ -130,9 +143,9 @@ __global__ __launch_bounds__(kSbWaves * 64) void small_batch_kernel(
     const bool sorting = SHRINK && sort.r != nullptr;
     int sort_tok = 0;  // sorting: token of row `lane` of the bucket (lanes past its rows: 0)
     if constexpr (SHRINK) {
-        bucket = blockIdx.y;
+        bucket = wg.y;
         if (sorting) {
-            if (blockIdx.z >= (unsigned)ksplit) return;  // a batch of one wavefront is one row tile
+            if (wg.z >= ksplit) return;  // a batch of one wavefront is one row tile
             int key = C + 1;  // lanes past the batch: no key at all
             if (lane < N) {
                 const int c = sort.r[lane];
@@ -152,7 +165,7 @@ __global__ __launch_bounds__(kSbWaves * 64) void small_batch_kernel(
             row_base = (int)__popcll(__ballot(key < bucket));  // sorted position of the bucket's first row
             nrows = (int)__popcll(mine);
             sort_tok = nth_lane(mine);
-            if (blockIdx.x == 0 && blockIdx.z == 0 && wave == 0) {
+            if (wg.x == 0 && wg.z == 0 && wave == 0) {
                 if (lane == 0) sort.offsets[bucket] = row_base;
                 if (lane < nrows) sort.perm[row_base + lane] = sort_tok;
                 if (bucket == C - 1) {  // ... and once: the end of the lists, the tokens without adapter
@@ -166,18 +179,20 @@ __global__ __launch_bounds__(kSbWaves * 64) void small_batch_kernel(
             }
             if (nrows <= 0) return;  // an empty bucket: its adapters are not touched
         } else {
-            row_base = offsets[bucket] + 64 * (blockIdx.z / ksplit);  // 64-row tile of the bucket
+            row_base = offsets[bucket] + 64 * (wg.z / ksplit);  // 64-row tile of the bucket
             nrows = min(64, offsets[bucket + 1] - row_base);
             if (nrows <= 0) return;  // nothing (left) in this bucket: its adapters are not touched
         }
     } else {
-        row_base = blockIdx.y * 64;  // row tile of 64 sorted positions
+        row_base = wg.y * 64;  // row tile of 64 sorted positions
         nrows = min(64, N - row_base);
     }
     // A batch that fits one row tile keeps its rows in token order: x W then depends on nothing
     // the dispatch step produced, so the stream starts at once, and only the expand units (the
     // end of every wavefront's list) look up the sorted position of a row.
-    const bool direct = !SHRINK && gridDim.y == 1;
+    const bool direct = !SHRINK && wg.gy == 1;
+    constexpr bool base_only = !SHRINK && MODE == kSbBaseOnly;      // direct batches only (host)
+    constexpr bool expand_only = !SHRINK && MODE == kSbExpandOnly;  // direct batches only (host)
 
     // ---- this wavefront's share of W ----
     // Of the nub pieces of 64 k-rows of W (the last piece may be short) every 8th one, piece
@@ -186,10 +201,10 @@ __global__ __launch_bounds__(kSbWaves * 64) void small_batch_kernel(
     const int two_r = 2 * R;
     const int nub_all = (d_in + 63) / 64;
     // K slice of this workgroup (SHRINK with ksplit > 1): pieces [u_lo, u_lo + nub)
-    const int slice = SHRINK ? (int)(blockIdx.z % ksplit) : 0;
+    const int slice = SHRINK ? wg.z % ksplit : 0;
     const int per_slice = SHRINK ? (nub_all + ksplit - 1) / ksplit : nub_all;
     const int u_lo = slice * per_slice;
-    const int nub = max(0, min(nub_all, u_lo + per_slice) - u_lo);
+    const int nub = expand_only ? 0 : max(0, min(nub_all, u_lo + per_slice) - u_lo);
     const int nw = nub > wave ? (nub - wave + kSbWaves - 1) / kSbWaves : 0;
 
     const int pitch = SHRINK ? rank : d_out;  // elements between consecutive k-rows of W (A)
@@ -294,6 +309,21 @@ __global__ __launch_bounds__(kSbWaves * 64) void small_batch_kernel(
         }
     };
 
+    // expand alone: what h holds (the rows' x W) is fetched now and added at the end; in token
+    // order the row of h is the tile row, so nothing has to be looked up first
+    constexpr int kOutIters = (TM * 32 * (kSbCols / 4) + kSbWaves * 64 - 1) / (kSbWaves * 64);
+    f32x4 h_old[kOutIters];
+    if constexpr (expand_only) {
+#pragma unroll
+        for (int j = 0; j < kOutIters; ++j) {
+            const int it = tid + j * kSbWaves * 64;
+            const int row = it / (kSbCols / 4), col = n0 + (it % (kSbCols / 4)) * 4;
+            const bool ok = it < TM * 32 * (kSbCols / 4) && row < nrows && col < d_out;
+            // (rows and columns past the end: read again from the first element, never used)
+            h_old[j] = *(const f32x4 *)(h + (ok ? (int64_t)row * d_out + col : 0));
+        }
+    }
+
     f32x16 acc[TM][TN];
 #pragma unroll
     for (int i = 0; i < TM; ++i)
@@ -354,7 +384,7 @@ __global__ __launch_bounds__(kSbWaves * 64) void small_batch_kernel(
     if (wave == 0) {
         tile_perm[lane] = lane < nrows ? (sorting ? sort_tok : (direct ? lane : perm[row_base + lane])) : -1;
         tile_pos[lane] = direct ? 0x7fffffff : row_base + lane;
-        if (direct && lane < nrows) {
+        if (direct && !base_only && lane < nrows) {
             const int tok = perm[lane];
             if ((unsigned)tok < 64u) tile_pos[tok] = lane;  // same wavefront: after the line above
         }
@@ -362,7 +392,7 @@ __global__ __launch_bounds__(kSbWaves * 64) void small_batch_kernel(
     if (wave == kSbWaves - 1) {
         const uint64_t lower = (lane == 0) ? 0ull : (~0ull >> (64 - lane));
         int cnt = 0;
-        for (int c0 = 0; !SHRINK && c0 < C; c0 += 64) {
+        for (int c0 = 0; !SHRINK && !base_only && c0 < C; c0 += 64) {
             const int c = min(c0 + lane, C - 1);
             // the bucket's sorted positions inside this row tile
             const int lo = max(offsets[c], row_base), hi = min(offsets[c + 1], row_base + nrows);
@@ -420,11 +450,13 @@ __global__ __launch_bounds__(kSbWaves * 64) void small_batch_kernel(
     // the loads of the matching columns of t (both halves, [hi | lo]; zero for rows outside
     // the bucket) are all issued before the first is waited for, so a round costs one trip to
     // memory.  One read of a slab serves both halves of t.
-    if constexpr (!SHRINK) {
+    if constexpr (!SHRINK && !base_only) {
         const int nseg = __builtin_amdgcn_readfirstlane(*nseg_p);
         const int nsl = (R + 15) / 16;  // slabs per bucket
         const int nq = nseg * nsl;
-        constexpr int G = 4;  // slabs per round (8 measured no faster: the phase is bound by reading B)
+        // slabs per round: 4 behind the W stream (8 measured no faster: the phase is bound by
+        // reading B there), 8 when the expand runs alone (bound by its trips to memory)
+        constexpr int G = expand_only ? 8 : 4;
         static_assert(G * kSbSlot <= kSbWaveLds, "a round's slabs fit the wavefront's LDS");
         int p_row[TM];  // sorted position of this lane's rows
 #pragma unroll
@@ -507,7 +539,10 @@ __global__ __launch_bounds__(kSbWaves * 64) void small_batch_kernel(
                 *(float *)(ring + row * kSbRowBytes + (tn * 32 + m_lo) * 4) = acc[tm][tn][v];
         }
     __syncthreads();
-    for (int it = tid; it < TM * 32 * (kSbCols / 4); it += kSbWaves * 64) {
+#pragma unroll
+    for (int j = 0; j < kOutIters; ++j) {
+        const int it = tid + j * kSbWaves * 64;
+        if (it >= TM * 32 * (kSbCols / 4)) break;
         const int row = it / (kSbCols / 4), ch = it % (kSbCols / 4);
         const int tok = tile_perm[row];
         const int col = n0 + ch * 4;
@@ -525,8 +560,45 @@ __global__ __launch_bounds__(kSbWaves * 64) void small_batch_kernel(
             const float wj = mix.w != nullptr ? mix.w[(int64_t)tok * mix.k + col / rank] : 1.f;
             store_t_hi_lo(t_out + (int64_t)(row_base + row) * 2 * R, R, col, sum, wj);
         } else {
+            if constexpr (expand_only) sum += h_old[j];  // this row's x W, written by the launch before
             *(f32x4 *)(h + (int64_t)tok * d_out + col) = sum;
         }
+    }
+}
+
+template <int TM, int TN, bool SHRINK, int MODE>
+__global__ __launch_bounds__(kSbWaves * 64) void small_batch_kernel(
+    const uint16_t *__restrict__ x, const uint16_t *__restrict__ W, const uint16_t *__restrict__ B,
+    const uint16_t *__restrict__ t2, const int32_t *__restrict__ offsets,
+    const int32_t *__restrict__ perm, float *__restrict__ h, uint16_t *__restrict__ t_out, int N,
+    int d_in, int d_out, int C, int rank, Mix mix, int ksplit, SortArgs sort) {
+    small_batch_body<TM, TN, SHRINK, MODE>(x, W, B, t2, offsets, perm, h, t_out, N, d_in, d_out, C, rank, mix,
+                                           ksplit, sort,
+                                           SbBlock{(int)blockIdx.x, (int)blockIdx.y, (int)blockIdx.z,
+                                                   (int)gridDim.y});
+}
+
+// A decode-sized batch (N <= 64): the shrink (with the dispatch step inside, see SortArgs) and
+// the base projection h = x W in ONE launch.  Neither needs anything from the other -- the
+// base projection of a batch of one row tile runs in token order -- so the latency-bound
+// shrink (a dozen workgroups each draining one A_c) hides behind the stream of W instead of
+// preceding it.  Workgroups [0, n_shrink) are the shrink's grid (column groups of the rank x
+// buckets, K not split: there is no hurry now), the others the GEMM's column groups in
+// kSbBaseOnly mode.  The expand follows as a launch of its own (kSbExpandOnly).
+template <int TM, int TN>
+__global__ __launch_bounds__(kSbWaves * 64) void shrink_base_small_kernel(
+    const uint16_t *__restrict__ x, const uint16_t *__restrict__ W, const uint16_t *__restrict__ A,
+    float *__restrict__ h, uint16_t *__restrict__ t_out, int N, int d_in, int d_out, int C, int rank,
+    Mix mix, SortArgs sort, int shrink_groups, int n_shrink) {
+    const int b = (int)blockIdx.x;
+    if (b < n_shrink) {
+        small_batch_body<TM, 1, true>(x, A, nullptr, nullptr, nullptr, nullptr, nullptr, t_out, N, d_in,
+                                      mix.k * rank, C, rank, mix, 1, sort,
+                                      SbBlock{b % shrink_groups, b / shrink_groups, 0, C});
+    } else {
+        small_batch_body<TM, TN, false, kSbBaseOnly>(x, W, nullptr, nullptr, nullptr, nullptr, h, nullptr, N,
+                                                     d_in, d_out, C, rank, mix, 1, SortArgs{},
+                                                     SbBlock{b - n_shrink, 0, 0, 1});
     }
 }
 
@@ -560,19 +632,19 @@ __global__ __launch_bounds__(256) void shrink_reduce_kernel(const float *__restr
 }
 
 // more than 64 KB of dynamic LDS has to be asked for, once per device (see common.h)
-template <int TM, int TN, bool SHRINK>
+template <int TM, int TN, bool SHRINK, int MODE>
 struct SmallBatchKernel {
-    static inline LdsRegistrar lds{(const void *)small_batch_kernel<TM, TN, SHRINK>, SbGeom<TN>::LDS_BYTES};
+    static inline LdsRegistrar lds{(const void *)small_batch_kernel<TM, TN, SHRINK, MODE>, SbGeom<TN>::LDS_BYTES};
 };
 
-template <int TM, int TN, bool SHRINK>
+template <int TM, int TN, bool SHRINK, int MODE = 0>
 hipError_t launch_small(const uint16_t *x, const uint16_t *W, const uint16_t *B, const uint16_t *t2,
                         const int32_t *offsets, const int32_t *perm, float *h, uint16_t *t_out, int N,
                         int d_in, int d_out, int C, int rank, Mix mix, hipStream_t s, int ksplit,
                         SortArgs sort) {
     using Geo = SbGeom<TN>;
-    auto kern = small_batch_kernel<TM, TN, SHRINK>;
-    (void)&SmallBatchKernel<TM, TN, SHRINK>::lds;  // instantiates the registration
+    auto kern = small_batch_kernel<TM, TN, SHRINK, MODE>;
+    (void)&SmallBatchKernel<TM, TN, SHRINK, MODE>::lds;  // instantiates the registration
     const unsigned groups = (unsigned)((d_out + Geo::COLS - 1) / Geo::COLS);
     const unsigned row_tiles = (unsigned)((N + 63) / 64);
     // GEMM: row tiles of the batch.  SHRINK: buckets x row tiles a bucket can have at most
@@ -584,7 +656,7 @@ hipError_t launch_small(const uint16_t *x, const uint16_t *W, const uint16_t *B,
     return hipGetLastError();
 }
 
-template <bool SHRINK>
+template <bool SHRINK, int MODE = 0>
 hipError_t launch_small_tn(const uint16_t *x, const uint16_t *W, const uint16_t *B, const uint16_t *t2,
                            const int32_t *offsets, const int32_t *perm, float *h, uint16_t *t_out,
                            int N, int d_in, int d_out, int C, int rank, Mix mix, hipStream_t s,
@@ -595,7 +667,7 @@ hipError_t launch_small_tn(const uint16_t *x, const uint16_t *W, const uint16_t 
     const int64_t wgs64 = (int64_t)((d_out + 63) / 64) * ((N + 63) / 64);
     const bool narrow = SHRINK || wgs64 <= 128;
 #define MOLORA_SB_LAUNCH(TM, TN) \
-    launch_small<TM, TN, SHRINK>(x, W, B, t2, offsets, perm, h, t_out, N, d_in, d_out, C, rank, mix, s, ksplit, sort)
+    launch_small<TM, TN, SHRINK, MODE>(x, W, B, t2, offsets, perm, h, t_out, N, d_in, d_out, C, rank, mix, s, ksplit, sort)
     if (N <= 32) return narrow ? MOLORA_SB_LAUNCH(1, 1) : MOLORA_SB_LAUNCH(1, 2);
     return narrow ? MOLORA_SB_LAUNCH(2, 1) : MOLORA_SB_LAUNCH(2, 2);
 #undef MOLORA_SB_LAUNCH
@@ -609,6 +681,50 @@ hipError_t launch_small_batch_gemm(const uint16_t *x, const uint16_t *W, const u
                                    hipStream_t s) {
     return launch_small_tn<false>(x, W, B, t2, offsets, perm, h, nullptr, (int)N, d_in, d_out, C, rank,
                                   mix, s);
+}
+
+namespace {
+template <int TM, int TN>
+struct ShrinkBaseKernel {
+    static constexpr size_t LDS = (SbGeom<TN>::LDS_BYTES > SbGeom<1>::LDS_BYTES) ? SbGeom<TN>::LDS_BYTES
+                                                                               : SbGeom<1>::LDS_BYTES;
+    static inline LdsRegistrar lds{(const void *)shrink_base_small_kernel<TM, TN>, LDS};
+};
+template <int TM, int TN>
+hipError_t launch_shrink_base(const uint16_t *x, const uint16_t *W, const uint16_t *A, float *h,
+                              uint16_t *t_out, int N, int d_in, int d_out, int C, int rank, Mix mix,
+                              SortArgs sort, hipStream_t s) {
+    (void)&ShrinkBaseKernel<TM, TN>::lds;  // instantiates the registration
+    const int shrink_groups = (mix.k * rank + 31) / 32;
+    const int n_shrink = shrink_groups * C;
+    const int gemm_groups = (d_out + SbGeom<TN>::COLS - 1) / SbGeom<TN>::COLS;
+    auto kern = shrink_base_small_kernel<TM, TN>;
+    constexpr size_t lds_bytes = ShrinkBaseKernel<TM, TN>::LDS;
+    hipLaunchKernelGGL(kern, dim3((unsigned)(n_shrink + gemm_groups)), dim3(kSbWaves * 64), lds_bytes, s, x,
+                       W, A, h, t_out, N, d_in, d_out, C, rank, mix, sort, shrink_groups, n_shrink);
+    return hipGetLastError();
+}
+}  // namespace
+
+// N <= 64: dispatch + shrink + h = x W in one launch (sort.r, sort.offsets, sort.perm required)
+hipError_t launch_small_shrink_base(const uint16_t *x, const uint16_t *W, const uint16_t *A, float *h,
+                                    uint16_t *t_out, int64_t N, int d_in, int d_out, int C, int rank,
+                                    Mix mix, SortArgs sort, hipStream_t s) {
+    if (N < 1 || N > 64 || mix.k != 1 || !sort.r || !sort.offsets || !sort.perm) return hipErrorInvalidValue;
+    const bool narrow = (int64_t)((d_out + 63) / 64) <= 128;
+#define MOLORA_SBB(TM, TN) launch_shrink_base<TM, TN>(x, W, A, h, t_out, (int)N, d_in, d_out, C, rank, mix, sort, s)
+    if (N <= 32) return narrow ? MOLORA_SBB(1, 1) : MOLORA_SBB(1, 2);
+    return narrow ? MOLORA_SBB(2, 1) : MOLORA_SBB(2, 2);
+#undef MOLORA_SBB
+}
+
+// N <= 64: h += t B_c (the expand alone, after launch_small_shrink_base)
+hipError_t launch_small_expand(const uint16_t *B, const uint16_t *t2, const int32_t *offsets,
+                               const int32_t *perm, float *h, int64_t N, int d_in, int d_out, int C,
+                               int rank, Mix mix, hipStream_t s) {
+    if (N < 1 || N > 64) return hipErrorInvalidValue;
+    return launch_small_tn<false, kSbExpandOnly>(nullptr, nullptr, B, t2, offsets, perm, h, nullptr, (int)N, d_in,
+                                                 d_out, C, rank, mix, s);
 }
 
 int small_batch_shrink_ksplit(int64_t N, int d_in, int C, int R) {

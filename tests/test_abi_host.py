@@ -151,6 +151,11 @@ def test_one_launch_dispatch_and_shrink_reject_bad_arguments(lib):
                                                       ws, 0, None, None)
     assert call(N=65) == EINVAL and call(rank=32) == EINVAL and call(r=0) == EINVAL
     assert call(t=a + 8) == EALIGN
+    k1 = lambda N=64, rank=64, W=a, h=a: lib.molora_shrink_base_small(p(a), p(a), p(W), p(a), p(a), p(a), p(a), p(h),
+                                                                     N, 4096, 256, 16, rank, None, None)
+    assert k1(N=65) == EINVAL and k1(rank=32) == EINVAL and k1(W=0) == EINVAL and k1(h=a + 4) == EALIGN
+    k2 = lambda N=64, B=a, h=a: lib.molora_expand_small(p(B), p(a), p(a), p(a), p(h), N, 256, 16, 64, None)
+    assert k2(N=65) == EINVAL and k2(B=0) == EINVAL and k2(h=a + 4) == EALIGN and k2(N=0) == 0
     g = lib.molora_bucket_shrink
     assert g(p(a), p(a), p(a), p(a), p(a), p(a), 64, 4096, 2, 16, None, None) == EINVAL   # N <= 512
     assert g(p(a), p(a), p(a), p(a), p(a), p(a), 4096, 2048, 8, 16, None, None) == EINVAL  # C * rank > 64

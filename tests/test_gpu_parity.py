@@ -249,8 +249,20 @@ def test_bucket_shrink_small_one_launch(gpu, N, d_in, d_out, C, rank, structure,
         assert np.max(np.abs(got - ref_t) / np.maximum(1.0, np.abs(ref_t))) <= 2e-5, f"t of sorted position {p}"
     h = mb.molora_base_expand(x, W, B, t, offsets, perm)
     torch.cuda.synchronize()
-    gpu.assert_h_close(h.cpu().numpy(), oracle.apply(w.x, w.W, w.A, w.B, r), "dispatch inside the shrink, then expand")
-    assert torch.equal(h, gpu.gpu_apply(w, r)), "molora_apply takes the same path"
+    ref = oracle.apply(w.x, w.W, w.A, w.B, r)
+    gpu.assert_h_close(h.cpu().numpy(), ref, "dispatch inside the shrink, then expand")
+    # the two-launch form: dispatch + shrink + h = x W in one launch, then the expand added to h
+    o3, p3, t3, h3 = mb.molora_shrink_base_small(rd, x, W, A)
+    torch.cuda.synchronize()
+    assert np.array_equal(o3.cpu().numpy(), o_ref) and np.array_equal(p3.cpu().numpy(), p_ref)
+    t_unsplit = mb.molora_bucket_shrink_small(rd, x, A, workspace=None)[2]
+    assert torch.equal(t3[:n_routed], t_unsplit[:n_routed]), "t of the combined launch"
+    base = oracle.apply(w.x, w.W, w.A, w.B, np.full(N, -1, dtype=np.int32))   # no adapter anywhere: x W
+    gpu.assert_h_close(h3.cpu().numpy(), base, "base projection of the combined launch")
+    mb.molora_expand_small(B, t3, o3, p3, h3)
+    torch.cuda.synchronize()
+    gpu.assert_h_close(h3.cpu().numpy(), ref, "combined launch, then the expand added")
+    assert torch.equal(h3, gpu.gpu_apply(w, r)), "molora_apply takes the two-launch path"
 
 
 def test_gate_dispatch_shrink_matches_separate_calls(gpu):
