@@ -143,7 +143,6 @@ molora_status apply_common(const void *x, const void *W, const void *A, const vo
     }
     // a batch of at most 64 tokens: dispatch, shrink and the base projection in one launch (the
     // latency-bound shrink hides behind the stream of W), then the expand added to h
-    molora::SortArgs sort{};
     if (r != nullptr && molora::sort_in_shrink_ok(N, d_in, C, rank)) {
         const molora::Mix one{1, C, nullptr, nullptr};
         e = molora::launch_small_shrink_base(xb, static_cast<const uint16_t *>(W), Ab, h, ws.t2, N, d_in,
@@ -152,7 +151,8 @@ molora_status apply_common(const void *x, const void *W, const void *A, const vo
         if (e != hipSuccess) return MOLORA_EHIP;
         return from_hip(molora::launch_small_expand(static_cast<const uint16_t *>(B), ws.t2, ws.offsets,
                                                     ws.perm, h, N, d_in, d_out, C, rank, one, s));
-    } else if (r != nullptr) {
+    }
+    if (r != nullptr) {
         e = molora::launch_bucket(r, ws.offsets, ws.perm, N, C, nullptr, s);
         if (e != hipSuccess) return MOLORA_EHIP;
         offsets = ws.offsets;
@@ -160,7 +160,7 @@ molora_status apply_common(const void *x, const void *W, const void *A, const vo
     }
     const molora::Mix plain{1, C, nullptr, nullptr};
     e = molora::launch_shrink(xb, Ab, offsets, perm, ws.t2, N, d_in,
-                              C, rank, plain, s, ws.shrink_scratch, sort);
+                              C, rank, plain, s, ws.shrink_scratch);
     if (e != hipSuccess) return MOLORA_EHIP;
     e = molora::launch_fused_gemm(xb, static_cast<const uint16_t *>(W),
                                   static_cast<const uint16_t *>(B), ws.t2, offsets, perm, h, N,
