@@ -55,3 +55,15 @@ def test_zipf_is_skewed_toward_low_indices():
     cnt = np.bincount(r, minlength=16)
     w = np.arange(1, 17.0) ** -1.1
     assert np.all(np.abs(cnt / 20000 - w / w.sum()) < 0.015)
+
+
+def test_bench_refuses_more_than_one_gpu():
+    """The benchmark measures one GPU; asked for more it says so and exits without touching a GPU."""
+    import os
+    import subprocess
+    import sys
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    p = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--gpus", "2"], capture_output=True,
+                       text=True, timeout=120)
+    assert p.returncode != 0
+    assert "one GPU" in (p.stderr + p.stdout)
