@@ -70,3 +70,40 @@ def test_random_shape(i, N, d_in, d_out, C, rank, k, S, bad):
         h1 = mb.molora_apply(x, W, A, B, gpu.dev_i32(idx[:, 0]))
         torch.cuda.synchronize()
         gpu.assert_h_close(h1.cpu().numpy(), oracle.apply(w.x, w.W, w.A, w.B, idx[:, 0]), f"apply {i}")
+
+
+def _plain_cases():
+    """Shapes that take molora_apply's special routes: a few narrow adapters (dispatch and
+    token-order shrink in one launch) and decode-sized batches (dispatch, shrink and x W in one
+    launch, then the expand), with targets out of range in half of them."""
+    rng = np.random.default_rng(20260316)
+    out = []
+    for i in range(12):   # C * rank <= 64, N > 512
+        C, rank = [(1, 8), (2, 8), (4, 8), (8, 8), (1, 16), (2, 16), (4, 16), (3, 16), (1, 32), (2, 32), (1, 64),
+                   (5, 8)][i]
+        N = int(rng.integers(513, 6000))
+        out.append((i, N, int(rng.integers(2, 90)) * 8, int(rng.integers(2, 90)) * 8, C, rank, i % 2 == 1))
+    for i in range(12, 24):   # N <= 64, rank above 32
+        rank = int(rng.choice([40, 48, 64, 96, 128]))
+        out.append((i, int(rng.integers(1, 65)), int(rng.integers(2, 160)) * 8, int(rng.integers(2, 90)) * 8,
+                    int(rng.integers(1, 40)), rank, i % 2 == 1))
+    return out
+
+
+@pytest.mark.parametrize("i,N,d_in,d_out,C,rank,bad", _plain_cases())
+def test_random_shape_plain_routes(i, N, d_in, d_out, C, rank, bad):
+    import oracle
+    import torch
+    import gpu_helpers as gpu
+    from paper_2603_15965_amd import binding as mb
+    print(f"random plain shape {i}: N={N} {d_in}->{d_out} C={C} rank={rank} bad={bad}", flush=True)
+    assert mb.molora_dense_shrink_supported(N, d_in, C, rank) or mb.molora_bucket_shrink_small_supported(N, d_in, C, rank)
+    w = wl.custom("rndp", N, d_in, d_out, C, rank, wl.BASE_SEED + 32000 + i, structure="zipf" if i % 3 else "uniform")
+    r = w.r.copy()
+    if bad:
+        rng = np.random.default_rng(7100 + i)
+        r[rng.random(N) < 0.2] = int(rng.choice([-1, C, C + 5, -1000]))
+    x, W, A, B = (gpu.dev_bf16(t) for t in (w.x, w.W, w.A, w.B))
+    h = mb.molora_apply(x, W, A, B, gpu.dev_i32(r))
+    torch.cuda.synchronize()
+    gpu.assert_h_close(h.cpu().numpy(), oracle.apply(w.x, w.W, w.A, w.B, r), f"random plain shape {i}")
