@@ -62,6 +62,8 @@ def parse():
                          "warm-up and the timed region only)")
     ap.add_argument("--no-kernel-events", action="store_true",
                     help="leave the per-kernel HIP events out of the timed region")
+    ap.add_argument("--row-major-w", action="store_true",
+                    help="decode-sized batches: give the kernel the row-major base weight, not the packed one")
     ap.add_argument("--no-other-configs", action="store_true",
                     help="leave out the short runs of the other configurations (the `configs` object)")
     ap.add_argument("--copy-calibration", action="store_true",
@@ -179,8 +181,16 @@ def run_workload(args, workload, steps, warmup, full):
             d["t"] = torch.empty((sh.N, 2 * rk * (C if d["dense"] else 1)), dtype=torch.bfloat16, device="cuda")
             d["sws"] = mb.molora_shrink_workspace(sh.N, sh.d_in, C, rk)  # None for most sizes
             d["h"] = torch.empty((sh.N, sh.d_out), dtype=torch.float32, device="cuda")
+            # a decode-sized batch streams the base weight once: it is given in the layout that
+            # stream reads best (slabs of 16 rows, column group after column group: made once per
+            # weight by molora_pack_w, outside every timed region); same bits out
+            d["Wp"] = None
+            if d["small"] and base.v is None and not args.row_major_w and mb.molora_pack_w_cols(sh.d_out):
+                d["Wp"] = mb.molora_pack_w(d["W"])
             S[s].append(d)
         del base
+
+    use_packed = [True]  # False: the row-major weight although a packed one is there (second region)
 
     def route(d, stream=None):
         if "G" in d:
@@ -201,8 +211,9 @@ def run_workload(args, workload, steps, warmup, full):
         if d["small"] and "v" not in d:
             # a decode-sized batch: dispatch + shrink + h = x W in ONE launch (the latency-bound
             # shrink hides behind the stream of W); gemm() below then adds the expand
-            mb.molora_shrink_base_small(route(d, stream), d["x"], d["W"], d["A"], d["offsets"], d["perm"], d["t"],
-                                        d["h"], stream=stream)
+            packed = d["Wp"] is not None and use_packed[0]
+            mb.molora_shrink_base_small(route(d, stream), d["x"], d["Wp"] if packed else d["W"], d["A"],
+                                        d["offsets"], d["perm"], d["t"], d["h"], stream=stream, packed=packed)
             return
         if "v" in d:  # integer routing: gating inside the dispatch kernel (one launch)
             mb.molora_gate_dispatch(d["v"], d["breaks"], None, 1, d["r"], d["offsets"], d["perm"], stream=stream)
@@ -315,6 +326,22 @@ def run_workload(args, workload, steps, warmup, full):
     gemm_us = None
     if use_ev:
         gemm_us = sum(e[2 * j].elapsed_time(e[2 * j + 1]) for e in evs.values() for j in range(P)) / len(evs) * 1e3
+
+    # the same K steps on the row-major weight, where the step above used the packed one
+    row_major = None
+    if any(d["Wp"] is not None for d in S[0]) and not args.timed_only:
+        use_packed[0] = False
+        for i in range(warmup):
+            run_step(i)
+        torch.cuda.synchronize()
+        t1 = time.perf_counter()
+        for i in range(steps):
+            run_step(i)
+        torch.cuda.synchronize()
+        el = time.perf_counter() - t1
+        use_packed[0] = True
+        row_major = {"ms_per_step": 1e3 * el / steps, "value": N * steps / el, "unit": "tokens/s",
+                     "what": "the same steps with W row-major [d_in][d_out] (molora_shrink_base_small)"}
 
     skip_passes = bool(extra) or args.timed_only or not full
     latency = None
@@ -457,11 +484,15 @@ def run_workload(args, workload, steps, warmup, full):
         "config": {"workload": wname, "rotating_sets": sets, "prewarm_ms": PREWARM_S * 1e3,
                    "launch": "recorded sequence (HIP graph) per step" if graphs is not None
                    else "kernel by kernel" + (f", steps round-robin on {args.streams} streams" if extra else ""),
-                   "kernel_events_in_timed_region": (f"every {EV_EVERY}th step" if use_ev else False)},
+                   "kernel_events_in_timed_region": (f"every {EV_EVERY}th step" if use_ev else False),
+                   "w_layout": "packed once by molora_pack_w (slabs of 16 rows, column group after column "
+                               "group); row-major figure under row_major_w"
+                   if any(d["Wp"] is not None for d in S[0]) else "row-major [d_in][d_out]"},
         "roofline": roof,
         "step_roofline": step_roof,
         "latency": latency,
         "pipelined": pipelined,
+        "row_major_w": row_major,
         "layer": {"tflops": work["layer_flops"] / (elapsed / steps) / 1e12,
                   "gbs": work["layer_bytes"] / (elapsed / steps) / 1e9,
                   "routed_tokens": n_routed_all if P > 1 else n_routed_all[0],
@@ -512,6 +543,7 @@ def main():
             o = run_workload(args, name, min(st, args.steps), min(wu, args.warmup), full=False)
             others[name] = {"workload": o["config"]["workload"], "steps": o["steps"], "warmup": o["warmup"],
                             "ms_per_step": o["ms_per_step"], "tokens_per_s": o["value"],
+                            "w_layout": o["config"]["w_layout"], "row_major_w": o["row_major_w"],
                             "kernel": {k: o["roofline"][k] for k in ("kernel", "bound", "achieved", "peak",
                                                                       "unit", "frac", "kernel_us")},
                             "step": o["step_roofline"]}

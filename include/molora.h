@@ -279,6 +279,36 @@ molora_status molora_expand_small(const void *B, const void *t, const int32_t *o
                                   int32_t rank, void *stream);
 
 /*
+ * The base weight of a decode step in the layout its kernel streams best.  With at most 64
+ * rows the step of Eq. "pertok" is one read of W from HBM.  A workgroup owns a group of gc = 64
+ * (32 for d_out <= 8192) output columns and its wavefronts take 16 rows of W at a time: in the
+ * row-major W such a slab is sixteen pieces of 2*gc bytes, d_out elements apart.  W is constant
+ * while a model is served, so it can be stored once with every slab contiguous:
+ *
+ *     Wp, d_in * d_out bf16 elements: W cut into slabs of 16 rows (slab s = rows 16 s ..;
+ *     the last one holds 8 rows when d_in is not a multiple of 16) that start where they
+ *     start in W, at element 16 s * d_out; inside a slab of n rows column group g is an
+ *     [n][gc] matrix of its own at offset g * n * gc:
+ *     Wp[16 s * d_out + g * n * gc + i * gc + c] = W[16 s + i][g * gc + c]
+ *
+ * The workgroups advance through W together, so at any time the chip reads one contiguous
+ * region (measured at 64 x 4096 -> 12288: 27.0 us against 31.4 us for the launch).
+ * molora_pack_w_cols(d_out) returns gc, or 0 when d_out is not a multiple of it (no packed
+ * form: use molora_shrink_base_small).  molora_pack_w writes Wp from W (device pointers, 16-byte
+ * aligned, distinct buffers of d_in * d_out elements; MOLORA_EINVAL for a d_out without packed
+ * form).  molora_shrink_base_small_packed is molora_shrink_base_small with Wp in the place of
+ * W: the same arithmetic in the same order, so every output is bit-identical; MOLORA_EINVAL in
+ * the same cases and for a d_out without packed form.
+ */
+int32_t molora_pack_w_cols(int32_t d_out);
+molora_status molora_pack_w(const void *W, void *Wp, int32_t d_in, int32_t d_out, void *stream);
+molora_status molora_shrink_base_small_packed(const int32_t *r, const void *x, const void *Wp,
+                                              const void *A, int32_t *offsets, int32_t *perm, void *t,
+                                              float *h, int64_t N, int32_t d_in, int32_t d_out,
+                                              int32_t C, int32_t rank, int32_t *err_flag,
+                                              void *stream);
+
+/*
  * molora_base_expand with the height of the row tiles forced, for the tiling ablation (App.
  * "Adaptive Tiling", Table "tab:adaptive_tiling": tile shape chosen from the load against one
  * fixed shape).  tile_rows = 64 (the streaming kernel, W read once per 64-row tile), 128

@@ -18,7 +18,8 @@ EXPORTS = ["molora_route", "molora_route_vocab", "molora_bucket", "molora_apply_
            "molora_base_expand",
            "molora_base_expand_fixed", "molora_init", "molora_dense_shrink_supported", "molora_bucket_shrink",
            "molora_gate_dispatch_shrink", "molora_base_expand_dense", "molora_bucket_shrink_small_supported",
-           "molora_bucket_shrink_small", "molora_shrink_base_small", "molora_expand_small", "molora_apply_static", "molora_static_workspace_bytes",
+           "molora_bucket_shrink_small", "molora_shrink_base_small", "molora_expand_small",
+           "molora_pack_w_cols", "molora_pack_w", "molora_shrink_base_small_packed", "molora_apply_static", "molora_static_workspace_bytes",
            "molora_route_mlp_workspace_bytes", "molora_route_mlp", "molora_route_compose",
            "molora_gate_dispatch",
            "molora_apply_mix_workspace_bytes", "molora_apply_mix",
@@ -82,6 +83,12 @@ def load():
     lib.molora_bucket_shrink_small.restype = ctypes.c_int
     lib.molora_shrink_base_small.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, i64, i32, i32, i32, i32, vp, vp]
     lib.molora_shrink_base_small.restype = ctypes.c_int
+    lib.molora_shrink_base_small_packed.argtypes = lib.molora_shrink_base_small.argtypes
+    lib.molora_shrink_base_small_packed.restype = ctypes.c_int
+    lib.molora_pack_w_cols.argtypes = [i32]
+    lib.molora_pack_w_cols.restype = ctypes.c_int
+    lib.molora_pack_w.argtypes = [vp, vp, i32, i32, vp]
+    lib.molora_pack_w.restype = ctypes.c_int
     lib.molora_expand_small.argtypes = [vp, vp, vp, vp, vp, i64, i32, i32, i32, vp]
     lib.molora_expand_small.restype = ctypes.c_int
     lib.molora_base_expand_dense.argtypes = [vp, vp, vp, vp, vp, vp, vp, i64, i32, i32, i32, i32, vp]
@@ -418,11 +425,34 @@ def molora_bucket_shrink_small(r, x, A, offsets=None, perm=None, t=None, workspa
     return offsets, perm, t
 
 
-def molora_shrink_base_small(r, x, W, A, offsets=None, perm=None, t=None, h=None, err_flag=None, stream=None):
+def molora_pack_w_cols(d_out):
+    """Columns per group of the packed form of a base weight with d_out columns (0: none)."""
+    return int(load().molora_pack_w_cols(int(d_out)))
+
+
+def molora_pack_w(W, Wp=None, stream=None):
+    """W [d_in][d_out] -> Wp, the same elements in the order molora_shrink_base_small(packed=True)
+    streams: pieces of 64 rows, and inside a piece groups of molora_pack_w_cols(d_out) columns one
+    after the other (done once per weight).  Wp has W's shape; row 64 u starts piece u."""
+    d_in, d_out = _two(W, "W")
+    if molora_pack_w_cols(d_out) == 0:
+        raise ValueError(f"a base weight with {d_out} columns has no packed form")
+    if Wp is None:
+        Wp = torch.empty_like(W)
+    bf = torch.bfloat16
+    _call("molora_pack_w", _dev(W, bf, "W"), _dev(Wp, bf, "Wp", (d_in, d_out)), d_in, d_out, _stream(stream))
+    return Wp
+
+
+def molora_shrink_base_small(r, x, W, A, offsets=None, perm=None, t=None, h=None, err_flag=None, stream=None,
+                             packed=False):
     """A batch of at most 64 tokens: dispatch, shrink and h = x W in one launch:
-    (offsets, perm, t [N][2*rank] in bucket order, h [N][d_out] holding the base projection)."""
+    (offsets, perm, t [N][2*rank] in bucket order, h [N][d_out] holding the base projection).
+    packed=True: W is the output of molora_pack_w."""
     N, d_in = _two(x, "x")
     d_out = _two(W, "W")[1]
+    if packed and molora_pack_w_cols(d_out) == 0:
+        raise ValueError(f"a base weight with {d_out} columns has no packed form")
     C, _, rank = _three(A, "A")
     if offsets is None:
         offsets = torch.empty(C + 1, dtype=torch.int32, device=x.device)
@@ -433,7 +463,8 @@ def molora_shrink_base_small(r, x, W, A, offsets=None, perm=None, t=None, h=None
     if h is None:
         h = torch.empty((N, d_out), dtype=torch.float32, device=x.device)
     bf = torch.bfloat16
-    _call("molora_shrink_base_small", _dev(r, torch.int32, "r", (N,)), _dev(x, bf, "x"),
+    _call("molora_shrink_base_small_packed" if packed else "molora_shrink_base_small",
+          _dev(r, torch.int32, "r", (N,)), _dev(x, bf, "x"),
           _dev(W, bf, "W", (d_in, d_out)), _dev(A, bf, "A", (C, d_in, rank)),
           _dev(offsets, torch.int32, "offsets", (C + 1,)), _dev(perm, torch.int32, "perm", (N,)),
           _dev(t, bf, "t", (N, 2 * rank)), _dev(h, torch.float32, "h", (N, d_out)), N, d_in, d_out, C, rank,

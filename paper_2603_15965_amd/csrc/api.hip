@@ -382,12 +382,14 @@ molora_status molora_bucket_shrink_small(const int32_t *r, const void *x, const 
                                           molora::SortArgs{r, offsets, perm, err_flag}));
 }
 
-molora_status molora_shrink_base_small(const int32_t *r, const void *x, const void *W, const void *A,
+namespace {
+molora_status shrink_base_small_common(const int32_t *r, const void *x, const void *W, const void *A,
                                        int32_t *offsets, int32_t *perm, void *t, float *h, int64_t N,
                                        int32_t d_in, int32_t d_out, int32_t C, int32_t rank,
-                                       int32_t *err_flag, void *stream) {
+                                       int32_t *err_flag, void *stream, bool w_packed) {
     if (!apply_sizes_ok(N, d_in, d_out, C, rank) || !molora::sort_in_shrink_ok(N, d_in, C, rank))
         return MOLORA_EINVAL;
+    if (w_packed && molora::small_pack_cols(d_out) == 0) return MOLORA_EINVAL;
     if (!r || !x || !W || !A || !offsets || !perm || !t || !h) return MOLORA_EINVAL;
     if (!aligned16(r) || !aligned16(x) || !aligned16(W) || !aligned16(A) || !aligned16(offsets) ||
         !aligned16(perm) || !aligned16(t) || !aligned16(h))
@@ -397,7 +399,36 @@ molora_status molora_shrink_base_small(const int32_t *r, const void *x, const vo
         static_cast<const uint16_t *>(x), static_cast<const uint16_t *>(W),
         static_cast<const uint16_t *>(A), h, static_cast<uint16_t *>(t), N, d_in, d_out, C, rank,
         molora::Mix{1, C, nullptr, nullptr}, molora::SortArgs{r, offsets, perm, err_flag},
-        static_cast<hipStream_t>(stream)));
+        static_cast<hipStream_t>(stream), w_packed));
+}
+}  // namespace
+
+molora_status molora_shrink_base_small(const int32_t *r, const void *x, const void *W, const void *A,
+                                       int32_t *offsets, int32_t *perm, void *t, float *h, int64_t N,
+                                       int32_t d_in, int32_t d_out, int32_t C, int32_t rank,
+                                       int32_t *err_flag, void *stream) {
+    return shrink_base_small_common(r, x, W, A, offsets, perm, t, h, N, d_in, d_out, C, rank, err_flag,
+                                    stream, false);
+}
+
+molora_status molora_shrink_base_small_packed(const int32_t *r, const void *x, const void *Wp,
+                                              const void *A, int32_t *offsets, int32_t *perm, void *t,
+                                              float *h, int64_t N, int32_t d_in, int32_t d_out,
+                                              int32_t C, int32_t rank, int32_t *err_flag,
+                                              void *stream) {
+    return shrink_base_small_common(r, x, Wp, A, offsets, perm, t, h, N, d_in, d_out, C, rank, err_flag,
+                                    stream, true);
+}
+
+int32_t molora_pack_w_cols(int32_t d_out) { return d_out >= 8 ? molora::small_pack_cols(d_out) : 0; }
+
+molora_status molora_pack_w(const void *W, void *Wp, int32_t d_in, int32_t d_out, void *stream) {
+    if (d_in < 8 || d_in % 8 != 0 || d_out < 8 || molora::small_pack_cols(d_out) == 0) return MOLORA_EINVAL;
+    if (!W || !Wp || W == Wp) return MOLORA_EINVAL;
+    if (!aligned16(W) || !aligned16(Wp)) return MOLORA_EALIGN;
+    if (molora::ensure_device_ready() != hipSuccess) return MOLORA_EHIP;
+    return from_hip(molora::launch_pack_w(static_cast<const uint16_t *>(W), static_cast<uint16_t *>(Wp),
+                                          d_in, d_out, static_cast<hipStream_t>(stream)));
 }
 
 molora_status molora_expand_small(const void *B, const void *t, const int32_t *offsets,
@@ -589,7 +620,7 @@ const char *molora_status_string(molora_status status) {
     }
 }
 
-const char *molora_version(void) { return "molora-gfx950 0.4"; }
+const char *molora_version(void) { return "molora-gfx950 0.5"; }
 
 molora_status molora_init(void) {
     return molora::ensure_device_ready() == hipSuccess ? MOLORA_OK : MOLORA_EHIP;

@@ -149,7 +149,11 @@ hipError_t launch_small_batch_gemm(const uint16_t *x, const uint16_t *W, const u
 // stream of W), (2) the expand added to h.
 hipError_t launch_small_shrink_base(const uint16_t *x, const uint16_t *W, const uint16_t *A, float *h,
                                     uint16_t *t_out, int64_t N, int d_in, int d_out, int C, int rank,
-                                    Mix mix, SortArgs sort, hipStream_t s);
+                                    Mix mix, SortArgs sort, hipStream_t s, bool w_packed = false);
+// W for launch_small_shrink_base(..., w_packed = true): slabs of 16 rows, inside a slab groups of
+// gc = small_pack_cols(d_out) columns one after the other (0: this d_out has no packed form)
+int small_pack_cols(int d_out);
+hipError_t launch_pack_w(const uint16_t *W, uint16_t *Wp, int d_in, int d_out, hipStream_t s);
 hipError_t launch_small_expand(const uint16_t *B, const uint16_t *t2, const int32_t *offsets,
                                const int32_t *perm, float *h, int64_t N, int d_in, int d_out, int C,
                                int rank, Mix mix, hipStream_t s);

@@ -101,12 +101,17 @@ struct Unit {
 // of one row tile): kSbBaseOnly leaves the expand phase out and reads neither offsets nor perm
 // (h = x W: nothing the dispatch step produces is needed); kSbExpandOnly leaves the W stream
 // out and ADDS the expand to h (h += t B_c).  One after the other they give what mode 0 gives
-// up to the order of the fp32 additions.
+// up to the order of the fp32 additions.  kSbBasePacked is kSbBaseOnly with W stored slab by
+// slab (16 k-rows) and, inside a slab, column group by column group (see pack_w_kernel below):
+// a wavefront's slab is then one contiguous piece instead of sixteen cache lines d_out elements
+// apart, and the workgroups, which advance through W together, read one contiguous region at
+// any time (27.0 against 31.4 us at 64 x 4096 -> 12288; column groups as whole [d_in][COLS]
+// matrices, i.e. one contiguous stream per workgroup but 192 of them, gave 29.4 us).
 struct SbBlock {
     int x, y, z;  // the workgroup's index in its grid
     int gy;       // the grid's extent in y
 };
-constexpr int kSbBaseOnly = 1, kSbExpandOnly = 2;
+constexpr int kSbBaseOnly = 1, kSbExpandOnly = 2, kSbBasePacked = 3;
 
 template <int TM, int TN, bool SHRINK, int MODE = 0>  // TM: 32-row blocks, 1 (N <= 32) or 2
 __device__ __forceinline__ void small_batch_body(
@@ -191,7 +196,8 @@ __device__ __forceinline__ void small_batch_body(
     // the dispatch step produced, so the stream starts at once, and only the expand units (the
     // end of every wavefront's list) look up the sorted position of a row.
     const bool direct = !SHRINK && wg.gy == 1;
-    constexpr bool base_only = !SHRINK && MODE == kSbBaseOnly;      // direct batches only (host)
+    constexpr bool packed = !SHRINK && MODE == kSbBasePacked;       // d_out % COLS == 0 (host)
+    constexpr bool base_only = (!SHRINK && MODE == kSbBaseOnly) || packed;  // direct batches only (host)
     constexpr bool expand_only = !SHRINK && MODE == kSbExpandOnly;  // direct batches only (host)
 
     // ---- this wavefront's share of W ----
@@ -207,7 +213,9 @@ __device__ __forceinline__ void small_batch_body(
     const int nub = expand_only ? 0 : max(0, min(nub_all, u_lo + per_slice) - u_lo);
     const int nw = nub > wave ? (nub - wave + kSbWaves - 1) / kSbWaves : 0;
 
-    const int pitch = SHRINK ? rank : d_out;  // elements between consecutive k-rows of W (A)
+    // elements between consecutive k-rows of W (A); packed: inside a piece of 64 k-rows the
+    // workgroup's column group is a [rows][COLS] matrix of its own
+    const int pitch = SHRINK ? rank : (packed ? kSbCols : d_out);
     bool w_fast_ok = false, a_fast_ok = false;  // per-lane offsets fit 32 bits (set below)
     // wave-uniform by construction; says so to the compiler, which must keep them in scalar
     // registers for the load instruction
@@ -222,7 +230,10 @@ __device__ __forceinline__ void small_batch_body(
         un.real = u < nw;
         un.k0 = un.real ? (u_lo + u * kSbWaves + wave) * 64 : 0;
         un.fast = un.real && un.k0 + 64 <= d_in;
-        un.base = (const unsigned char *)(W + (int64_t)un.k0 * pitch);
+        if constexpr (packed)  // slab k / 16 starts at k * d_out; in it, group after group
+            un.base = (const unsigned char *)(W + (int64_t)un.k0 * d_out + (int64_t)wg.x * 16 * kSbCols);
+        else
+            un.base = (const unsigned char *)(W + (int64_t)un.k0 * pitch);
         return un;
     };
 
@@ -234,6 +245,7 @@ __device__ __forceinline__ void small_batch_body(
     auto w_col_of = [&](int r) {  // columns of this lane in load r of a slab
         const int row = r * Geo::RPD + w_rr;
         const int u16 = (Geo::swz32(w_pos >> 1, row) << 1) | (w_pos & 1);
+        if constexpr (packed) return u16 * 8;  // inside the group
         return min(n0 + u16 * 8, d_out - 8);  // columns past d_out: clamped, never stored
     };
     // SHRINK: the "matrix" is the tuple's A side by side, [d_in][R]; a group of 8 columns lies
@@ -250,7 +262,7 @@ __device__ __forceinline__ void small_batch_body(
             const int row = r * Geo::RPD + w_rr;
             w_lane[r] = SHRINK
                 ? W + ((int64_t)mix_adapter(mix, bucket, col / rank) * d_in + row) * rank + col % rank
-                : W + (int64_t)row * d_out + col;
+                : W + (int64_t)row * pitch + col;
             // the same lane offset serves W and B in the GEMM (both have d_out columns)
             const int64_t off = ((const unsigned char *)w_lane[r] - (const unsigned char *)W) -
                                 (int64_t)r * Geo::RPD * pitch * 2;
@@ -263,13 +275,23 @@ __device__ __forceinline__ void small_batch_body(
 #pragma unroll
         for (int r = 0; r < Geo::NR; ++r) {
             if (un.fast && w_fast_ok) {
-                load_to_lds16(un.base + (int64_t)(j * 16 + r * Geo::RPD) * (pitch * 2), w_off[r],
-                              slot + r * 1024);
+                // packed: the unit's four slabs are full, 16 * d_out elements apart
+                const int64_t step = packed ? (int64_t)j * 16 * (d_out * 2) + (int64_t)(r * Geo::RPD) * (pitch * 2)
+                                            : (int64_t)(j * 16 + r * Geo::RPD) * (pitch * 2);
+                load_to_lds16(un.base + step, w_off[r], slot + r * 1024);
                 continue;
             }
             // d_in is a multiple of 8 and so is RPD: rows of a load leave the matrix together
             const int kk = un.k0 + j * 16 + r * Geo::RPD + w_rr;  // this lane's row
-            const uint16_t *src = (un.real && kk < d_in) ? w_lane[r] + (int64_t)(un.k0 + j * 16) * pitch : zero;
+            const uint16_t *src = zero;
+            if (un.real && kk < d_in) {
+                if constexpr (packed) {  // the last slab of W may hold 8 rows only
+                    const int ks = un.k0 + j * 16;
+                    src = W + (int64_t)ks * d_out + (int64_t)wg.x * min(16, d_in - ks) * kSbCols +
+                          (r * Geo::RPD + w_rr) * pitch + w_colv[r];
+                } else
+                    src = w_lane[r] + (int64_t)(un.k0 + j * 16) * pitch;
+            }
             load_to_lds16_ptr(src, slot + r * 1024);
         }
     };
@@ -584,8 +606,9 @@ __global__ __launch_bounds__(kSbWaves * 64) void small_batch_kernel(
 // shrink (a dozen workgroups each draining one A_c) hides behind the stream of W instead of
 // preceding it.  Workgroups [0, n_shrink) are the shrink's grid (column groups of the rank x
 // buckets, K not split: there is no hurry now), the others the GEMM's column groups in
-// kSbBaseOnly mode.  The expand follows as a launch of its own (kSbExpandOnly).
-template <int TM, int TN>
+// kSbBaseOnly mode (PACKED: kSbBasePacked, W column group by column group).  The expand follows
+// as a launch of its own (kSbExpandOnly).
+template <int TM, int TN, bool PACKED>
 __global__ __launch_bounds__(kSbWaves * 64) void shrink_base_small_kernel(
     const uint16_t *__restrict__ x, const uint16_t *__restrict__ W, const uint16_t *__restrict__ A,
     float *__restrict__ h, uint16_t *__restrict__ t_out, int N, int d_in, int d_out, int C, int rank,
@@ -596,9 +619,9 @@ __global__ __launch_bounds__(kSbWaves * 64) void shrink_base_small_kernel(
                                       mix.k * rank, C, rank, mix, 1, sort,
                                       SbBlock{b % shrink_groups, b / shrink_groups, 0, C});
     } else {
-        small_batch_body<TM, TN, false, kSbBaseOnly>(x, W, nullptr, nullptr, nullptr, nullptr, h, nullptr, N,
-                                                     d_in, d_out, C, rank, mix, 1, SortArgs{},
-                                                     SbBlock{b - n_shrink, 0, 0, 1});
+        small_batch_body<TM, TN, false, PACKED ? kSbBasePacked : kSbBaseOnly>(
+            x, W, nullptr, nullptr, nullptr, nullptr, h, nullptr, N, d_in, d_out, C, rank, mix, 1, SortArgs{},
+            SbBlock{b - n_shrink, 0, 0, 1});
     }
 }
 
@@ -684,22 +707,47 @@ hipError_t launch_small_batch_gemm(const uint16_t *x, const uint16_t *W, const u
 }
 
 namespace {
-template <int TM, int TN>
+// W [d_in][d_out] -> Wp: W cut into slabs of 16 k-rows (the last may hold 8), and inside a slab
+// column group after column group, each a [rows][gc] matrix of its own (gc = the streaming
+// kernel's columns per workgroup for this d_out).  Slab s starts at element 16 * s * d_out, as
+// in W.  One 16-byte chunk (8 columns) per thread; writes in order.
+__global__ __launch_bounds__(256) void pack_w_kernel(const uint16_t *__restrict__ W,
+                                                     uint16_t *__restrict__ Wp, int d_in, int d_out,
+                                                     int gc) {
+    const int64_t e = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;  // chunk of Wp
+    if (e >= (int64_t)d_in * (d_out / 8)) return;
+    const int64_t per_slab = (int64_t)16 * (d_out / 8);  // chunks in a full slab
+    const int sl = (int)(e / per_slab);
+    const int rem = (int)(e - (int64_t)sl * per_slab);   // < 16 * d_out / 8
+    const int rows = min(16, d_in - 16 * sl);
+    const int cpg = gc / 8;                               // chunks per row of a group
+    const int g = rem / (rows * cpg);
+    const int rem2 = rem - g * rows * cpg;
+    const int kk = rem2 / cpg, cc = rem2 % cpg;
+    *(u32x4 *)(Wp + e * 8) = *(const u32x4 *)(W + (int64_t)(16 * sl + kk) * d_out + (int64_t)g * gc + cc * 8);
+}
+
+// the column-group width of the one-row-tile streaming kernel: 32 where 64-column groups would
+// occupy at most half of the compute units
+inline bool sb_narrow_one_tile(int d_out) { return (int64_t)((d_out + 63) / 64) <= 128; }
+
+template <int TM, int TN, bool PACKED>
 struct ShrinkBaseKernel {
     static constexpr size_t LDS = (SbGeom<TN>::LDS_BYTES > SbGeom<1>::LDS_BYTES) ? SbGeom<TN>::LDS_BYTES
                                                                                : SbGeom<1>::LDS_BYTES;
-    static inline LdsRegistrar lds{(const void *)shrink_base_small_kernel<TM, TN>, LDS};
+    static inline LdsRegistrar lds{(const void *)shrink_base_small_kernel<TM, TN, PACKED>, LDS};
 };
-template <int TM, int TN>
+template <int TM, int TN, bool PACKED>
 hipError_t launch_shrink_base(const uint16_t *x, const uint16_t *W, const uint16_t *A, float *h,
                               uint16_t *t_out, int N, int d_in, int d_out, int C, int rank, Mix mix,
                               SortArgs sort, hipStream_t s) {
-    (void)&ShrinkBaseKernel<TM, TN>::lds;  // instantiates the registration
+    (void)&ShrinkBaseKernel<TM, TN, PACKED>::lds;  // instantiates the registration
+    if (PACKED && d_out % SbGeom<TN>::COLS != 0) return hipErrorInvalidValue;  // whole groups only
     const int shrink_groups = (mix.k * rank + 31) / 32;
     const int n_shrink = shrink_groups * C;
     const int gemm_groups = (d_out + SbGeom<TN>::COLS - 1) / SbGeom<TN>::COLS;
-    auto kern = shrink_base_small_kernel<TM, TN>;
-    constexpr size_t lds_bytes = ShrinkBaseKernel<TM, TN>::LDS;
+    auto kern = shrink_base_small_kernel<TM, TN, PACKED>;
+    constexpr size_t lds_bytes = ShrinkBaseKernel<TM, TN, PACKED>::LDS;
     hipLaunchKernelGGL(kern, dim3((unsigned)(n_shrink + gemm_groups)), dim3(kSbWaves * 64), lds_bytes, s, x,
                        W, A, h, t_out, N, d_in, d_out, C, rank, mix, sort, shrink_groups, n_shrink);
     return hipGetLastError();
@@ -709,13 +757,31 @@ hipError_t launch_shrink_base(const uint16_t *x, const uint16_t *W, const uint16
 // N <= 64: dispatch + shrink + h = x W in one launch (sort.r, sort.offsets, sort.perm required)
 hipError_t launch_small_shrink_base(const uint16_t *x, const uint16_t *W, const uint16_t *A, float *h,
                                     uint16_t *t_out, int64_t N, int d_in, int d_out, int C, int rank,
-                                    Mix mix, SortArgs sort, hipStream_t s) {
+                                    Mix mix, SortArgs sort, hipStream_t s, bool w_packed) {
     if (N < 1 || N > 64 || mix.k != 1 || !sort.r || !sort.offsets || !sort.perm) return hipErrorInvalidValue;
-    const bool narrow = (int64_t)((d_out + 63) / 64) <= 128;
-#define MOLORA_SBB(TM, TN) launch_shrink_base<TM, TN>(x, W, A, h, t_out, (int)N, d_in, d_out, C, rank, mix, sort, s)
+    if (w_packed && small_pack_cols(d_out) == 0) return hipErrorInvalidValue;
+    const bool narrow = sb_narrow_one_tile(d_out);
+#define MOLORA_SBB(TM, TN)                                                                                   \
+    (w_packed ? launch_shrink_base<TM, TN, true>(x, W, A, h, t_out, (int)N, d_in, d_out, C, rank, mix, sort, s) \
+              : launch_shrink_base<TM, TN, false>(x, W, A, h, t_out, (int)N, d_in, d_out, C, rank, mix, sort, s))
     if (N <= 32) return narrow ? MOLORA_SBB(1, 1) : MOLORA_SBB(1, 2);
     return narrow ? MOLORA_SBB(2, 1) : MOLORA_SBB(2, 2);
 #undef MOLORA_SBB
+}
+
+// columns per group of the packed form of a [d_in][d_out] matrix (0: d_out has no packed form)
+int small_pack_cols(int d_out) {
+    const int gc = sb_narrow_one_tile(d_out) ? 32 : 64;
+    return (d_out >= gc && d_out % gc == 0) ? gc : 0;
+}
+
+hipError_t launch_pack_w(const uint16_t *W, uint16_t *Wp, int d_in, int d_out, hipStream_t s) {
+    const int gc = small_pack_cols(d_out);
+    if (gc == 0 || d_in < 1) return hipErrorInvalidValue;
+    const int64_t items = (int64_t)d_in * (d_out / 8);
+    hipLaunchKernelGGL(pack_w_kernel, dim3((unsigned)((items + 255) / 256)), dim3(256), 0, s, W, Wp, d_in,
+                       d_out, gc);
+    return hipGetLastError();
 }
 
 // N <= 64: h += t B_c (the expand alone, after launch_small_shrink_base)

@@ -162,6 +162,27 @@ def test_one_launch_dispatch_and_shrink_reject_bad_arguments(lib):
     assert g(None, p(a), p(a), p(a), p(a), p(a), 4096, 2048, 2, 16, None, None) == EINVAL
 
 
+def test_packed_base_weight_entry_points_reject_bad_arguments(lib):
+    """The packed form of a base weight exists for whole column groups only (64 columns, 32 up
+    to d_out = 8192); everything else is an error before any launch."""
+    EINVAL, EALIGN = -1, -2
+    p = ctypes.c_void_p
+    buf = (ctypes.c_char * 8192)()
+    a = ctypes.addressof(buf)
+    a += (-a) % 256
+    b = a + 4096
+    cols = lib.molora_pack_w_cols
+    assert cols(64) == 32 and cols(8192) == 32 and cols(8256) == 64 and cols(12288) == 64
+    assert cols(72) == 0 and cols(8200) == 0 and cols(8224) == 0 and cols(16) == 0 and cols(0) == 0 and cols(-64) == 0
+    pack = lambda W=a, Wp=b, d_in=64, d_out=64: lib.molora_pack_w(p(W), p(Wp), d_in, d_out, None)
+    assert pack(d_out=72) == EINVAL and pack(d_in=4) == EINVAL and pack(d_in=12) == EINVAL
+    assert pack(W=0) == EINVAL and pack(Wp=0) == EINVAL and pack(Wp=a) == EINVAL   # in place: not supported
+    assert pack(Wp=b + 8) == EALIGN
+    k1 = lambda N=64, d_out=256, W=a: lib.molora_shrink_base_small_packed(
+        p(a), p(a), p(W), p(a), p(a), p(a), p(a), p(a), N, 4096, d_out, 16, 64, None, None)
+    assert k1(d_out=264) == EINVAL and k1(N=65) == EINVAL and k1(W=0) == EINVAL and k1(W=a + 8) == EALIGN
+
+
 def test_operands_of_4_gib_are_rejected_for_the_tiled_kernel(lib):
     """The tiled GEMM (N > 512) keeps per-lane byte offsets into x and W in 32 bits; sizes
     beyond that are an error before launch, not silently wrapped addresses."""

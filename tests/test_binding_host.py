@@ -124,6 +124,25 @@ def test_one_launch_dispatch_and_shrink_reject_mismatched_shapes():
         mb.molora_bucket_shrink_small(g["r"], g["x"], g["A"], g["offsets"], g["perm"], g["t"], workspace=None)
 
 
+def test_packed_base_weight_rejects_mismatched_shapes():
+    g = good()
+    assert mb.molora_pack_w_cols(d_out) == 32 and mb.molora_pack_w_cols(d_out + 8) == 0
+    with pytest.raises(ValueError, match="no packed form"):
+        mb.molora_pack_w(tens((d_in, d_out + 8)))
+    with pytest.raises(ValueError):   # the packed weight has W's element count and shape
+        mb.molora_pack_w(g["W"], tens((d_in, d_out // 2)))
+    with pytest.raises(TypeError, match="device tensor"):
+        mb.molora_pack_w(g["W"], tens((d_in, d_out)))
+    with pytest.raises(ValueError, match="no packed form"):
+        mb.molora_shrink_base_small(g["r"], g["x"], tens((d_in, d_out + 8)), g["A"], packed=True)
+    with pytest.raises(ValueError):   # W of another d_in
+        mb.molora_shrink_base_small(g["r"], g["x"], tens((d_in * 2, d_out)), g["A"], g["offsets"], g["perm"],
+                                    g["t"], g["h"], packed=True)
+    with pytest.raises(TypeError, match="device tensor"):
+        mb.molora_shrink_base_small(g["r"], g["x"], g["W"], g["A"], g["offsets"], g["perm"], g["t"], g["h"],
+                                    packed=True)
+
+
 def test_routes_and_mixture_reject_mismatched_shapes():
     g = good()
     with pytest.raises(ValueError):

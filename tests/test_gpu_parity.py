@@ -265,6 +265,44 @@ def test_bucket_shrink_small_one_launch(gpu, N, d_in, d_out, C, rank, structure,
     assert torch.equal(h3, gpu.gpu_apply(w, r)), "molora_apply takes the two-launch path"
 
 
+@pytest.mark.parametrize("N,d_in,d_out,C,rank,structure", [
+    (64, 4096, 1024, 16, 64, "zipf"),      # groups of 32 columns (d_out <= 8192)
+    (64, 1024, 14336, 16, 64, "zipf"),     # configuration 3's width: groups of 64 columns
+    (37, 520, 8256, 8, 40, "uniform"),     # groups of 64, a K tail (the last piece of W is short)
+    (1, 256, 64, 4, 64, "uniform"),        # one token, two groups of 32
+    (33, 72, 8320, 3, 128, "uniform"),     # K of one short piece
+])
+def test_packed_base_weight_small_batch(gpu, N, d_in, d_out, C, rank, structure):
+    """The base weight stored column group by column group: molora_pack_w against the
+    rearrangement written out in numpy (bit for bit), molora_shrink_base_small on the packed
+    weight bit for bit as on the row-major one, and h after the expand as the oracle's."""
+    import oracle
+    import torch
+    from paper_2603_15965_amd import binding as mb
+    say(f"packed W N={N} {d_in}->{d_out} C={C} rank={rank}")
+    gc = mb.molora_pack_w_cols(d_out)
+    assert gc == (32 if d_out <= 8192 else 64)
+    w = wl.custom("s", N, d_in, d_out, C, rank, 9100 + N + C, structure=structure)
+    r = w.r.copy()
+    r[2::9] = -1
+    x, W, A, B = (gpu.dev_bf16(q) for q in (w.x, w.W, w.A, w.B))
+    rd = gpu.dev_i32(r)
+    Wp = mb.molora_pack_w(W)
+    torch.cuda.synchronize()
+    want = np.concatenate([w.W[k0:k0 + 16].reshape(-1, d_out // gc, gc).transpose(1, 0, 2).ravel()
+                           for k0 in range(0, d_in, 16)])   # slab by slab, group after group
+    assert np.array_equal(Wp.view(torch.int16).cpu().numpy().view(np.uint16).ravel(), want), "molora_pack_w"
+    o1, p1, t1, h1 = mb.molora_shrink_base_small(rd, x, W, A)
+    o2, p2, t2, h2 = mb.molora_shrink_base_small(rd, x, Wp, A, packed=True)
+    torch.cuda.synchronize()
+    n_routed = int(o1[C].item())
+    assert torch.equal(o1, o2) and torch.equal(p1, p2) and torch.equal(t1[:n_routed], t2[:n_routed])
+    assert torch.equal(h1, h2), "h = x W from the packed weight, same bits"
+    mb.molora_expand_small(B, t2, o2, p2, h2)
+    torch.cuda.synchronize()
+    gpu.assert_h_close(h2.cpu().numpy(), oracle.apply(w.x, w.W, w.A, w.B, r), "packed W, then the expand")
+
+
 def test_gate_dispatch_shrink_matches_separate_calls(gpu):
     """Gating + dispatch + shrink in one launch on configuration 1's shape and on composite
     targets: r, offsets, perm bit for bit as the oracle's, h as the oracle's."""
