@@ -181,12 +181,15 @@ def run_workload(args, workload, steps, warmup, full):
             d["t"] = torch.empty((sh.N, 2 * rk * (C if d["dense"] else 1)), dtype=torch.bfloat16, device="cuda")
             d["sws"] = mb.molora_shrink_workspace(sh.N, sh.d_in, C, rk)  # None for most sizes
             d["h"] = torch.empty((sh.N, sh.d_out), dtype=torch.float32, device="cuda")
-            # a decode-sized batch streams the base weight once: it is given in the layout that
-            # stream reads best (slabs of 16 rows, column group after column group: made once per
-            # weight by molora_pack_w, outside every timed region); same bits out
-            d["Wp"] = None
+            # a decode-sized batch streams the base weight and the touched B_c once: they are given
+            # in the layout that stream reads best (slabs of 16 rows, column group after column
+            # group: made once per weight by molora_pack_w / molora_pack_b, outside every timed
+            # region); same bits out
+            d["Wp"], d["Bp"] = None, None
             if d["small"] and base.v is None and not args.row_major_w and mb.molora_pack_w_cols(sh.d_out):
                 d["Wp"] = mb.molora_pack_w(d["W"])
+                if rk % 16 == 0:
+                    d["Bp"] = mb.molora_pack_b(d["B"])
             S[s].append(d)
         del base
 
@@ -223,7 +226,9 @@ def run_workload(args, workload, steps, warmup, full):
 
     def gemm(d, stream=None):
         if d["small"] and "v" not in d:
-            return mb.molora_expand_small(d["B"], d["t"], d["offsets"], d["perm"], d["h"], stream=stream)
+            packed = d["Bp"] is not None and use_packed[0]
+            return mb.molora_expand_small(d["Bp"] if packed else d["B"], d["t"], d["offsets"], d["perm"], d["h"],
+                                          stream=stream, packed=packed)
         f = mb.molora_base_expand_dense if d["dense"] else mb.molora_base_expand
         f(d["x"], d["W"], d["B"], d["t"], d["offsets"], d["perm"], d["h"], stream=stream)
 
@@ -231,21 +236,19 @@ def run_workload(args, workload, steps, warmup, full):
         return d["small"] and "v" not in d
 
     def step(projs, ev=None, stream=None):
+        # ev: one launch timer per projection; armed right before the call whose launch holds the
+        # base projection, which then records its own start and end on it
         for j, d in enumerate(projs):
             if two_launch(d):
                 if ev is not None:
-                    ev[2 * j].record()
+                    ev[j].arm()
                 dispatch_and_shrink(d, stream)   # dispatch + shrink + h = x W
-                if ev is not None:
-                    ev[2 * j + 1].record()
                 gemm(d, stream)                  # h += t B
                 continue
             dispatch_and_shrink(d, stream)
             if ev is not None:
-                ev[2 * j].record()
+                ev[j].arm()
             gemm(d, stream)
-            if ev is not None:
-                ev[2 * j + 1].record()
 
     if args.copy_calibration and full:
         a = torch.empty(256 << 20, dtype=torch.uint8, device="cuda")
@@ -295,15 +298,17 @@ def run_workload(args, workload, steps, warmup, full):
             n_pre += 1
         torch.cuda.synchronize()
 
-    # A pair of HIP events costs the stream ~3 us each on this path, a visible share of a 70 us
-    # step, so the dominant kernel is bracketed on every EV_EVERY-th step of the timed region
-    # only, and the per-step latency distribution is taken in a second pass of the same length
-    # after the timed region.
+    # The dominant kernel is timed inside the timed region by HIP events that the launch itself
+    # records at its start and at its end (molora_launch_timer: hipExtLaunchKernelGGL), i.e. the
+    # interval a kernel trace reports.  Events recorded around the call are marker packets of
+    # their own: they read 5 us more at config 1 (46.0 against 40.7 us, kernel trace 40.1) and
+    # cost the stream ~3 us each; a timed launch costs the step ~0.3 us, and every 4th step is
+    # timed.  The per-step latency distribution is taken in a second pass after the timed region.
     use_ev = not args.no_kernel_events and graphs is None and not extra
     P = len(shapes)
     EV_EVERY = 4 if steps >= 16 else 1
     ev_steps = [i for i in range(steps) if i % EV_EVERY == EV_EVERY - 1] or [steps - 1]
-    evs = {i: [torch.cuda.Event(enable_timing=True) for _ in range(2 * P)] for i in ev_steps} if use_ev else {}
+    evs = {i: [mb.LaunchTimer() for _ in range(P)] for i in ev_steps} if use_ev else {}
     # One untimed burst enqueued exactly as the timed region is (same depth, same events).  The
     # first time a process has this many launches outstanding, the HIP runtime holds the host
     # for ~30 ms once (measured: 30 steps of 4 launches take 33 ms to enqueue the first time and
@@ -325,11 +330,14 @@ def run_workload(args, workload, steps, warmup, full):
     ms_per_step = 1e3 * elapsed / steps
     gemm_us = None
     if use_ev:
-        gemm_us = sum(e[2 * j].elapsed_time(e[2 * j + 1]) for e in evs.values() for j in range(P)) / len(evs) * 1e3
+        gemm_us = sum(t.elapsed_us() for e in evs.values() for t in e) / len(evs)
+        for e in evs.values():
+            for t in e:
+                t.destroy()
 
     # the same K steps on the row-major weight, where the step above used the packed one
     row_major = None
-    if any(d["Wp"] is not None for d in S[0]) and not args.timed_only:
+    if any(d["Wp"] is not None for d in S[0]) and not args.timed_only and graphs is None:
         use_packed[0] = False
         for i in range(warmup):
             run_step(i)
@@ -341,7 +349,8 @@ def run_workload(args, workload, steps, warmup, full):
         el = time.perf_counter() - t1
         use_packed[0] = True
         row_major = {"ms_per_step": 1e3 * el / steps, "value": N * steps / el, "unit": "tokens/s",
-                     "what": "the same steps with W row-major [d_in][d_out] (molora_shrink_base_small)"}
+                     "what": "the same steps with W [d_in][d_out] and B [C][rank][d_out] row-major "
+                             "(molora_shrink_base_small, molora_expand_small)"}
 
     skip_passes = bool(extra) or args.timed_only or not full
     latency = None
@@ -448,7 +457,9 @@ def run_workload(args, workload, steps, warmup, full):
         kname += f", {P} launches per step summed"
     roof.update({"kernel": kname, "kernel_us": t_gemm * 1e6, "traffic": traffic, "traffic_from": traffic_from,
                  "kernel_event_samples": len(evs) if gemm_us is not None else 0,
-                 "kernel_us_from": f"HIP events around the launch on every {EV_EVERY}th step of the timed region"
+                 "kernel_us_from": f"HIP events recorded by the launch itself at its start and end "
+                                   f"(molora_launch_timer, hipExtLaunchKernelGGL) on every {EV_EVERY}th step of "
+                                   f"the timed region"
                  if gemm_us is not None
                  else "HIP events around the call, outside the timed region",
                  "algorithmic_flops": dom_flops, "algorithmic_bytes": dom_bytes})
@@ -485,8 +496,8 @@ def run_workload(args, workload, steps, warmup, full):
                    "launch": "recorded sequence (HIP graph) per step" if graphs is not None
                    else "kernel by kernel" + (f", steps round-robin on {args.streams} streams" if extra else ""),
                    "kernel_events_in_timed_region": (f"every {EV_EVERY}th step" if use_ev else False),
-                   "w_layout": "packed once by molora_pack_w (slabs of 16 rows, column group after column "
-                               "group); row-major figure under row_major_w"
+                   "w_layout": "W and B packed once by molora_pack_w / molora_pack_b (slabs of 16 rows, column "
+                               "group after column group); row-major figure under row_major_w"
                    if any(d["Wp"] is not None for d in S[0]) else "row-major [d_in][d_out]"},
         "roofline": roof,
         "step_roofline": step_roof,

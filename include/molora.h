@@ -299,6 +299,12 @@ molora_status molora_expand_small(const void *B, const void *t, const int32_t *o
  * form).  molora_shrink_base_small_packed is molora_shrink_base_small with Wp in the place of
  * W: the same arithmetic in the same order, so every output is bit-identical; MOLORA_EINVAL in
  * the same cases and for a d_out without packed form.
+ *
+ * The adapters' B are static too: B [C][rank][d_out] is a [C * rank][d_out] matrix, and
+ * molora_pack_w(B, Bp, C * rank, d_out) stores it the same way (with rank a multiple of 16 a
+ * slab lies inside one adapter).  molora_expand_small_packed is molora_expand_small with Bp
+ * in the place of B: bit-identical h; MOLORA_EINVAL in the same cases, for a rank that is
+ * not a multiple of 16 and for a d_out without packed form.
  */
 int32_t molora_pack_w_cols(int32_t d_out);
 molora_status molora_pack_w(const void *W, void *Wp, int32_t d_in, int32_t d_out, void *stream);
@@ -307,6 +313,9 @@ molora_status molora_shrink_base_small_packed(const int32_t *r, const void *x, c
                                               float *h, int64_t N, int32_t d_in, int32_t d_out,
                                               int32_t C, int32_t rank, int32_t *err_flag,
                                               void *stream);
+molora_status molora_expand_small_packed(const void *Bp, const void *t, const int32_t *offsets,
+                                         const int32_t *perm, float *h, int64_t N, int32_t d_out,
+                                         int32_t C, int32_t rank, void *stream);
 
 /*
  * molora_base_expand with the height of the row tiles forced, for the tiling ablation (App.
@@ -409,6 +418,26 @@ molora_status molora_graph_begin(void *stream);
 molora_status molora_graph_end(void *stream, molora_graph **graph);
 molora_status molora_graph_launch(molora_graph *graph, void *stream);
 void molora_graph_destroy(molora_graph *graph);
+
+/*
+ * For benchmarks (no passage of the paper: a measuring aid): the device-side duration of one
+ * launch of the kernel that holds the base projection, taken from the launch's own dispatch,
+ * which is the interval a kernel trace reports.  molora_launch_timer_create makes a timer (two
+ * HIP events; the one place where the library creates anything).  molora_launch_timer_arm
+ * hands it to the calling thread's next launch of such a kernel -- the tiled GEMM of
+ * molora_base_expand* / molora_apply*, the small-batch GEMM of the same calls, the launch of
+ * molora_shrink_base_small* -- which records its start and end on it; other launches pass it
+ * by, a timer armed later replaces it, and a launch under stream capture must not be given one.
+ * molora_launch_timer_elapsed_us waits for that launch to finish (the only call of the
+ * library that blocks) and returns its duration; MOLORA_EHIP if no launch took the timer.  A
+ * timer can be armed again after it has been read.  molora_launch_timer_destroy frees it
+ * (NULL is ignored).  MOLORA_EINVAL for NULL arguments.
+ */
+typedef struct molora_launch_timer molora_launch_timer;
+molora_status molora_launch_timer_create(molora_launch_timer **timer);
+molora_status molora_launch_timer_arm(molora_launch_timer *timer);
+molora_status molora_launch_timer_elapsed_us(molora_launch_timer *timer, double *us);
+void molora_launch_timer_destroy(molora_launch_timer *timer);
 
 /*
  * Once-per-device set-up on the current device: tells the runtime which kernels use more than

@@ -19,11 +19,13 @@ EXPORTS = ["molora_route", "molora_route_vocab", "molora_bucket", "molora_apply_
            "molora_base_expand_fixed", "molora_init", "molora_dense_shrink_supported", "molora_bucket_shrink",
            "molora_gate_dispatch_shrink", "molora_base_expand_dense", "molora_bucket_shrink_small_supported",
            "molora_bucket_shrink_small", "molora_shrink_base_small", "molora_expand_small",
-           "molora_pack_w_cols", "molora_pack_w", "molora_shrink_base_small_packed", "molora_apply_static", "molora_static_workspace_bytes",
+           "molora_pack_w_cols", "molora_pack_w", "molora_shrink_base_small_packed", "molora_expand_small_packed", "molora_apply_static", "molora_static_workspace_bytes",
            "molora_route_mlp_workspace_bytes", "molora_route_mlp", "molora_route_compose",
            "molora_gate_dispatch",
            "molora_apply_mix_workspace_bytes", "molora_apply_mix",
            "molora_graph_begin", "molora_graph_end", "molora_graph_launch", "molora_graph_destroy",
+           "molora_launch_timer_create", "molora_launch_timer_arm", "molora_launch_timer_elapsed_us",
+           "molora_launch_timer_destroy",
            "molora_status_string", "molora_version"]
 
 _lib = None
@@ -91,6 +93,8 @@ def load():
     lib.molora_pack_w.restype = ctypes.c_int
     lib.molora_expand_small.argtypes = [vp, vp, vp, vp, vp, i64, i32, i32, i32, vp]
     lib.molora_expand_small.restype = ctypes.c_int
+    lib.molora_expand_small_packed.argtypes = lib.molora_expand_small.argtypes
+    lib.molora_expand_small_packed.restype = ctypes.c_int
     lib.molora_base_expand_dense.argtypes = [vp, vp, vp, vp, vp, vp, vp, i64, i32, i32, i32, i32, vp]
     lib.molora_base_expand_dense.restype = ctypes.c_int
     lib.molora_init.argtypes = []
@@ -115,6 +119,14 @@ def load():
     lib.molora_graph_launch.restype = ctypes.c_int
     lib.molora_graph_destroy.argtypes = [vp]
     lib.molora_graph_destroy.restype = None
+    lib.molora_launch_timer_create.argtypes = [ctypes.POINTER(vp)]
+    lib.molora_launch_timer_create.restype = ctypes.c_int
+    lib.molora_launch_timer_arm.argtypes = [vp]
+    lib.molora_launch_timer_arm.restype = ctypes.c_int
+    lib.molora_launch_timer_elapsed_us.argtypes = [vp, ctypes.POINTER(ctypes.c_double)]
+    lib.molora_launch_timer_elapsed_us.restype = ctypes.c_int
+    lib.molora_launch_timer_destroy.argtypes = [vp]
+    lib.molora_launch_timer_destroy.restype = None
     lib.molora_status_string.argtypes = [ctypes.c_int]
     lib.molora_status_string.restype = ctypes.c_char_p
     lib.molora_version.argtypes = []
@@ -472,12 +484,31 @@ def molora_shrink_base_small(r, x, W, A, offsets=None, perm=None, t=None, h=None
     return offsets, perm, t, h
 
 
-def molora_expand_small(B, t, offsets, perm, h, stream=None):
-    """h[perm[p]] += t_p B_c (a batch of at most 64 tokens; after molora_shrink_base_small)."""
+def molora_pack_b(B, Bp=None, stream=None):
+    """B [C][rank][d_out] -> the same elements in the order molora_expand_small(packed=True) streams
+    (molora_pack_w on the stacked [C * rank][d_out] matrix; rank a multiple of 16)."""
+    C, rank, d_out = _three(B, "B")
+    if rank % 16 != 0:
+        raise ValueError(f"a packed B needs a rank that is a multiple of 16, not {rank}")
+    if Bp is None:
+        Bp = torch.empty_like(B)
+    _three(Bp, "Bp")
+    if tuple(Bp.shape) != tuple(B.shape):
+        raise ValueError(f"Bp has shape {tuple(Bp.shape)}, B {tuple(B.shape)}")
+    molora_pack_w(B.view(C * rank, d_out), Bp.view(C * rank, d_out), stream=stream)
+    return Bp
+
+
+def molora_expand_small(B, t, offsets, perm, h, stream=None, packed=False):
+    """h[perm[p]] += t_p B_c (a batch of at most 64 tokens; after molora_shrink_base_small).
+    packed=True: B is the output of molora_pack_b."""
     C, rank, d_out = _three(B, "B")
     N = int(h.shape[0])
+    if packed and (rank % 16 != 0 or molora_pack_w_cols(d_out) == 0):
+        raise ValueError(f"no packed form of B for rank {rank}, {d_out} columns")
     bf = torch.bfloat16
-    _call("molora_expand_small", _dev(B, bf, "B"), _dev(t, bf, "t", (N, 2 * rank)),
+    _call("molora_expand_small_packed" if packed else "molora_expand_small", _dev(B, bf, "B"),
+          _dev(t, bf, "t", (N, 2 * rank)),
           _dev(offsets, torch.int32, "offsets", (C + 1,)), _dev(perm, torch.int32, "perm", (N,)),
           _dev(h, torch.float32, "h", (N, d_out)), N, d_out, C, rank, _stream(stream))
     return h
@@ -647,4 +678,31 @@ class Graph:
     def destroy(self):
         if self._handle is not None:
             load().molora_graph_destroy(self._handle)
+            self._handle = None
+
+
+class LaunchTimer:
+    """Device-side duration of one base-projection launch (what a kernel trace reports):
+
+        t = LaunchTimer()
+        t.arm(); molora_base_expand(...)     # the call's GEMM launch records its own start and end
+        us = t.elapsed_us()                  # waits for that launch
+    """
+
+    def __init__(self):
+        h = ctypes.c_void_p()
+        _check(load().molora_launch_timer_create(ctypes.byref(h)), "molora_launch_timer_create")
+        self._handle = h
+
+    def arm(self):
+        _check(load().molora_launch_timer_arm(self._handle), "molora_launch_timer_arm")
+
+    def elapsed_us(self):
+        us = ctypes.c_double()
+        _check(load().molora_launch_timer_elapsed_us(self._handle, ctypes.byref(us)), "molora_launch_timer_elapsed_us")
+        return float(us.value)
+
+    def destroy(self):
+        if self._handle is not None:
+            load().molora_launch_timer_destroy(self._handle)
             self._handle = None

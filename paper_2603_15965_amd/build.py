@@ -8,7 +8,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 OBJDIR = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libmolora.so")
-SOURCES = ["api.hip", "bucket.hip", "route.hip", "shrink.hip", "gemm.hip", "small_batch.hip", "graph.hip", "router.hip", "dispatch_shrink.hip"]
+SOURCES = ["api.hip", "bucket.hip", "route.hip", "shrink.hip", "gemm.hip", "small_batch.hip", "graph.hip", "router.hip", "dispatch_shrink.hip", "timer.hip"]
 
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 # -packed-fp32-ops is switched off on purpose: the compiler must not form v_pk_*_f32.

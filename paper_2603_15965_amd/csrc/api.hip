@@ -51,6 +51,16 @@ hipError_t ensure_device_ready() {
 }
 
 namespace {
+thread_local LaunchEvents t_launch_events;
+}
+void arm_launch_events(hipEvent_t start, hipEvent_t stop) { t_launch_events = LaunchEvents{start, stop}; }
+LaunchEvents take_launch_events() {
+    const LaunchEvents ev = t_launch_events;
+    t_launch_events = LaunchEvents{};
+    return ev;
+}
+
+namespace {
 // the current device's copy of `scratch` (nullptr before ensure_device_ready() succeeded there)
 void *static_scratch_of_current_device() {
     int dev = 0;
@@ -431,11 +441,13 @@ molora_status molora_pack_w(const void *W, void *Wp, int32_t d_in, int32_t d_out
                                           d_in, d_out, static_cast<hipStream_t>(stream)));
 }
 
-molora_status molora_expand_small(const void *B, const void *t, const int32_t *offsets,
+namespace {
+molora_status expand_small_common(const void *B, const void *t, const int32_t *offsets,
                                   const int32_t *perm, float *h, int64_t N, int32_t d_out, int32_t C,
-                                  int32_t rank, void *stream) {
+                                  int32_t rank, void *stream, bool b_packed) {
     const int32_t d_in = 8;  // the step does not touch x or W
     if (!apply_sizes_ok(N, d_in, d_out, C, rank) || N > 64) return MOLORA_EINVAL;
+    if (b_packed && (rank % 16 != 0 || molora::small_pack_cols(d_out) == 0)) return MOLORA_EINVAL;
     if (N == 0) return MOLORA_OK;
     if (!B || !t || !offsets || !perm || !h) return MOLORA_EINVAL;
     if (!aligned16(B) || !aligned16(t) || !aligned16(offsets) || !aligned16(perm) || !aligned16(h))
@@ -444,7 +456,20 @@ molora_status molora_expand_small(const void *B, const void *t, const int32_t *o
     return from_hip(molora::launch_small_expand(static_cast<const uint16_t *>(B),
                                                 static_cast<const uint16_t *>(t), offsets, perm, h, N, d_in,
                                                 d_out, C, rank, molora::Mix{1, C, nullptr, nullptr},
-                                                static_cast<hipStream_t>(stream)));
+                                                static_cast<hipStream_t>(stream), b_packed));
+}
+}  // namespace
+
+molora_status molora_expand_small(const void *B, const void *t, const int32_t *offsets,
+                                  const int32_t *perm, float *h, int64_t N, int32_t d_out, int32_t C,
+                                  int32_t rank, void *stream) {
+    return expand_small_common(B, t, offsets, perm, h, N, d_out, C, rank, stream, false);
+}
+
+molora_status molora_expand_small_packed(const void *Bp, const void *t, const int32_t *offsets,
+                                         const int32_t *perm, float *h, int64_t N, int32_t d_out,
+                                         int32_t C, int32_t rank, void *stream) {
+    return expand_small_common(Bp, t, offsets, perm, h, N, d_out, C, rank, stream, true);
 }
 
 molora_status molora_gate_dispatch_shrink(const int32_t *v, const int32_t *adapter,

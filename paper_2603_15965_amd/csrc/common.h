@@ -1,6 +1,7 @@
 // Internal declarations shared by the HIP translation units of libmolora (gfx950 only).
 #pragma once
 #include <hip/hip_runtime.h>
+#include <hip/hip_ext.h>
 #include <stdint.h>
 
 namespace molora {
@@ -74,6 +75,25 @@ struct LdsRegistrar {
     LdsRegistrar(const void *fn, size_t bytes) : node{fn, (int)bytes, nullptr} { register_kernel_lds(&node); }
 };
 hipError_t ensure_device_ready();
+
+// ---- benchmark aid: the device-side duration of a base-projection launch ----
+// A pair of events armed by the calling thread is attached to the next launch of a kernel that
+// holds the base projection (the tiled GEMM, the small-batch GEMM, the decode step's first
+// launch): the launch records its own start and end on them (hipExtLaunchKernelGGL), which is
+// the duration a kernel trace reports, with no marker packets beside the kernel.
+struct LaunchEvents {
+    hipEvent_t start = nullptr, stop = nullptr;
+};
+void arm_launch_events(hipEvent_t start, hipEvent_t stop);
+LaunchEvents take_launch_events();  // the calling thread's pending pair, which is cleared
+template <typename K, typename... Args>
+inline void launch_base_kernel(K kern, dim3 grid, dim3 block, size_t lds, hipStream_t s, Args... args) {
+    const LaunchEvents ev = take_launch_events();
+    if (ev.start != nullptr && ev.stop != nullptr)
+        hipExtLaunchKernelGGL(kern, grid, block, (uint32_t)lds, s, ev.start, ev.stop, 0, args...);
+    else
+        hipLaunchKernelGGL(kern, grid, block, lds, s, args...);
+}
 
 // the tiled GEMM keeps per-lane byte offsets into x and W in 32 bits: false when the kernel
 // that launch_fused_gemm would pick for these sizes (force_tile as there) cannot address them
@@ -156,7 +176,7 @@ int small_pack_cols(int d_out);
 hipError_t launch_pack_w(const uint16_t *W, uint16_t *Wp, int d_in, int d_out, hipStream_t s);
 hipError_t launch_small_expand(const uint16_t *B, const uint16_t *t2, const int32_t *offsets,
                                const int32_t *perm, float *h, int64_t N, int d_in, int d_out, int C,
-                               int rank, Mix mix, hipStream_t s);
+                               int rank, Mix mix, hipStream_t s, bool b_packed = false);
 // ksplit > 1 (with planes, fp32 [ksplit][N][R]): K cut into slices over workgroups, second pass adds them
 int small_batch_shrink_ksplit(int64_t N, int d_in, int C, int R);
 hipError_t launch_small_batch_shrink(const uint16_t *x, const uint16_t *A, const int32_t *offsets,

@@ -532,8 +532,8 @@ hipError_t launch_cfg(const uint16_t *x, const uint16_t *W, const uint16_t *B, c
     const int tiles_n = (d_out + Cfg::BN - 1) / Cfg::BN;
     const int total = tiles_m * tiles_n;
     const unsigned blocks = (unsigned)(((total + 7) / 8) * 8);
-    hipLaunchKernelGGL(kern, dim3(blocks), dim3(Cfg::NT), Cfg::LDS_BYTES, s, x, W, B, t2, offsets,
-                       perm, h, (int)N, d_in, d_out, C, rank, tiles_m, tiles_n, mix);
+    launch_base_kernel(kern, dim3(blocks), dim3(Cfg::NT), Cfg::LDS_BYTES, s, x, W, B, t2, offsets, perm, h,
+                       (int)N, d_in, d_out, C, rank, tiles_m, tiles_n, mix);
     return hipGetLastError();
 }
 

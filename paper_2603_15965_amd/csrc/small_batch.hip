@@ -111,7 +111,7 @@ struct SbBlock {
     int x, y, z;  // the workgroup's index in its grid
     int gy;       // the grid's extent in y
 };
-constexpr int kSbBaseOnly = 1, kSbExpandOnly = 2, kSbBasePacked = 3;
+constexpr int kSbBaseOnly = 1, kSbExpandOnly = 2, kSbBasePacked = 3, kSbExpandPacked = 4;
 
 template <int TM, int TN, bool SHRINK, int MODE = 0>  // TM: 32-row blocks, 1 (N <= 32) or 2
 __device__ __forceinline__ void small_batch_body(
@@ -196,9 +196,11 @@ __device__ __forceinline__ void small_batch_body(
     // the dispatch step produced, so the stream starts at once, and only the expand units (the
     // end of every wavefront's list) look up the sorted position of a row.
     const bool direct = !SHRINK && wg.gy == 1;
-    constexpr bool packed = !SHRINK && MODE == kSbBasePacked;       // d_out % COLS == 0 (host)
-    constexpr bool base_only = (!SHRINK && MODE == kSbBaseOnly) || packed;  // direct batches only (host)
-    constexpr bool expand_only = !SHRINK && MODE == kSbExpandOnly;  // direct batches only (host)
+    // packed: the streamed matrix (W, or the stacked B of the expand alone) is stored slab by
+    // slab, column group after column group; d_out % COLS == 0, and rank % 16 == 0 for B (host)
+    constexpr bool packed = !SHRINK && (MODE == kSbBasePacked || MODE == kSbExpandPacked);
+    constexpr bool base_only = !SHRINK && (MODE == kSbBaseOnly || MODE == kSbBasePacked);      // direct batches only (host)
+    constexpr bool expand_only = !SHRINK && (MODE == kSbExpandOnly || MODE == kSbExpandPacked);  // direct batches only (host)
 
     // ---- this wavefront's share of W ----
     // Of the nub pieces of 64 k-rows of W (the last piece may be short) every 8th one, piece
@@ -499,12 +501,18 @@ __device__ __forceinline__ void small_batch_body(
                     const int col = part * 16;
                     const int jj = (col >= rank) + (col >= 2 * rank) + (col >= 3 * rank);
                     const int ad = __builtin_amdgcn_readfirstlane(seg_ad[sg * 4 + jj]);
-                    bb = uniform_ptr(B + ((int64_t)ad * rank + (col - jj * rank)) * d_out);
+                    // (packed: the slab's rows of this column group follow one another)
+                    const int64_t grp = packed ? (int64_t)wg.x * 16 * kSbCols : 0;
+                    bb = uniform_ptr(B + ((int64_t)ad * rank + (col - jj * rank)) * d_out + grp);
                 }
 #pragma unroll
                 for (int r = 0; r < Geo::NR; ++r) {
                     if (whole) {
-                        load_to_lds16(bb + (int64_t)(r * Geo::RPD) * (d_out * 2), w_off[r], slot + r * 1024);
+                        load_to_lds16(bb + (int64_t)(r * Geo::RPD) * (pitch * 2), w_off[r], slot + r * 1024);
+                        continue;
+                    }
+                    if constexpr (packed) {  // a packed B has whole slabs only (host): never here
+                        load_to_lds16_ptr(zero, slot + r * 1024);
                         continue;
                     }
                     const int col = part * 16 + r * Geo::RPD + w_rr;  // this lane's row of the stacked B
@@ -674,8 +682,12 @@ hipError_t launch_small(const uint16_t *x, const uint16_t *W, const uint16_t *B,
     // (workgroups past a bucket's end leave at once)
     // (a K-split shrink: one workgroup per K slice of each of them)
     const dim3 grid = SHRINK ? dim3(groups, (unsigned)C, row_tiles * (unsigned)ksplit) : dim3(groups, row_tiles);
-    hipLaunchKernelGGL(kern, grid, dim3(kSbWaves * 64), Geo::LDS_BYTES, s, x, W, B, t2, offsets, perm,
-                       h, t_out, N, d_in, d_out, C, rank, mix, ksplit, sort);
+    if constexpr (!SHRINK && MODE == 0)  // the small-batch GEMM: base projection and expand
+        launch_base_kernel(kern, grid, dim3(kSbWaves * 64), Geo::LDS_BYTES, s, x, W, B, t2, offsets, perm, h,
+                           t_out, N, d_in, d_out, C, rank, mix, ksplit, sort);
+    else
+        hipLaunchKernelGGL(kern, grid, dim3(kSbWaves * 64), Geo::LDS_BYTES, s, x, W, B, t2, offsets, perm,
+                           h, t_out, N, d_in, d_out, C, rank, mix, ksplit, sort);
     return hipGetLastError();
 }
 
@@ -748,8 +760,8 @@ hipError_t launch_shrink_base(const uint16_t *x, const uint16_t *W, const uint16
     const int gemm_groups = (d_out + SbGeom<TN>::COLS - 1) / SbGeom<TN>::COLS;
     auto kern = shrink_base_small_kernel<TM, TN, PACKED>;
     constexpr size_t lds_bytes = ShrinkBaseKernel<TM, TN, PACKED>::LDS;
-    hipLaunchKernelGGL(kern, dim3((unsigned)(n_shrink + gemm_groups)), dim3(kSbWaves * 64), lds_bytes, s, x,
-                       W, A, h, t_out, N, d_in, d_out, C, rank, mix, sort, shrink_groups, n_shrink);
+    launch_base_kernel(kern, dim3((unsigned)(n_shrink + gemm_groups)), dim3(kSbWaves * 64), lds_bytes, s, x, W,
+                       A, h, t_out, N, d_in, d_out, C, rank, mix, sort, shrink_groups, n_shrink);
     return hipGetLastError();
 }
 }  // namespace
@@ -784,11 +796,18 @@ hipError_t launch_pack_w(const uint16_t *W, uint16_t *Wp, int d_in, int d_out, h
     return hipGetLastError();
 }
 
-// N <= 64: h += t B_c (the expand alone, after launch_small_shrink_base)
+// N <= 64: h += t B_c (the expand alone, after launch_small_shrink_base).  b_packed: the
+// stacked B, [C * rank][d_out], in the slab order of pack_w_kernel (rank a multiple of 16, so
+// that a slab lies inside one adapter).
 hipError_t launch_small_expand(const uint16_t *B, const uint16_t *t2, const int32_t *offsets,
                                const int32_t *perm, float *h, int64_t N, int d_in, int d_out, int C,
-                               int rank, Mix mix, hipStream_t s) {
+                               int rank, Mix mix, hipStream_t s, bool b_packed) {
     if (N < 1 || N > 64) return hipErrorInvalidValue;
+    if (b_packed) {
+        if (rank % 16 != 0 || mix.k != 1 || small_pack_cols(d_out) == 0) return hipErrorInvalidValue;
+        return launch_small_tn<false, kSbExpandPacked>(nullptr, nullptr, B, t2, offsets, perm, h, nullptr, (int)N,
+                                                       d_in, d_out, C, rank, mix, s);
+    }
     return launch_small_tn<false, kSbExpandOnly>(nullptr, nullptr, B, t2, offsets, perm, h, nullptr, (int)N, d_in,
                                                  d_out, C, rank, mix, s);
 }

@@ -181,6 +181,10 @@ def test_packed_base_weight_entry_points_reject_bad_arguments(lib):
     k1 = lambda N=64, d_out=256, W=a: lib.molora_shrink_base_small_packed(
         p(a), p(a), p(W), p(a), p(a), p(a), p(a), p(a), N, 4096, d_out, 16, 64, None, None)
     assert k1(d_out=264) == EINVAL and k1(N=65) == EINVAL and k1(W=0) == EINVAL and k1(W=a + 8) == EALIGN
+    k2 = lambda N=64, d_out=256, rank=64, B=a: lib.molora_expand_small_packed(p(B), p(a), p(a), p(a), p(a), N, d_out,
+                                                                              16, rank, None)
+    assert k2(rank=40) == EINVAL and k2(d_out=264) == EINVAL and k2(N=65) == EINVAL and k2(B=0) == EINVAL
+    assert k2(B=a + 8) == EALIGN and k2(N=0) == 0
 
 
 def test_operands_of_4_gib_are_rejected_for_the_tiled_kernel(lib):

@@ -141,6 +141,19 @@ def test_packed_base_weight_rejects_mismatched_shapes():
     with pytest.raises(TypeError, match="device tensor"):
         mb.molora_shrink_base_small(g["r"], g["x"], g["W"], g["A"], g["offsets"], g["perm"], g["t"], g["h"],
                                     packed=True)
+    B16 = tens((C, 16, d_out))
+    with pytest.raises(ValueError, match="multiple of 16"):   # rank 8: a slab would straddle two adapters
+        mb.molora_pack_b(g["B"])
+    with pytest.raises(ValueError):
+        mb.molora_pack_b(B16, tens((C, 16, d_out // 2)))
+    with pytest.raises(TypeError, match="device tensor"):
+        mb.molora_pack_b(B16)
+    with pytest.raises(ValueError, match="no packed form"):
+        mb.molora_expand_small(g["B"], g["t"], g["offsets"], g["perm"], g["h"], packed=True)
+    with pytest.raises(ValueError):   # t of another rank
+        mb.molora_expand_small(B16, g["t"], g["offsets"], g["perm"], g["h"], packed=True)
+    with pytest.raises(TypeError, match="device tensor"):
+        mb.molora_expand_small(B16, tens((N, 32)), g["offsets"], g["perm"], g["h"], packed=True)
 
 
 def test_routes_and_mixture_reject_mismatched_shapes():

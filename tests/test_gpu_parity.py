@@ -298,9 +298,23 @@ def test_packed_base_weight_small_batch(gpu, N, d_in, d_out, C, rank, structure)
     n_routed = int(o1[C].item())
     assert torch.equal(o1, o2) and torch.equal(p1, p2) and torch.equal(t1[:n_routed], t2[:n_routed])
     assert torch.equal(h1, h2), "h = x W from the packed weight, same bits"
+    h3 = h2.clone()
     mb.molora_expand_small(B, t2, o2, p2, h2)
     torch.cuda.synchronize()
     gpu.assert_h_close(h2.cpu().numpy(), oracle.apply(w.x, w.W, w.A, w.B, r), "packed W, then the expand")
+    if rank % 16 == 0:   # the adapters' B packed the same way (a slab of 16 rows lies inside one adapter)
+        Bp = mb.molora_pack_b(B)
+        torch.cuda.synchronize()
+        stacked = w.B.reshape(C * rank, d_out)
+        want_b = np.concatenate([stacked[k0:k0 + 16].reshape(-1, d_out // gc, gc).transpose(1, 0, 2).ravel()
+                                 for k0 in range(0, C * rank, 16)])
+        assert np.array_equal(Bp.view(torch.int16).cpu().numpy().view(np.uint16).ravel(), want_b), "molora_pack_b"
+        mb.molora_expand_small(Bp, t2, o2, p2, h3, packed=True)
+        torch.cuda.synchronize()
+        assert torch.equal(h2, h3), "expand from the packed B, same bits"
+    else:
+        with pytest.raises(ValueError):
+            mb.molora_pack_b(B)
 
 
 def test_gate_dispatch_shrink_matches_separate_calls(gpu):

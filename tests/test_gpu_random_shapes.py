@@ -110,6 +110,9 @@ def test_random_shape_plain_routes(i, N, d_in, d_out, C, rank, bad):
     if N <= 64 and mb.molora_pack_w_cols(d_out):   # the packed base weight: the two launches, same bits as apply
         rd = gpu.dev_i32(r)
         o, p, t, h2 = mb.molora_shrink_base_small(rd, x, mb.molora_pack_w(W), A, packed=True)
-        mb.molora_expand_small(B, t, o, p, h2)
+        if rank % 16 == 0:
+            mb.molora_expand_small(mb.molora_pack_b(B), t, o, p, h2, packed=True)
+        else:
+            mb.molora_expand_small(B, t, o, p, h2)
         torch.cuda.synchronize()
-        assert torch.equal(h, h2), f"random plain shape {i}: packed base weight"
+        assert torch.equal(h, h2), f"random plain shape {i}: packed base weight (and B)"
