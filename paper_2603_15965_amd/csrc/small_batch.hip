@@ -215,7 +215,7 @@ __device__ __forceinline__ void small_batch_body(
     const int nub = expand_only ? 0 : max(0, min(nub_all, u_lo + per_slice) - u_lo);
     const int nw = nub > wave ? (nub - wave + kSbWaves - 1) / kSbWaves : 0;
 
-    // elements between consecutive k-rows of W (A); packed: inside a piece of 64 k-rows the
+    // elements between consecutive k-rows of W (A); packed: inside a slab of 16 k-rows the
     // workgroup's column group is a [rows][COLS] matrix of its own
     const int pitch = SHRINK ? rank : (packed ? kSbCols : d_out);
     bool w_fast_ok = false, a_fast_ok = false;  // per-lane offsets fit 32 bits (set below)
@@ -614,8 +614,8 @@ __global__ __launch_bounds__(kSbWaves * 64) void small_batch_kernel(
 // shrink (a dozen workgroups each draining one A_c) hides behind the stream of W instead of
 // preceding it.  Workgroups [0, n_shrink) are the shrink's grid (column groups of the rank x
 // buckets, K not split: there is no hurry now), the others the GEMM's column groups in
-// kSbBaseOnly mode (PACKED: kSbBasePacked, W column group by column group).  The expand follows
-// as a launch of its own (kSbExpandOnly).
+// kSbBaseOnly mode (PACKED: kSbBasePacked, W in the order of pack_w_kernel).  The expand follows
+// as a launch of its own (kSbExpandOnly, or kSbExpandPacked for a B in that order).
 template <int TM, int TN, bool PACKED>
 __global__ __launch_bounds__(kSbWaves * 64) void shrink_base_small_kernel(
     const uint16_t *__restrict__ x, const uint16_t *__restrict__ W, const uint16_t *__restrict__ A,
