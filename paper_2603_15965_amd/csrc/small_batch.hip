@@ -86,11 +86,11 @@ struct Unit {
 
 // SHRINK = false: the fused GEMM above (grid: column groups x row tiles of 64 sorted rows; a
 //                 batch of more than 64 rows re-reads W once per row tile, from L2).
-// SHRINK = true:  the shrink step t_p = x[perm[p]] A_c for the rows of bucket c = blockIdx.y
+// SHRINK = true:  the shrink step t_p = x[perm[p]] A_c for the rows of bucket c = wg.y
 //                 (grid: column groups of the rank x buckets x 64-row tiles of a bucket); W is
 //                 A, d_out is rank, there are no expand units and the result goes to t_out as
 //                 [hi | lo] bf16 halves.  With ksplit > 1 the K range is cut into ksplit
-//                 slices, one workgroup each (blockIdx.z = tile * ksplit + slice): a batch of
+//                 slices, one workgroup each (wg.z = tile * ksplit + slice): a batch of
 //                 a few dozen tokens has too few (bucket, tile) pairs to draw the touched A_c
 //                 from HBM at speed, a workgroup draws ~50 GB/s.  A slice's sums then go, in
 //                 fp32, to plane `slice` of h [ksplit][N][R]; shrink_reduce_kernel adds the
@@ -602,10 +602,18 @@ __global__ __launch_bounds__(kSbWaves * 64) void small_batch_kernel(
     const uint16_t *__restrict__ t2, const int32_t *__restrict__ offsets,
     const int32_t *__restrict__ perm, float *__restrict__ h, uint16_t *__restrict__ t_out, int N,
     int d_in, int d_out, int C, int rank, Mix mix, int ksplit, SortArgs sort) {
+    // SHRINK: y numbers the buckets, rotated by one for every 4 steps of z (the tile and K
+    // slice).  Workgroups go to the XCDs round-robin, so with bucket = y and 32 buckets every tile
+    // of a bucket sat on the same XCD: good while the buckets are level (an XCD's L2 then holds
+    // the A_c of four buckets instead of all), but a batch routed to a single adapter ran on an
+    // eighth of the chip (412 us at 16384 tokens).  Measured, level buckets / one bucket, for a
+    // rotation every 1, 2, 4, 8 steps: 44.9 / 36.5, 41.3 / 37.4, 39.3 / 38.8, 38.3 / 60.3 us.
+    // The tiles a bucket can have at most are mostly empty, and the low tile indices, which are
+    // the ones in use, stay the first workgroups of the launch.
+    const int by = (int)blockIdx.y, bz = (int)blockIdx.z, ny = (int)gridDim.y;
+    const SbBlock wg = SbBlock{(int)blockIdx.x, SHRINK ? (by + ny - (bz >> 2) % ny) % ny : by, bz, ny};
     small_batch_body<TM, TN, SHRINK, MODE>(x, W, B, t2, offsets, perm, h, t_out, N, d_in, d_out, C, rank, mix,
-                                           ksplit, sort,
-                                           SbBlock{(int)blockIdx.x, (int)blockIdx.y, (int)blockIdx.z,
-                                                   (int)gridDim.y});
+                                           ksplit, sort, wg);
 }
 
 // A decode-sized batch (N <= 64): the shrink (with the dispatch step inside, see SortArgs) and
