@@ -148,9 +148,19 @@ __device__ __forceinline__ void bucket_body(const int32_t *__restrict__ r, int32
         const int32_t c = eval_target<GATE>(gate, my_b, b_top, raw);
         return (c >= 0 && c < C) ? c : C;
     };
+    // (all lanes of the wavefront call it together)
     auto count_other = [&](int i, int32_t k) {
-        if (i < n_other)
-            __hip_atomic_fetch_add(i < own_lo ? &pre[k] : &post[k], 1, __ATOMIC_RELAXED,
+        const bool in = i < n_other;
+        const int code = i < own_lo ? k : keys + k;  // pre[k] : post[k]
+        // one target for the whole group of 64 (skewed or run-structured routing): one add of
+        // the group's size by lane 0 instead of 64 adds that the LDS serves one after the other
+        // (i grows with the lane: lane 0 is inside whenever any lane is).  No branch: the
+        // callers issue a batch of loads before the first call and must stay straight-line.
+        const bool uni = __all(!in || code == __builtin_amdgcn_readfirstlane(code));
+        const int32_t group = (int32_t)__popcll(__ballot(in));  // (a ballot is taken by all lanes, outside any condition)
+        const int32_t add = uni ? (lane == 0 ? group : 0) : (in ? 1 : 0);
+        if (add != 0)
+            __hip_atomic_fetch_add(i < own_lo ? &pre[k] : &post[k], add, __ATOMIC_RELAXED,
                                    __HIP_MEMORY_SCOPE_WORKGROUP);
     };
     constexpr int kEarly = 16;
@@ -186,6 +196,13 @@ __device__ __forceinline__ void bucket_body(const int32_t *__restrict__ r, int32
                 const uint64_t same = match_lanes(key[u], valid, nbits);
                 if (valid && (same & lower) == 0)
                     __hip_atomic_fetch_add(&cnt[key[u] * kBucketWaves + w], __popcll(same),
+                                           __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+            } else if (__all(!valid || key[u] == __builtin_amdgcn_readfirstlane(key[u]))) {
+                // one target for the whole group (lane 0 holds a token whenever the group does):
+                // one add of the group's size
+                const uint64_t m = __ballot(valid);
+                if (lane == 0)
+                    __hip_atomic_fetch_add(&cnt[key[u] * kBucketWaves + w], (int32_t)__popcll(m),
                                            __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
             } else if (valid) {
                 // one LDS add per lane, without return value: nothing to wait for, and a count
@@ -276,7 +293,22 @@ __device__ __forceinline__ void bucket_body(const int32_t *__restrict__ r, int32
             for (int u = 0; u < kUnroll; ++u) {
                 m[u] = 0;
                 first[u] = 0;
-                if (base + u * 64 + lane < end) {
+                const bool valid = base + u * 64 + lane < end;
+                const int32_t k0 = __builtin_amdgcn_readfirstlane(key[u]);
+                if (__all(!valid || key[u] == k0)) {
+                    // one target for the whole group: the mask is the group itself, and one lane
+                    // advances the running base (read by all lanes first: issue order)
+                    const uint64_t vm = __ballot(valid);
+                    if (vm == 0) continue;
+                    int32_t *cp = &cnt[k0 * kBucketWaves + w];
+                    m[u] = vm;
+                    first[u] = __hip_atomic_load(cp, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+                    if (lane == 0)
+                        __hip_atomic_fetch_add(cp, (int32_t)__popcll(vm), __ATOMIC_RELAXED,
+                                               __HIP_MEMORY_SCOPE_WORKGROUP);
+                    continue;
+                }
+                if (valid) {
                     uint64_t *mp = my_mask + key[u];
                     int32_t *cp = &cnt[key[u] * kBucketWaves + w];
                     __hip_atomic_fetch_or(mp, bit, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
