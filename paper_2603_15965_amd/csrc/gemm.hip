@@ -5,7 +5,8 @@
 // One bf16 MFMA GEMM over the rows in bucket order.  The grouped expand is not a second
 // kernel: after the d_in-long K loop over (x, W) the same accumulators take a few extra
 // K tiles whose A operand is the low-rank intermediate t (as [hi | lo] bf16 halves, K =
-// 2*rank) and whose B operand is [B_c; B_c] for each bucket c that owns rows of the tile;
+// 2*rank) and whose B operand is [B_c; B_c] for each bucket c that owns rows of the tile
+// (narrow adapters, 2*rank = 16 or 32, lie two or four to a tile, side by side in k);
 // rows of other buckets are zero in that operand.  h is then written once, in fp32, to the
 // rows' original positions (the "scatter to original positions" of the paper's pipeline).
 // Rows past offsets[C] (tokens without adapter) simply have no extra tiles.
@@ -113,6 +114,14 @@ __global__ __launch_bounds__(Cfg::NT) void fused_gemm_kernel(
     const int R = mix.k * rank;  // width of a bucket's intermediate (k adapters side by side)
     const int two_r = 2 * R;
     const int tps = (two_r + BK - 1) / BK;  // extra K tiles per bucket
+    // Narrow adapters share an expand tile: with 2 * R = 16 or 32 a K tile has room for
+    // BK / (2 * R) buckets side by side in k (bucket s of the tile at k = s * 2R: its rows read
+    // their t there and zeros elsewhere, its [B; B] lies in those k-rows), so a row tile that
+    // many small buckets cross pays one extra K tile per 2-4 of them, not one each.  (Not for
+    // the token-order intermediate, whose tiles hold one or two buckets anyway.)
+    const int pk_shift = (!mix.t_dense && 2 * two_r <= BK && (two_r & (two_r - 1)) == 0)
+                             ? __builtin_ctz(BK) - __builtin_ctz(two_r) : 0;
+    const int two_r_shift = __builtin_ctz(two_r | BK);  // log2(2R) when buckets share a tile
     const int nkf = d_in / BK;              // full K tiles
     const int nkb = (d_in + BK - 1) / BK;   // K tiles of x.W, the last one possibly partial
 
@@ -226,7 +235,8 @@ __global__ __launch_bounds__(Cfg::NT) void fused_gemm_kernel(
     }
     __syncthreads();
     const int nseg = *nseg_p;
-    const int nk = nkb + nseg * tps;  // all K tiles of this output tile
+    // all K tiles of this output tile
+    const int nk = nkb + (pk_shift ? (nseg + (1 << pk_shift) - 1) >> pk_shift : nseg * tps);
 #pragma unroll
     for (int i = 0; i < Cfg::LPW; ++i) {  // x pieces: the gathered row of every lane
         if (!slot_is_a(i)) continue;
@@ -243,31 +253,36 @@ __global__ __launch_bounds__(Cfg::NT) void fused_gemm_kernel(
         const uint16_t *zero = (const uint16_t *)g_zero_page;
         // expand tile: A operand = t rows of one bucket (others zero), B operand = [B_c; B_c]
         const int e = T - nkb;
-        const int sg = e / tps, sub = e % tps;
-        const int lo = seg_lo[sg], hi = seg_hi[sg];
 #pragma unroll
         for (int i = 0; i < Cfg::LPW; ++i) {
-            const uint16_t *src;
+            const uint16_t *src = zero;
             int row, col;
             slot_geom(i, row, col);
-            if (slot_is_a(i)) {
-                const int p = p0 + row, vk = sub * BK + col * 8;
-                const bool own = p >= lo && p < hi && vk < two_r;
-                if (mix.t_dense) {
-                    // token-order intermediate: the row of this token, the bucket's adapter;
-                    // high parts in the first C * rank values, remainders in the second
-                    const int64_t trow = (int64_t)max(tile_perm[row], 0) * (2 * mix.C * rank);
-                    const int in_half = vk < rank ? vk : vk - rank;
-                    src = own ? t2 + trow + (vk < rank ? 0 : mix.C * rank) + seg_c[sg] * rank + in_half : zero;
+            const int kk = slot_is_a(i) ? col * 8 : row;  // k inside the tile
+            // the bucket that owns this k, and k inside that bucket's 2R (buckets side by side
+            // in k, or one bucket over tps tiles)
+            const int sg = pk_shift ? (e << pk_shift) + (kk >> two_r_shift) : e / tps;
+            const int vk = pk_shift ? (kk & (two_r - 1)) : (e % tps) * BK + kk;
+            if (sg < nseg && vk < two_r) {
+                if (slot_is_a(i)) {
+                    const int p = p0 + row;
+                    if (p >= seg_lo[sg] && p < seg_hi[sg]) {
+                        if (mix.t_dense) {
+                            // token-order intermediate: the row of this token, the bucket's adapter;
+                            // high parts in the first C * rank values, remainders in the second
+                            const int64_t trow = (int64_t)max(tile_perm[row], 0) * (2 * mix.C * rank);
+                            const int in_half = vk < rank ? vk : vk - rank;
+                            src = t2 + trow + (vk < rank ? 0 : mix.C * rank) + seg_c[sg] * rank + in_half;
+                        } else {
+                            src = t2 + (int64_t)p * two_r + vk;
+                        }
+                    }
                 } else {
-                    src = own ? t2 + (int64_t)p * two_r + vk : zero;
+                    const int j = vk < R ? vk : vk - R;        // row of the tuple's stacked B
+                    const int jj = mix.k > 1 ? j / rank : 0;   // which adapter of the tuple
+                    const int64_t brow = (int64_t)seg_ad[sg * 4 + jj] * rank + (j - jj * rank);
+                    src = B + brow * d_out + col;
                 }
-            } else {
-                const int vk = sub * BK + row;
-                const int j = vk < R ? vk : vk - R;        // row of the tuple's stacked B
-                const int jj = mix.k > 1 ? j / rank : 0;   // which adapter of the tuple
-                const int64_t brow = (int64_t)seg_ad[sg * 4 + jj] * rank + (j - jj * rank);
-                src = (vk < two_r) ? B + brow * d_out + col : zero;
             }
             load_to_lds16_ptr(src, stage + piece_of(i) * 1024);
         }

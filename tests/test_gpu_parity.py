@@ -317,6 +317,27 @@ def test_packed_base_weight_small_batch(gpu, N, d_in, d_out, C, rank, structure)
             mb.molora_pack_b(B)
 
 
+@pytest.mark.parametrize("N,d_in,d_out,C,rank,structure", [
+    (1500, 256, 320, 200, 8, "zipf"),       # four buckets of rank 8 per expand tile, a long tail of small buckets
+    (1500, 264, 320, 200, 16, "uniform"),   # two of rank 16; ~7 tokens per bucket, a K tail
+    (2100, 128, 512, 37, 8, "zipf"),        # the 256-row tile (2100 x 512 gives enough of them)
+    (700, 128, 136, 90, 16, "uniform"),     # ragged everything
+    (1300, 128, 256, 60, 24, "uniform"),    # 2R = 48: no sharing (not a power of two)
+])
+def test_many_small_buckets_share_expand_tiles(gpu, N, d_in, d_out, C, rank, structure):
+    """Row tiles crossed by many small buckets: buckets of rank 8 / 16 lie side by side in the
+    k range of one expand tile.  h against the oracle, targets out of range included."""
+    import oracle
+    import torch
+    say(f"many small buckets N={N} {d_in}->{d_out} C={C} rank={rank} {structure}")
+    w = wl.custom("s", N, d_in, d_out, C, rank, 9300 + N + C, structure=structure)
+    r = w.r.copy()
+    r[4::13] = -1
+    r[6::17] = C + 3
+    h = gpu.gpu_apply(w, r)
+    gpu.assert_h_close(h.cpu().numpy(), oracle.apply(w.x, w.W, w.A, w.B, r), "many small buckets")
+
+
 def test_gate_dispatch_shrink_matches_separate_calls(gpu):
     """Gating + dispatch + shrink in one launch on configuration 1's shape and on composite
     targets: r, offsets, perm bit for bit as the oracle's, h as the oracle's."""
