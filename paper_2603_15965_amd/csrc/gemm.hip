@@ -5,8 +5,7 @@
 // One bf16 MFMA GEMM over the rows in bucket order.  The grouped expand is not a second
 // kernel: after the d_in-long K loop over (x, W) the same accumulators take a few extra
 // K tiles whose A operand is the low-rank intermediate t (as [hi | lo] bf16 halves, K =
-// 2*rank) and whose B operand is [B_c; B_c] for each bucket c that owns rows of the tile
-// (narrow adapters, 2*rank = 16 or 32, lie two or four to a tile, side by side in k);
+// 2*rank) and whose B operand is [B_c; B_c] for each bucket c that owns rows of the tile;
 // rows of other buckets are zero in that operand.  h is then written once, in fp32, to the
 // rows' original positions (the "scatter to original positions" of the paper's pipeline).
 // Rows past offsets[C] (tokens without adapter) simply have no extra tiles.
@@ -77,7 +76,11 @@ struct GemmCfg {
     }
 };
 
-template <class Cfg>
+// PACK: narrow adapters share an expand tile (launch_cfg picks it from the rank).  A template
+// parameter, not a run-time branch: the kernel with 256 x 256 tiles has no register to spare,
+// and with both forms of the expand tile in one kernel the ordinary form ran 2-3 % slower on
+// expand-heavy shapes (top-2 / top-3 mixtures), with one form computing both 9-20 % slower.
+template <class Cfg, bool PACK>
 __global__ __launch_bounds__(Cfg::NT) void fused_gemm_kernel(
     const uint16_t *__restrict__ x, const uint16_t *__restrict__ W, const uint16_t *__restrict__ B,
     const uint16_t *__restrict__ t2, const int32_t *__restrict__ offsets,
@@ -114,14 +117,14 @@ __global__ __launch_bounds__(Cfg::NT) void fused_gemm_kernel(
     const int R = mix.k * rank;  // width of a bucket's intermediate (k adapters side by side)
     const int two_r = 2 * R;
     const int tps = (two_r + BK - 1) / BK;  // extra K tiles per bucket
-    // Narrow adapters share an expand tile: with 2 * R = 16 or 32 a K tile has room for
-    // BK / (2 * R) buckets side by side in k (bucket s of the tile at k = s * 2R: its rows read
-    // their t there and zeros elsewhere, its [B; B] lies in those k-rows), so a row tile that
-    // many small buckets cross pays one extra K tile per 2-4 of them, not one each.  (Not for
-    // the token-order intermediate, whose tiles hold one or two buckets anyway.)
-    const int pk_shift = (!mix.t_dense && 2 * two_r <= BK && (two_r & (two_r - 1)) == 0)
-                             ? __builtin_ctz(BK) - __builtin_ctz(two_r) : 0;
-    const int two_r_shift = __builtin_ctz(two_r | BK);  // log2(2R) when buckets share a tile
+    // Narrow adapters share an expand tile (PACK; the host has checked that 2R is 16 or 32, a
+    // power of two at most BK / 2, and that t is in bucket order): a K tile has room for
+    // BK / 2R buckets side by side in k (bucket s of the tile at k = s * 2R: its rows read their
+    // t there and zeros elsewhere, its [B; B] lies in those k-rows), so a row tile that many
+    // small buckets cross pays one extra K tile per 2-4 of them, not one each.  Every row still
+    // gets exactly its own products in the same order, plus exact zeros: same bits.
+    const int two_r_shift = __builtin_ctz(two_r | BK);              // log2(2R) when PACK
+    const int pk_shift = PACK ? __builtin_ctz(BK) - two_r_shift : 0;  // log2(buckets per tile)
     const int nkf = d_in / BK;              // full K tiles
     const int nkb = (d_in + BK - 1) / BK;   // K tiles of x.W, the last one possibly partial
 
@@ -236,7 +239,7 @@ __global__ __launch_bounds__(Cfg::NT) void fused_gemm_kernel(
     __syncthreads();
     const int nseg = *nseg_p;
     // all K tiles of this output tile
-    const int nk = nkb + (pk_shift ? (nseg + (1 << pk_shift) - 1) >> pk_shift : nseg * tps);
+    const int nk = nkb + (PACK ? (nseg + (1 << pk_shift) - 1) >> pk_shift : nseg * tps);
 #pragma unroll
     for (int i = 0; i < Cfg::LPW; ++i) {  // x pieces: the gathered row of every lane
         if (!slot_is_a(i)) continue;
@@ -253,36 +256,55 @@ __global__ __launch_bounds__(Cfg::NT) void fused_gemm_kernel(
         const uint16_t *zero = (const uint16_t *)g_zero_page;
         // expand tile: A operand = t rows of one bucket (others zero), B operand = [B_c; B_c]
         const int e = T - nkb;
+        if constexpr (PACK) {  // several narrow buckets side by side in k
+#pragma unroll
+            for (int i = 0; i < Cfg::LPW; ++i) {
+                const uint16_t *src = zero;
+                int row, col;
+                slot_geom(i, row, col);
+                const int kk = slot_is_a(i) ? col * 8 : row;            // k inside the tile
+                const int sg = (e << pk_shift) + (kk >> two_r_shift);  // the bucket that owns this k
+                const int vk = kk & (two_r - 1);                         // k inside the bucket's 2R
+                if (sg < nseg) {
+                    if (slot_is_a(i)) {
+                        const int p = p0 + row;
+                        if (p >= seg_lo[sg] && p < seg_hi[sg]) src = t2 + (int64_t)p * two_r + vk;
+                    } else {
+                        const int j = vk < R ? vk : vk - R;
+                        const int jj = mix.k > 1 ? j / rank : 0;
+                        const int64_t brow = (int64_t)seg_ad[sg * 4 + jj] * rank + (j - jj * rank);
+                        src = B + brow * d_out + col;
+                    }
+                }
+                load_to_lds16_ptr(src, stage + piece_of(i) * 1024);
+            }
+            return;
+        }
+        const int sg = e / tps, sub = e % tps;
+        const int lo = seg_lo[sg], hi = seg_hi[sg];
 #pragma unroll
         for (int i = 0; i < Cfg::LPW; ++i) {
-            const uint16_t *src = zero;
+            const uint16_t *src;
             int row, col;
             slot_geom(i, row, col);
-            const int kk = slot_is_a(i) ? col * 8 : row;  // k inside the tile
-            // the bucket that owns this k, and k inside that bucket's 2R (buckets side by side
-            // in k, or one bucket over tps tiles)
-            const int sg = pk_shift ? (e << pk_shift) + (kk >> two_r_shift) : e / tps;
-            const int vk = pk_shift ? (kk & (two_r - 1)) : (e % tps) * BK + kk;
-            if (sg < nseg && vk < two_r) {
-                if (slot_is_a(i)) {
-                    const int p = p0 + row;
-                    if (p >= seg_lo[sg] && p < seg_hi[sg]) {
-                        if (mix.t_dense) {
-                            // token-order intermediate: the row of this token, the bucket's adapter;
-                            // high parts in the first C * rank values, remainders in the second
-                            const int64_t trow = (int64_t)max(tile_perm[row], 0) * (2 * mix.C * rank);
-                            const int in_half = vk < rank ? vk : vk - rank;
-                            src = t2 + trow + (vk < rank ? 0 : mix.C * rank) + seg_c[sg] * rank + in_half;
-                        } else {
-                            src = t2 + (int64_t)p * two_r + vk;
-                        }
-                    }
+            if (slot_is_a(i)) {
+                const int p = p0 + row, vk = sub * BK + col * 8;
+                const bool own = p >= lo && p < hi && vk < two_r;
+                if (mix.t_dense) {
+                    // token-order intermediate: the row of this token, the bucket's adapter;
+                    // high parts in the first C * rank values, remainders in the second
+                    const int64_t trow = (int64_t)max(tile_perm[row], 0) * (2 * mix.C * rank);
+                    const int in_half = vk < rank ? vk : vk - rank;
+                    src = own ? t2 + trow + (vk < rank ? 0 : mix.C * rank) + seg_c[sg] * rank + in_half : zero;
                 } else {
-                    const int j = vk < R ? vk : vk - R;        // row of the tuple's stacked B
-                    const int jj = mix.k > 1 ? j / rank : 0;   // which adapter of the tuple
-                    const int64_t brow = (int64_t)seg_ad[sg * 4 + jj] * rank + (j - jj * rank);
-                    src = B + brow * d_out + col;
+                    src = own ? t2 + (int64_t)p * two_r + vk : zero;
                 }
+            } else {
+                const int vk = sub * BK + row;
+                const int j = vk < R ? vk : vk - R;        // row of the tuple's stacked B
+                const int jj = mix.k > 1 ? j / rank : 0;   // which adapter of the tuple
+                const int64_t brow = (int64_t)seg_ad[sg * 4 + jj] * rank + (j - jj * rank);
+                src = (vk < two_r) ? B + brow * d_out + col : zero;
             }
             load_to_lds16_ptr(src, stage + piece_of(i) * 1024);
         }
@@ -532,17 +554,17 @@ __global__ __launch_bounds__(Cfg::NT) void fused_gemm_kernel(
 }
 
 // more than 64 KB of dynamic LDS has to be asked for, once per device (see common.h)
-template <class Cfg>
+template <class Cfg, bool PACK>
 struct GemmKernel {
-    static inline LdsRegistrar lds{(const void *)fused_gemm_kernel<Cfg>, Cfg::LDS_BYTES};
+    static inline LdsRegistrar lds{(const void *)fused_gemm_kernel<Cfg, PACK>, Cfg::LDS_BYTES};
 };
 
-template <class Cfg>
-hipError_t launch_cfg(const uint16_t *x, const uint16_t *W, const uint16_t *B, const uint16_t *t2,
-                      const int32_t *offsets, const int32_t *perm, float *h, int64_t N, int d_in,
-                      int d_out, int C, int rank, Mix mix, hipStream_t s) {
-    auto kern = fused_gemm_kernel<Cfg>;
-    (void)&GemmKernel<Cfg>::lds;  // instantiates the registration
+template <class Cfg, bool PACK>
+hipError_t launch_cfg_pack(const uint16_t *x, const uint16_t *W, const uint16_t *B, const uint16_t *t2,
+                           const int32_t *offsets, const int32_t *perm, float *h, int64_t N, int d_in,
+                           int d_out, int C, int rank, Mix mix, hipStream_t s) {
+    auto kern = fused_gemm_kernel<Cfg, PACK>;
+    (void)&GemmKernel<Cfg, PACK>::lds;  // instantiates the registration
     const int tiles_m = (int)((N + Cfg::BM - 1) / Cfg::BM);
     const int tiles_n = (d_out + Cfg::BN - 1) / Cfg::BN;
     const int total = tiles_m * tiles_n;
@@ -550,6 +572,18 @@ hipError_t launch_cfg(const uint16_t *x, const uint16_t *W, const uint16_t *B, c
     launch_base_kernel(kern, dim3(blocks), dim3(Cfg::NT), Cfg::LDS_BYTES, s, x, W, B, t2, offsets, perm, h,
                        (int)N, d_in, d_out, C, rank, tiles_m, tiles_n, mix);
     return hipGetLastError();
+}
+
+template <class Cfg>
+hipError_t launch_cfg(const uint16_t *x, const uint16_t *W, const uint16_t *B, const uint16_t *t2,
+                      const int32_t *offsets, const int32_t *perm, float *h, int64_t N, int d_in,
+                      int d_out, int C, int rank, Mix mix, hipStream_t s) {
+    // narrow adapters share an expand tile: 2R a power of two and at most half a K tile (16 or
+    // 32 with 64-deep tiles), t in bucket order
+    const int two_r = 2 * mix.k * rank;
+    const bool pack = !mix.t_dense && 2 * two_r <= Cfg::BK && (two_r & (two_r - 1)) == 0;
+    return pack ? launch_cfg_pack<Cfg, true>(x, W, B, t2, offsets, perm, h, N, d_in, d_out, C, rank, mix, s)
+                : launch_cfg_pack<Cfg, false>(x, W, B, t2, offsets, perm, h, N, d_in, d_out, C, rank, mix, s);
 }
 
 }  // namespace
