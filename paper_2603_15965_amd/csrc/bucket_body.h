@@ -197,18 +197,18 @@ __device__ __forceinline__ void bucket_body(const int32_t *__restrict__ r, int32
                 if (valid && (same & lower) == 0)
                     __hip_atomic_fetch_add(&cnt[key[u] * kBucketWaves + w], __popcll(same),
                                            __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
-            } else if (__all(!valid || key[u] == __builtin_amdgcn_readfirstlane(key[u]))) {
-                // one target for the whole group (lane 0 holds a token whenever the group does):
-                // one add of the group's size
-                const uint64_t m = __ballot(valid);
-                if (lane == 0)
-                    __hip_atomic_fetch_add(&cnt[key[u] * kBucketWaves + w], (int32_t)__popcll(m),
-                                           __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
-            } else if (valid) {
+            } else {
                 // one LDS add per lane, without return value: nothing to wait for, and a count
-                // does not depend on the order in which the lanes are served
-                __hip_atomic_fetch_add(&cnt[key[u] * kBucketWaves + w], 1, __ATOMIC_RELAXED,
-                                       __HIP_MEMORY_SCOPE_WORKGROUP);
+                // does not depend on the order in which the lanes are served.  One target for the
+                // whole group (lane 0 holds a token whenever the group does): lane 0 adds the
+                // group's size instead, as in count_other (same compact form: the kernel is short
+                // enough for the size of its code to show in its time).
+                const bool uni = __all(!valid || key[u] == __builtin_amdgcn_readfirstlane(key[u]));
+                const int32_t group = (int32_t)__popcll(__ballot(valid));
+                const int32_t add = uni ? (lane == 0 ? group : 0) : (valid ? 1 : 0);
+                if (add != 0)
+                    __hip_atomic_fetch_add(&cnt[key[u] * kBucketWaves + w], add, __ATOMIC_RELAXED,
+                                           __HIP_MEMORY_SCOPE_WORKGROUP);
             }
         }
     }
@@ -294,28 +294,24 @@ __device__ __forceinline__ void bucket_body(const int32_t *__restrict__ r, int32
                 m[u] = 0;
                 first[u] = 0;
                 const bool valid = base + u * 64 + lane < end;
-                const int32_t k0 = __builtin_amdgcn_readfirstlane(key[u]);
-                if (__all(!valid || key[u] == k0)) {
-                    // one target for the whole group: the mask is the group itself, and one lane
-                    // advances the running base (read by all lanes first: issue order)
-                    const uint64_t vm = __ballot(valid);
-                    if (vm == 0) continue;
-                    int32_t *cp = &cnt[k0 * kBucketWaves + w];
-                    m[u] = vm;
-                    first[u] = __hip_atomic_load(cp, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
-                    if (lane == 0)
-                        __hip_atomic_fetch_add(cp, (int32_t)__popcll(vm), __ATOMIC_RELAXED,
-                                               __HIP_MEMORY_SCOPE_WORKGROUP);
-                    continue;
-                }
-                if (valid) {
-                    uint64_t *mp = my_mask + key[u];
-                    int32_t *cp = &cnt[key[u] * kBucketWaves + w];
+                // one target for the whole group: the mask is the group itself (no mask words
+                // touched, which would all be one word), and lane 0 advances the running base
+                const bool uni = __all(!valid || key[u] == __builtin_amdgcn_readfirstlane(key[u]));
+                const uint64_t vm = __ballot(valid);
+                uint64_t *mp = my_mask + key[u];
+                int32_t *cp = &cnt[key[u] * kBucketWaves + w];
+                uint64_t mine = 0;
+                if (valid && !uni) {
                     __hip_atomic_fetch_or(mp, bit, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
-                    m[u] = __hip_atomic_load(mp, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+                    mine = __hip_atomic_load(mp, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
                     __hip_atomic_fetch_and(mp, ~bit, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+                }
+                m[u] = uni ? vm : mine;
+                const int32_t add = uni ? (lane == 0 ? (int32_t)__popcll(vm) : 0) : 1;
+                if (valid) {
                     first[u] = __hip_atomic_load(cp, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
-                    __hip_atomic_fetch_add(cp, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+                    if (add != 0)
+                        __hip_atomic_fetch_add(cp, add, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
                 }
             }
 #pragma unroll
