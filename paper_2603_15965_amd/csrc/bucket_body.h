@@ -156,9 +156,11 @@ __device__ __forceinline__ void bucket_body(const int32_t *__restrict__ r, int32
         // the group's size by lane 0 instead of 64 adds that the LDS serves one after the other
         // (i grows with the lane: lane 0 is inside whenever any lane is).  No branch: the
         // callers issue a batch of loads before the first call and must stay straight-line.
-        const bool uni = __all(!in || code == __builtin_amdgcn_readfirstlane(code));
-        const int32_t group = (int32_t)__popcll(__ballot(in));  // (a ballot is taken by all lanes, outside any condition)
-        const int32_t add = uni ? (lane == 0 ? group : 0) : (in ? 1 : 0);
+        // (ballots and the lane-0 read are taken by all lanes, outside any condition; written
+        // with masks, not with || and &&, which the compiler turns into branches around them)
+        const uint64_t in_m = __ballot(in);
+        const bool uni = (__ballot(code != __builtin_amdgcn_readfirstlane(code)) & in_m) == 0;
+        const int32_t add = uni ? (lane == 0 ? (int32_t)__popcll(in_m) : 0) : (in ? 1 : 0);
         if (add != 0)
             __hip_atomic_fetch_add(i < own_lo ? &pre[k] : &post[k], add, __ATOMIC_RELAXED,
                                    __HIP_MEMORY_SCOPE_WORKGROUP);
@@ -203,9 +205,9 @@ __device__ __forceinline__ void bucket_body(const int32_t *__restrict__ r, int32
                 // whole group (lane 0 holds a token whenever the group does): lane 0 adds the
                 // group's size instead, as in count_other (same compact form: the kernel is short
                 // enough for the size of its code to show in its time).
-                const bool uni = __all(!valid || key[u] == __builtin_amdgcn_readfirstlane(key[u]));
-                const int32_t group = (int32_t)__popcll(__ballot(valid));
-                const int32_t add = uni ? (lane == 0 ? group : 0) : (valid ? 1 : 0);
+                const uint64_t vm = __ballot(valid);
+                const bool uni = (__ballot(key[u] != __builtin_amdgcn_readfirstlane(key[u])) & vm) == 0;
+                const int32_t add = uni ? (lane == 0 ? (int32_t)__popcll(vm) : 0) : (valid ? 1 : 0);
                 if (add != 0)
                     __hip_atomic_fetch_add(&cnt[key[u] * kBucketWaves + w], add, __ATOMIC_RELAXED,
                                            __HIP_MEMORY_SCOPE_WORKGROUP);
@@ -296,8 +298,8 @@ __device__ __forceinline__ void bucket_body(const int32_t *__restrict__ r, int32
                 const bool valid = base + u * 64 + lane < end;
                 // one target for the whole group: the mask is the group itself (no mask words
                 // touched, which would all be one word), and lane 0 advances the running base
-                const bool uni = __all(!valid || key[u] == __builtin_amdgcn_readfirstlane(key[u]));
                 const uint64_t vm = __ballot(valid);
+                const bool uni = (__ballot(key[u] != __builtin_amdgcn_readfirstlane(key[u])) & vm) == 0;
                 uint64_t *mp = my_mask + key[u];
                 int32_t *cp = &cnt[key[u] * kBucketWaves + w];
                 uint64_t mine = 0;
