@@ -77,8 +77,10 @@ struct BucketLds {
     int kBucketWaves;  // wavefronts per workgroup
     bool masks;
     __host__ __device__ BucketLds(int C, int waves) : keys(C + 1), kBucketWaves(waves), masks(C + 1 > 4 && C + 1 <= kMaskMaxKeys) {}
-    __host__ __device__ size_t cnt_off() const { return 0; }                                    // [keys][16]
-    __host__ __device__ size_t pre_off() const { return (size_t)keys * kBucketWaves * 4; }     // [keys]
+    // a row of cnt is one word longer than the wavefronts number: the lanes of a wavefront all
+    // address column w, and with rows of 16 words they would share two banks
+    __host__ __device__ size_t cnt_off() const { return 0; }                                      // [keys][waves + 1]
+    __host__ __device__ size_t pre_off() const { return (size_t)keys * (kBucketWaves + 1) * 4; } // [keys]
     __host__ __device__ size_t post_off() const { return pre_off() + (size_t)keys * 4; }       // [keys]
     __host__ __device__ size_t tot_off() const { return post_off() + (size_t)keys * 4; }       // [keys]
     __host__ __device__ size_t mask_off() const { return (tot_off() + (size_t)keys * 4 + 7) & ~size_t(7); }
@@ -97,9 +99,10 @@ __device__ __forceinline__ void bucket_body(const int32_t *__restrict__ r, int32
                                             int32_t *__restrict__ perm, int N, int C, int32_t *err_flag,
                                             const GateArgs &gate, int G, int g) {
     constexpr int kBucketWaves = BW, kBucketThreads = BW * 64;
+    constexpr int kCntRow = BW + 1;  // words per row of cnt (see BucketLds)
     extern __shared__ __attribute__((aligned(16))) unsigned char lds_raw[];
     const BucketLds L(C, BW);
-    int32_t *cnt = (int32_t *)(lds_raw + L.cnt_off());    // cnt[b * 16 + w]: own part, by wavefront
+    int32_t *cnt = (int32_t *)(lds_raw + L.cnt_off());    // cnt[b * kCntRow + w]: own part, by wavefront
     int32_t *pre = (int32_t *)(lds_raw + L.pre_off());    // tokens of target b before the own part
     int32_t *post = (int32_t *)(lds_raw + L.post_off());  // ... after it
     int32_t *tot = (int32_t *)(lds_raw + L.tot_off());    // per-target totals, then their prefix
@@ -197,7 +200,7 @@ __device__ __forceinline__ void bucket_body(const int32_t *__restrict__ r, int32
                 // few targets: group the lanes (three ballots), one add per group by its lowest lane
                 const uint64_t same = match_lanes(key[u], valid, nbits);
                 if (valid && (same & lower) == 0)
-                    __hip_atomic_fetch_add(&cnt[key[u] * kBucketWaves + w], __popcll(same),
+                    __hip_atomic_fetch_add(&cnt[key[u] * kCntRow + w], __popcll(same),
                                            __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
             } else {
                 // one LDS add per lane, without return value: nothing to wait for, and a count
@@ -209,7 +212,7 @@ __device__ __forceinline__ void bucket_body(const int32_t *__restrict__ r, int32
                 const bool uni = (__ballot(key[u] != __builtin_amdgcn_readfirstlane(key[u])) & vm) == 0;
                 const int32_t add = uni ? (lane == 0 ? (int32_t)__popcll(vm) : 0) : (valid ? 1 : 0);
                 if (add != 0)
-                    __hip_atomic_fetch_add(&cnt[key[u] * kBucketWaves + w], add, __ATOMIC_RELAXED,
+                    __hip_atomic_fetch_add(&cnt[key[u] * kCntRow + w], add, __ATOMIC_RELAXED,
                                            __HIP_MEMORY_SCOPE_WORKGROUP);
             }
         }
@@ -240,7 +243,7 @@ __device__ __forceinline__ void bucket_body(const int32_t *__restrict__ r, int32
     for (int b = lo; b < hi; ++b) {
         int32_t sum = pre[b] + post[b];
 #pragma unroll
-        for (int j = 0; j < kBucketWaves; ++j) sum += cnt[b * kBucketWaves + j];
+        for (int j = 0; j < kBucketWaves; ++j) sum += cnt[b * kCntRow + j];
         tot[b] = sum;
         mine += sum;
     }
@@ -261,8 +264,8 @@ __device__ __forceinline__ void bucket_body(const int32_t *__restrict__ r, int32
         int32_t run = before + pre[b];
 #pragma unroll
         for (int j = 0; j < kBucketWaves; ++j) {
-            const int32_t c = cnt[b * kBucketWaves + j];
-            cnt[b * kBucketWaves + j] = run;
+            const int32_t c = cnt[b * kCntRow + j];
+            cnt[b * kCntRow + j] = run;
             run += c;
         }
         // offsets[C] counts the routed tokens: fewer than N means some target was out of range
@@ -301,7 +304,7 @@ __device__ __forceinline__ void bucket_body(const int32_t *__restrict__ r, int32
                 const uint64_t vm = __ballot(valid);
                 const bool uni = (__ballot(key[u] != __builtin_amdgcn_readfirstlane(key[u])) & vm) == 0;
                 uint64_t *mp = my_mask + key[u];
-                int32_t *cp = &cnt[key[u] * kBucketWaves + w];
+                int32_t *cp = &cnt[key[u] * kCntRow + w];
                 uint64_t mine = 0;
                 if (valid && !uni) {
                     __hip_atomic_fetch_or(mp, bit, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
@@ -333,7 +336,7 @@ __device__ __forceinline__ void bucket_body(const int32_t *__restrict__ r, int32
             const uint64_t same = match_lanes(key[u], valid, nbits);
             int32_t got = 0;
             if (valid && (same & lower) == 0)
-                got = __hip_atomic_fetch_add(&cnt[key[u] * kBucketWaves + w], __popcll(same),
+                got = __hip_atomic_fetch_add(&cnt[key[u] * kCntRow + w], __popcll(same),
                                              __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
             const int first = same ? __ffsll((long long)same) - 1 : 0;
             const int32_t base_pos = __shfl(got, first, 64);
