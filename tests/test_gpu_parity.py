@@ -445,9 +445,18 @@ def test_configs_0_to_3_end_to_end(gpu, name):
     r_ref = gpu.oracle_route(w)
     assert np.array_equal(r_gpu.cpu().numpy(), r_ref)
     gpu.check_bucket(r_ref, w.shape.C)
-    h = gpu.gpu_apply(w, r_ref).cpu().numpy()
+    h_dev = gpu.gpu_apply(w, r_ref)
+    h = h_dev.cpu().numpy()
     rel = gpu.assert_h_close(h, oracle.apply(w.x, w.W, w.A, w.B, r_ref), name)
     say(f"  {name}: max err / rms = {rel:.2e}")
+    if name == "decode_up8":   # the launch configuration the benchmark times: the two calls on packed weights
+        import torch
+        from paper_2603_15965_amd import binding as mb
+        x, W, A, B = (gpu.dev_bf16(t) for t in (w.x, w.W, w.A, w.B))
+        o, p, t, h2 = mb.molora_shrink_base_small(gpu.dev_i32(r_ref), x, mb.molora_pack_w(W), A, packed=True)
+        mb.molora_expand_small(mb.molora_pack_b(B), t, o, p, h2, packed=True)
+        torch.cuda.synchronize()
+        assert torch.equal(h_dev, h2), "decode step on packed weights: same bits as molora_apply"
 
 
 @pytest.mark.parametrize("proj", ["q", "k", "v", "o", "gate", "up", "down"])
