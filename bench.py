@@ -509,6 +509,9 @@ def run_workload(args, workload, steps, warmup, full):
                   "routed_tokens": n_routed_all if P > 1 else n_routed_all[0],
                   "touched_adapters": touched_all if P > 1 else touched_all[0]},
         "breakdown_us": breakdown,
+        "breakdown_how": "HIP events recorded around single calls, outside the timed region: every figure "
+                         "includes 5-10 us of launch gap and event overhead (the kernels' own durations are "
+                         "in profiles/step_<workload>.md; roofline.kernel_us is the launch's own duration)",
     }
     if full and not args.no_cpu_baseline:
         if P == 1:
