@@ -597,6 +597,14 @@ using GemmSmall = GemmCfg<128, 128, 2, 2, 64, 2>;
 // 128 x 128 tiles with at most one workgroup per compute unit: a third stage replaces the
 // second resident workgroup as the way to cover the load latency
 using GemmMid = GemmCfg<128, 128, 2, 2, 64, 3>;
+// 128 x 256 tiles, eight wavefronts, three stages, one workgroup per compute unit: for shapes
+// with too few 256 x 256 tiles to fill the chip whose 128 x 256 tiles number at most one per
+// compute unit.  A K tile moves 48 KB for 128 x 256 x 64 products where two 128 x 128
+// workgroups move 64 KB, and the loop runs at the rate at which lines arrive; its start and
+// end cost more (one workgroup per unit: nothing overlaps them).  Measured against 128 x 128
+// tiles at 4096 x K x 2048: level at K = 2048 (36.7 / 36.5 us), 67.3 / 76.0 us at K = 4096,
+// 125.8 / 145.5 us at K = 8192.
+using GemmWide = GemmCfg<128, 256, 2, 4, 64, 3>;
 
 bool fused_gemm_sizes_ok(int64_t N, int d_in, int d_out, int force_tile) {
     const bool tiled = force_tile == 128 || force_tile == 256 || (force_tile == 0 && N > kSmallBatchMax);
@@ -625,6 +633,8 @@ hipError_t launch_fused_gemm(const uint16_t *x, const uint16_t *W, const uint16_
     // with fewer, 128 x 128 tiles keep more of the chip busy
     const int64_t t128 = ((N + 127) / 128) * ((d_out + 127) / 128);
     if (t128 <= 256) return launch_cfg<GemmMid>(MOLORA_GEMM_ARGS);
+    const int64_t twide = ((N + 127) / 128) * ((d_out + 255) / 256);
+    if (twide <= 256 && d_in >= 3072) return launch_cfg<GemmWide>(MOLORA_GEMM_ARGS);
     return launch_cfg<GemmSmall>(MOLORA_GEMM_ARGS);
 #undef MOLORA_GEMM_ARGS
 }

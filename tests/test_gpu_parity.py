@@ -146,6 +146,9 @@ def test_route_gate_bit_exact_full_configs(gpu, name):
     (1000, 128, 136, 4, 128, "uniform"),    # maximum rank
     (2304, 192, 2560, 6, 16, "all0"),       # large-tile path (>= 512 tiles), one bucket
     (2500, 128, 4000, 9, 8, "uniform"),     # large-tile path, ragged everything
+    (4000, 3080, 1992, 5, 24, "zipf"),      # 128 x 256 tiles with three stages (K >= 3072), ragged everything, K tail
+    (1100, 3072, 3800, 12, 16, "uniform"),  # the same tiles, two narrow buckets per expand tile
+    (4090, 4096, 2048, 3, 8, "zipf"),       # the same tiles with the token-order intermediate (C * rank <= 64)
 ])
 def test_apply_small_shapes(gpu, N, d_in, d_out, C, rank, structure):
     import oracle
