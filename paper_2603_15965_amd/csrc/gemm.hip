@@ -629,9 +629,13 @@ hipError_t launch_fused_gemm(const uint16_t *x, const uint16_t *W, const uint16_
     if (force_tile == 256) return launch_cfg<GemmBig>(MOLORA_GEMM_ARGS);
     if (N <= kSmallBatchMax) return launch_small_batch_gemm(MOLORA_GEMM_ARGS);
     const int64_t t256 = ((N + 255) / 256) * ((d_out + 255) / 256);
-    if (t256 >= kBigMinTiles) return launch_cfg<GemmBig>(MOLORA_GEMM_ARGS);
-    // with fewer, 128 x 128 tiles keep more of the chip busy
     const int64_t t128 = ((N + 127) / 128) * ((d_out + 127) / 128);
+    // 256 x 256 tiles from one per compute unit on -- and already when the 128 x 128 tiles would
+    // not fit one round of two per compute unit: 544 of them take 56.8 us where the 136 large
+    // tiles of the same shape take 43.5 us (4352 x 2048 x 2048; 10-29 % over the whole range of
+    // 136 .. 192 large tiles, K = 1024 .. 8192), while 512 take 36.6 us against 42.6 us
+    if (t256 >= kBigMinTiles || t128 > 512) return launch_cfg<GemmBig>(MOLORA_GEMM_ARGS);
+    // with fewer, 128 x 128 tiles keep more of the chip busy
     if (t128 <= 256) return launch_cfg<GemmMid>(MOLORA_GEMM_ARGS);
     const int64_t twide = ((N + 127) / 128) * ((d_out + 255) / 256);
     if (twide <= 256 && d_in >= 3072) return launch_cfg<GemmWide>(MOLORA_GEMM_ARGS);
