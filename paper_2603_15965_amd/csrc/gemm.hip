@@ -613,6 +613,45 @@ bool fused_gemm_sizes_ok(int64_t N, int d_in, int d_out, int force_tile) {
     return (uint64_t)N * (uint64_t)d_in * 2 < lim && (uint64_t)d_in * (uint64_t)d_out * 2 < lim;
 }
 
+namespace {
+// Streaming kernel (64-row tiles, W re-read per row tile) or 128 x 128 tiles, for batches of
+// 129 .. 4096 rows?  Both run in rounds of 256 workgroups whose time grows with K; fitted to a
+// sweep of 96 shapes (launch timer, rotating inputs; us, K in units of 1024):
+//   streaming: ceil(workgroups / 256) * (5.0 + 3.3 K), workgroups = column groups of 64 (of 32
+//              when that leaves at most 128) x row tiles of 64;
+//   tiles:     8.0 + 6.6 K for up to 256 tiles (one per compute unit), 1.6 times that per 512
+//              beyond (two per compute unit); K counts the expand tiles too, 64 k for each of the
+//              ~(1 + 128 C / N, at most C) buckets that cross a 128-row tile and each 64 of its 2R
+//              (narrow adapters share a tile), and a tie goes to the streaming kernel, whose
+//              expand works on 16-row slabs (512 rows, 4096 -> 4096, 8 adapters of rank 64: 45.9
+//              against 50.5 us).
+// The fixed boundary at 512 rows that this replaces lost up to 1.9x on both sides of it: a
+// narrow output (4096 -> 1024) streams faster up to ~1500 rows (19 against 34 us at 576), a wide
+// one (1024 -> 8192, 4096 -> 12288) is faster in tiles from ~200 rows on (17 against 32 us at 512).
+bool streaming_beats_tiles(int64_t N, int d_in, int d_out, int C, int two_r) {
+    // one row of 128 x 128 tiles: level with or behind the streaming kernel on eight of ten shapes
+    // (4096 -> 12288 at 97-128 rows: 46-47 against 43-45 us; 2048 -> 16384 the other way, 24 / 30)
+    if (N <= 128) return true;
+    if (N > 4096) return false;
+    // operands beyond the tiled kernel's 32-bit offsets: up to kSmallBatchMax rows the streaming
+    // kernel takes them (fused_gemm_sizes_ok refuses them above)
+    const uint64_t lim = uint64_t(1) << 32;
+    if (N <= kSmallBatchMax && ((uint64_t)N * (uint64_t)d_in * 2 >= lim || (uint64_t)d_in * (uint64_t)d_out * 2 >= lim))
+        return true;
+    int64_t wgs = (int64_t)((d_out + 63) / 64) * ((N + 63) / 64);
+    if (wgs <= 128) wgs *= 2;     // the narrow form: groups of 32 columns
+    const int64_t t128 = ((N + 127) / 128) * ((d_out + 127) / 128);
+    const int64_t stream = ((wgs + 255) / 256) * (50 * 1024 + 33 * (int64_t)d_in);          // 10 * 1024 * us
+    int64_t crossing = 1 + 128 * (int64_t)C / N;  // buckets that cross a 128-row tile
+    if (crossing > C) crossing = C;
+    const bool share = 2 * two_r <= 64 && (two_r & (two_r - 1)) == 0;  // as launch_cfg packs them
+    const int64_t expand_k = share ? ((crossing * two_r + 63) / 64) * 64 : crossing * ((two_r + 63) / 64) * 64;
+    const int64_t tile1 = 80 * 1024 + 66 * ((int64_t)d_in + expand_k);
+    const int64_t tiles = t128 <= 256 ? tile1 : ((t128 + 511) / 512) * tile1 * 16 / 10;
+    return stream * 100 <= tiles * 105;
+}
+}  // namespace
+
 // force_tile: 0 = the choice below; 64 / 128 / 256 = that row-tile height whatever the shape
 // (the tiling ablation compares the choice with fixed tiles).
 hipError_t launch_fused_gemm(const uint16_t *x, const uint16_t *W, const uint16_t *B,
@@ -627,7 +666,9 @@ hipError_t launch_fused_gemm(const uint16_t *x, const uint16_t *W, const uint16_
     if (force_tile == 64) return launch_small_batch_gemm(MOLORA_GEMM_ARGS);
     if (force_tile == 128) return launch_cfg<GemmSmall>(MOLORA_GEMM_ARGS);
     if (force_tile == 256) return launch_cfg<GemmBig>(MOLORA_GEMM_ARGS);
-    if (N <= kSmallBatchMax) return launch_small_batch_gemm(MOLORA_GEMM_ARGS);
+    // (the token-order intermediate, N > 512, is read by the tiled kernel only)
+    if (!mix.t_dense && streaming_beats_tiles(N, d_in, d_out, C, 2 * mix.k * rank))
+        return launch_small_batch_gemm(MOLORA_GEMM_ARGS);
     const int64_t t256 = ((N + 255) / 256) * ((d_out + 255) / 256);
     const int64_t t128 = ((N + 127) / 128) * ((d_out + 127) / 128);
     // 256 x 256 tiles from one per compute unit on -- and already when the 128 x 128 tiles would

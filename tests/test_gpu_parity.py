@@ -205,6 +205,36 @@ def test_apply_few_narrow_adapters_one_launch_dispatch_and_shrink(gpu, N, d_in, 
     assert torch.equal(h, h3), "molora_apply_bucketed: the token-order shrink alone, same bits"
 
 
+@pytest.mark.parametrize("N,d_in,d_out,C,rank,structure", [
+    (384, 1024, 8192, 6, 16, "uniform"),    # at most 512 rows, wide output: the choice is 128 x 128 tiles
+    (200, 4096, 12288, 16, 64, "zipf"),     # the same with a long K and many column tiles
+    (576, 4096, 1024, 8, 32, "uniform"),    # more than 512 rows, narrow output: the choice is the streaming kernel
+    (1500, 4104, 520, 5, 24, "zipf"),       # the same, ragged, K tail, 24 row tiles of 64
+    (130, 264, 328, 9, 8, "uniform"),       # just above the rows that always stream
+    (4096, 512, 72, 3, 8, "uniform"),       # the largest batch the rule looks at
+])
+def test_kernel_choice_and_forced_tile_heights(gpu, N, d_in, d_out, C, rank, structure):
+    """The fused base + expand through the kernel the shape-driven choice picks and through every
+    forced row-tile height (64: the streaming kernel at any N; 128 and 256: the tiled kernel,
+    also below 512 rows): h against the oracle each time, targets out of range included."""
+    import oracle
+    import torch
+    from paper_2603_15965_amd import binding as mb
+    say(f"kernel choice N={N} {d_in}->{d_out} C={C} rank={rank} {structure}")
+    w = wl.custom("s", N, d_in, d_out, C, rank, 9700 + N + C, structure=structure)
+    r = w.r.copy()
+    r[1::19] = -1
+    ref = oracle.apply(w.x, w.W, w.A, w.B, r)
+    gpu.assert_h_close(gpu.gpu_apply(w, r).cpu().numpy(), ref, "the choice, through molora_apply")
+    x, W, A, B = (gpu.dev_bf16(q) for q in (w.x, w.W, w.A, w.B))
+    o, p = mb.molora_bucket(gpu.dev_i32(r), C)
+    t = mb.molora_shrink(x, A, o, p, workspace="auto")
+    for tile_rows in (None, 64, 128, 256):
+        h = mb.molora_base_expand(x, W, B, t, o, p, tile_rows=tile_rows)
+        torch.cuda.synchronize()
+        gpu.assert_h_close(h.cpu().numpy(), ref, f"tile_rows={tile_rows}")
+
+
 @pytest.mark.parametrize("N,d_in,d_out,C,rank,structure,invalid", [
     (64, 4096, 1024, 16, 64, "zipf", False),    # configuration 3's shape class: K split over 4 slices
     (64, 1024, 264, 16, 64, "uniform", True),   # K split over 2 slices, targets out of range
