@@ -132,9 +132,9 @@ size_t molora_apply_workspace_bytes(int64_t N, int32_t d_in, int32_t d_out,
  *   workspace DEVICE, 256-byte aligned, workspace_bytes >= molora_apply_workspace_bytes.
  *   0 <= N < 2^31; d_in, d_out >= 8 and multiples of 8; rank a multiple of 8,
  *   8 <= rank <= MOLORA_MAX_RANK; 1 <= C <= MOLORA_MAX_TARGETS.  For N > 512 (where the
- *   tiled kernel may be taken) x and W must each be smaller than 4 GiB (N * d_in < 2^31 and d_in * d_out < 2^31
- *   elements): larger ones are MOLORA_EINVAL, here and in molora_apply_bucketed,
- *   molora_base_expand and molora_apply_mix.
+ *   tiled kernel may be taken) x and W must each be smaller than 4 GiB
+ *   (N * d_in < 2^31 and d_in * d_out < 2^31 elements): larger ones are MOLORA_EINVAL,
+ *   here and in molora_apply_bucketed, molora_base_expand and molora_apply_mix.
  */
 molora_status molora_apply(const void *x, const void *W, const void *A, const void *B,
                            const int32_t *r, float *h,
