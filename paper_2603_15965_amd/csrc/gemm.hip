@@ -22,10 +22,9 @@
 // linear).  Whatever has to read as zero -- k past d_in, t rows of other buckets, padding of
 // 2*rank up to the tile depth -- is fetched from a small all-zero page instead, so the K
 // tail and the expand tiles travel the same path as the base tiles.
-// Two main loops share the rest of the kernel: large problems (MFMA bound) use two LDS
-// stages with the operand fragments of the next k-step prefetched into registers behind the
-// MFMAs; small batches (N <= 64, bound by streaming W) use a deep ring of LDS stages so that
-// about 100 KB per compute unit is in flight.
+// One main loop for two to four LDS stages, with the operand fragments of the next k-step
+// prefetched into registers behind the MFMAs.  (Small batches, which are bound by streaming W
+// once, have a kernel of their own in small_batch.hip; launch_fused_gemm chooses.)
 // Workgroups are numbered so that the 8 XCDs (blockIdx % 8) each walk a compact group of
 // tiles and share x rows / W columns in their own L2.
 #include <type_traits>

@@ -1,5 +1,5 @@
-// Fused base projection + grouped expand for small batches (up to a few hundred tokens, in row
-// tiles of 64; Eq. "pertok"):
+// Fused base projection + grouped expand for small batches (row tiles of 64; which shapes take
+// this kernel and which the tiled one, launch_fused_gemm decides; Eq. "pertok"):
 //
 //     h[perm[p]][:] = x[perm[p]] W  +  t_p B_{c(p)}
 //
