@@ -41,6 +41,21 @@ def _cases():
         S = None if rng.random() < 0.5 else C + int(rng.integers(0, 5))
         bad = bool(rng.random() < 0.3)
         out.append((i, N, d_in, d_out, C, rank, k, S, bad))
+    # both sides of the choice between the streaming kernel and the tiled one (129 .. 4096 rows:
+    # decided by a cost of both, not by a fixed number of rows), many adapters included
+    for i in range(64, 88):
+        N = int([rng.integers(129, 600), rng.integers(600, 1500), rng.integers(1500, 4300)][i % 3])
+        d_in = int(rng.integers(1, 160)) * 8
+        d_out = int(rng.integers(1, 200)) * 8 if i % 4 else int(rng.integers(8, 100)) * 64
+        while N * d_in * d_out > 2e9:
+            d_in = max(8, d_in // 16 * 8)
+        k = int(rng.choice([1, 1, 1, 2, 3, 4]))
+        rank = int(rng.choice([r for r in ranks if r * k <= 128]))
+        cmax = {1: 200, 2: 31, 3: 10, 4: 5}[k]
+        C = int(rng.integers(max(k, 1), cmax + 1))
+        S = None if rng.random() < 0.5 else C + int(rng.integers(0, 5))
+        bad = bool(rng.random() < 0.3)
+        out.append((i, N, d_in, d_out, C, rank, k, S, bad))
     return out
 
 
