@@ -105,12 +105,19 @@ __global__ __launch_bounds__(Cfg::NT) void fused_gemm_kernel(
     const int per_xcd = (total + 7) / 8;
     const int logical = (int)(blockIdx.x % 8) * per_xcd + (int)(blockIdx.x / 8);
     if (logical >= total) return;
-    const int group_size = kGroupM * tiles_n;
-    const int g = logical / group_size;
-    const int first_m = g * kGroupM;
-    const int gm = min(tiles_m - first_m, kGroupM);
-    const int tile_m = first_m + (logical % group_size) % gm;
-    const int tile_n = (logical % group_size) / gm;
+    // Group g holds the row tiles g, g + ng, g + 2 ng, ... (at most kGroupM of them), not
+    // kGroupM consecutive ones: the rows are gathered through perm, so consecutive row tiles
+    // share nothing, but under a skewed routing the LAST row tiles are the ones crossed by many
+    // small buckets (many expand tiles each), and consecutive grouping put them all on one XCD.
+    const int ng = (tiles_m + kGroupM - 1) / kGroupM;
+    const int q = tiles_m / ng, rem = tiles_m % ng;  // the first rem groups have q + 1 row tiles
+    const int big = rem * (q + 1) * tiles_n;         // output tiles in those groups
+    const int gm = logical < big ? q + 1 : q;
+    const int rest = logical < big ? logical : logical - big;
+    const int g = (logical < big ? 0 : rem) + rest / (gm * tiles_n);
+    const int in_group = rest % (gm * tiles_n);
+    const int tile_m = g + ng * (in_group % gm);
+    const int tile_n = in_group / gm;
     const int p0 = tile_m * BM, n0 = tile_n * BN;
 
     const int R = mix.k * rank;  // width of a bucket's intermediate (k adapters side by side)
