@@ -39,7 +39,7 @@ namespace {
 bool shrink_streams(int64_t N, int d_in, int C, int64_t R) {
     return N <= 64 || (N <= 2048 && d_in * R >= (1 << 17)) ||
            (N * (int64_t)d_in >= (1 << 24) && N >= 128 * (int64_t)C &&
-            ((N + 63) / 64) * C <= 32768);  // its grid has a slot per (bucket, tile)
+            ((N + 63) / 64) * C <= 32768);  // (not too many buckets: every workgroup scans all offsets)
 }
 bool shrink_tiny(int64_t N, int64_t R) { return N <= kShrinkTinyMax && (R + 15) / 16 <= 2; }
 }  // namespace

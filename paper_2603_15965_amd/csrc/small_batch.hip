@@ -33,13 +33,13 @@ namespace molora {
 
 namespace {
 
-constexpr int kSbWaves = 8;                    // wavefronts per workgroup = K splits
+constexpr int kSbWaves = 8;                    // wavefronts per workgroup = K splits (4 in one form of the shrink)
 constexpr int kSbRing = 5;                     // slab slots per wavefront
 constexpr int kSbStage = 64 * 128;             // x / t staging tile: 64 rows x 64 k
 
 // TN = 32-column blocks per workgroup: 2 (64 columns, 128-byte pieces of W rows) where the
 // column groups alone fill the chip, 1 (32 columns) where they would leave it idle.
-template <int TN>
+template <int TN, int NWV = kSbWaves>
 struct SbGeom {
     static constexpr int COLS = 32 * TN;                // output columns per workgroup
     static constexpr int SLOT = 16 * COLS * 2;          // one 16-k slab of W
@@ -48,7 +48,7 @@ struct SbGeom {
     static constexpr int RPD = 64 / CPR;                // slab rows per load instruction
     static constexpr int ROW_BYTES = COLS * 4 + 16;     // partial tile row in LDS (+16: bank shift)
     static constexpr int WAVE_LDS = kSbRing * SLOT + kSbStage;  // per wavefront; partial tile reuses it
-    static constexpr size_t LDS_BYTES = (size_t)kSbWaves * WAVE_LDS + (8 * 64 + 4) * sizeof(int32_t);
+    static constexpr size_t LDS_BYTES = (size_t)NWV * WAVE_LDS + (8 * 64 + 4) * sizeof(int32_t);
     static_assert(64 * ROW_BYTES <= WAVE_LDS, "partial tile fits the wavefront's region");
     // 32-byte chunk position inside a slab row that holds column chunk cc of k-row `row`
     // (keeps the transpose reads of the four 16-lane groups on different banks)
@@ -87,7 +87,8 @@ struct Unit {
 // SHRINK = false: the fused GEMM above (grid: column groups x row tiles of 64 sorted rows; a
 //                 batch of more than 64 rows re-reads W once per row tile, from L2).
 // SHRINK = true:  the shrink step t_p = x[perm[p]] A_c for the rows of bucket c = wg.y
-//                 (grid: column groups of the rank x buckets x 64-row tiles of a bucket); W is
+//                 (workgroup = column group of the rank x 64-row tile of a bucket; which tile a
+//                 workgroup is, small_batch_kernel finds from offsets); W is
 //                 A, d_out is rank, there are no expand units and the result goes to t_out as
 //                 [hi | lo] bf16 halves.  With ksplit > 1 the K range is cut into ksplit
 //                 slices, one workgroup each (wg.z = tile * ksplit + slice): a batch of
@@ -113,17 +114,17 @@ struct SbBlock {
 };
 constexpr int kSbBaseOnly = 1, kSbExpandOnly = 2, kSbBasePacked = 3, kSbExpandPacked = 4;
 
-template <int TM, int TN, bool SHRINK, int MODE = 0>  // TM: 32-row blocks, 1 (N <= 32) or 2
+template <int TM, int TN, bool SHRINK, int MODE = 0, int NWV = kSbWaves>  // TM: 32-row blocks, 1 (N <= 32) or 2
 __device__ __forceinline__ void small_batch_body(
     const uint16_t *__restrict__ x, const uint16_t *__restrict__ W, const uint16_t *__restrict__ B,
     const uint16_t *__restrict__ t2, const int32_t *__restrict__ offsets,
     const int32_t *__restrict__ perm, float *__restrict__ h, uint16_t *__restrict__ t_out, int N,
     int d_in, int d_out, int C, int rank, Mix mix, int ksplit, SortArgs sort, SbBlock wg) {
-    using Geo = SbGeom<TN>;
+    using Geo = SbGeom<TN, NWV>;
     constexpr int kSbCols = Geo::COLS, kSbSlot = Geo::SLOT, kSbRowBytes = Geo::ROW_BYTES,
                   kSbWaveLds = Geo::WAVE_LDS;
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
-    int32_t *tile_perm = (int32_t *)(smem + kSbWaves * kSbWaveLds);  // [64] token per row, -1 = none
+    int32_t *tile_perm = (int32_t *)(smem + NWV * kSbWaveLds);  // [64] token per row, -1 = none
     int32_t *tile_pos = tile_perm + 64;                              // [64] sorted position per row
     int32_t *seg_lo = tile_pos + 64;                                 // buckets that own rows, ascending:
     int32_t *seg_hi = seg_lo + 64;                                   // their sorted-position ranges
@@ -213,7 +214,7 @@ __device__ __forceinline__ void small_batch_body(
     const int per_slice = SHRINK ? (nub_all + ksplit - 1) / ksplit : nub_all;
     const int u_lo = slice * per_slice;
     const int nub = expand_only ? 0 : max(0, min(nub_all, u_lo + per_slice) - u_lo);
-    const int nw = nub > wave ? (nub - wave + kSbWaves - 1) / kSbWaves : 0;
+    const int nw = nub > wave ? (nub - wave + NWV - 1) / NWV : 0;
 
     // elements between consecutive k-rows of W (A); packed: inside a slab of 16 k-rows the
     // workgroup's column group is a [rows][COLS] matrix of its own
@@ -230,7 +231,7 @@ __device__ __forceinline__ void small_batch_body(
     auto unit_of = [&](int u) {  // u-th unit of this wavefront
         Unit un;
         un.real = u < nw;
-        un.k0 = un.real ? (u_lo + u * kSbWaves + wave) * 64 : 0;
+        un.k0 = un.real ? (u_lo + u * NWV + wave) * 64 : 0;
         un.fast = un.real && un.k0 + 64 <= d_in;
         if constexpr (packed)  // slab k / 16 starts at k * d_out; in it, group after group
             un.base = (const unsigned char *)(W + (int64_t)un.k0 * d_out + (int64_t)wg.x * 16 * kSbCols);
@@ -335,12 +336,12 @@ __device__ __forceinline__ void small_batch_body(
 
     // expand alone: what h holds (the rows' x W) is fetched now and added at the end; in token
     // order the row of h is the tile row, so nothing has to be looked up first
-    constexpr int kOutIters = (TM * 32 * (kSbCols / 4) + kSbWaves * 64 - 1) / (kSbWaves * 64);
+    constexpr int kOutIters = (TM * 32 * (kSbCols / 4) + NWV * 64 - 1) / (NWV * 64);
     f32x4 h_old[kOutIters];
     if constexpr (expand_only) {
 #pragma unroll
         for (int j = 0; j < kOutIters; ++j) {
-            const int it = tid + j * kSbWaves * 64;
+            const int it = tid + j * NWV * 64;
             const int row = it / (kSbCols / 4), col = n0 + (it % (kSbCols / 4)) * 4;
             const bool ok = it < TM * 32 * (kSbCols / 4) && row < nrows && col < d_out;
             // (rows and columns past the end: read again from the first element, never used)
@@ -413,7 +414,7 @@ __device__ __forceinline__ void small_batch_body(
             if ((unsigned)tok < 64u) tile_pos[tok] = lane;  // same wavefront: after the line above
         }
     }
-    if (wave == kSbWaves - 1) {
+    if (wave == NWV - 1) {
         const uint64_t lower = (lane == 0) ? 0ull : (~0ull >> (64 - lane));
         int cnt = 0;
         for (int c0 = 0; !SHRINK && !base_only && c0 < C; c0 += 64) {
@@ -485,11 +486,11 @@ __device__ __forceinline__ void small_batch_body(
         int p_row[TM];  // sorted position of this lane's rows
 #pragma unroll
         for (int tm = 0; tm < TM; ++tm) p_row[tm] = tile_pos[tm * 32 + m_lo];
-        for (int q0 = wave; q0 < nq; q0 += kSbWaves * G) {
+        for (int q0 = wave; q0 < nq; q0 += NWV * G) {
             bf16x8 ta[G][2][TM];
 #pragma unroll
             for (int g = 0; g < G; ++g) {
-                const int q = q0 + kSbWaves * g;
+                const int q = q0 + NWV * g;
                 if (q >= nq) break;
                 const int sg = nsl == 1 ? q : q / nsl;
                 const int part = q - sg * nsl;
@@ -540,7 +541,7 @@ __device__ __forceinline__ void small_batch_body(
             wait_vmcnt<0>();
 #pragma unroll
             for (int g = 0; g < G; ++g) {
-                if (q0 + kSbWaves * g >= nq) break;
+                if (q0 + NWV * g >= nq) break;
                 bf16x8 bfr[TN];
 #pragma unroll
                 for (int tn = 0; tn < TN; ++tn) bfr[tn] = load_b_frag(ring + g * kSbSlot, tn);
@@ -557,7 +558,7 @@ __device__ __forceinline__ void small_batch_body(
         }
     }
 
-    // ---- add the 8 partial tiles, every row to its original position ----
+    // ---- add the wavefronts' partial tiles, every row to its original position ----
     // acc[tm][tn][v]: row tm*32 + (v/4)*8 + (lane/32)*4 + v%4, column tn*32 + lane%32
 #pragma unroll
     for (int tm = 0; tm < TM; ++tm)
@@ -571,7 +572,7 @@ __device__ __forceinline__ void small_batch_body(
     __syncthreads();
 #pragma unroll
     for (int j = 0; j < kOutIters; ++j) {
-        const int it = tid + j * kSbWaves * 64;
+        const int it = tid + j * NWV * 64;
         if (it >= TM * 32 * (kSbCols / 4)) break;
         const int row = it / (kSbCols / 4), ch = it % (kSbCols / 4);
         const int tok = tile_perm[row];
@@ -579,7 +580,7 @@ __device__ __forceinline__ void small_batch_body(
         if (tok < 0 || col >= d_out) continue;
         f32x4 sum = *(const f32x4 *)(smem + row * kSbRowBytes + ch * 16);
 #pragma unroll
-        for (int w = 1; w < kSbWaves; ++w)
+        for (int w = 1; w < NWV; ++w)
             sum += *(const f32x4 *)(smem + w * kSbWaveLds + row * kSbRowBytes + ch * 16);
         if (SHRINK && ksplit > 1) {
             // partial sums of this K slice; weights and the bf16 split wait for the reduction
@@ -596,24 +597,81 @@ __device__ __forceinline__ void small_batch_body(
     }
 }
 
-template <int TM, int TN, bool SHRINK, int MODE>
-__global__ __launch_bounds__(kSbWaves * 64) void small_batch_kernel(
+template <int TM, int TN, bool SHRINK, int MODE, int NWV>
+__global__ __launch_bounds__(NWV * 64) void small_batch_kernel(
     const uint16_t *__restrict__ x, const uint16_t *__restrict__ W, const uint16_t *__restrict__ B,
     const uint16_t *__restrict__ t2, const int32_t *__restrict__ offsets,
     const int32_t *__restrict__ perm, float *__restrict__ h, uint16_t *__restrict__ t_out, int N,
     int d_in, int d_out, int C, int rank, Mix mix, int ksplit, SortArgs sort) {
-    // SHRINK: y numbers the buckets, rotated by one for every 4 steps of z (the tile and K
-    // slice).  Workgroups go to the XCDs round-robin, so with bucket = y and 32 buckets every tile
-    // of a bucket sat on the same XCD: good while the buckets are level (an XCD's L2 then holds
-    // the A_c of four buckets instead of all), but a batch routed to a single adapter ran on an
-    // eighth of the chip (412 us at 16384 tokens).  Measured, level buckets / one bucket, for a
-    // rotation every 1, 2, 4, 8 steps: 44.9 / 36.5, 41.3 / 37.4, 39.3 / 38.8, 38.3 / 60.3 us.
-    // The tiles a bucket can have at most are mostly empty, and the low tile indices, which are
-    // the ones in use, stay the first workgroups of the launch.
-    const int by = (int)blockIdx.y, bz = (int)blockIdx.z, ny = (int)gridDim.y;
-    const SbBlock wg = SbBlock{(int)blockIdx.x, SHRINK ? (by + ny - (bz >> 2) % ny) % ny : by, bz, ny};
-    small_batch_body<TM, TN, SHRINK, MODE>(x, W, B, t2, offsets, perm, h, t_out, N, d_in, d_out, C, rank, mix,
-                                           ksplit, sort, wg);
+    SbBlock wg = SbBlock{(int)blockIdx.x, (int)blockIdx.y, (int)blockIdx.z, (int)gridDim.y};
+    if constexpr (SHRINK) {
+        if (sort.r == nullptr) {
+            // Grid (work items, column groups, K slices): the work items are the 64-row tiles of
+            // the buckets, bucket after bucket, and every wavefront finds its own from `offsets`
+            // (there are at most ceil(N / 64) + C of them; workgroups past the last leave).
+            // Workgroups go to the XCDs round-robin and item = XCD-major, so an XCD takes a
+            // contiguous range of tiles: a few whole buckets when the buckets are level (its L2
+            // then holds their A_c, not everyone's), its share of the tiles when one bucket
+            // holds most rows.  (The grid this replaces had a slot for every (bucket, tile a
+            // bucket can have at most): 8192 workgroups for the 256-272 tiles of 16384 tokens in
+            // 32 buckets.  While the buckets are level the tiles in use are the first workgroups
+            // of such a grid and the empty ones cost little; under a skewed routing the tiles of
+            // the long buckets lie far apart in it, one or two in every 32 workgroups, and the
+            // launch took 87 us instead of 45 (zipf), 48 instead of 30-33 us (one bucket).)
+            const int lane = threadIdx.x & 63;
+            // tiles of the buckets of one group of 64: this lane's bucket, its inclusive prefix
+            int lo = 0, hi = 0, tiles = 0, incl = 0;
+            auto scan_group = [&](int c0) {
+                const int c = c0 + lane;
+                lo = hi = 0;
+                if (c < C) {
+                    lo = offsets[c];
+                    hi = offsets[c + 1];
+                }
+                tiles = max(0, (hi - lo + 63) / 64);
+                incl = tiles;
+#pragma unroll
+                for (int d = 1; d < 64; d <<= 1) {
+                    const int up = __shfl_up(incl, d, 64);
+                    if (lane >= d) incl += up;
+                }
+            };
+            int total = 0;  // work items of the launch
+            for (int c0 = 0; c0 < C; c0 += 64) {
+                scan_group(c0);
+                total += __shfl(incl, 63, 64);
+            }
+            // XCD j takes items [j * per_xcd, (j + 1) * per_xcd): an equal share of the items there
+            // are, not of the slots of the grid (36 slots against 32 items per XCD made a second
+            // round of workgroups on seven XCDs)
+            const int per_xcd = (total + 7) / 8;
+            const int in_xcd = (int)(blockIdx.x / 8);
+            const int item = (int)(blockIdx.x % 8) * per_xcd + in_xcd;
+            int bucket = -1, tile = 0;
+            if (in_xcd < per_xcd && item < total) {
+                int running = 0;  // tiles of the buckets before the current group
+                for (int c0 = 0; c0 < C && bucket < 0; c0 += 64) {
+                    if (C > 64) scan_group(c0);  // (one group: still in registers)
+                    const int rel = item - (running + incl - tiles);
+                    const uint64_t m = __ballot(rel >= 0 && rel < tiles);
+                    if (m) {
+                        const int src = __ffsll((long long)m) - 1;
+                        bucket = __shfl(c0 + lane, src, 64);
+                        tile = __shfl(rel, src, 64);
+                    }
+                    running += __shfl(incl, 63, 64);
+                }
+            }
+            if (bucket < 0) return;  // (the same for every wavefront of the workgroup)
+            // (every lane holds the same pair; said explicitly, so that what is derived from
+            // it stays in scalar registers)
+            bucket = __builtin_amdgcn_readfirstlane(bucket);
+            tile = __builtin_amdgcn_readfirstlane(tile);
+            wg = SbBlock{(int)blockIdx.y, bucket, tile * ksplit + (int)blockIdx.z, C};
+        }
+    }
+    small_batch_body<TM, TN, SHRINK, MODE, NWV>(x, W, B, t2, offsets, perm, h, t_out, N, d_in, d_out, C, rank,
+                                                mix, ksplit, sort, wg);
 }
 
 // A decode-sized batch (N <= 64): the shrink (with the dispatch step inside, see SortArgs) and
@@ -671,30 +729,34 @@ __global__ __launch_bounds__(256) void shrink_reduce_kernel(const float *__restr
 }
 
 // more than 64 KB of dynamic LDS has to be asked for, once per device (see common.h)
-template <int TM, int TN, bool SHRINK, int MODE>
+template <int TM, int TN, bool SHRINK, int MODE, int NWV>
 struct SmallBatchKernel {
-    static inline LdsRegistrar lds{(const void *)small_batch_kernel<TM, TN, SHRINK, MODE>, SbGeom<TN>::LDS_BYTES};
+    static inline LdsRegistrar lds{(const void *)small_batch_kernel<TM, TN, SHRINK, MODE, NWV>,
+                                   SbGeom<TN, NWV>::LDS_BYTES};
 };
 
-template <int TM, int TN, bool SHRINK, int MODE = 0>
+template <int TM, int TN, bool SHRINK, int MODE = 0, int NWV = kSbWaves>
 hipError_t launch_small(const uint16_t *x, const uint16_t *W, const uint16_t *B, const uint16_t *t2,
                         const int32_t *offsets, const int32_t *perm, float *h, uint16_t *t_out, int N,
                         int d_in, int d_out, int C, int rank, Mix mix, hipStream_t s, int ksplit,
                         SortArgs sort) {
-    using Geo = SbGeom<TN>;
-    auto kern = small_batch_kernel<TM, TN, SHRINK, MODE>;
-    (void)&SmallBatchKernel<TM, TN, SHRINK, MODE>::lds;  // instantiates the registration
+    using Geo = SbGeom<TN, NWV>;
+    auto kern = small_batch_kernel<TM, TN, SHRINK, MODE, NWV>;
+    (void)&SmallBatchKernel<TM, TN, SHRINK, MODE, NWV>::lds;  // instantiates the registration
     const unsigned groups = (unsigned)((d_out + Geo::COLS - 1) / Geo::COLS);
     const unsigned row_tiles = (unsigned)((N + 63) / 64);
-    // GEMM: row tiles of the batch.  SHRINK: buckets x row tiles a bucket can have at most
-    // (workgroups past a bucket's end leave at once)
-    // (a K-split shrink: one workgroup per K slice of each of them)
-    const dim3 grid = SHRINK ? dim3(groups, (unsigned)C, row_tiles * (unsigned)ksplit) : dim3(groups, row_tiles);
+    // GEMM: column groups x row tiles of the batch.  SHRINK: the 64-row tiles of the buckets (at
+    // most row_tiles + C, rounded up to the eight XCDs) x column groups x K slices; with the
+    // dispatch step inside (one row tile) column groups x buckets x K slices.
+    const unsigned items = (row_tiles + (unsigned)C + 7) / 8 * 8;
+    const dim3 grid = !SHRINK ? dim3(groups, row_tiles)
+                              : (sort.r != nullptr ? dim3(groups, (unsigned)C, (unsigned)ksplit)
+                                                   : dim3(items, groups, (unsigned)ksplit));
     if constexpr (!SHRINK && MODE == 0)  // the small-batch GEMM: base projection and expand
-        launch_base_kernel(kern, grid, dim3(kSbWaves * 64), Geo::LDS_BYTES, s, x, W, B, t2, offsets, perm, h,
+        launch_base_kernel(kern, grid, dim3(NWV * 64), Geo::LDS_BYTES, s, x, W, B, t2, offsets, perm, h,
                            t_out, N, d_in, d_out, C, rank, mix, ksplit, sort);
     else
-        hipLaunchKernelGGL(kern, grid, dim3(kSbWaves * 64), Geo::LDS_BYTES, s, x, W, B, t2, offsets, perm,
+        hipLaunchKernelGGL(kern, grid, dim3(NWV * 64), Geo::LDS_BYTES, s, x, W, B, t2, offsets, perm,
                            h, t_out, N, d_in, d_out, C, rank, mix, ksplit, sort);
     return hipGetLastError();
 }
@@ -711,6 +773,17 @@ hipError_t launch_small_tn(const uint16_t *x, const uint16_t *W, const uint16_t 
     const bool narrow = SHRINK || wgs64 <= 128;
 #define MOLORA_SB_LAUNCH(TM, TN) \
     launch_small<TM, TN, SHRINK, MODE>(x, W, B, t2, offsets, perm, h, t_out, N, d_in, d_out, C, rank, mix, s, ksplit, sort)
+    if constexpr (SHRINK) {
+        // A shrink with more 64-row tiles than compute units (the buckets' ragged last tiles
+        // included: about C / 2 of them) runs workgroups of four wavefronts, three of which fit a
+        // compute unit's LDS, so that all tiles are resident at once.  With eight wavefronts a
+        // compute unit holds one workgroup, and the 16 tiles that 16384 tokens in 32 buckets have
+        // beyond 256 made a second round on an otherwise idle chip (40 us against 25 us for
+        // the 256 tiles of 32 buckets of exactly 512 rows).
+        if (sort.r == nullptr && N > 64 && (N + 63) / 64 + C / 2 > 256)
+            return launch_small<2, 1, true, 0, 4>(x, W, B, t2, offsets, perm, h, t_out, N, d_in, d_out, C, rank,
+                                                  mix, s, ksplit, sort);
+    }
     if (N <= 32) return narrow ? MOLORA_SB_LAUNCH(1, 1) : MOLORA_SB_LAUNCH(1, 2);
     return narrow ? MOLORA_SB_LAUNCH(2, 1) : MOLORA_SB_LAUNCH(2, 2);
 #undef MOLORA_SB_LAUNCH
