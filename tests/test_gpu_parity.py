@@ -371,6 +371,31 @@ def test_many_small_buckets_share_expand_tiles(gpu, N, d_in, d_out, C, rank, str
     gpu.assert_h_close(h.cpu().numpy(), oracle.apply(w.x, w.W, w.A, w.B, r), "many small buckets")
 
 
+@pytest.mark.parametrize("N,d_in,C,rank,structure", [
+    (16500, 1024, 12, 32, "zipf"),      # more tiles than compute units: workgroups of four wavefronts
+    (16500, 1024, 12, 32, "one"),       # every token on one adapter: its tiles spread over the XCDs
+    (9000, 2048, 70, 16, "zipf"),       # more than 64 buckets: two groups in the search; eight wavefronts
+    (20000, 1024, 5, 64, "runs"),       # two column groups of the rank
+])
+def test_streaming_shrink_finds_its_tiles_under_skew(gpu, N, d_in, C, rank, structure):
+    """The streaming shrink numbers the 64-row tiles that are in use and every workgroup finds
+    its bucket and tile from offsets: skewed, single-target and run-structured routing, some
+    targets out of range; h against the oracle."""
+    import oracle
+    say(f"streaming shrink N={N} d_in={d_in} C={C} rank={rank} {structure}")
+    d_out = 64
+    w = wl.custom("ss", N, d_in, d_out, C, rank, 9700 + N + C, structure="zipf" if structure == "zipf" else "uniform")
+    r = w.r.copy()
+    if structure == "one":
+        r[:] = C // 2
+    elif structure == "runs":
+        r = np.repeat(np.random.default_rng(N).integers(0, C, N // 90 + 1), 90)[:N].astype(np.int32)
+    r[5::19] = -1
+    r[7::23] = C + 1
+    h = gpu.gpu_apply(w, r)
+    gpu.assert_h_close(h.cpu().numpy(), oracle.apply(w.x, w.W, w.A, w.B, r), "streaming shrink under skew")
+
+
 def test_gate_dispatch_shrink_matches_separate_calls(gpu):
     """Gating + dispatch + shrink in one launch on configuration 1's shape and on composite
     targets: r, offsets, perm bit for bit as the oracle's, h as the oracle's."""
