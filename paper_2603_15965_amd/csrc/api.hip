@@ -645,7 +645,7 @@ const char *molora_status_string(molora_status status) {
     }
 }
 
-const char *molora_version(void) { return "molora-gfx950 0.7"; }
+const char *molora_version(void) { return "molora-gfx950 0.8"; }
 
 molora_status molora_init(void) {
     return molora::ensure_device_ready() == hipSuccess ? MOLORA_OK : MOLORA_EHIP;
