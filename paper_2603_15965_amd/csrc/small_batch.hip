@@ -902,6 +902,12 @@ int small_batch_shrink_ksplit(int64_t N, int d_in, int C, int R) {
     const int64_t wgs = groups * pairs;
     if (wgs <= 64 && d_in >= 2048) return 4;
     if (wgs <= 128 && d_in >= 1024) return 2;
+    // A few more tiles than compute units (the buckets' ragged last tiles) and a long K: the
+    // launch takes as long as the compute unit that got two tiles, and quarter tiles level the
+    // shares.  It pays the second launch only when K is long: 16384 x 12288, 32 buckets of rank
+    // 32: 119.5 -> 102.3 us; at d_in = 4096 45.0 -> 45.4 us (one bucket: 32.9 -> 37.6 us).
+    const int64_t tiles = (N + 63) / 64 + C / 2;
+    if (N > 64 && groups == 1 && tiles > 256 && tiles <= 512 && d_in >= 8192) return 4;
     return 1;
 }
 
