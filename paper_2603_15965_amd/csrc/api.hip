@@ -645,7 +645,7 @@ const char *molora_status_string(molora_status status) {
     }
 }
 
-const char *molora_version(void) { return "molora-gfx950 0.8"; }
+const char *molora_version(void) { return "molora-gfx950 0.9"; }
 
 molora_status molora_init(void) {
     return molora::ensure_device_ready() == hipSuccess ? MOLORA_OK : MOLORA_EHIP;
